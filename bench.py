@@ -1,0 +1,133 @@
+#!/usr/bin/env python3
+"""Throughput of the CADA hot path on one MI355X: worker-iterations/s.
+
+A step is one call of cada_step(): both minibatch gradients of all M workers, the
+communication rule, the masked refresh, the aggregate, the AMSGrad-type update and the
+ring push.  Inputs (features, labels, the whole index schedule) are resident in HBM before
+the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_step(cfg) -> float:
+    """Bytes the method itself must move per step for the logistic models: the B gathered
+    rows of every worker once (4 B p), the reference iterate read (4p) and the fresh
+    gradient write (4p) per worker (CADA1: stored innovation read + fresh innovation write
+    instead of the reference read), and the server's pass over the M stored gradients
+    plus the five p-vectors it reads/writes (32p)."""
+    M, p, B = cfg.M, cfg.p, cfg.B
+    per_worker = 4.0 * B * p + 4.0 * p + 4.0 * p
+    if cfg.rule == 1:
+        per_worker += 4.0 * p
+    return M * per_worker + 4.0 * M * p + 32.0 * p
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the HBM-bound logistic workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: every box here has one, and the path uses no collectives "
+              "(--gpus %d refused)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from cada_synth import configs, generators, native
+    from paper_2012_15469_amd import binding
+    from paper_2012_15469_amd.binding import Cada
+
+    cfg = configs.ALL[args.config]
+    dev = torch.device("cuda:0")
+    K, W = args.steps, args.warmup
+    t0 = time.time()
+    prob = generators.make_problem(cfg)
+    if prob.X is None:                  # counter-based recipe: generated in HBM
+        shift = torch.from_numpy(prob.shift).to(dev)
+        X = torch.empty((cfg.M * cfg.N_m, cfg.p), dtype=torch.float32, device=dev)
+        y = torch.empty(cfg.M * cfg.N_m, dtype=torch.float32, device=dev)
+        native.fill_device(cfg, shift, X, y)
+    else:
+        X, y = torch.from_numpy(prob.X).to(dev), torch.from_numpy(prob.y).to(dev)
+    theta0 = torch.from_numpy(prob.theta0).to(dev)
+    sched = torch.from_numpy(generators.make_schedule(cfg, W + K)).to(dev)
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+
+    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0)
+    for k in range(W):
+        eng.step(sched[k])
+    torch.cuda.synchronize()
+    binding.cada_profile_begin(eng.ctx, K)
+    t1 = time.perf_counter()
+    for k in range(W, W + K):
+        eng.step(sched[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    prof = binding.cada_profile_end(eng.ctx)
+    st = eng.state()
+    torch.cuda.synchronize()
+    uploads = int(st["uploads_total"].item())
+    assert int(st["error_flags"].item()) == 0
+    assert bool(torch.isfinite(st["theta"]).all())
+
+    value = cfg.M * K / dt
+    out = {"metric": "worker-iterations/sec (grads+CADA rule+AMSGrad)", "value": value, "unit": "worker-iterations/s",
+           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": 1e3 * dt / K, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32" if cfg.gemm_dtype == "fp32" else "bf16",
+           "data": "synthetic",
+           "config": {"workload": cfg.name, "M": cfg.M, "p": cfg.p, "B": cfg.B, "N_m": cfg.N_m,
+                      "rule": "CADA%d" % cfg.rule, "D": cfg.D, "d_max": cfg.d_max, "c": cfg.c,
+                      "uploads_per_worker_step": uploads / float(cfg.M * (W + K)), "setup_s": round(t_setup, 1)},
+           "kernel_ms": {k: v for k, v in prof.items() if k != "steps"}}
+
+    if cfg.model == "logreg":
+        # the two streaming passes over the gathered rows together form the gradient phase;
+        # its algorithmic bytes are those of the whole step (rows counted once)
+        grad_ms = prof["logreg_dots"] + prof["logreg_grad"]
+        alg = algorithmic_bytes_per_step(cfg)
+        achieved = alg / (grad_ms * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": "logreg_dots+logreg_grad", "achieved": achieved,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                           "algorithmic_bytes_per_launch": alg, "avg_launch_ms": grad_ms}
+
+    if not args.no_cpu_baseline:
+        from oracle.driver import oracle_for
+        # bounded sample: a few steps of the first Ms workers of the same workload
+        Ms = min(cfg.M, 8 if cfg.p >= 4096 else cfg.M)
+        sub = cfg.scaled(M=Ms)
+        sprob = generators.Problem(sub, None if prob.X is None else prob.X[:Ms * cfg.N_m],
+                                   None if prob.y is None else prob.y[:Ms * cfg.N_m], prob.theta0,
+                                   None if prob.shift is None else prob.shift[:Ms])
+        ssched = generators.make_schedule(sub, 64)
+        o = oracle_for(sub, sprob)
+        tc = time.perf_counter()
+        n = 0
+        while n < 64 and (n < 2 or time.perf_counter() - tc < 10.0):
+            o.step(ssched[n])
+            n += 1
+        dtc = time.perf_counter() - tc
+        out["cpu_baseline"] = {"value": Ms * n / dtc, "unit": "worker-iterations/s",
+                               "cores": len(os.sched_getaffinity(0)), "kind": "oracle",
+                               "sample": "%d steps of the first %d of %d workers, same p/B/N_m, fp64 numpy" % (n, Ms, cfg.M)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -37,6 +37,9 @@ class Problem:
         if self.X is not None:
             g = m * self.cfg.N_m + np.asarray(local_rows, dtype=np.int64)
             return self.X[g], self.y[g]
+        from . import native
+        if native.have_cpu():          # same function, in C
+            return native.rows_cpu(self.cfg.seed, m, local_rows, self.cfg.d0, self.shift[m])
         return philox.counter_rows(self.cfg.seed, m, local_rows, self.cfg.d0, self.shift[m])
 
 

@@ -1,0 +1,161 @@
+/*
+ * cada.h - C ABI of the CADA (Communication-Adaptive Distributed Adam) hot path
+ *          for all M simulated workers on one AMD MI355X (gfx950).
+ *
+ * One call to cada_step() is one iteration k of the paper's Algorithm 1:
+ *   - every worker m evaluates its minibatch stochastic gradient at theta^k and at
+ *     its reference point on the SAME samples (CADA1: the snapshot theta-tilde,
+ *     refreshed when k mod D == 0; CADA2: theta^{k - tau_m^k}, the iterate of its
+ *     last upload);
+ *   - the squared norm of the rule's left-hand side (Section 2.2, condition
+ *     (workerrule1) for CADA1, (workerrule2) for CADA2) is compared with
+ *         (c / d_max) * sum_{d=1..d_max} |theta^{k+1-d} - theta^{k-d}|^2 ;
+ *     a worker uploads iff the condition is violated or tau_m^k >= D;
+ *   - uploading workers refresh their stored gradient (tau_m <- 1), the others
+ *     keep the stale one (tau_m <- tau_m + 1);
+ *   - the server forms nabla^k = (1/M) sum_m (stored gradient of m) and applies
+ *     equations (CADA-1)-(CADA-3) of Section 1.2:
+ *         h <- beta1 h + (1-beta1) nabla,  v <- beta2 vhat + (1-beta2) nabla^2,
+ *         vhat <- max(v, vhat),  theta <- theta - alpha * h / sqrt(eps + vhat),
+ *     and records |theta^{k+1}-theta^k|^2 among the last d_max squared steps.
+ *
+ * Conventions
+ *   - Pointers marked DEVICE are HIP device pointers owned by the caller; HOST
+ *     pointers are ordinary host memory and are only read during the call.
+ *   - The library never allocates or frees device memory: all state lives in the
+ *     caller's workspace (size from cada_workspace_bytes()).
+ *   - cada_init / cada_step / cada_run enqueue work on the given stream and never
+ *     synchronise the host.  X, y, idx, replay and the workspace must stay valid
+ *     until that work has completed.
+ *   - Every function returns 0 on success or a negative CADA_E* code; the text of
+ *     the last error on the calling thread is available from cada_last_error().
+ *     Nothing aborts or throws across this boundary.
+ */
+#ifndef CADA_H
+#define CADA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cada_ctx cada_ctx; /* opaque, host memory owned by the library */
+
+enum { CADA_RULE_CADA1 = 1, CADA_RULE_CADA2 = 2 };   /* Section 2.2 */
+enum { CADA_MODEL_LOGREG = 0, CADA_MODEL_MLP = 1 };
+enum { CADA_GEMM_FP32 = 0, CADA_GEMM_BF16 = 1 };
+
+enum {
+  CADA_OK = 0,
+  CADA_EINVAL = -1,     /* bad argument (message says which) */
+  CADA_EWORKSPACE = -2, /* workspace too small or misaligned */
+  CADA_EHIP = -3,       /* a HIP call failed */
+  CADA_EUNSUPPORTED = -4
+};
+
+#define CADA_REPLAY_FREE 255 /* replay byte that leaves the decision to the rule */
+#define CADA_MAX_LAYERS 8
+#define CADA_MAX_B 4096      /* minibatch rows per worker */
+#define CADA_MAX_DMAX 1024
+
+/* Problem statement of Section 1 (M workers, theta in R^p, local data per worker)
+ * plus the inputs of Algorithm 1 (alpha, c, D) and of the rules (d_max). */
+typedef struct cada_config {
+  int32_t M;                 /* workers */
+  int64_t p;                 /* parameters; checked against the model */
+  int32_t model;             /* CADA_MODEL_* */
+  int32_t n_layers;          /* LOGREG: 1 ; MLP: number of weight layers L */
+  const int32_t *layer_dims; /* HOST [n_layers+1]; LOGREG: {p, 1}; MLP: {d0,...,dL} */
+  int32_t B;                 /* minibatch rows per worker per step, 1..CADA_MAX_B */
+  const int64_t *n_samples;  /* HOST [M]; worker m owns rows [off_m, off_m+N_m) of X,
+                                off_m = N_0 + ... + N_{m-1} */
+  const float *X;            /* DEVICE, row-major [sum N_m, d0] float32, read-only */
+  const void *y;             /* DEVICE [sum N_m]: float32 +1/-1 (LOGREG), int32 class (MLP) */
+  float alpha, beta1, beta2, eps; /* (CADA-1)-(CADA-3); constant stepsize */
+  float lambda_l2;           /* LOGREG: (lambda/2)|theta|^2 is part of the loss */
+  float c;                   /* threshold constant of the rules, >= 0 */
+  int32_t d_max;             /* squared steps averaged on the right-hand side */
+  int32_t D;                 /* max delay (forced upload) and CADA1 snapshot period */
+  int32_t rule;              /* CADA_RULE_* */
+  int32_t gemm_dtype;        /* MLP contractions: CADA_GEMM_* (LOGREG ignores it) */
+  int64_t trace_steps;       /* steps of per-step trace to keep (0 = none) */
+  void *workspace;           /* DEVICE, 256-byte aligned, caller-owned */
+  size_t workspace_bytes;
+  void *stream;              /* hipStream_t; NULL = the default stream */
+} cada_config;
+
+/* Device pointers into the workspace (valid until cada_destroy, contents change
+ * with every step) and host-side counters. */
+typedef struct cada_state {
+  const float *theta, *h, *v, *vhat, *nabla; /* DEVICE [p] */
+  const int32_t *tau;                        /* DEVICE [M], tau_m^k for the next step */
+  const float *ring;                         /* DEVICE [d_max], slot j mod d_max = |theta^{j+1}-theta^j|^2 */
+  const uint8_t *mask;                       /* DEVICE [M], uploads of the last step */
+  const float *lhs;                          /* DEVICE [M], rule left-hand sides of the last step */
+  const uint64_t *uploads_total;             /* DEVICE [1], sum of all masks so far */
+  const uint32_t *error_flags;               /* DEVICE [1], bit 0: a minibatch index was out of range (clamped) */
+  int64_t k;                                 /* steps enqueued so far */
+  int64_t trace_steps;                       /* capacity of the trace */
+  const uint8_t *trace_mask;                 /* DEVICE [trace_steps, M] applied masks */
+  const uint8_t *trace_own_mask;             /* DEVICE [trace_steps, M] the rule's own decision */
+  const float *trace_lhs;                    /* DEVICE [trace_steps, M] */
+  const float *trace_rhs;                    /* DEVICE [trace_steps] */
+  const int32_t *trace_tau;                  /* DEVICE [trace_steps, M] tau_m^k before the step */
+} cada_state;
+
+/* Bytes of device workspace cada_init needs for this configuration (only the
+ * shape fields, rule, model, gemm_dtype, D, d_max and trace_steps are read).
+ * Returns 0 and sets the error text if the configuration is invalid. */
+size_t cada_workspace_bytes(const cada_config *cfg);
+
+/* Validates cfg, lays the state out in cfg->workspace and enqueues its
+ * initialisation: theta <- theta0 (DEVICE [p]), h = v = vhat = 0, stored
+ * gradients 0, tau_m = D (so every worker uploads at k = 0), all squared steps 0
+ * (theta^{-D} = ... = theta^0, supplement "Supporting Lemmas").  *out receives the
+ * context.  theta0 may be released once the stream has passed this call. */
+int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out);
+
+/* One iteration of Algorithm 1.  idx: DEVICE int32 [M, B], worker-local row ids
+ * in [0, N_m) (duplicates allowed; out-of-range ids are clamped and flagged).
+ * replay: DEVICE uint8 [M] or NULL; 0 / 1 force "skip" / "upload" for that
+ * worker, CADA_REPLAY_FREE leaves the decision to the rule.  The rule's own
+ * decision is always evaluated and traced. */
+int cada_step(cada_ctx *ctx, const int32_t *idx, const uint8_t *replay);
+
+/* n_steps iterations back to back: idx_sched DEVICE int32 [n_steps, M, B],
+ * replay_sched DEVICE uint8 [n_steps, M] or NULL. */
+int cada_run(cada_ctx *ctx, const int32_t *idx_sched, const uint8_t *replay_sched, int64_t n_steps);
+
+/* Fills *out with device pointers and host counters.  Does not synchronise:
+ * read the device memory after synchronising the stream. */
+int cada_get_state(cada_ctx *ctx, cada_state *out);
+
+/* Enqueues a copy of the M stored (possibly stale) gradients, one row per
+ * worker, into out (DEVICE float32 [M, p]). */
+int cada_copy_stored_gradients(cada_ctx *ctx, float *out);
+
+/* Measurement hooks (not part of the method).  cada_profile_begin creates HIP events
+ * for up to max_steps steps; while profiling, every step records an event on the
+ * context's stream before and after each of its phases (a phase is one kernel, or one
+ * group of kernels, named by cada_profile_phase_name).  cada_profile_end waits for
+ * the last recorded event (this one call does synchronise the host), writes the
+ * summed duration of each phase in milliseconds into ms_out (HOST, n_out doubles,
+ * n_out >= cada_profile_phases(ctx)), the number of profiled steps into *steps_out,
+ * and destroys the events. */
+int cada_profile_phases(cada_ctx *ctx);
+const char *cada_profile_phase_name(cada_ctx *ctx, int phase);
+int cada_profile_begin(cada_ctx *ctx, int64_t max_steps);
+int cada_profile_end(cada_ctx *ctx, double *ms_out, int n_out, int64_t *steps_out);
+
+/* Frees the host context.  Device memory is the caller's. */
+void cada_destroy(cada_ctx *ctx);
+
+/* Text of the last error on this thread ("" if none). */
+const char *cada_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CADA_H */

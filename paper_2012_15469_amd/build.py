@@ -1,0 +1,39 @@
+"""Builds the HIP libraries in-tree for gfx950 with hipcc (cross-compiles without a GPU)."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+
+LIBCADA = os.path.join(HERE, "libcada.so")
+LIBCADA_SRC = [os.path.join(HERE, "csrc", f) for f in
+               ("cada_api.hip", "cada_logreg.hip", "cada_server.hip", "cada_mlp.hip")]
+
+
+def _run(cmd):
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if r.returncode != 0:
+        raise RuntimeError("build failed: %s\n%s" % (" ".join(cmd), out))
+    return out
+
+
+def build_libcada() -> str:
+    _run([HIPCC, *HIP_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIBCADA, *LIBCADA_SRC])
+    return LIBCADA
+
+
+def build_all() -> None:
+    build_libcada()
+
+
+if __name__ == "__main__":
+    build_all()
+    print("built", LIBCADA)
+    sys.exit(0)

@@ -1,0 +1,397 @@
+// C ABI of libcada: argument checking, workspace layout, initialisation and the per-step
+// launch sequence of Algorithm 1 (declared and documented in cada.h).
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "cada_internal.h"
+
+namespace cada {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int ring_finalize(Ctx *c);
+
+struct Prof {
+  std::vector<hipEvent_t> ev;
+  int64_t max_steps = 0;
+  size_t used = 0;
+};
+
+void prof_mark(Ctx *c) {
+  Prof *p = static_cast<Prof *>(c->prof);
+  if (!p || p->used >= p->ev.size()) return;
+  if (hipEventRecord(p->ev[p->used], c->stream) == hipSuccess) p->used += 1;
+}
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Walks the workspace; with base == nullptr only sizes are computed.
+struct Carver {
+  char *base;
+  size_t off = 0;
+  template <typename T> T *take(size_t n) {
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off = align_up(off + n * sizeof(T));
+    return p;
+  }
+};
+
+struct Geometry {
+  int vec;
+  int n_col_chunks;
+  int64_t chunk_cols;
+  int n_lhs_part;
+  int n_ring_part;
+  int64_t total_rows;
+};
+
+bool check_config(const cada_config *cfg, Geometry *g) {
+  if (!cfg) { set_error("cfg is NULL"); return false; }
+  if (cfg->M < 1 || cfg->M > 65535) { set_error("M must be in [1, 65535] (got %d)", cfg->M); return false; }
+  if (cfg->p < 1) { set_error("p must be >= 1"); return false; }
+  if (cfg->B < 1 || cfg->B > CADA_MAX_B) { set_error("B must be in [1, %d] (got %d)", CADA_MAX_B, cfg->B); return false; }
+  if (cfg->d_max < 1 || cfg->d_max > CADA_MAX_DMAX) { set_error("d_max must be in [1, %d]", CADA_MAX_DMAX); return false; }
+  if (cfg->D < 1) { set_error("D must be >= 1"); return false; }
+  if (cfg->rule != CADA_RULE_CADA1 && cfg->rule != CADA_RULE_CADA2) { set_error("rule must be CADA_RULE_CADA1 or CADA_RULE_CADA2"); return false; }
+  if (cfg->model != CADA_MODEL_LOGREG && cfg->model != CADA_MODEL_MLP) { set_error("unknown model %d", cfg->model); return false; }
+  if (!cfg->layer_dims) { set_error("layer_dims is NULL"); return false; }
+  if (!cfg->n_samples) { set_error("n_samples is NULL"); return false; }
+  if (cfg->trace_steps < 0) { set_error("trace_steps must be >= 0"); return false; }
+  if (cfg->n_layers < 1 || cfg->n_layers > CADA_MAX_LAYERS) { set_error("n_layers must be in [1, %d]", CADA_MAX_LAYERS); return false; }
+  int64_t p = 0;
+  if (cfg->model == CADA_MODEL_LOGREG) {
+    if (cfg->n_layers != 1) { set_error("LOGREG needs n_layers == 1"); return false; }
+    p = cfg->layer_dims[0];
+  } else {
+    for (int l = 0; l < cfg->n_layers; ++l) {
+      if (cfg->layer_dims[l] < 1 || cfg->layer_dims[l + 1] < 1) { set_error("layer_dims must be positive"); return false; }
+      p += (int64_t)cfg->layer_dims[l] * cfg->layer_dims[l + 1] + cfg->layer_dims[l + 1];
+    }
+  }
+  if (p != cfg->p) { set_error("p = %lld does not match the model (%lld parameters)", (long long)cfg->p, (long long)p); return false; }
+  int64_t rows = 0;
+  for (int m = 0; m < cfg->M; ++m) {
+    if (cfg->n_samples[m] < 1) { set_error("n_samples[%d] must be >= 1", m); return false; }
+    rows += cfg->n_samples[m];
+  }
+  g->total_rows = rows;
+  // float4 access needs every row start, every p-vector and every chunk start 16-byte aligned.
+  g->vec = (cfg->p % 4 == 0) ? 4 : 1;
+  // pass 1: one column chunk per block, at most 8192 columns (8 iterations of 256 float4 lanes)
+  g->chunk_cols = 8192;
+  g->n_col_chunks = (int)((cfg->p + g->chunk_cols - 1) / g->chunk_cols);
+  const int64_t per_block = (int64_t)kBlock * g->vec;
+  g->n_lhs_part = (int)((cfg->p + per_block - 1) / per_block);
+  g->n_ring_part = g->n_lhs_part;
+  return true;
+}
+
+// Lays out the common state.  Returns bytes used so far.
+void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState *s, Ctx *c) {
+  const size_t p = (size_t)cfg->p, M = (size_t)cfg->M;
+  float *theta = w.take<float>(p), *h = w.take<float>(p), *v = w.take<float>(p);
+  float *vhat = w.take<float>(p), *nabla = w.take<float>(p);
+  float *gbuf = w.take<float>(2 * M * p);
+  float *hist = nullptr, *snap = nullptr, *dtl = nullptr;
+  if (cfg->rule == CADA_RULE_CADA2) {
+    hist = w.take<float>((size_t)(cfg->D + 1) * p);
+  } else {
+    snap = w.take<float>(p);
+    dtl = w.take<float>(2 * M * p);
+  }
+  int32_t *tau = w.take<int32_t>(M), *sel = w.take<int32_t>(M);
+  float *lhs = w.take<float>(M);
+  float *lhs_part = w.take<float>(M * (size_t)g.n_lhs_part);
+  uint8_t *mask = w.take<uint8_t>(M);
+  float *ring = w.take<float>((size_t)cfg->d_max);
+  float *ring_part = w.take<float>((size_t)g.n_ring_part);
+  uint64_t *uploads = w.take<uint64_t>(1);
+  uint32_t *err = w.take<uint32_t>(1);
+  int64_t *row_off = w.take<int64_t>(M + 1);
+  const size_t T = (size_t)cfg->trace_steps;
+  uint8_t *t_mask = w.take<uint8_t>(T * M), *t_own = w.take<uint8_t>(T * M);
+  float *t_lhs = w.take<float>(T * M), *t_rhs = w.take<float>(T);
+  int32_t *t_tau = w.take<int32_t>(T * M);
+  float *zpart = nullptr;
+  if (cfg->model == CADA_MODEL_LOGREG) zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
+  if (!s) return;
+  s->theta = theta; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
+  s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl;
+  s->tau = tau; s->sel = sel; s->lhs = lhs; s->lhs_part = lhs_part; s->mask = mask;
+  s->ring = ring; s->ring_part = ring_part; s->uploads = uploads; s->err = err;
+  s->row_off = row_off;
+  s->t_mask = t_mask; s->t_own = t_own; s->t_lhs = t_lhs; s->t_rhs = t_rhs; s->t_tau = t_tau;
+  s->trace_steps = cfg->trace_steps;
+  c->zpart = zpart;
+}
+
+__global__ void k_fill_i32(int32_t *p, int32_t v, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// dst[r][i] = src[i] for r < reps
+__global__ void k_broadcast_rows(float *dst, const float *src, int64_t p, int64_t reps) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= p) return;
+  const float v = src[i];
+  for (int64_t r = 0; r < reps; ++r) dst[r * p + i] = v;
+}
+
+// out[m][i] = gbuf[sel[m]][m][i]
+__global__ void k_gather_stored(const DevState s, float *out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int m = blockIdx.y;
+  if (i < s.p) out[(int64_t)m * s.p + i] = s.gbuf[((int64_t)s.sel[m] * s.M + m) * s.p + i];
+}
+
+#define HIP_TRY(expr)                                                        \
+  do {                                                                       \
+    hipError_t e_ = (expr);                                                  \
+    if (e_ != hipSuccess) {                                                  \
+      set_error("%s failed: %s", #expr, hipGetErrorString(e_));              \
+      return CADA_EHIP;                                                      \
+    }                                                                        \
+  } while (0)
+
+}  // namespace
+}  // namespace cada
+
+using namespace cada;
+
+struct cada_ctx {
+  Ctx c;
+  std::vector<int64_t> row_off_host;
+};
+
+extern "C" {
+
+const char *cada_last_error(void) { return g_err; }
+
+size_t cada_workspace_bytes(const cada_config *cfg) {
+  Geometry g;
+  if (!check_config(cfg, &g)) return 0;
+  Carver w{nullptr};
+  carve_common(w, cfg, g, nullptr, nullptr);
+  size_t total = w.off;
+  if (cfg->model == CADA_MODEL_MLP) {
+    const size_t extra = mlp_workspace_bytes(cfg, g.total_rows);
+    if (extra == 0) return 0;
+    total += extra;
+  }
+  return total;
+}
+
+int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
+  if (!out) { set_error("out is NULL"); return CADA_EINVAL; }
+  *out = nullptr;
+  Geometry g;
+  if (!check_config(cfg, &g)) return CADA_EINVAL;
+  if (!theta0) { set_error("theta0 is NULL"); return CADA_EINVAL; }
+  if (!cfg->X || !cfg->y) { set_error("X and y must be device pointers"); return CADA_EINVAL; }
+  if (!cfg->workspace) { set_error("workspace is NULL"); return CADA_EWORKSPACE; }
+  if (reinterpret_cast<uintptr_t>(cfg->workspace) % kAlign != 0) { set_error("workspace must be %zu-byte aligned", kAlign); return CADA_EWORKSPACE; }
+  if (g.vec == 4 && reinterpret_cast<uintptr_t>(cfg->X) % 16 != 0) g.vec = 1;
+  const size_t need = cada_workspace_bytes(cfg);
+  if (need == 0) return CADA_EINVAL;
+  if (cfg->workspace_bytes < need) {
+    set_error("workspace too small: %zu bytes given, %zu needed", cfg->workspace_bytes, need);
+    return CADA_EWORKSPACE;
+  }
+  cada_ctx *h = new (std::nothrow) cada_ctx();
+  if (!h) { set_error("out of host memory"); return CADA_EINVAL; }
+  Ctx *c = &h->c;
+  memset(c, 0, sizeof(Ctx));
+  DevState &s = c->s;
+  c->stream = static_cast<hipStream_t>(cfg->stream);
+  c->model = cfg->model;
+  c->gemm_dtype = cfg->gemm_dtype;
+  c->n_layers = cfg->n_layers;
+  for (int l = 0; l <= cfg->n_layers; ++l) c->dims[l] = cfg->layer_dims[l];
+  c->vec = g.vec;
+  c->n_col_chunks = g.n_col_chunks;
+  c->chunk_cols = g.chunk_cols;
+  c->ws_bytes = need;
+  Carver w{static_cast<char *>(cfg->workspace)};
+  carve_common(w, cfg, g, &s, c);
+  s.X = cfg->X; s.y = cfg->y;
+  s.M = cfg->M; s.B = cfg->B; s.d_max = cfg->d_max; s.D = cfg->D; s.R = cfg->D + 1; s.rule = cfg->rule;
+  s.n_lhs_part = g.n_lhs_part; s.n_ring_part = g.n_ring_part;
+  s.p = cfg->p; s.k = 0;
+  s.alpha = cfg->alpha; s.beta1 = cfg->beta1; s.beta2 = cfg->beta2; s.eps = cfg->eps;
+  s.lam = cfg->lambda_l2; s.c = cfg->c;
+  if (cfg->model == CADA_MODEL_LOGREG) {
+    c->n_phases = 4;
+    c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad";
+    c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
+  }
+  if (cfg->model == CADA_MODEL_MLP) {
+    size_t off = w.off;
+    const int rc = mlp_plan(c, cfg, static_cast<char *>(cfg->workspace), &off, g.total_rows);
+    if (rc != CADA_OK) { delete h; return rc; }
+  }
+
+  h->row_off_host.resize((size_t)cfg->M + 1);
+  h->row_off_host[0] = 0;
+  for (int m = 0; m < cfg->M; ++m) h->row_off_host[m + 1] = h->row_off_host[m] + cfg->n_samples[m];
+
+  hipStream_t st = c->stream;
+  const size_t p = (size_t)s.p, M = (size_t)s.M;
+  auto fail = [&](hipError_t e, const char *what) {
+    set_error("%s failed: %s", what, hipGetErrorString(e));
+    mlp_free(c);
+    delete h;
+    return CADA_EHIP;
+  };
+  hipError_t e;
+  // whole workspace to zero, then the non-zero pieces
+  if ((e = hipMemsetAsync(cfg->workspace, 0, need, st)) != hipSuccess) return fail(e, "hipMemsetAsync(workspace)");
+  if ((e = hipMemcpyAsync(s.theta, theta0, p * sizeof(float), hipMemcpyDeviceToDevice, st)) != hipSuccess) return fail(e, "copy theta0");
+  if ((e = hipMemcpyAsync(const_cast<int64_t *>(s.row_off), h->row_off_host.data(), (M + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st)) != hipSuccess) return fail(e, "copy row offsets");
+  const int tb = 256;
+  hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((M + tb - 1) / tb)), dim3(tb), 0, st, s.tau, (int32_t)s.D, (int64_t)M);
+  const unsigned pb = (unsigned)((p + tb - 1) / tb);
+  if (s.rule == CADA_RULE_CADA2)
+    hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.hist, theta0, (int64_t)p, (int64_t)s.R);
+  else
+    hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.snap, theta0, (int64_t)p, (int64_t)1);
+  if ((e = hipGetLastError()) != hipSuccess) return fail(e, "init kernels");
+  if (cfg->model == CADA_MODEL_MLP) {
+    const int rc = mlp_init_state(c, theta0);
+    if (rc != CADA_OK) { mlp_free(c); delete h; return rc; }
+  }
+  *out = h;
+  return CADA_OK;
+}
+
+int cada_step(cada_ctx *ctx, const int32_t *idx, const uint8_t *replay) {
+  if (!ctx) { set_error("ctx is NULL"); return CADA_EINVAL; }
+  if (!idx) { set_error("idx is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  int rc = (c->model == CADA_MODEL_LOGREG) ? logreg_gradients(c, idx) : mlp_gradients(c, idx);
+  if (rc != CADA_OK) return rc;
+  rc = rule_and_server(c, replay);
+  if (rc != CADA_OK) return rc;
+  c->k += 1;
+  return CADA_OK;
+}
+
+int cada_run(cada_ctx *ctx, const int32_t *idx_sched, const uint8_t *replay_sched, int64_t n_steps) {
+  if (!ctx) { set_error("ctx is NULL"); return CADA_EINVAL; }
+  if (n_steps < 0) { set_error("n_steps must be >= 0"); return CADA_EINVAL; }
+  if (n_steps > 0 && !idx_sched) { set_error("idx_sched is NULL"); return CADA_EINVAL; }
+  const int64_t M = ctx->c.s.M, B = ctx->c.s.B;
+  for (int64_t i = 0; i < n_steps; ++i) {
+    const int rc = cada_step(ctx, idx_sched + i * M * B, replay_sched ? replay_sched + i * M : nullptr);
+    if (rc != CADA_OK) return rc;
+  }
+  return CADA_OK;
+}
+
+int cada_get_state(cada_ctx *ctx, cada_state *out) {
+  if (!ctx || !out) { set_error("ctx/out is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  const int rc = ring_finalize(c);   // fold the last step's squared step into the ring
+  if (rc != CADA_OK) return rc;
+  const DevState &s = c->s;
+  out->theta = s.theta; out->h = s.h; out->v = s.v; out->vhat = s.vhat; out->nabla = s.nabla;
+  out->tau = s.tau; out->ring = s.ring; out->mask = s.mask; out->lhs = s.lhs;
+  out->uploads_total = s.uploads; out->error_flags = s.err;
+  out->k = c->k; out->trace_steps = s.trace_steps;
+  out->trace_mask = s.t_mask; out->trace_own_mask = s.t_own; out->trace_lhs = s.t_lhs;
+  out->trace_rhs = s.t_rhs; out->trace_tau = s.t_tau;
+  return CADA_OK;
+}
+
+int cada_copy_stored_gradients(cada_ctx *ctx, float *out) {
+  if (!ctx || !out) { set_error("ctx/out is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  const int tb = 256;
+  hipLaunchKernelGGL(k_gather_stored, dim3((unsigned)((c->s.p + tb - 1) / tb), c->s.M), dim3(tb), 0, c->stream, c->s, out);
+  HIP_TRY(hipGetLastError());
+  return CADA_OK;
+}
+
+int cada_profile_phases(cada_ctx *ctx) { return ctx ? ctx->c.n_phases : 0; }
+
+const char *cada_profile_phase_name(cada_ctx *ctx, int phase) {
+  if (!ctx || phase < 0 || phase >= ctx->c.n_phases) return "";
+  return ctx->c.phase_names[phase];
+}
+
+static void prof_drop(Ctx *c) {
+  Prof *p = static_cast<Prof *>(c->prof);
+  if (!p) return;
+  for (hipEvent_t e : p->ev) (void)hipEventDestroy(e);
+  delete p;
+  c->prof = nullptr;
+}
+
+int cada_profile_begin(cada_ctx *ctx, int64_t max_steps) {
+  if (!ctx || max_steps < 1 || max_steps > (1 << 20)) { set_error("cada_profile_begin: bad arguments"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  prof_drop(c);
+  Prof *p = new (std::nothrow) Prof();
+  if (!p) { set_error("out of host memory"); return CADA_EINVAL; }
+  p->max_steps = max_steps;
+  p->ev.resize((size_t)max_steps * (size_t)(c->n_phases + 1));
+  for (size_t i = 0; i < p->ev.size(); ++i) {
+    const hipError_t e = hipEventCreate(&p->ev[i]);
+    if (e != hipSuccess) {
+      p->ev.resize(i);
+      c->prof = p;
+      prof_drop(c);
+      set_error("hipEventCreate failed: %s", hipGetErrorString(e));
+      return CADA_EHIP;
+    }
+  }
+  c->prof = p;
+  return CADA_OK;
+}
+
+int cada_profile_end(cada_ctx *ctx, double *ms_out, int n_out, int64_t *steps_out) {
+  if (!ctx || !ms_out || !steps_out) { set_error("cada_profile_end: NULL argument"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  Prof *p = static_cast<Prof *>(c->prof);
+  if (!p) { set_error("profiling is not active"); return CADA_EINVAL; }
+  if (n_out < c->n_phases) { set_error("ms_out too small"); return CADA_EINVAL; }
+  const size_t per = (size_t)c->n_phases + 1;
+  const size_t steps = p->used / per;
+  for (int i = 0; i < n_out; ++i) ms_out[i] = 0.0;
+  int rc = CADA_OK;
+  if (steps > 0) {
+    hipError_t e = hipEventSynchronize(p->ev[steps * per - 1]);
+    for (size_t s = 0; s < steps && e == hipSuccess; ++s)
+      for (int ph = 0; ph < c->n_phases && e == hipSuccess; ++ph) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, p->ev[s * per + ph], p->ev[s * per + ph + 1]);
+        ms_out[ph] += ms;
+      }
+    if (e != hipSuccess) { set_error("profiling events: %s", hipGetErrorString(e)); rc = CADA_EHIP; }
+  }
+  *steps_out = (int64_t)steps;
+  prof_drop(c);
+  return rc;
+}
+
+void cada_destroy(cada_ctx *ctx) {
+  if (!ctx) return;
+  prof_drop(&ctx->c);
+  mlp_free(&ctx->c);
+  delete ctx;
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+// Internal declarations shared by the HIP translation units of libcada.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "cada.h"
+
+namespace cada {
+
+constexpr int kBlock = 256;          // threads per workgroup = 4 wavefronts of 64
+constexpr int kWave = 64;
+
+// Everything the kernels need to find the state; passed by value.
+struct DevState {
+  // server vectors [p]
+  float *theta, *h, *v, *vhat, *nabla;
+  // stored / fresh stochastic gradients: gbuf[s][m][p], s in {0,1}.  Worker m's stored
+  // gradient is gbuf[sel[m]][m]; the fresh one of the current step is written to
+  // gbuf[1-sel[m]][m] and an upload is sel[m] ^= 1 (no copy).
+  float *gbuf;
+  // CADA2: hist[R][p], slot j mod R holds theta^j, R = D+1.  theta^{k-tau_m} is read here.
+  float *hist;
+  // CADA1: snapshot theta-tilde [p] and innovations dtl[s][m][p] indexed by sel like gbuf.
+  float *snap, *dtl;
+  int32_t *tau, *sel;     // [M]
+  float *lhs;             // [M]
+  float *lhs_part;        // [M][n_lhs_part] partial sums of the left-hand side
+  uint8_t *mask;          // [M]
+  float *ring;            // [d_max]
+  float *ring_part;       // [n_ring_part] per-block partial sums of the last squared step,
+                          // folded into ring[(k-1) mod d_max] by the next rule kernel
+  uint64_t *uploads;
+  uint32_t *err;
+  // trace
+  uint8_t *t_mask, *t_own;
+  float *t_lhs, *t_rhs;
+  int32_t *t_tau;
+  int64_t trace_steps;
+  // problem
+  const float *X;
+  const void *y;
+  const int64_t *row_off;   // device [M+1], prefix sums of N_m
+  int32_t M, B, d_max, D, R, rule, n_lhs_part, n_ring_part;
+  int64_t p;
+  int64_t k;                // iteration of the launch this copy is passed to
+  float alpha, beta1, beta2, eps, lam, c;
+};
+
+// Reference point of worker m at iteration k (Algorithm 1: theta-tilde for CADA1,
+// theta^{k - tau_m^k} for CADA2).
+__device__ __forceinline__ const float *theta_ref(const DevState &s, int m, int64_t k) {
+  if (s.rule == CADA_RULE_CADA1) return s.snap;
+  int64_t j = k - (int64_t)s.tau[m];
+  int64_t slot = j % s.R;
+  if (slot < 0) slot += s.R;
+  return s.hist + slot * s.p;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+// Sum over the 256 threads of a block in a fixed order; result valid in every thread.
+__device__ __forceinline__ float block_sum(float x, float *red /* [4] LDS */) {
+  x = wave_sum(x);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = x;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+struct LogregLaunch;   // defined in cada_logreg.hip
+
+// Host context.
+struct Ctx {
+  DevState s;
+  hipStream_t stream;
+  int64_t k;                 // steps enqueued
+  int32_t model, gemm_dtype, n_layers;
+  int32_t dims[CADA_MAX_LAYERS + 1];
+  size_t ws_bytes;
+  // logistic launch geometry
+  int vec;                   // 4 if rows can be read as float4, else 1
+  int n_col_chunks;          // column chunks of the dot-product kernel
+  int64_t chunk_cols;
+  float *zpart;              // [M][B][n_col_chunks][2]
+  int n_server_blocks;
+  void *mlp;                 // MLP plan (cada_mlp.hip), or nullptr
+  void *prof;                // profiling events (cada_api.hip), or nullptr
+  int n_phases;              // phases per step = marks per step - 1
+  const char *phase_names[16];
+};
+
+void set_error(const char *fmt, ...);
+// Records the next profiling event on the stream when profiling is active (else no-op).
+void prof_mark(Ctx *c);
+
+// S1+S2 for the logistic model: fresh gradients into gbuf[1-sel], left-hand sides into lhs_part.
+int logreg_gradients(Ctx *c, const int32_t *idx);
+// S1+S2 for the MLP.
+int mlp_gradients(Ctx *c, const int32_t *idx);
+size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows);
+int mlp_plan(Ctx *c, const cada_config *cfg, char *base, size_t *offset, int64_t total_rows);
+int mlp_init_state(Ctx *c, const float *theta0);
+void mlp_free(Ctx *c);
+// S3: rule, mask, tau.  S5-S7: aggregate, AMSGrad, ring push.
+int rule_and_server(Ctx *c, const uint8_t *replay);
+
+}  // namespace cada

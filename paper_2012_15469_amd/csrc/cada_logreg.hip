@@ -1,0 +1,246 @@
+// Dual minibatch gradient of the l2-regularised logistic loss for all workers, and the
+// left-hand side of the communication rule (Section 2.2, conditions (workerrule1) and
+// (workerrule2)); Algorithm 1, the workers' two gradient evaluations on the same samples.
+//
+// With z_b = x_b.theta, d = theta - theta_ref and dz_b = x_b.d (so x_b.theta_ref = z_b - dz_b),
+//     r_b  = -y_b sigma(-y_b z_b)                         residual at theta
+//     dr_b = r_b - r_ref,b = y_b sigma(a) sigma(-b') expm1(y_b dz_b),  a = -y_b z_b, b' = a + y_b dz_b
+//     g      = X_B^T r / B + lambda theta                 fresh gradient
+//     innov  = X_B^T dr / B + lambda d                    g(theta) - g(theta_ref), no cancellation
+// The difference of the two gradients is formed from d and dr directly: subtracting two
+// float32 gradients of nearby points would lose the digits the rule's comparison needs.
+//
+// Pass 1 (k_dots) streams the B gathered rows once for z and dz; pass 2 (k_grad) streams
+// them again for g and innov, column-parallel, and reduces |innov|^2 (CADA2) or
+// |innov - stored innovation|^2 (CADA1) per block in a fixed order.
+#include "cada_internal.h"
+
+namespace cada {
+
+constexpr int kRowsPerBlock = 8;   // rows sharing one load of theta and d in pass 1
+
+struct LogregArgs {
+  DevState s;
+  const int32_t *idx;    // [M][B]
+  float *zpart;          // [M][B][nc][2]
+  int nc;
+  int64_t chunk_cols;
+};
+
+template <int VEC> struct Vec;
+template <> struct Vec<4> { using T = float4; };
+template <> struct Vec<1> { using T = float; };
+
+template <int VEC> __device__ __forceinline__ void load_vec(const float *p, float (&o)[VEC]) {
+  if constexpr (VEC == 4) {
+    const float4 t = *reinterpret_cast<const float4 *>(p);
+    o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w;
+  } else {
+    o[0] = *p;
+  }
+}
+template <int VEC> __device__ __forceinline__ void store_vec(float *p, const float (&o)[VEC]) {
+  if constexpr (VEC == 4) {
+    *reinterpret_cast<float4 *>(p) = make_float4(o[0], o[1], o[2], o[3]);
+  } else {
+    *p = o[0];
+  }
+}
+
+__device__ __forceinline__ int64_t clamp_row(const DevState &s, int m, int32_t local, bool *bad) {
+  const int64_t n = s.row_off[m + 1] - s.row_off[m];
+  int64_t r = local;
+  if (r < 0) { r = 0; *bad = true; }
+  if (r >= n) { r = n - 1; *bad = true; }
+  return s.row_off[m] + r;
+}
+
+// grid (nc, ceil(B / kRowsPerBlock), M)
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_dots(const LogregArgs a) {
+  const DevState &s = a.s;
+  const int m = blockIdx.z;
+  const int r0 = blockIdx.y * kRowsPerBlock;
+  const int64_t k = s.k;
+  const float *__restrict__ th = s.theta;
+  const float *__restrict__ tr = theta_ref(s, m, k);
+  const int32_t *idx = a.idx + (int64_t)m * s.B;
+
+  const float *xrow[kRowsPerBlock];
+  bool bad = false;
+#pragma unroll
+  for (int r = 0; r < kRowsPerBlock; ++r) {
+    const int b = min(r0 + r, s.B - 1);
+    xrow[r] = s.X + clamp_row(s, m, idx[b], &bad) * s.p;
+  }
+  if (bad && threadIdx.x == 0) atomicOr(s.err, 1u);
+
+  float z[kRowsPerBlock], dz[kRowsPerBlock];
+#pragma unroll
+  for (int r = 0; r < kRowsPerBlock; ++r) { z[r] = 0.f; dz[r] = 0.f; }
+
+  const int64_t c0 = (int64_t)blockIdx.x * a.chunk_cols;
+  const int64_t c1 = min(s.p, c0 + a.chunk_cols);
+  for (int64_t j = c0 + (int64_t)threadIdx.x * VEC; j < c1; j += (int64_t)kBlock * VEC) {
+    float t[VEC], d[VEC];
+    load_vec<VEC>(th + j, t);
+    load_vec<VEC>(tr + j, d);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) d[v] = t[v] - d[v];
+    float x[kRowsPerBlock][VEC];
+#pragma unroll
+    for (int r = 0; r < kRowsPerBlock; ++r) load_vec<VEC>(xrow[r] + j, x[r]);
+#pragma unroll
+    for (int r = 0; r < kRowsPerBlock; ++r) {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) {
+        z[r] = fmaf(x[r][v], t[v], z[r]);
+        dz[r] = fmaf(x[r][v], d[v], dz[r]);
+      }
+    }
+  }
+
+  __shared__ float red[4][2 * kRowsPerBlock];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+  for (int r = 0; r < kRowsPerBlock; ++r) {
+    const float zs = wave_sum(z[r]);
+    const float ds = wave_sum(dz[r]);
+    if (lane == 0) { red[w][2 * r] = zs; red[w][2 * r + 1] = ds; }
+  }
+  __syncthreads();
+  if (threadIdx.x < 2 * kRowsPerBlock) {
+    const int r = threadIdx.x >> 1;
+    if (r0 + r < s.B) {
+      const float v = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+      a.zpart[(((int64_t)m * s.B + r0 + r) * a.nc + blockIdx.x) * 2 + (threadIdx.x & 1)] = v;
+    }
+  }
+}
+
+__device__ __forceinline__ float sigmoidf(float a) { return 1.0f / (1.0f + expf(-a)); }
+
+// grid (ceil(p / (kBlock*VEC)), M); dynamic LDS: B * (2 floats + 1 int64)
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_grad(const LogregArgs a) {
+  const DevState &s = a.s;
+  extern __shared__ __align__(16) unsigned char smem[];
+  int64_t *off_s = reinterpret_cast<int64_t *>(smem);
+  float *r_s = reinterpret_cast<float *>(smem + sizeof(int64_t) * s.B);
+  float *dr_s = r_s + s.B;
+  __shared__ float red[4];
+
+  const int m = blockIdx.y;
+  const int64_t k = s.k;
+  const int32_t *idx = a.idx + (int64_t)m * s.B;
+  const float *yv = static_cast<const float *>(s.y);
+  const float invB = 1.0f / (float)s.B;
+
+  for (int b = threadIdx.x; b < s.B; b += kBlock) {
+    bool bad = false;
+    const int64_t row = clamp_row(s, m, idx[b], &bad);
+    const float *zp = a.zpart + ((int64_t)m * s.B + b) * a.nc * 2;
+    float z = 0.f, dz = 0.f;
+    for (int c = 0; c < a.nc; ++c) { z += zp[2 * c]; dz += zp[2 * c + 1]; }
+    const float y = yv[row];
+    const float aa = -y * z;                 // -y x.theta
+    const float bb = aa + y * dz;            // -y x.theta_ref
+    const float sa = sigmoidf(aa);
+    r_s[b] = -y * sa * invB;
+    dr_s[b] = y * sa * sigmoidf(-bb) * expm1f(y * dz) * invB;
+    off_s[b] = row * s.p;
+  }
+  __syncthreads();
+
+  const int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+  float sq = 0.f;
+  if (j < s.p) {
+    float g[VEC], iv[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { g[v] = 0.f; iv[v] = 0.f; }
+    const float *__restrict__ X = s.X + j;
+    int b = 0;
+    for (; b + 8 <= s.B; b += 8) {
+      float x[8][VEC];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) load_vec<VEC>(X + off_s[b + u], x[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float r = r_s[b + u], dr = dr_s[b + u];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          g[v] = fmaf(r, x[u][v], g[v]);
+          iv[v] = fmaf(dr, x[u][v], iv[v]);
+        }
+      }
+    }
+    for (; b < s.B; ++b) {
+      float x[VEC];
+      load_vec<VEC>(X + off_s[b], x);
+      const float r = r_s[b], dr = dr_s[b];
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) {
+        g[v] = fmaf(r, x[v], g[v]);
+        iv[v] = fmaf(dr, x[v], iv[v]);
+      }
+    }
+    float t[VEC], d[VEC];
+    load_vec<VEC>(s.theta + j, t);
+    load_vec<VEC>(theta_ref(s, m, k) + j, d);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      d[v] = t[v] - d[v];
+      g[v] = fmaf(s.lam, t[v], g[v]);
+      iv[v] = fmaf(s.lam, d[v], iv[v]);
+    }
+    const int cur = s.sel[m];
+    const int64_t mp = (int64_t)s.M * s.p;
+    store_vec<VEC>(s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + j, g);
+    if (s.rule == CADA_RULE_CADA1) {
+      // left-hand side of (workerrule1): fresh innovation minus the stored one
+      float st[VEC];
+      load_vec<VEC>(s.dtl + (int64_t)cur * mp + (int64_t)m * s.p + j, st);
+      store_vec<VEC>(s.dtl + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + j, iv);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) { const float e = iv[v] - st[v]; sq = fmaf(e, e, sq); }
+    } else {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) sq = fmaf(iv[v], iv[v], sq);
+    }
+  }
+  const float tot = block_sum(sq, red);
+  if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + blockIdx.x] = tot;
+}
+
+int logreg_gradients(Ctx *c, const int32_t *idx) {
+  LogregArgs a;
+  a.s = c->s;
+  a.s.k = c->k;
+  a.idx = idx;
+  a.zpart = c->zpart;
+  a.nc = c->n_col_chunks;
+  a.chunk_cols = c->chunk_cols;
+  const DevState &s = c->s;
+  const dim3 g1(c->n_col_chunks, (s.B + kRowsPerBlock - 1) / kRowsPerBlock, s.M);
+  const dim3 g2(s.n_lhs_part, s.M);
+  const size_t lds = (size_t)s.B * (sizeof(int64_t) + 2 * sizeof(float));
+  prof_mark(c);
+  if (c->vec == 4) {
+    hipLaunchKernelGGL(k_dots<4>, g1, dim3(kBlock), 0, c->stream, a);
+    prof_mark(c);
+    hipLaunchKernelGGL(k_grad<4>, g2, dim3(kBlock), lds, c->stream, a);
+  } else {
+    hipLaunchKernelGGL(k_dots<1>, g1, dim3(kBlock), 0, c->stream, a);
+    prof_mark(c);
+    hipLaunchKernelGGL(k_grad<1>, g2, dim3(kBlock), lds, c->stream, a);
+  }
+  prof_mark(c);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_error("logistic gradient launch failed: %s", hipGetErrorString(e));
+    return CADA_EHIP;
+  }
+  return CADA_OK;
+}
+
+}  // namespace cada

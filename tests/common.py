@@ -1,0 +1,106 @@
+"""Shared helpers of the GPU parity tests: upload a seeded problem, run the library
+through its C ABI binding, and compare with the CPU oracle under the protocol
+  (i)  free run: masks equal up to the first disagreement, which must sit where the
+       oracle's rule margin |LHS-RHS|/RHS is <= 1e-5;
+  (ii) replay of the oracle's masks: the library's own rule decision is compared at every
+       step (disagreements only at margins <= 1e-5 for float32 arithmetic) and theta after
+       K steps must agree to the stated relative L2 error.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from cada_synth import generators
+from oracle.cada_oracle import margins
+from oracle.driver import oracle_for
+
+MARGIN = 1e-5
+
+
+def to_dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def upload(prob):
+    """Device copies (X, y, theta0) of a host-resident problem."""
+    X = to_dev(prob.X)
+    y = to_dev(prob.y)
+    return X, y, to_dev(prob.theta0)
+
+
+def run_library(cfg, dev, sched, replay=None, **kw):
+    """K = len(sched) steps through cada_run; returns the state as numpy arrays."""
+    from paper_2012_15469_amd.binding import Cada
+    X, y, th0 = dev
+    K = sched.shape[0]
+    eng = Cada.from_config(cfg, X, y, th0, trace_steps=K, **kw)
+    idx = to_dev(sched.astype(np.int32))
+    rp = None if replay is None else to_dev(np.ascontiguousarray(replay, dtype=np.uint8))
+    eng.run(idx, rp)
+    torch.cuda.synchronize()
+    st = eng.state()
+    torch.cuda.synchronize()
+    out = {k: (v.cpu().numpy().copy() if isinstance(v, torch.Tensor) else v) for k, v in st.items()}
+    out["stored"] = eng.stored_gradients().cpu().numpy()
+    eng.close()
+    return out
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64); b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def oracle_run(cfg, prob, sched, replay=None):
+    o = oracle_for(cfg, prob)
+    o.run(sched, replay)
+    return o, o.trace_arrays()
+
+
+def check_protocol(cfg, prob, dev, sched, theta_tol, lhs_rtol=None, own_mask_exact=True, report=None, **kw):
+    o, tr = oracle_run(cfg, prob, sched)
+    mg = margins(tr["lhs"], tr["rhs"])
+    K = sched.shape[0]
+    # (i) free run
+    free = run_library(cfg, dev, sched, **kw)
+    assert free["error_flags"][0] == 0
+    diff = free["trace_mask"] != tr["mask"]
+    first_bad = None
+    if diff.any():
+        kk = int(np.argmax(diff.any(axis=1)))
+        first_bad = kk
+        for m in np.flatnonzero(diff[kk]):
+            assert mg[kk, m] <= MARGIN, (
+                "free run: first mask disagreement at step %d worker %d has oracle margin %.3e" % (kk, m, mg[kk, m]))
+    # (ii) replay of the oracle's masks
+    rep = run_library(cfg, dev, sched, replay=tr["mask"], **kw)
+    assert np.array_equal(rep["trace_mask"], tr["mask"])
+    assert np.array_equal(rep["trace_tau"], tr["tau"])
+    own_diff = rep["trace_own_mask"] != tr["own_mask"]
+    wide = own_diff & (mg > MARGIN)
+    if own_mask_exact:
+        assert wide.sum() == 0, "own-rule disagreements outside the margin: %d (first at %s)" % (
+            wide.sum(), np.argwhere(wide)[:3].tolist())
+    err_theta = rel_l2(rep["theta"], o.theta)
+    assert err_theta <= theta_tol, "theta relative L2 error %.3e > %.1e" % (err_theta, theta_tol)
+    assert rep["uploads_total"][0] == o.uploads_total
+    assert np.array_equal(rep["tau"], o.tau)
+    if lhs_rtol is not None:
+        scale = np.maximum(tr["lhs"], 1e-30)
+        big = tr["lhs"] > 1e-12 * max(tr["lhs"].max(), 1e-300)
+        rel = np.abs(rep["trace_lhs"] - tr["lhs"]) / scale
+        assert rel[big].max() <= lhs_rtol, "LHS relative error %.3e" % rel[big].max()
+        rr = np.abs(rep["trace_rhs"] - tr["rhs"]) / np.maximum(tr["rhs"], 1e-300)
+        assert rr[tr["rhs"] > 0].max() <= lhs_rtol, "RHS relative error %.3e" % rr[tr["rhs"] > 0].max()
+    stats = {"K": K, "first_free_disagreement": first_bad, "own_disagreements": int(own_diff.sum()),
+             "own_disagreements_outside_margin": int(wide.sum()), "theta_rel_l2": err_theta,
+             "h_rel_l2": rel_l2(rep["h"], o.h), "vhat_rel_l2": rel_l2(rep["vhat"], o.vhat),
+             "nabla_rel_l2": rel_l2(rep["nabla"], o.nabla), "ring_rel": rel_l2(rep["ring"], o.ring),
+             "stored_rel_l2": rel_l2(rep["stored"], o.G), "uploads": int(o.uploads_total)}
+    if report is not None:
+        report.update(stats)
+    return stats, o, tr, rep

@@ -1,0 +1,125 @@
+"""GPU parity of the logistic path with the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from cada_synth import configs, generators
+
+from common import check_protocol, upload, run_library, oracle_run, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+FP32_TOL = 1e-4      # theta relative L2 after K steps (float32 path)
+
+
+def _case(cfg):
+    prob = generators.make_problem(cfg)
+    return prob, upload(prob), generators.make_schedule(cfg)
+
+
+def test_cfg1_full():
+    cfg = configs.CFG1
+    prob, dev, sched = _case(cfg)
+    stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
+    print("cfg1", stats)
+    assert stats["h_rel_l2"] < 1e-4 and stats["vhat_rel_l2"] < 1e-4 and stats["ring_rel"] < 1e-4
+    assert stats["stored_rel_l2"] < 1e-5
+
+
+def test_cfg2_full():
+    cfg = configs.CFG2
+    prob, dev, sched = _case(cfg)
+    stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
+    print("cfg2", stats)
+    assert stats["stored_rel_l2"] < 1e-5
+
+
+@pytest.mark.parametrize("p,rule", [(8200, 2), (8200, 1), (4099, 2), (4099, 1)])
+def test_cfg3_reduced_ragged(p, rule):
+    """The high-dimensional recipe at reduced size: several column chunks with a ragged
+    tail (p = 8200 = 8192 + 8), a row count that is no multiple of the row group (B = 20)
+    and the scalar-load path (p = 4099 is not a multiple of 4)."""
+    cfg = configs.CFG3.scaled(layer_dims=(p,), M=5, N_m=64, B=20, K=60, D=10, rule=rule, alpha=0.02)
+    prob = generators.make_problem(cfg)
+    if p % 2:   # the counter recipe needs an even p: fall back to host-generated Gaussians
+        cfg = cfg.scaled(data="gauss_shifted")
+        prob = generators.make_problem(cfg)
+        prob.X *= np.float32(1.0 / np.sqrt(p))
+    else:
+        Xs, ys = zip(*(prob.rows(m, np.arange(cfg.N_m)) for m in range(cfg.M)))
+        prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
+    sched = generators.make_schedule(cfg)
+    stats, *_ = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4)
+    print(p, rule, stats)
+
+
+def test_special_cases_c0_and_huge_c():
+    cfg = configs.CFG1.scaled(c=0.0, K=50)
+    prob, dev, sched = _case(cfg)
+    out = run_library(cfg, dev, sched)
+    assert out["trace_mask"].all() and out["uploads_total"][0] == cfg.M * cfg.K
+    cfg = configs.CFG1.scaled(c=1e30, K=120)
+    sched = generators.make_schedule(cfg)
+    out = run_library(cfg, dev, sched)
+    for k in range(cfg.K):
+        assert out["trace_mask"][k].all() == (k % cfg.D == 0) and out["trace_mask"][k].any() == (k % cfg.D == 0)
+
+
+def test_single_worker_and_single_row():
+    cfg = configs.CFG1.scaled(M=1, B=1, N_m=50, K=40, D=5)
+    prob, dev, sched = _case(cfg)
+    check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
+
+
+def test_duplicate_rows_and_out_of_range_flag():
+    cfg = configs.CFG1.scaled(K=8)
+    prob, dev, sched = _case(cfg)
+    sched[:, :, 1] = sched[:, :, 0]                    # duplicate rows are legal
+    check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
+    bad = sched.copy(); bad[3, 2, 0] = cfg.N_m + 5     # clamped to the last row and flagged
+    out = run_library(cfg, dev, bad)
+    assert out["error_flags"][0] & 1
+    fixed = bad.copy(); fixed[3, 2, 0] = cfg.N_m - 1
+    ref = run_library(cfg, dev, fixed)
+    assert np.array_equal(out["theta"], ref["theta"])
+
+
+def test_runs_are_bitwise_reproducible():
+    cfg = configs.CFG2.scaled(K=100)
+    prob, dev, sched = _case(cfg)
+    a = run_library(cfg, dev, sched)
+    b = run_library(cfg, dev, sched)
+    for key in ("theta", "h", "vhat", "trace_mask", "trace_lhs", "trace_rhs", "ring"):
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_step_by_step_equals_run():
+    from paper_2012_15469_amd.binding import Cada
+    from common import to_dev
+    cfg = configs.CFG1.scaled(K=30)
+    prob, dev, sched = _case(cfg)
+    ref = run_library(cfg, dev, sched)
+    eng = Cada.from_config(cfg, *dev, trace_steps=cfg.K)
+    idx = to_dev(sched)
+    for k in range(cfg.K):
+        eng.step(idx[k])
+        if k == 10:   # reading the state mid-run must not disturb it
+            torch.cuda.synchronize(); _ = eng.state()["ring"].cpu()
+    torch.cuda.synchronize()
+    st = eng.state(); torch.cuda.synchronize()
+    assert np.array_equal(st["theta"].cpu().numpy(), ref["theta"])
+    assert np.array_equal(st["ring"].cpu().numpy(), ref["ring"])
+
+
+def test_bad_arguments_are_errors():
+    from paper_2012_15469_amd import binding as b
+    cfg = configs.CFG1
+    prob, dev, sched = _case(cfg)
+    with pytest.raises(b.CadaError, match="B must be"):
+        b.Cada.from_config(cfg.scaled(B=0), *dev)
+    with pytest.raises(b.CadaError, match="rule"):
+        b.Cada.from_config(cfg, *dev, rule=7)
+    with pytest.raises(b.CadaError, match="d_max"):
+        b.Cada.from_config(cfg.scaled(d_max=0), *dev)
+    with pytest.raises(b.CadaError, match="does not match"):
+        b.Cada.from_config(cfg, dev[0], dev[1], dev[2][:50].contiguous())
