@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#pragma clang fp contract(off)
+
 namespace {
 
 constexpr uint32_t kM0 = 0xD2511F53u, kM1 = 0xCD9E8D57u, kW0 = 0x9E3779B9u, kW1 = 0xBB67AE85u;
@@ -54,10 +56,12 @@ __global__ __launch_bounds__(256) void k_rows(uint32_t seed, int64_t N_m, int64_
     const float4 s4 = *reinterpret_cast<const float4 *>(sh + j);
     const int4 t4 = *reinterpret_cast<const int4 *>(tdir + j);
     float4 o;
-    o.x = __fadd_rn(__fmul_rn((float)ih0, scale), s4.x);
-    o.y = __fadd_rn(__fmul_rn((float)ih1, scale), s4.y);
-    o.z = __fadd_rn(__fmul_rn((float)ih2, scale), s4.z);
-    o.w = __fadd_rn(__fmul_rn((float)ih3, scale), s4.w);
+    // product and sum are rounded separately (the definition has two roundings): this file
+    // is compiled with -ffp-contract=off so that no fused multiply-add is formed
+    o.x = (float)ih0 * scale + s4.x;
+    o.y = (float)ih1 * scale + s4.y;
+    o.z = (float)ih2 * scale + s4.z;
+    o.w = (float)ih3 * scale + s4.w;
     *reinterpret_cast<float4 *>(xr + j) = o;
     score += (long long)ih0 * t4.x + (long long)ih1 * t4.y + (long long)ih2 * t4.z + (long long)ih3 * t4.w;
   }

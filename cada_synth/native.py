@@ -19,7 +19,7 @@ def build() -> None:
     subprocess.run(["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", "-o", CPU_LIB,
                     os.path.join(HERE, "csrc", "rowgen_cpu.c")], check=True)
     r = subprocess.run([os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), "-O3", "--offload-arch=gfx950", "-std=c++17",
-                        "-shared", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        "-shared", "-fPIC", "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                         "-o", HIP_LIB, os.path.join(HERE, "csrc", "rowgen.hip")],
                        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:

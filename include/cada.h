@@ -73,9 +73,11 @@ typedef struct cada_config {
                                 off_m = N_0 + ... + N_{m-1} */
   const float *X;            /* DEVICE, row-major [sum N_m, d0] float32, read-only */
   const void *y;             /* DEVICE [sum N_m]: float32 +1/-1 (LOGREG), int32 class (MLP) */
-  float alpha, beta1, beta2, eps; /* (CADA-1)-(CADA-3); constant stepsize */
-  float lambda_l2;           /* LOGREG: (lambda/2)|theta|^2 is part of the loss */
-  float c;                   /* threshold constant of the rules, >= 0 */
+  double alpha, beta1, beta2, eps; /* (CADA-1)-(CADA-3); constant stepsize.  Doubles so that
+                                1-beta1 and 1-beta2 are formed before rounding to float32
+                                (1.0f-0.999f is off by 1.3e-5 relative) */
+  double lambda_l2;          /* LOGREG: (lambda/2)|theta|^2 is part of the loss */
+  double c;                  /* threshold constant of the rules, >= 0 */
   int32_t d_max;             /* squared steps averaged on the right-hand side */
   int32_t D;                 /* max delay (forced upload) and CADA1 snapshot period */
   int32_t rule;              /* CADA_RULE_* */
@@ -90,6 +92,8 @@ typedef struct cada_config {
  * with every step) and host-side counters. */
 typedef struct cada_state {
   const float *theta, *h, *v, *vhat, *nabla; /* DEVICE [p] */
+  const float *theta_lo;                     /* DEVICE [p]: the iterate is theta + theta_lo, a
+                                                two-float sum (|theta_lo| <= ulp(theta)/2) */
   const int32_t *tau;                        /* DEVICE [M], tau_m^k for the next step */
   const float *ring;                         /* DEVICE [d_max], slot j mod d_max = |theta^{j+1}-theta^j|^2 */
   const uint8_t *mask;                       /* DEVICE [M], uploads of the last step */

@@ -31,14 +31,14 @@ class cada_config(C.Structure):
     _fields_ = [("M", C.c_int32), ("p", C.c_int64), ("model", C.c_int32), ("n_layers", C.c_int32),
                 ("layer_dims", C.POINTER(C.c_int32)), ("B", C.c_int32),
                 ("n_samples", C.POINTER(C.c_int64)), ("X", C.c_void_p), ("y", C.c_void_p),
-                ("alpha", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("lambda_l2", C.c_float), ("c", C.c_float), ("d_max", C.c_int32), ("D", C.c_int32),
+                ("alpha", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("lambda_l2", C.c_double), ("c", C.c_double), ("d_max", C.c_int32), ("D", C.c_int32),
                 ("rule", C.c_int32), ("gemm_dtype", C.c_int32), ("trace_steps", C.c_int64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
 class cada_state(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("theta", "h", "v", "vhat", "nabla", "tau", "ring", "mask", "lhs",
+    _fields_ = [(n, C.c_void_p) for n in ("theta", "h", "v", "vhat", "nabla", "theta_lo", "tau", "ring", "mask", "lhs",
                                            "uploads_total", "error_flags")] + \
                [("k", C.c_int64), ("trace_steps", C.c_int64)] + \
                [(n, C.c_void_p) for n in ("trace_mask", "trace_own_mask", "trace_lhs", "trace_rhs", "trace_tau")]
@@ -203,7 +203,7 @@ class Cada:
         st = cada_get_state(self.ctx)
         M, p, T = self.M, self.p, min(int(st.trace_steps), int(st.k))
         f32, i32, u8 = torch.float32, torch.int32, torch.uint8
-        out = {n: self._view(getattr(st, n), p, f32) for n in ("theta", "h", "v", "vhat", "nabla")}
+        out = {n: self._view(getattr(st, n), p, f32) for n in ("theta", "theta_lo", "h", "v", "vhat", "nabla")}
         out["tau"] = self._view(st.tau, M, i32)
         out["ring"] = self._view(st.ring, self.d_max, f32)
         out["mask"] = self._view(st.mask, M, u8)

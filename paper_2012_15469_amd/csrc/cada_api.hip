@@ -2,6 +2,7 @@
 // launch sequence of Algorithm 1 (declared and documented in cada.h).
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -65,6 +66,9 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   if (cfg->B < 1 || cfg->B > CADA_MAX_B) { set_error("B must be in [1, %d] (got %d)", CADA_MAX_B, cfg->B); return false; }
   if (cfg->d_max < 1 || cfg->d_max > CADA_MAX_DMAX) { set_error("d_max must be in [1, %d]", CADA_MAX_DMAX); return false; }
   if (cfg->D < 1) { set_error("D must be >= 1"); return false; }
+  if (!(cfg->c >= 0.0)) { set_error("c must be >= 0"); return false; }
+  if (!(cfg->beta1 >= 0.0 && cfg->beta1 < 1.0 && cfg->beta2 >= 0.0 && cfg->beta2 < 1.0)) { set_error("beta1, beta2 must be in [0, 1)"); return false; }
+  if (!(cfg->eps >= 0.0)) { set_error("eps must be >= 0"); return false; }
   if (cfg->rule != CADA_RULE_CADA1 && cfg->rule != CADA_RULE_CADA2) { set_error("rule must be CADA_RULE_CADA1 or CADA_RULE_CADA2"); return false; }
   if (cfg->model != CADA_MODEL_LOGREG && cfg->model != CADA_MODEL_MLP) { set_error("unknown model %d", cfg->model); return false; }
   if (!cfg->layer_dims) { set_error("layer_dims is NULL"); return false; }
@@ -102,14 +106,16 @@ bool check_config(const cada_config *cfg, Geometry *g) {
 // Lays out the common state.  Returns bytes used so far.
 void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState *s, Ctx *c) {
   const size_t p = (size_t)cfg->p, M = (size_t)cfg->M;
-  float *theta = w.take<float>(p), *h = w.take<float>(p), *v = w.take<float>(p);
+  float *theta = w.take<float>(p), *theta_lo = w.take<float>(p), *h = w.take<float>(p), *v = w.take<float>(p);
   float *vhat = w.take<float>(p), *nabla = w.take<float>(p);
   float *gbuf = w.take<float>(2 * M * p);
-  float *hist = nullptr, *snap = nullptr, *dtl = nullptr;
+  float *hist = nullptr, *hist_lo = nullptr, *snap = nullptr, *snap_lo = nullptr, *dtl = nullptr;
   if (cfg->rule == CADA_RULE_CADA2) {
     hist = w.take<float>((size_t)(cfg->D + 1) * p);
+    hist_lo = w.take<float>((size_t)(cfg->D + 1) * p);
   } else {
     snap = w.take<float>(p);
+    snap_lo = w.take<float>(p);
     dtl = w.take<float>(2 * M * p);
   }
   int32_t *tau = w.take<int32_t>(M), *sel = w.take<int32_t>(M);
@@ -128,7 +134,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   float *zpart = nullptr;
   if (cfg->model == CADA_MODEL_LOGREG) zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
   if (!s) return;
-  s->theta = theta; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
+  s->theta = theta; s->theta_lo = theta_lo; s->hist_lo = hist_lo; s->snap_lo = snap_lo; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
   s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl;
   s->tau = tau; s->sel = sel; s->lhs = lhs; s->lhs_part = lhs_part; s->mask = mask;
   s->ring = ring; s->ring_part = ring_part; s->uploads = uploads; s->err = err;
@@ -225,14 +231,16 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   c->n_col_chunks = g.n_col_chunks;
   c->chunk_cols = g.chunk_cols;
   c->ws_bytes = need;
+  if (const char *e = getenv("CADA_LOGREG_GROUP")) c->logreg_group = atoi(e);   // tuning knob
   Carver w{static_cast<char *>(cfg->workspace)};
   carve_common(w, cfg, g, &s, c);
   s.X = cfg->X; s.y = cfg->y;
   s.M = cfg->M; s.B = cfg->B; s.d_max = cfg->d_max; s.D = cfg->D; s.R = cfg->D + 1; s.rule = cfg->rule;
   s.n_lhs_part = g.n_lhs_part; s.n_ring_part = g.n_ring_part;
   s.p = cfg->p; s.k = 0;
-  s.alpha = cfg->alpha; s.beta1 = cfg->beta1; s.beta2 = cfg->beta2; s.eps = cfg->eps;
-  s.lam = cfg->lambda_l2; s.c = cfg->c;
+  s.alpha = (float)cfg->alpha; s.beta1 = (float)cfg->beta1; s.beta2 = (float)cfg->beta2;
+  s.omb1 = (float)(1.0 - cfg->beta1); s.omb2 = (float)(1.0 - cfg->beta2);
+  s.eps = (float)cfg->eps; s.lam = (float)cfg->lambda_l2; s.c = cfg->c;
   if (cfg->model == CADA_MODEL_LOGREG) {
     c->n_phases = 4;
     c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad";
@@ -307,7 +315,7 @@ int cada_get_state(cada_ctx *ctx, cada_state *out) {
   const int rc = ring_finalize(c);   // fold the last step's squared step into the ring
   if (rc != CADA_OK) return rc;
   const DevState &s = c->s;
-  out->theta = s.theta; out->h = s.h; out->v = s.v; out->vhat = s.vhat; out->nabla = s.nabla;
+  out->theta = s.theta; out->theta_lo = s.theta_lo; out->h = s.h; out->v = s.v; out->vhat = s.vhat; out->nabla = s.nabla;
   out->tau = s.tau; out->ring = s.ring; out->mask = s.mask; out->lhs = s.lhs;
   out->uploads_total = s.uploads; out->error_flags = s.err;
   out->k = c->k; out->trace_steps = s.trace_steps;

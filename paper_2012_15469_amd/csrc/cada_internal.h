@@ -14,16 +14,20 @@ constexpr int kWave = 64;
 
 // Everything the kernels need to find the state; passed by value.
 struct DevState {
-  // server vectors [p]
-  float *theta, *h, *v, *vhat, *nabla;
+  // server vectors [p].  The iterate is kept as an unevaluated sum theta + theta_lo of two
+  // floats (|theta_lo| <= ulp(theta)/2): theta - theta_ref, which the rules' left-hand side
+  // is a function of, is then accurate to float32 relative precision of the DIFFERENCE even
+  // when it is a single small step (rounding theta alone perturbs a one-step difference by
+  // 1e-5..1e-4 relative, more than the rule comparison tolerates).
+  float *theta, *theta_lo, *h, *v, *vhat, *nabla;
   // stored / fresh stochastic gradients: gbuf[s][m][p], s in {0,1}.  Worker m's stored
   // gradient is gbuf[sel[m]][m]; the fresh one of the current step is written to
   // gbuf[1-sel[m]][m] and an upload is sel[m] ^= 1 (no copy).
   float *gbuf;
   // CADA2: hist[R][p], slot j mod R holds theta^j, R = D+1.  theta^{k-tau_m} is read here.
-  float *hist;
+  float *hist, *hist_lo;
   // CADA1: snapshot theta-tilde [p] and innovations dtl[s][m][p] indexed by sel like gbuf.
-  float *snap, *dtl;
+  float *snap, *snap_lo, *dtl;
   int32_t *tau, *sel;     // [M]
   float *lhs;             // [M]
   float *lhs_part;        // [M][n_lhs_part] partial sums of the left-hand side
@@ -45,17 +49,19 @@ struct DevState {
   int32_t M, B, d_max, D, R, rule, n_lhs_part, n_ring_part;
   int64_t p;
   int64_t k;                // iteration of the launch this copy is passed to
-  float alpha, beta1, beta2, eps, lam, c;
+  float alpha, beta1, beta2, omb1, omb2, eps, lam;   // omb = 1 - beta, rounded once from double
+  double c;
 };
 
 // Reference point of worker m at iteration k (Algorithm 1: theta-tilde for CADA1,
 // theta^{k - tau_m^k} for CADA2).
-__device__ __forceinline__ const float *theta_ref(const DevState &s, int m, int64_t k) {
-  if (s.rule == CADA_RULE_CADA1) return s.snap;
-  int64_t j = k - (int64_t)s.tau[m];
+struct RefPtr { const float *hi, *lo; };
+__device__ __forceinline__ RefPtr theta_ref(const DevState &s, int m, int64_t k) {
+  if (s.rule == CADA_RULE_CADA1) return RefPtr{s.snap, s.snap_lo};
+  int64_t j = k - (int64_t)min(s.tau[m], s.D);   // tau <= D unless a replay kept m silent longer
   int64_t slot = j % s.R;
   if (slot < 0) slot += s.R;
-  return s.hist + slot * s.p;
+  return RefPtr{s.hist + slot * s.p, s.hist_lo + slot * s.p};
 }
 
 __device__ __forceinline__ float wave_sum(float x) {
@@ -90,6 +96,7 @@ struct Ctx {
   int64_t chunk_cols;
   float *zpart;              // [M][B][n_col_chunks][2]
   int n_server_blocks;
+  int logreg_group;          // workers per launch pair of the logistic gradient kernels (0 = all)
   void *mlp;                 // MLP plan (cada_mlp.hip), or nullptr
   void *prof;                // profiling events (cada_api.hip), or nullptr
   int n_phases;              // phases per step = marks per step - 1

@@ -25,6 +25,7 @@ struct LogregArgs {
   float *zpart;          // [M][B][nc][2]
   int nc;
   int64_t chunk_cols;
+  int m0;                // first worker of this launch
 };
 
 template <int VEC> struct Vec;
@@ -59,11 +60,12 @@ __device__ __forceinline__ int64_t clamp_row(const DevState &s, int m, int32_t l
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void k_dots(const LogregArgs a) {
   const DevState &s = a.s;
-  const int m = blockIdx.z;
+  const int m = a.m0 + blockIdx.z;
   const int r0 = blockIdx.y * kRowsPerBlock;
   const int64_t k = s.k;
   const float *__restrict__ th = s.theta;
-  const float *__restrict__ tr = theta_ref(s, m, k);
+  const float *__restrict__ tl = s.theta_lo;
+  const RefPtr ref = theta_ref(s, m, k);
   const int32_t *idx = a.idx + (int64_t)m * s.B;
 
   const float *xrow[kRowsPerBlock];
@@ -82,11 +84,13 @@ __global__ __launch_bounds__(kBlock) void k_dots(const LogregArgs a) {
   const int64_t c0 = (int64_t)blockIdx.x * a.chunk_cols;
   const int64_t c1 = min(s.p, c0 + a.chunk_cols);
   for (int64_t j = c0 + (int64_t)threadIdx.x * VEC; j < c1; j += (int64_t)kBlock * VEC) {
-    float t[VEC], d[VEC];
+    float t[VEC], d[VEC], lo[VEC], rlo[VEC];
     load_vec<VEC>(th + j, t);
-    load_vec<VEC>(tr + j, d);
+    load_vec<VEC>(ref.hi + j, d);
+    load_vec<VEC>(tl + j, lo);
+    load_vec<VEC>(ref.lo + j, rlo);
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) d[v] = t[v] - d[v];
+    for (int v = 0; v < VEC; ++v) d[v] = (t[v] - d[v]) + (lo[v] - rlo[v]);
     float x[kRowsPerBlock][VEC];
 #pragma unroll
     for (int r = 0; r < kRowsPerBlock; ++r) load_vec<VEC>(xrow[r] + j, x[r]);
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(kBlock) void k_grad(const LogregArgs a) {
   float *dr_s = r_s + s.B;
   __shared__ float red[4];
 
-  const int m = blockIdx.y;
+  const int m = a.m0 + blockIdx.y;
   const int64_t k = s.k;
   const int32_t *idx = a.idx + (int64_t)m * s.B;
   const float *yv = static_cast<const float *>(s.y);
@@ -184,12 +188,15 @@ __global__ __launch_bounds__(kBlock) void k_grad(const LogregArgs a) {
         iv[v] = fmaf(dr, x[v], iv[v]);
       }
     }
-    float t[VEC], d[VEC];
+    float t[VEC], d[VEC], lo[VEC], rlo[VEC];
+    const RefPtr ref = theta_ref(s, m, k);
     load_vec<VEC>(s.theta + j, t);
-    load_vec<VEC>(theta_ref(s, m, k) + j, d);
+    load_vec<VEC>(ref.hi + j, d);
+    load_vec<VEC>(s.theta_lo + j, lo);
+    load_vec<VEC>(ref.lo + j, rlo);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-      d[v] = t[v] - d[v];
+      d[v] = (t[v] - d[v]) + (lo[v] - rlo[v]);
       g[v] = fmaf(s.lam, t[v], g[v]);
       iv[v] = fmaf(s.lam, d[v], iv[v]);
     }
@@ -221,19 +228,25 @@ int logreg_gradients(Ctx *c, const int32_t *idx) {
   a.nc = c->n_col_chunks;
   a.chunk_cols = c->chunk_cols;
   const DevState &s = c->s;
-  const dim3 g1(c->n_col_chunks, (s.B + kRowsPerBlock - 1) / kRowsPerBlock, s.M);
-  const dim3 g2(s.n_lhs_part, s.M);
   const size_t lds = (size_t)s.B * (sizeof(int64_t) + 2 * sizeof(float));
+  // Workers are processed in groups: the second pass over a group's rows follows its first
+  // pass closely enough for the rows to still be in the memory-side cache.
+  const int group = c->logreg_group > 0 ? c->logreg_group : s.M;
   prof_mark(c);
-  if (c->vec == 4) {
-    hipLaunchKernelGGL(k_dots<4>, g1, dim3(kBlock), 0, c->stream, a);
-    prof_mark(c);
-    hipLaunchKernelGGL(k_grad<4>, g2, dim3(kBlock), lds, c->stream, a);
-  } else {
-    hipLaunchKernelGGL(k_dots<1>, g1, dim3(kBlock), 0, c->stream, a);
-    prof_mark(c);
-    hipLaunchKernelGGL(k_grad<1>, g2, dim3(kBlock), lds, c->stream, a);
+  for (int m0 = 0; m0 < s.M; m0 += group) {
+    const int gm = min(group, s.M - m0);
+    a.m0 = m0;
+    const dim3 g1(c->n_col_chunks, (s.B + kRowsPerBlock - 1) / kRowsPerBlock, gm);
+    const dim3 g2(s.n_lhs_part, gm);
+    if (c->vec == 4) {
+      hipLaunchKernelGGL(k_dots<4>, g1, dim3(kBlock), 0, c->stream, a);
+      hipLaunchKernelGGL(k_grad<4>, g2, dim3(kBlock), lds, c->stream, a);
+    } else {
+      hipLaunchKernelGGL(k_dots<1>, g1, dim3(kBlock), 0, c->stream, a);
+      hipLaunchKernelGGL(k_grad<1>, g2, dim3(kBlock), lds, c->stream, a);
+    }
   }
+  prof_mark(c);
   prof_mark(c);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) {

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kBlock) void k_rule(const DevState s, const uint8_t
   if (threadIdx.x == 0) {
     double sum = 0.0;
     for (int j = 0; j < s.d_max; ++j) sum += (double)s.ring[j];
-    rhs_s = ((double)s.c / (double)s.d_max) * sum;
+    rhs_s = (s.c / (double)s.d_max) * sum;
     cnt = 0;
   }
   __syncthreads();
@@ -99,21 +99,33 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
       }
     }
     const float fM = (float)s.M;
-    float th[VEC], hh[VEC], vv[VEC], vh[VEC];
+    float th[VEC], tl[VEC], hh[VEC], vv[VEC], vh[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
       const int64_t i = j + v;
       nab[v] = nab[v] / fM;
-      hh[v] = s.beta1 * s.h[i] + (1.0f - s.beta1) * nab[v];
+      // beta*x + (1-beta)*y written as x + (1-beta)*(y - x): float32(0.999) is off by 1.3e-8
+      // relative, which compounds to 1e-5 over the ~1000-step memory of vhat, whereas
+      // float32(1-beta) enters only linearly
+      const float ho = s.h[i];
+      hh[v] = fmaf(s.omb1, nab[v] - ho, ho);
       const float vo = s.vhat[i];
-      vv[v] = s.beta2 * vo + (1.0f - s.beta2) * (nab[v] * nab[v]);
+      vv[v] = fmaf(s.omb2, nab[v] * nab[v] - vo, vo);
       vh[v] = fmaxf(vv[v], vo);
       const float step = s.alpha * hh[v] / sqrtf(s.eps + vh[v]);
-      th[v] = s.theta[i] - step;
+      // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
+      const float a = s.theta[i], ms = -step;
+      const float sum = a + ms;
+      const float bb = sum - a;
+      const float err = (a - (sum - bb)) + (ms - bb);
+      const float lo = s.theta_lo[i] + err;
+      th[v] = sum + lo;
+      tl[v] = lo - (th[v] - sum);
       sq = fmaf(step, step, sq);
     }
     const bool snap = (s.rule == CADA_RULE_CADA1) && ((s.k + 1) % s.D == 0);
     float *hs = (s.rule == CADA_RULE_CADA2) ? s.hist + ((s.k + 1) % s.R) * s.p : nullptr;
+    float *hl = (s.rule == CADA_RULE_CADA2) ? s.hist_lo + ((s.k + 1) % s.R) * s.p : nullptr;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
       const int64_t i = j + v;
@@ -122,8 +134,9 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
       s.v[i] = vv[v];
       s.vhat[i] = vh[v];
       s.theta[i] = th[v];
-      if (hs) hs[i] = th[v];
-      if (snap) s.snap[i] = th[v];
+      s.theta_lo[i] = tl[v];
+      if (hs) { hs[i] = th[v]; hl[i] = tl[v]; }
+      if (snap) { s.snap[i] = th[v]; s.snap_lo[i] = tl[v]; }
     }
   }
   const float tot = block_sum(sq, red);

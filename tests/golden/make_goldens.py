@@ -1,0 +1,68 @@
+#!/usr/bin/env python3
+"""Writes the stored expected values of the full-size parity cases.
+
+Calls only the CPU oracle (oracle/) and the seeded input generators (cada_synth/); nothing
+here touches the GPU library.  Each .npz holds the oracle's trace (mask, lhs, rhs, tau),
+the final iterate (all of it up to 2^17 coordinates, else every `stride`-th coordinate plus
+its norm) and a fingerprint of the inputs so that a test can tell a stale file.
+
+    python tests/golden/make_goldens.py [case ...]
+"""
+from __future__ import annotations
+
+import os
+import sys
+import time
+import zlib
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
+
+from cada_synth import configs, generators  # noqa: E402
+from oracle.driver import oracle_for        # noqa: E402
+
+# name -> (config, steps)
+CASES = {
+    "cfg3_full_c0.3": (configs.CFG3, 3),
+    "cfg3_full_c1e-4": (configs.CFG3.scaled(c=1e-4), 4),
+}
+
+
+def fingerprint(cfg, prob, sched) -> int:
+    """CRC of the schedule, the initial iterate and the first minibatch of worker 0."""
+    X0, y0 = prob.rows(0, sched[0, 0])
+    h = zlib.crc32(np.ascontiguousarray(sched).tobytes())
+    h = zlib.crc32(np.ascontiguousarray(prob.theta0).tobytes(), h)
+    h = zlib.crc32(np.ascontiguousarray(X0).tobytes(), h)
+    h = zlib.crc32(np.ascontiguousarray(y0).tobytes(), h)
+    return h
+
+
+def theta_sample(theta):
+    stride = 1 if theta.size <= (1 << 17) else int(np.ceil(theta.size / (1 << 17)))
+    return theta[::stride].copy(), stride
+
+
+def make(name):
+    cfg, K = CASES[name]
+    t0 = time.time()
+    prob = generators.make_problem(cfg)
+    sched = generators.make_schedule(cfg, K)
+    o = oracle_for(cfg, prob)
+    for k in range(K):
+        o.step(sched[k])
+        print("  %s step %d/%d  %.0fs" % (name, k + 1, K, time.time() - t0), flush=True)
+    tr = o.trace_arrays()
+    th, stride = theta_sample(o.theta)
+    np.savez_compressed(os.path.join(HERE, name + ".npz"), mask=tr["mask"], own_mask=tr["own_mask"], lhs=tr["lhs"],
+                        rhs=tr["rhs"], tau=tr["tau"], tau_final=o.tau, theta=th, theta_stride=stride,
+                        theta_norm=np.linalg.norm(o.theta), h_norm=np.linalg.norm(o.h),
+                        vhat_norm=np.linalg.norm(o.vhat), ring=o.ring, uploads_total=o.uploads_total,
+                        fingerprint=fingerprint(cfg, prob, sched), K=K)
+
+
+if __name__ == "__main__":
+    for n in (sys.argv[1:] or list(CASES)):
+        make(n)

@@ -39,7 +39,9 @@ def test_cfg3_reduced_ragged(p, rule):
     """The high-dimensional recipe at reduced size: several column chunks with a ragged
     tail (p = 8200 = 8192 + 8), a row count that is no multiple of the row group (B = 20)
     and the scalar-load path (p = 4099 is not a multiple of 4)."""
-    cfg = configs.CFG3.scaled(layer_dims=(p,), M=5, N_m=64, B=20, K=60, D=10, rule=rule, alpha=0.02)
+    # c is lowered from the workload's 0.3: a minibatch spans only B of the p directions, so
+    # with c = 0.3 the rule never fires at this size and only forced uploads would be tested
+    cfg = configs.CFG3.scaled(layer_dims=(p,), M=5, N_m=64, B=20, K=60, D=10, rule=rule, alpha=0.02, c=1e-4)
     prob = generators.make_problem(cfg)
     if p % 2:   # the counter recipe needs an even p: fall back to host-generated Gaussians
         cfg = cfg.scaled(data="gauss_shifted")
@@ -49,8 +51,10 @@ def test_cfg3_reduced_ragged(p, rule):
         Xs, ys = zip(*(prob.rows(m, np.arange(cfg.N_m)) for m in range(cfg.M)))
         prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
     sched = generators.make_schedule(cfg)
-    stats, *_ = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4)
+    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4)
     print(p, rule, stats)
+    free = tr["tau"] < cfg.D
+    assert 0.1 < tr["mask"][free].mean() < 0.9, "the case must mix rule-driven uploads and skips"
 
 
 def test_special_cases_c0_and_huge_c():
