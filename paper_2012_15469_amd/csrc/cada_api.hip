@@ -132,8 +132,13 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   float *t_lhs = w.take<float>(T * M), *t_rhs = w.take<float>(T);
   int32_t *t_tau = w.take<int32_t>(T * M);
   float *zpart = nullptr;
-  if (cfg->model == CADA_MODEL_LOGREG) zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
+  unsigned long long *post = nullptr;
+  if (cfg->model == CADA_MODEL_LOGREG) {
+    zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
+    post = w.take<unsigned long long>(kFusedPostWords);
+  }
   if (!s) return;
+  c->fused_post = post;
   s->theta = theta; s->theta_lo = theta_lo; s->hist_lo = hist_lo; s->snap_lo = snap_lo; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
   s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl;
   s->tau = tau; s->sel = sel; s->lhs = lhs; s->lhs_part = lhs_part; s->mask = mask;
@@ -242,6 +247,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   s.omb1 = (float)(1.0 - cfg->beta1); s.omb2 = (float)(1.0 - cfg->beta2);
   s.eps = (float)cfg->eps; s.lam = (float)cfg->lambda_l2; s.c = cfg->c;
   if (cfg->model == CADA_MODEL_LOGREG) {
+    if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = c->fused_Q;
     c->n_phases = 4;
     c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad";
     c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
@@ -289,7 +295,8 @@ int cada_step(cada_ctx *ctx, const int32_t *idx, const uint8_t *replay) {
   if (!ctx) { set_error("ctx is NULL"); return CADA_EINVAL; }
   if (!idx) { set_error("idx is NULL"); return CADA_EINVAL; }
   Ctx *c = &ctx->c;
-  int rc = (c->model == CADA_MODEL_LOGREG) ? logreg_gradients(c, idx) : mlp_gradients(c, idx);
+  int rc = (c->model != CADA_MODEL_LOGREG) ? mlp_gradients(c, idx)
+           : (c->fused ? logreg_gradients_fused(c, idx) : logreg_gradients(c, idx));
   if (rc != CADA_OK) return rc;
   rc = rule_and_server(c, replay);
   if (rc != CADA_OK) return rc;

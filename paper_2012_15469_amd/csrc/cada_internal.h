@@ -96,6 +96,11 @@ struct Ctx {
   int64_t chunk_cols;
   float *zpart;              // [M][B][n_col_chunks][2]
   int n_server_blocks;
+  // single-pass (register-resident) logistic path, cada_logreg_fused.hip
+  int fused, fused_Q, fused_clusters, fused_rs;
+  int64_t fused_cols;
+  uint32_t fused_seq, fused_seq_per_step;
+  unsigned long long *fused_post;
   int logreg_group;          // workers per launch pair of the logistic gradient kernels (0 = all)
   void *mlp;                 // MLP plan (cada_mlp.hip), or nullptr
   void *prof;                // profiling events (cada_api.hip), or nullptr
@@ -109,6 +114,9 @@ void prof_mark(Ctx *c);
 
 // S1+S2 for the logistic model: fresh gradients into gbuf[1-sel], left-hand sides into lhs_part.
 int logreg_gradients(Ctx *c, const int32_t *idx);
+bool fused_plan(Ctx *c, int64_t p, int B, int M);
+int logreg_gradients_fused(Ctx *c, const int32_t *idx);
+constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgroups x 4 buffers x 16 values
 // S1+S2 for the MLP.
 int mlp_gradients(Ctx *c, const int32_t *idx);
 size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows);
