@@ -33,6 +33,18 @@ def algorithmic_bytes_per_step(cfg) -> float:
     return M * per_worker + 4.0 * M * p + 32.0 * p
 
 
+def algorithmic_flops_per_step(cfg) -> float:
+    """MLP: two gradient evaluations per worker-iteration, each = forward 2 B sum(in*out),
+    weight gradients (the same) and activation gradients for layers >= 2."""
+    d = cfg.layer_dims
+    fwd = sum(2.0 * cfg.B * d[i] * d[i + 1] for i in range(len(d) - 1))
+    dact = sum(2.0 * cfg.B * d[i] * d[i + 1] for i in range(1, len(d) - 1))
+    return cfg.M * 2.0 * (2.0 * fwd + dact)
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +117,15 @@ def main() -> int:
         out["roofline"] = {"bound": "hbm", "kernel": "logreg_dots+logreg_grad", "achieved": achieved,
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                            "algorithmic_bytes_per_launch": alg, "avg_launch_ms": grad_ms}
+
+    if cfg.model == "mlp":
+        fl = algorithmic_flops_per_step(cfg)
+        ms = prof["mlp_gradients"]
+        achieved = fl / (ms * 1e-3) / 1e12
+        out["roofline"] = {"bound": "mfma", "kernel": "mlp_gradients (all GEMM and elementwise kernels of S1+S2)",
+                           "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                           "algorithmic_flops_per_launch": fl, "avg_launch_ms": ms}
 
     if not args.no_cpu_baseline:
         from oracle.driver import oracle_for
