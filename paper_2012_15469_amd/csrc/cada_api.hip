@@ -100,10 +100,7 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   const int64_t per_block = (int64_t)kBlock * g->vec;
   g->n_lhs_part = (int)((cfg->p + per_block - 1) / per_block);
   g->n_ring_part = g->n_lhs_part;
-  if (cfg->model == CADA_MODEL_MLP) {   // one block per 32768 coordinates sums the left-hand side
-    const int64_t nb = (cfg->p + 32767) / 32768;
-    g->n_lhs_part = (int)(nb < 1 ? 1 : (nb > 256 ? 256 : nb));
-  }
+  if (cfg->model == CADA_MODEL_MLP) g->n_lhs_part = mlp_lhs_slots(cfg);
   return true;
 }
 

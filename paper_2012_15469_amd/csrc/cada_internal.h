@@ -119,6 +119,7 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx);
 constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgroups x 4 buffers x 16 values
 // S1+S2 for the MLP.
 int mlp_gradients(Ctx *c, const int32_t *idx);
+int mlp_lhs_slots(const cada_config *cfg);
 size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows);
 int mlp_plan(Ctx *c, const cada_config *cfg, char *base, size_t *offset, int64_t total_rows);
 int mlp_init_state(Ctx *c, const float *theta0);

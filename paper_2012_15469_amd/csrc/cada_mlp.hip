@@ -3,9 +3,9 @@
 // rule (Section 2.2, conditions (workerrule1)/(workerrule2); Algorithm 1, the two gradient
 // evaluations on the same samples).
 //
-// The second gradient is never formed by itself.  With d = theta - theta_ref (float32, from
-// the two-float iterate) every quantity of the reference evaluation is carried as a
-// difference to the evaluation at theta, and the differences are propagated exactly:
+// The second gradient is never formed by itself.  With d = theta - theta_ref every quantity
+// of the reference evaluation is carried as a difference to the evaluation at theta, and the
+// differences are propagated exactly:
 //   forward   dZ_1 = A_0 dW_1 + db_1,           dZ_l = dA_{l-1} W_l + Aref_{l-1} dW_l + db_l
 //             A_l = relu(Z_l), Aref_l = relu(Z_l - dZ_l), dA_l = A_l - Aref_l
 //   loss      G_L = (softmax(Z_L) - onehot)/B,  dG_L = (softmax(Z_L) - softmax(Z_L - dZ_L))/B
@@ -14,26 +14,30 @@
 //             G_{l-1} = GA_{l-1} [Z>0],         Gref_{l-1} = (GA - dGA)_{l-1} [Zref>0]
 // (Gref = G - dG).  Rounding W and W_ref to bf16 separately would bury their difference (one
 // Adam step is about one bf16 ulp of a weight); rounding d itself keeps 8 significant bits
-// of the difference, which is what the rule's comparison needs.
+// of the difference.
 //
 // Precision.  The difference of two ReLU-network gradients at nearby points is dominated by
 // the few units whose pre-activation changes sign between the two points, so the rule's
 // left-hand side is only as good as the pre-activations Z_l are near zero: they must be
 // resolved well below |dZ_l| ~ 1e-3 |Z_l|, which a single bf16 product (2^-9 per operand)
-// cannot do.  The forward contractions Z_l = A_{l-1} W_l therefore use split operands
-// x = hi + lo (two bf16 values, 16 significant bits) and three MFMA products
-// hi*hi + hi*lo + lo*hi accumulated in float32.  The backward contractions of the gradient at
-// theta (grad W_l, GA_l) are split the same way: the server's update divides by sqrt(vhat),
-// so a coordinate whose gradient is smaller than its rounding error moves by a full
-// +-alpha-sized step in a random direction, and with single bf16 products (0.2% gradient
-// error) the iterate drifts from the fp64 trajectory by percents within tens of steps.
-// Only the difference contractions (dZ, dGA, the innovation) are single bf16 products.
+// cannot do.  Every contraction of the evaluation at theta (Z_l, grad W_l, GA_l) therefore
+// uses split operands x = hi + lo (two bf16 values, 16 significant bits) and three MFMA
+// products hi*hi + hi*lo + lo*hi accumulated in float32.  The backward ones need it because
+// the server's update divides by sqrt(vhat): a coordinate whose gradient is smaller than its
+// rounding error moves by a full alpha-sized step in a random direction, and with single
+// bf16 products (0.2% gradient error) the iterate drifts from the fp64 trajectory by
+// percents within tens of steps.  The difference contractions are single bf16 products.
 //
-// One GEMM kernel serves every contraction: C = sum over up to four operand pairs of
-// A_i B_i^T, 128x128 output tile per workgroup, 4 wavefronts of 64x64, K step 32,
-// v_mfma_f32_32x32x16_bf16.  Either operand may be stored K-contiguous or M/N-contiguous
-// (transposed while it is staged into LDS), rows may be gathered through an index array, and
-// a batch index (the worker) offsets all three matrices.
+// One kernel, k_mm5, serves all three contraction shapes (forward, weight gradient,
+// activation gradient).  For a 128 x 128 output tile of worker m it accumulates
+//     C1 = Ah Bh^T + Ah Bl^T + Al Bh^T          (evaluation at theta, split operands)
+//     C2 = Ad Bx^T + Ar Bd^T                    (difference to the reference evaluation)
+// from up to four A-side and four B-side bf16 tensors, all stored with the contraction index
+// contiguous, staged through LDS in 128 x 32 tiles, with v_mfma_f32_32x32x16_bf16 on four
+// wavefronts of 64 x 64.  The epilogues apply bias/ReLU/masks, split results into hi/lo,
+// write the tensors the later contractions need in both orientations, reduce bias gradients
+// and the squared norm of the innovation, so no float32 intermediate except the logits
+// round-trips through HBM.
 #include <cstdlib>
 #include <new>
 
@@ -53,168 +57,345 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
 }
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-inline int64_t P8(int64_t x) { return (x + 7) / 8 * 8; }
-
-// ------------------------------------------------------------------------------------------
-// GEMM
-// ------------------------------------------------------------------------------------------
-struct Operand {
-  const bf16_t *ptr;
-  int64_t ld;            // leading dimension of the row-major source (multiple of 8)
-  int64_t batch_stride;  // elements added per batch index
-  const int64_t *gather; // optional: source row r is read at row gather[batch*gather_stride + r]
-  int64_t gather_stride;
-  int kmajor;            // 1: source rows are the M (or N) index, K contiguous
-                         // 0: source rows are the K index, M (or N) contiguous
-};
-
-struct GemmArgs {
-  Operand A[4], B[4];
-  int K[4];
-  int npairs;
-  int M, N;
-  float *C;
-  int64_t ldc, c_batch_stride;
-  const int32_t *sel;      // optional: C += (1 - sel[batch]) * c_sel_stride  (fresh half of a double buffer)
-  int64_t c_sel_stride;
-};
+static inline int64_t P8(int64_t x) { return (x + 7) / 8 * 8; }
 
 constexpr int BM = 128, BN = 128, BK = 32, PITCH = BK + 8;
+constexpr int TILE = 128 * PITCH;                 // bf16 elements of one staged tile
+constexpr int kMaxSlots = 4;
+constexpr size_t kMm5Lds = (size_t)2 * kMaxSlots * TILE * sizeof(bf16_t);   // 80 KB
 
-struct Chunk { uint4 v; };
+enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
 
-// Loads the two 16-byte chunks this thread contributes to a 128 x 32 operand tile.
-// rows0: first M/N index of the tile, k0: first K index, R: extent of the M/N index.
-__device__ __forceinline__ void load_chunks(const Operand &op, const bf16_t *base, const int64_t *gat, int rows0, int R, int k0, int K,
-                                            uint4 (&out)[2]) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (op.kmajor) {
-      const int row = rows0 + (t >> 2) + c * 64;       // 4 chunks of 8 k per row
-      const int k = k0 + (t & 3) * 8;
-      if (row < R && k < K) {
-        const int64_t src = gat ? gat[row] : (int64_t)row;
-        v = *reinterpret_cast<const uint4 *>(base + src * op.ld + k);
-      }
-    } else {
-      const int k = k0 + (t >> 4) + c * 16;            // 16 chunks of 8 m per k-row
-      const int row = rows0 + (t & 15) * 8;
-      if (k < K && row < R) {
-        const int64_t src = gat ? gat[k] : (int64_t)k;
-        v = *reinterpret_cast<const uint4 *>(base + src * op.ld + row);
-      }
-    }
-    out[c] = v;
-  }
+// Up to four tensors that share the row index of one side of the product.
+struct Side {
+  const bf16_t *ptr[kMaxSlots];
+  int64_t ld[kMaxSlots];        // elements between consecutive rows (multiple of 8)
+  int64_t bstride[kMaxSlots];   // elements added per worker
+  int n;
+};
+
+struct Mm5Args {
+  DevState s;
+  Side A, B;
+  const int64_t *gatherA;       // optional: A row r of worker m is source row gatherA[m*gstride + r]
+  int64_t gstride;
+  int a_h, a_l, a_d, a_r;       // role -> slot of A (-1: absent)
+  int b_h, b_l, b_x, b_d;       // role -> slot of B
+  int M, N, K;                  // extents of the tile index spaces and of the contraction
+  int Bp;                       // padded rows per worker
+  int64_t Rp;                   // M_workers * Bp
+  // EPI_FWD_HIDDEN / EPI_DA: bias offset, row-major and transposed outputs
+  int64_t offb;
+  bf16_t *o_h, *o_l, *o_d, *o_r;        // row-major [Rp][ldo]
+  bf16_t *t_h, *t_l, *t_d, *t_r;        // transposed [N][Rp]
+  int64_t ldo;
+  const bf16_t *m_on, *m_onref;         // EPI_DA: activations whose sign is the ReLU mask, [Rp][ldm]
+  int64_t ldm;
+  float *dbpart, *ddbpart;              // EPI_DA: [M_workers][row tiles][N]
+  // EPI_STORE2
+  float *c1, *c2;                       // [Rp][N]
+  // EPI_DW
+  int64_t offW;
+  int lhs_slot0;
+};
+
+__device__ __forceinline__ float delta_theta(const DevState &s, const RefPtr &ref, int64_t i) {
+  return (s.theta[i] - ref.hi[i]) + (s.theta_lo[i] - ref.lo[i]);
+}
+__device__ __forceinline__ float *fresh_grad(const DevState &s, int m) {
+  return s.gbuf + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.p;
 }
 
-__device__ __forceinline__ void store_chunks(const Operand &op, bf16_t *lds, const uint4 (&in)[2]) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    if (op.kmajor) {
-      const int row = (t >> 2) + c * 64, kc = (t & 3) * 8;
-      *reinterpret_cast<uint4 *>(lds + row * PITCH + kc) = in[c];
-    } else {
-      const int k = (t >> 4) + c * 16, row = (t & 15) * 8;
-      const uint32_t w[4] = {in[c].x, in[c].y, in[c].z, in[c].w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) lds[(row + e) * PITCH + k] = (bf16_t)(w[e >> 1] >> ((e & 1) * 16));
-    }
-  }
+__device__ __forceinline__ uint2 pack4(const bf16_t (&v)[4]) {
+  return make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
 }
 
-// grid (ceil(N/128), ceil(M/128), batches)
-__global__ __launch_bounds__(kBlock) void k_gemm(const GemmArgs g) {
-  __shared__ __align__(16) bf16_t As[BM * PITCH];
-  __shared__ __align__(16) bf16_t Bs[BN * PITCH];
+template <int EPI>
+__global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t *lds = reinterpret_cast<bf16_t *>(smem_raw);
+  bf16_t *ldsA = lds, *ldsB = lds + kMaxSlots * TILE;
+  const DevState &s = g.s;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int wy = w >> 1, wx = w & 1;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int64_t batch = blockIdx.z;
+  const int wk = blockIdx.z;                         // worker
+  const int64_t *gat = g.gatherA ? g.gatherA + (int64_t)wk * g.gstride : nullptr;
 
-  f32x16 acc[2][2];
+  f32x16 acc1[2][2], acc2[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 16; ++r) { acc1[i][j][r] = 0.f; acc2[i][j][r] = 0.f; }
 
-  for (int pr = 0; pr < g.npairs; ++pr) {
-    const Operand &oa = g.A[pr], &ob = g.B[pr];
-    const bf16_t *abase = oa.ptr + batch * oa.batch_stride;
-    const bf16_t *bbase = ob.ptr + batch * ob.batch_stride;
-    const int64_t *agat = oa.gather ? oa.gather + batch * oa.gather_stride : nullptr;
-    const int64_t *bgat = ob.gather ? ob.gather + batch * ob.gather_stride : nullptr;
-    const int K = g.K[pr];
-    uint4 ra[2], rb[2];
-    load_chunks(oa, abase, agat, m0, g.M, 0, K, ra);
-    load_chunks(ob, bbase, bgat, n0, g.N, 0, K, rb);
-    for (int k0 = 0; k0 < K; k0 += BK) {
-      __syncthreads();                       // previous tile fully consumed
-      store_chunks(oa, As, ra);
-      store_chunks(ob, Bs, rb);
-      __syncthreads();
-      if (k0 + BK < K) {
-        load_chunks(oa, abase, agat, m0, g.M, k0 + BK, K, ra);
-        load_chunks(ob, bbase, bgat, n0, g.N, k0 + BK, K, rb);
+  // this thread's two 16-byte chunks of a 128 x 32 tile: rows (t>>2) and (t>>2)+64, k offset (t&3)*8
+  const int crow = t >> 2, ck = (t & 3) * 8;
+  uint4 ra[kMaxSlots][2], rb[kMaxSlots][2];
+  auto load_tiles = [&](int k0) {
+    const int k = k0 + ck;
+#pragma unroll
+    for (int sl = 0; sl < kMaxSlots; ++sl) {
+      if (sl < g.A.n) {
+        const bf16_t *base = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const int row = m0 + crow + c * 64;
+          uint4 v = make_uint4(0u, 0u, 0u, 0u);
+          if (row < g.M && k < g.K) {
+            const int64_t src = gat ? gat[row] : (int64_t)row;
+            v = *reinterpret_cast<const uint4 *>(base + src * g.A.ld[sl] + k);
+          }
+          ra[sl][c] = v;
+        }
+      }
+      if (sl < g.B.n) {
+        const bf16_t *base = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const int row = n0 + crow + c * 64;
+          uint4 v = make_uint4(0u, 0u, 0u, 0u);
+          if (row < g.N && k < g.K) v = *reinterpret_cast<const uint4 *>(base + (int64_t)row * g.B.ld[sl] + k);
+          rb[sl][c] = v;
+        }
+      }
+    }
+  };
+  auto store_tiles = [&]() {
+#pragma unroll
+    for (int sl = 0; sl < kMaxSlots; ++sl) {
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        if (sl < g.A.n) *reinterpret_cast<uint4 *>(ldsA + sl * TILE + (crow + c * 64) * PITCH + ck) = ra[sl][c];
+        if (sl < g.B.n) *reinterpret_cast<uint4 *>(ldsB + sl * TILE + (crow + c * 64) * PITCH + ck) = rb[sl][c];
+      }
+    }
+  };
+
+  const bool has_lo = g.a_l >= 0, has_d = g.a_d >= 0, has_r = g.a_r >= 0;
+  const int fro = (lane & 31) * PITCH + (lane >> 5) * 8;   // fragment offset of this lane inside a 32-row band
+  load_tiles(0);
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+    __syncthreads();
+    store_tiles();
+    __syncthreads();
+    if (k0 + BK < g.K) load_tiles(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      bf16x8 ah[2], al[2], ad[2], ar[2], bh[2], bl[2], bx[2], bd[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int o = (wy * 64 + i * 32) * PITCH + fro + ks;
+        ah[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_h * TILE + o);
+        if (has_lo) al[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_l * TILE + o);
+        if (has_d) ad[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_d * TILE + o);
+        if (has_r) ar[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_r * TILE + o);
       }
 #pragma unroll
-      for (int ks = 0; ks < BK; ks += 16) {
-        bf16x8 a[2], b[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          a[i] = *reinterpret_cast<const bf16x8 *>(As + (wy * 64 + i * 32 + (lane & 31)) * PITCH + ks + (lane >> 5) * 8);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          b[j] = *reinterpret_cast<const bf16x8 *>(Bs + (wx * 64 + j * 32 + (lane & 31)) * PITCH + ks + (lane >> 5) * 8);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 2; ++j) {
+        const int o = (wx * 64 + j * 32) * PITCH + fro + ks;
+        bh[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_h * TILE + o);
+        if (has_lo) bl[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_l * TILE + o);
+        if (has_d) bx[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_x * TILE + o);
+        if (has_r) bd[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_d * TILE + o);
       }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          if (has_lo) {
+            acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc1[i][j], 0, 0, 0);
+            acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc1[i][j], 0, 0, 0);
+          }
+          acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc1[i][j], 0, 0, 0);
+          if (has_d) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad[i], bx[j], acc2[i][j], 0, 0, 0);
+          if (has_r) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ar[i], bd[j], acc2[i][j], 0, 0, 0);
+        }
     }
   }
+  __syncthreads();   // LDS is free for the epilogue
 
-  float *C = g.C + batch * g.c_batch_stride;
-  if (g.sel) C += (int64_t)(1 - g.sel[batch]) * g.c_sel_stride;
+  // accumulator element (i, j, r) is output (row, col):
+  //   row = m0 + wy*64 + i*32 + 8*(r>>2) + 4*(lane>>5) + (r&3),  col = n0 + wx*64 + j*32 + (lane&31)
+  const int rbase = m0 + wy * 64 + 4 * (lane >> 5);
+  const int cbase = n0 + wx * 64 + (lane & 31);
+  const int64_t rp0 = (int64_t)wk * g.Bp;            // first padded row of this worker
+
+  if constexpr (EPI == EPI_STORE2) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = cbase + j * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < g.M && col < g.N) {
+            g.c1[(rp0 + row) * g.N + col] = acc1[i][j][r];
+            g.c2[(rp0 + row) * g.N + col] = acc2[i][j][r];
+          }
+        }
+      }
+  } else if constexpr (EPI == EPI_FWD_HIDDEN) {
+    const RefPtr ref = theta_ref(s, wk, s.k);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wx * 64 + j * 32 + (lane & 31);
+      const int col = cbase + j * 32;
+      const bool cok = col < g.N;
+      const float b = cok ? s.theta[g.offb + col] : 0.f;
+      const float db = cok ? delta_theta(s, ref, g.offb + col) : 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wy * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < g.M && col < g.N) C[(int64_t)row * g.ldc + col] = acc[i][j][r];
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {        // four groups of four consecutive rows
+          const int row0 = rbase + i * 32 + 8 * q;
+          bf16_t vh[4], vl[4], vd[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int row = row0 + e;
+            const float z = acc1[i][j][4 * q + e] + b;
+            const float dz = acc2[i][j][4 * q + e] + db;
+            const float act = fmaxf(z, 0.f), aref = fmaxf(z - dz, 0.f);
+            const bf16_t hi = f2bf(act);
+            vh[e] = hi; vl[e] = f2bf(act - bf2f(hi)); vd[e] = f2bf(act - aref);
+            if (cok && row < g.M) {
+              const int64_t o = (rp0 + row) * g.ldo + col;
+              g.o_h[o] = hi; g.o_l[o] = vl[e]; g.o_d[o] = vd[e]; g.o_r[o] = f2bf(aref);
+            }
+          }
+          if (cok) {
+            const int64_t ot = (int64_t)col * g.Rp + rp0 + row0;
+            if (row0 + 3 < g.M) {
+              *reinterpret_cast<uint2 *>(g.t_h + ot) = pack4(vh);
+              *reinterpret_cast<uint2 *>(g.t_l + ot) = pack4(vl);
+              *reinterpret_cast<uint2 *>(g.t_d + ot) = pack4(vd);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (row0 + e < g.M) { g.t_h[ot + e] = vh[e]; g.t_l[ot + e] = vl[e]; g.t_d[ot + e] = vd[e]; }
+            }
+          }
+        }
       }
     }
+  } else if constexpr (EPI == EPI_DA) {
+    // ReLU masks of the layer below, hi/lo split of the signal, bias-gradient partial sums
+    float *red = reinterpret_cast<float *>(smem_raw);          // [2 (wy)][128 cols][2]
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = cbase + j * 32;
+      const bool cok = col < g.N;
+      float sg = 0.f, sd = 0.f;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row0 = rbase + i * 32 + 8 * q;
+          bf16_t vh[4], vl[4], vd[4], vr[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int row = row0 + e;
+            float gl = 0.f, gref = 0.f;
+            if (cok && row < g.M) {
+              const int64_t om = (rp0 + row) * g.ldm + col;
+              const float ga = acc1[i][j][4 * q + e], dga = acc2[i][j][4 * q + e];
+              gl = bf2f(g.m_on[om]) > 0.f ? ga : 0.f;
+              gref = bf2f(g.m_onref[om]) > 0.f ? (ga - dga) : 0.f;
+            }
+            const float dg = gl - gref;
+            const bf16_t hi = f2bf(gl);
+            vh[e] = hi; vl[e] = f2bf(gl - bf2f(hi)); vd[e] = f2bf(dg); vr[e] = f2bf(gref);
+            sg += gl; sd += dg;
+            if (g.o_h && cok && row < g.M) {
+              const int64_t o = (rp0 + row) * g.ldo + col;
+              g.o_h[o] = hi; g.o_l[o] = vl[e]; g.o_d[o] = vd[e]; g.o_r[o] = vr[e];
+            }
+          }
+          if (cok) {
+            const int64_t ot = (int64_t)col * g.Rp + rp0 + row0;
+            if (row0 + 3 < g.M) {
+              *reinterpret_cast<uint2 *>(g.t_h + ot) = pack4(vh);
+              *reinterpret_cast<uint2 *>(g.t_l + ot) = pack4(vl);
+              *reinterpret_cast<uint2 *>(g.t_d + ot) = pack4(vd);
+              *reinterpret_cast<uint2 *>(g.t_r + ot) = pack4(vr);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (row0 + e < g.M) { g.t_h[ot + e] = vh[e]; g.t_l[ot + e] = vl[e]; g.t_d[ot + e] = vd[e]; g.t_r[ot + e] = vr[e]; }
+            }
+          }
+        }
+      }
+      // the other half-wave holds the rows offset by 4: add it, then one value per column and wave
+      sg += __shfl_xor(sg, 32, 64);
+      sd += __shfl_xor(sd, 32, 64);
+      if (lane < 32) {
+        const int cl = wx * 64 + j * 32 + lane;
+        red[(wy * 128 + cl) * 2] = sg;
+        red[(wy * 128 + cl) * 2 + 1] = sd;
+      }
+    }
+    __syncthreads();
+    if (t < 128 && n0 + t < g.N) {
+      const int64_t o = ((int64_t)wk * gridDim.y + blockIdx.y) * g.N + n0 + t;
+      g.dbpart[o] = red[t * 2] + red[(128 + t) * 2];
+      g.ddbpart[o] = red[t * 2 + 1] + red[(128 + t) * 2 + 1];
+    }
+  } else {   // EPI_DW
+    float *red = reinterpret_cast<float *>(smem_raw);
+    float *gf = fresh_grad(s, wk) + g.offW;
+    const bool cada1 = s.rule == CADA_RULE_CADA1;
+    const int cur = s.sel[wk];
+    float *ivf = cada1 ? s.dtl + ((int64_t)(1 - cur) * s.M + wk) * s.p + g.offW : nullptr;
+    const float *ivs = cada1 ? s.dtl + ((int64_t)cur * s.M + wk) * s.p + g.offW : nullptr;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = cbase + j * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < g.M && col < g.N) {
+            const int64_t o = (int64_t)row * g.N + col;
+            gf[o] = acc1[i][j][r];
+            float iv = acc2[i][j][r];
+            if (cada1) { ivf[o] = iv; iv -= ivs[o]; }
+            sq = fmaf(iv, iv, sq);
+          }
+        }
+      }
+    const float tot = block_sum(sq, red);
+    if (t == 0) s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + blockIdx.y * gridDim.x + blockIdx.x] = tot;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
 // plan
 // ------------------------------------------------------------------------------------------
 struct MlpPlan {
-  int L, M, B, rule;
-  int64_t R;                      // M * B rows per step
+  int L, M, B, Bp, rule, RT;
+  int64_t Rp;                     // M * Bp padded rows per step
   int64_t total_rows;             // rows of X
   int d[CADA_MAX_LAYERS + 1];
-  int64_t offW[CADA_MAX_LAYERS], offb[CADA_MAX_LAYERS];   // offsets into theta
-  int64_t ldw[CADA_MAX_LAYERS];                           // P8(d_l): ld of the bf16 weights of layer l
-  int64_t wb_off[CADA_MAX_LAYERS], wb_total;              // offsets into the bf16 weight copy
-  int64_t lda[CADA_MAX_LAYERS + 1];                       // P8(d_l): ld of bf16 activations of width d_l
-  int nW;                                                 // 1 (CADA1) or M (CADA2) delta-weight copies
-  bf16_t *Xb, *Xl; int64_t ldx;          // features: hi and lo parts
+  int64_t offW[CADA_MAX_LAYERS], offb[CADA_MAX_LAYERS];   // offsets into theta, index l-1
+  int64_t lda[CADA_MAX_LAYERS + 1];                       // P8(d_l)
+  int64_t wt_off[CADA_MAX_LAYERS], wt_total;              // W_l^T [d_l][P8(d_{l-1})], index l-1
+  int64_t wn_off[CADA_MAX_LAYERS], wn_total;              // W_l   [d_{l-1}][P8(d_l)], l >= 2
+  int lhs_w_slot[CADA_MAX_LAYERS], lhs_b_slot[CADA_MAX_LAYERS];
+  int nW;                                                 // delta-weight copies: 1 (CADA1) or M (CADA2)
+  bf16_t *Xh, *Xl; int64_t ldx;
+  bf16_t *XTh, *XTl;                                      // gathered minibatch, transposed [d0][Rp]
   int64_t *grow;
-  bf16_t *Wb, *Wl, *dWb;                 // weights hi, lo; delta weights
-  float *Z[CADA_MAX_LAYERS], *dZ[CADA_MAX_LAYERS];         // [R][d_l], index l-1
-  bf16_t *A[CADA_MAX_LAYERS], *Al[CADA_MAX_LAYERS], *dA[CADA_MAX_LAYERS], *Aref[CADA_MAX_LAYERS];   // hidden l = 1..L-1, index l
-  bf16_t *G[CADA_MAX_LAYERS], *Gl[CADA_MAX_LAYERS], *dG[CADA_MAX_LAYERS], *Gref[CADA_MAX_LAYERS];   // index l-1; (G, Gl) = hi, lo
-  float *GA[CADA_MAX_LAYERS], *dGA[CADA_MAX_LAYERS];       // [R][d_l], hidden l, index l
-  float *innov;                                            // CADA2: [M][p]
+  bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;
+  bf16_t *Ah[CADA_MAX_LAYERS], *Al[CADA_MAX_LAYERS], *dA[CADA_MAX_LAYERS], *Aref[CADA_MAX_LAYERS];   // hidden l, row-major
+  bf16_t *AhT[CADA_MAX_LAYERS], *AlT[CADA_MAX_LAYERS], *dAT[CADA_MAX_LAYERS];                        // hidden l, transposed
+  bf16_t *Gh[CADA_MAX_LAYERS + 1], *Gl[CADA_MAX_LAYERS + 1], *dG[CADA_MAX_LAYERS + 1], *Gref[CADA_MAX_LAYERS + 1];       // layer l >= 2, row-major
+  bf16_t *GhT[CADA_MAX_LAYERS + 1], *GlT[CADA_MAX_LAYERS + 1], *dGT[CADA_MAX_LAYERS + 1], *GrefT[CADA_MAX_LAYERS + 1];   // layer l, transposed
+  float *ZL, *dZL;                                        // logits [Rp][C]
+  float *dbpart, *ddbpart;                                // [M][RT][max hidden width]
 };
 
 namespace {
@@ -228,46 +409,68 @@ struct Carve {
   }
 };
 
+int tiles128(int x) { return (x + 127) / 128; }
+
 void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.L = cfg->n_layers; P.M = cfg->M; P.B = cfg->B; P.rule = cfg->rule;
-  P.R = (int64_t)cfg->M * cfg->B;
+  P.Bp = (int)P8(cfg->B);
+  P.RT = tiles128(cfg->B);
+  P.Rp = (int64_t)cfg->M * P.Bp;
   P.total_rows = total_rows;
-  int64_t o = 0, wo = 0;
   for (int l = 0; l <= P.L; ++l) { P.d[l] = cfg->layer_dims[l]; P.lda[l] = P8(P.d[l]); }
-  for (int l = 0; l < P.L; ++l) {
-    P.offW[l] = o; o += (int64_t)P.d[l] * P.d[l + 1];
-    P.offb[l] = o; o += P.d[l + 1];
-    P.ldw[l] = P8(P.d[l + 1]);
-    P.wb_off[l] = wo; wo += (int64_t)P.d[l] * P.ldw[l];
+  int64_t o = 0, wt = 0, wn = 0;
+  int slot = 0, maxh = 1;
+  for (int l = 1; l <= P.L; ++l) {
+    P.offW[l - 1] = o; o += (int64_t)P.d[l - 1] * P.d[l];
+    P.offb[l - 1] = o; o += P.d[l];
+    P.wt_off[l - 1] = wt; wt += (int64_t)P.d[l] * P8(P.d[l - 1]);
+    P.wn_off[l - 1] = wn; if (l >= 2) wn += (int64_t)P.d[l - 1] * P8(P.d[l]);
+    P.lhs_w_slot[l - 1] = slot; slot += tiles128(P.d[l - 1]) * tiles128(P.d[l]);
+    P.lhs_b_slot[l - 1] = slot; slot += (P.d[l] + 255) / 256;
+    if (l < P.L && P.d[l] > maxh) maxh = P.d[l];
   }
-  P.wb_total = wo;
+  P.wt_total = wt; P.wn_total = wn;
   P.nW = (cfg->rule == CADA_RULE_CADA2) ? cfg->M : 1;
   P.ldx = P8(P.d[0]);
-  P.Xb = w.take<bf16_t>((size_t)total_rows * P.ldx);
+  const size_t Rp = (size_t)P.Rp;
+  P.Xh = w.take<bf16_t>((size_t)total_rows * P.ldx);
   P.Xl = w.take<bf16_t>((size_t)total_rows * P.ldx);
-  P.grow = w.take<int64_t>((size_t)P.R);
-  P.Wb = w.take<bf16_t>((size_t)P.wb_total);
-  P.Wl = w.take<bf16_t>((size_t)P.wb_total);
-  P.dWb = w.take<bf16_t>((size_t)P.wb_total * P.nW);
+  P.XTh = w.take<bf16_t>((size_t)P.d[0] * Rp);
+  P.XTl = w.take<bf16_t>((size_t)P.d[0] * Rp);
+  P.grow = w.take<int64_t>(Rp);
+  P.WTh = w.take<bf16_t>((size_t)wt); P.WTl = w.take<bf16_t>((size_t)wt); P.dWT = w.take<bf16_t>((size_t)wt * P.nW);
+  P.WNh = w.take<bf16_t>((size_t)wn + 8); P.WNl = w.take<bf16_t>((size_t)wn + 8); P.dWN = w.take<bf16_t>((size_t)wn * P.nW + 8);
+  for (int l = 1; l < P.L; ++l) {
+    P.Ah[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Al[l] = w.take<bf16_t>(Rp * P.lda[l]);
+    P.dA[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Aref[l] = w.take<bf16_t>(Rp * P.lda[l]);
+    P.AhT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp); P.AlT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
+    P.dAT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
+  }
   for (int l = 1; l <= P.L; ++l) {
-    P.Z[l - 1] = w.take<float>((size_t)P.R * P.d[l]);
-    P.dZ[l - 1] = w.take<float>((size_t)P.R * P.d[l]);
-    P.G[l - 1] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-    P.Gl[l - 1] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-    P.dG[l - 1] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-    P.Gref[l - 1] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-    if (l < P.L) {
-      P.A[l] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-      P.Al[l] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-      P.dA[l] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-      P.Aref[l] = w.take<bf16_t>((size_t)P.R * P.lda[l]);
-      P.GA[l] = w.take<float>((size_t)P.R * P.d[l]);
-      P.dGA[l] = w.take<float>((size_t)P.R * P.d[l]);
+    P.GhT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp); P.GlT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
+    P.dGT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp); P.GrefT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
+    if (l >= 2) {
+      P.Gh[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Gl[l] = w.take<bf16_t>(Rp * P.lda[l]);
+      P.dG[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Gref[l] = w.take<bf16_t>(Rp * P.lda[l]);
+    } else {
+      P.Gh[l] = P.Gl[l] = P.dG[l] = P.Gref[l] = nullptr;
     }
   }
-  P.innov = (cfg->rule == CADA_RULE_CADA2) ? w.take<float>((size_t)cfg->M * (size_t)cfg->p) : nullptr;
+  P.ZL = w.take<float>(Rp * P.d[P.L]);
+  P.dZL = w.take<float>(Rp * P.d[P.L]);
+  P.dbpart = w.take<float>((size_t)cfg->M * P.RT * maxh);
+  P.ddbpart = w.take<float>((size_t)cfg->M * P.RT * maxh);
 }
 }  // namespace
+
+// Number of partial sums of the left-hand side per worker (one per weight-gradient tile and
+// per 256 biases).
+int mlp_lhs_slots(const cada_config *cfg) {
+  int slot = 0;
+  for (int l = 1; l <= cfg->n_layers; ++l)
+    slot += tiles128(cfg->layer_dims[l - 1]) * tiles128(cfg->layer_dims[l]) + (cfg->layer_dims[l] + 255) / 256;
+  return slot;
+}
 
 size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows) {
   if (cfg->gemm_dtype != CADA_GEMM_BF16) { set_error("the MLP model computes its contractions in bf16 (gemm_dtype must be CADA_GEMM_BF16)"); return 0; }
@@ -287,9 +490,8 @@ int mlp_plan(Ctx *c, const cada_config *cfg, char *base, size_t *offset, int64_t
   layout(*P, cfg, total_rows, w);
   *offset = w.off;
   c->mlp = P;
-  c->n_phases = 4;
-  c->phase_names[0] = "mlp_gradients"; c->phase_names[1] = "mlp_lhs";
-  c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
+  c->n_phases = 3;
+  c->phase_names[0] = "mlp_gradients"; c->phase_names[1] = "rule"; c->phase_names[2] = "server_update";
   return CADA_OK;
 }
 
@@ -299,116 +501,122 @@ void mlp_free(Ctx *c) {
 }
 
 // ------------------------------------------------------------------------------------------
-// elementwise kernels
+// small kernels
 // ------------------------------------------------------------------------------------------
-// float32 features -> bf16 copy with padded leading dimension (once, at init)
-__global__ void k_x_to_bf16(const float *X, bf16_t *Xb, bf16_t *Xl, int64_t rows, int d0, int64_t ldx) {
+// float32 features -> bf16 hi/lo copies with padded leading dimension (once, at init)
+__global__ void k_x_to_bf16(const float *X, bf16_t *Xh, bf16_t *Xl, int64_t rows, int d0, int64_t ldx) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= rows * ldx) return;
   const int64_t r = i / ldx; const int c = (int)(i % ldx);
   const float x = c < d0 ? X[r * d0 + c] : 0.f;
   const bf16_t hi = f2bf(x);
-  Xb[i] = hi;
+  Xh[i] = hi;
   Xl[i] = f2bf(x - bf2f(hi));
 }
 
-// grow[m*B + b] = global row of worker m's b-th minibatch sample
-__global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow) {
+// grow[m*Bp + b] = global row of worker m's b-th minibatch sample (b < B)
+__global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow, int Bp) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)s.M * s.B) return;
-  const int m = (int)(i / s.B);
+  const int m = (int)(i / s.B), b = (int)(i % s.B);
   const int64_t n = s.row_off[m + 1] - s.row_off[m];
   int64_t r = idx[i];
   if (r < 0 || r >= n) { atomicOr(s.err, 1u); r = r < 0 ? 0 : n - 1; }
-  grow[i] = s.row_off[m] + r;
+  grow[(int64_t)m * Bp + b] = s.row_off[m] + r;
+}
+
+// Transposed copy of the gathered minibatch: XT[c][m*Bp + b] = X[grow[m*Bp + b]][c].
+// grid (ceil(d0/64), ceil(B/64), M), block 256; 64 x 64 tile through LDS.
+__global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, const bf16_t *Xl, int64_t ldx, const int64_t *grow,
+                                                             bf16_t *XTh, bf16_t *XTl, int d0, int B, int Bp, int64_t Rp) {
+  __shared__ bf16_t th[64][66], tl[64][66];
+  const int m = blockIdx.z, c0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4) {
+    const int b = b0 + r, c = c0 + tx;
+    bf16_t vh = 0, vl = 0;
+    if (b < B && c < d0) {
+      const int64_t src = grow[(int64_t)m * Bp + b] * ldx + c;
+      vh = Xh[src]; vl = Xl[src];
+    }
+    th[r][tx] = vh; tl[r][tx] = vl;
+  }
+  __syncthreads();
+  for (int r = ty; r < 64; r += 4) {
+    const int c = c0 + r, b = b0 + tx;
+    if (c < d0 && b < B) {
+      const int64_t o = (int64_t)c * Rp + (int64_t)m * Bp + b;
+      XTh[o] = th[tx][r]; XTl[o] = tl[tx][r];
+    }
+  }
 }
 
 struct PrepArgs {
   DevState s;
-  bf16_t *Wb, *Wl, *dWb;
-  int64_t offW, wb_off, wb_total;
+  bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;   // already offset to this layer
+  int64_t offW, wt_total, wn_total;
   int din, dout;
-  int64_t ldw;
-  int nW;
+  int64_t ldt, ldn;      // P8(din), P8(dout)
+  int want_n;            // also write the [in][out] orientation (layers >= 2)
 };
 
-// bf16 copies of one layer's weights and of its difference to each reference point.
-// grid (ceil(din*dout/256), nW + 1): y = 0 -> W, y = 1 + m -> d_m = theta - theta_ref(m)
-__global__ void k_prep_weights(const PrepArgs a) {
+// bf16 copies of one layer's weights (hi, lo) and of its difference to each reference point,
+// in the orientation(s) the contractions read.  grid (ceil(dout/64), ceil(din/64), nW + 1):
+// z = 0 -> W, z = 1 + m -> theta - theta_ref(m).  64 x 64 tile through LDS.
+__global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
   const DevState &s = a.s;
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= (int64_t)a.din * a.dout) return;
-  const int i = (int)(e / a.dout), o = (int)(e % a.dout);
-  const int64_t src = a.offW + e, dst = a.wb_off + (int64_t)i * a.ldw + o;
-  if (blockIdx.y == 0) {
-    const float wv = s.theta[src];
-    const bf16_t hi = f2bf(wv);
-    a.Wb[dst] = hi;
-    a.Wl[dst] = f2bf(wv - bf2f(hi));
-  } else {
-    const int m = blockIdx.y - 1;
-    const RefPtr ref = theta_ref(s, m, s.k);
-    const float d = (s.theta[src] - ref.hi[src]) + (s.theta_lo[src] - ref.lo[src]);
-    a.dWb[(int64_t)m * a.wb_total + dst] = f2bf(d);
-  }
-}
-
-struct FwdArgs {
-  DevState s;
-  const float *Z, *dZ;         // [R][d]
-  bf16_t *A, *Al, *dA, *Aref;  // [R][lda]; (A, Al) = hi and lo parts of the activation
-  int64_t offb;                // bias offset in theta
-  int d; int64_t lda;
-};
-
-// hidden layer: bias, ReLU at theta and at the reference point, activation difference
-__global__ void k_hidden_fwd(const FwdArgs a) {
-  const DevState &s = a.s;
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t R = (int64_t)s.M * s.B;
-  if (e >= R * a.d) return;
-  const int64_t r = e / a.d; const int c = (int)(e % a.d);
-  const int m = (int)(r / s.B);
+  __shared__ float tile[64][65];
+  const int o0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const bool is_w = blockIdx.z == 0;
+  const int m = is_w ? 0 : blockIdx.z - 1;
   const RefPtr ref = theta_ref(s, m, s.k);
-  const int64_t bi = a.offb + c;
-  const float b = s.theta[bi];
-  const float db = (b - ref.hi[bi]) + (s.theta_lo[bi] - ref.lo[bi]);
-  const float z = a.Z[e] + b;
-  const float dz = a.dZ[e] + db;
-  const float act = fmaxf(z, 0.f), aref = fmaxf(z - dz, 0.f);
-  const int64_t o = r * a.lda + c;
-  const bf16_t hi = f2bf(act);
-  a.A[o] = hi;
-  a.Al[o] = f2bf(act - bf2f(hi));
-  a.Aref[o] = f2bf(aref);
-  a.dA[o] = f2bf(act - aref);
+  for (int r = ty; r < 64; r += 4) {
+    const int i = i0 + r, o = o0 + tx;
+    float v = 0.f;
+    if (i < a.din && o < a.dout) {
+      const int64_t src = a.offW + (int64_t)i * a.dout + o;
+      v = is_w ? s.theta[src] : delta_theta(s, ref, src);
+      if (a.want_n) {
+        const int64_t dn = (int64_t)i * a.ldn + o;
+        if (is_w) { const bf16_t hi = f2bf(v); a.WNh[dn] = hi; a.WNl[dn] = f2bf(v - bf2f(hi)); }
+        else a.dWN[(int64_t)m * a.wn_total + dn] = f2bf(v);
+      }
+    }
+    tile[r][tx] = v;
+  }
+  __syncthreads();
+  for (int r = ty; r < 64; r += 4) {
+    const int o = o0 + r, i = i0 + tx;
+    if (o < a.dout && i < a.din) {
+      const float v = tile[tx][r];
+      const int64_t dt = (int64_t)o * a.ldt + i;
+      if (is_w) { const bf16_t hi = f2bf(v); a.WTh[dt] = hi; a.WTl[dt] = f2bf(v - bf2f(hi)); }
+      else a.dWT[(int64_t)m * a.wt_total + dt] = f2bf(v);
+    }
+  }
 }
 
 struct LossArgs {
   DevState s;
-  const float *Z, *dZ;          // logits without bias [R][C]
-  bf16_t *G, *Gl, *dG, *Gref;   // [R][ldg]; (G, Gl) = hi and lo parts
+  const float *Z, *dZ;            // logits without bias [Rp][C]
+  bf16_t *Gh, *Gl, *dG, *Gref;    // row-major [Rp][ldg]
+  bf16_t *GhT, *GlT, *dGT, *GrefT;   // transposed [C][Rp]
   const int64_t *grow;
-  int64_t offb;
-  int C; int64_t ldg;
-  float *innov;                 // CADA2 scratch [M][p] or nullptr (CADA1 writes dtl)
+  int64_t offb, Rp;
+  int C, Bp; int64_t ldg;
+  int lhs_slot;
 };
 
-__device__ __forceinline__ float *fresh_grad(const DevState &s, int m) {
-  return s.gbuf + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.p;
-}
-__device__ __forceinline__ float *fresh_innov(const DevState &s, float *innov, int m) {
-  if (s.rule == CADA_RULE_CADA1) return s.dtl + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.p;
-  return innov + (int64_t)m * s.p;
-}
-
 // softmax cross-entropy: G = (P - onehot)/B, dG = (P - Pref)/B with
-// P_i - Pref_i = P_i (sum_j P_j expm1(-dz_j) - expm1(-dz_i)) / (1 + sum_j P_j expm1(-dz_j)).
-// One block per worker; also the bias gradient of the last layer and its innovation.
+// P_i - Pref_i = P_i (S - expm1(-dz_i)) / (1 + S),  S = sum_j P_j expm1(-dz_j).
+// One block per worker; also the last layer's bias gradient, its innovation and the
+// innovation's contribution to the rule's left-hand side.
 __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
   const DevState &s = a.s;
   constexpr int MAXC = 32;
   __shared__ float red[kBlock];
+  __shared__ float sqs;
   const int m = blockIdx.x;
   const RefPtr ref = theta_ref(s, m, s.k);
   const int32_t *yv = static_cast<const int32_t *>(s.y);
@@ -417,17 +625,15 @@ __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) { sumG[c] = 0.f; sumD[c] = 0.f; }
   for (int b = threadIdx.x; b < s.B; b += kBlock) {
-    const int64_t r = (int64_t)m * s.B + b;
+    const int64_t r = (int64_t)m * a.Bp + b;
     float z[MAXC], dz[MAXC];
     float zmax = -INFINITY;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
       if (c < a.C) {
         const int64_t bi = a.offb + c;
-        const float bb = s.theta[bi];
-        const float db = (bb - ref.hi[bi]) + (s.theta_lo[bi] - ref.lo[bi]);
-        z[c] = a.Z[r * a.C + c] + bb;
-        dz[c] = a.dZ[r * a.C + c] + db;
+        z[c] = a.Z[r * a.C + c] + s.theta[bi];
+        dz[c] = a.dZ[r * a.C + c] + delta_theta(s, ref, bi);
         zmax = fmaxf(zmax, z[c]);
       }
     }
@@ -443,19 +649,21 @@ __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
       if (c < a.C) {
         const float gl = (z[c] - (c == label ? 1.f : 0.f)) * invB;
         const float dg = z[c] * (S - dz[c]) / (1.0f + S) * invB;
-        const int64_t o = r * a.ldg + c;
-        const bf16_t hi = f2bf(gl);
-        a.G[o] = hi;
-        a.Gl[o] = f2bf(gl - bf2f(hi));
-        a.dG[o] = f2bf(dg);
-        a.Gref[o] = f2bf(gl - dg);
+        const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
+        const int64_t o = r * a.ldg + c, ot = (int64_t)c * a.Rp + r;
+        a.Gh[o] = hi; a.Gl[o] = lo; a.dG[o] = bd; a.Gref[o] = br;
+        a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
         sumG[c] += gl;
         sumD[c] += dg;
       }
     }
   }
   float *gf = fresh_grad(s, m) + a.offb;
-  float *iv = fresh_innov(s, a.innov, m) + a.offb;
+  const bool cada1 = s.rule == CADA_RULE_CADA1;
+  const int cur = s.sel[m];
+  float *ivf = cada1 ? s.dtl + ((int64_t)(1 - cur) * s.M + m) * s.p + a.offb : nullptr;
+  const float *ivs = cada1 ? s.dtl + ((int64_t)cur * s.M + m) * s.p + a.offb : nullptr;
+  if (threadIdx.x == 0) sqs = 0.f;
   for (int c = 0; c < a.C; ++c) {
     float vg = 0.f, vd = 0.f;
 #pragma unroll
@@ -469,75 +677,40 @@ __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
     red[threadIdx.x] = vd;
     __syncthreads();
     for (int o = kBlock / 2; o > 0; o >>= 1) { if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o]; __syncthreads(); }
-    if (threadIdx.x == 0) iv[c] = red[0];
-  }
-}
-
-struct BwdArgs {
-  DevState s;
-  const float *GA, *dGA;         // [R][d]: gradient w.r.t. the activations and its difference
-  const bf16_t *A, *Aref;        // [R][lda] activations (their sign is the ReLU mask)
-  bf16_t *G, *Gl, *dG, *Gref;    // [R][lda]
-  int64_t offb;
-  int d; int64_t lda;
-  float *innov;
-};
-
-// hidden layer backward through the two ReLUs; bias gradient and its innovation.
-// grid (ceil(d/64), M), block 256 = 64 columns x 4 row lanes
-__global__ __launch_bounds__(kBlock) void k_hidden_bwd(const BwdArgs a) {
-  const DevState &s = a.s;
-  __shared__ float redg[4][64], redd[4][64];
-  const int m = blockIdx.y;
-  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl;
-  float sg = 0.f, sd = 0.f;
-  if (c < a.d) {
-    for (int b = rl; b < s.B; b += 4) {
-      const int64_t r = (int64_t)m * s.B + b;
-      const int64_t o = r * a.lda + c;
-      const float ga = a.GA[r * a.d + c], dga = a.dGA[r * a.d + c];
-      const bool on = bf2f(a.A[o]) > 0.f, onref = bf2f(a.Aref[o]) > 0.f;
-      const float gl = on ? ga : 0.f;
-      const float gref = onref ? (ga - dga) : 0.f;
-      const float dg = gl - gref;
-      const bf16_t hi = f2bf(gl);
-      a.G[o] = hi;
-      a.Gl[o] = f2bf(gl - bf2f(hi));
-      a.Gref[o] = f2bf(gref);
-      a.dG[o] = f2bf(dg);
-      sg += gl;
-      sd += dg;
+    if (threadIdx.x == 0) {
+      float iv = red[0];
+      if (cada1) { ivf[c] = iv; iv -= ivs[c]; }
+      sqs = fmaf(iv, iv, sqs);
     }
   }
-  redg[rl][cl] = sg;
-  redd[rl][cl] = sd;
   __syncthreads();
-  if (rl == 0 && c < a.d) {
-    fresh_grad(s, m)[a.offb + c] = (redg[0][cl] + redg[1][cl]) + (redg[2][cl] + redg[3][cl]);
-    fresh_innov(s, a.innov, m)[a.offb + c] = (redd[0][cl] + redd[1][cl]) + (redd[2][cl] + redd[3][cl]);
-  }
+  if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + a.lhs_slot] = sqs;
 }
 
-// Left-hand side partial sums: CADA2 |innov_m|^2, CADA1 |innov_m - stored innovation_m|^2.
-// grid (n_lhs_part, M)
-__global__ __launch_bounds__(kBlock) void k_mlp_lhs(const DevState s, const float *innov) {
+// Hidden-layer bias gradient and its innovation from the per-tile partial sums of k_mm5<EPI_DA>.
+// grid (ceil(d/256), M)
+__global__ __launch_bounds__(kBlock) void k_bias_finish(const DevState s, const float *dbpart, const float *ddbpart, int RT, int d,
+                                                        int64_t offb, int lhs_slot) {
   __shared__ float red[4];
   const int m = blockIdx.y;
-  const int64_t per = (s.p + s.n_lhs_part - 1) / s.n_lhs_part;
-  const int64_t e0 = (int64_t)blockIdx.x * per, e1 = min(s.p, e0 + per);
+  const int c = blockIdx.x * kBlock + threadIdx.x;
   float sq = 0.f;
-  if (s.rule == CADA_RULE_CADA1) {
-    const int cur = s.sel[m];
-    const float *fr = s.dtl + ((int64_t)(1 - cur) * s.M + m) * s.p;
-    const float *st = s.dtl + ((int64_t)cur * s.M + m) * s.p;
-    for (int64_t e = e0 + threadIdx.x; e < e1; e += kBlock) { const float d = fr[e] - st[e]; sq = fmaf(d, d, sq); }
-  } else {
-    const float *fr = innov + (int64_t)m * s.p;
-    for (int64_t e = e0 + threadIdx.x; e < e1; e += kBlock) { const float d = fr[e]; sq = fmaf(d, d, sq); }
+  if (c < d) {
+    float gsum = 0.f, dsum = 0.f;
+    for (int rt = 0; rt < RT; ++rt) {
+      gsum += dbpart[((int64_t)m * RT + rt) * d + c];
+      dsum += ddbpart[((int64_t)m * RT + rt) * d + c];
+    }
+    fresh_grad(s, m)[offb + c] = gsum;
+    if (s.rule == CADA_RULE_CADA1) {
+      const int cur = s.sel[m];
+      s.dtl[((int64_t)(1 - cur) * s.M + m) * s.p + offb + c] = dsum;
+      dsum -= s.dtl[((int64_t)cur * s.M + m) * s.p + offb + c];
+    }
+    sq = dsum * dsum;
   }
   const float tot = block_sum(sq, red);
-  if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + blockIdx.x] = tot;
+  if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + lhs_slot + blockIdx.x] = tot;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -545,25 +718,37 @@ __global__ __launch_bounds__(kBlock) void k_mlp_lhs(const DevState s, const floa
 // ------------------------------------------------------------------------------------------
 namespace {
 
-Operand op(const bf16_t *p, int64_t ld, int64_t bstride, int kmajor, const int64_t *gather = nullptr, int64_t gstride = 0) {
-  Operand o;
-  o.ptr = p; o.ld = ld; o.batch_stride = bstride; o.gather = gather; o.gather_stride = gstride; o.kmajor = kmajor;
-  return o;
+void side_add(Side &sd, const bf16_t *p, int64_t ld, int64_t bstride) {
+  sd.ptr[sd.n] = p; sd.ld[sd.n] = ld; sd.bstride[sd.n] = bstride; sd.n += 1;
 }
 
-void launch_gemm(Ctx *c, GemmArgs &g, int batches) {
-  const dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, batches);
-  hipLaunchKernelGGL(k_gemm, grid, dim3(kBlock), 0, c->stream, g);
+template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
+  const dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, workers);
+  hipLaunchKernelGGL(k_mm5<EPI>, grid, dim3(kBlock), kMm5Lds, c->stream, g);
+}
+
+Mm5Args blank(const DevState &s, const MlpPlan &P) {
+  Mm5Args g{};
+  g.s = s; g.Bp = P.Bp; g.Rp = P.Rp;
+  g.a_h = g.a_l = g.a_d = g.a_r = -1;
+  g.b_h = g.b_l = g.b_x = g.b_d = -1;
+  return g;
 }
 
 }  // namespace
 
-// One-time work at init: the bf16 copy of the features.
+// One-time work at init: the bf16 copies of the features and the kernels' LDS allowance.
 int mlp_init_state(Ctx *c, const float *) {
   MlpPlan &P = *static_cast<MlpPlan *>(c->mlp);
+  hipError_t e = hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_FWD_HIDDEN>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_STORE2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_DW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_DA>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
+  if (e != hipSuccess) { set_error("hipFuncSetAttribute(LDS size) failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
   const int64_t n = P.total_rows * P.ldx;
-  hipLaunchKernelGGL(k_x_to_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->s.X, P.Xb, P.Xl, P.total_rows, P.d[0], P.ldx);
-  const hipError_t e = hipGetLastError();
+  hipLaunchKernelGGL(k_x_to_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->s.X, P.Xh, P.Xl, P.total_rows, P.d[0], P.ldx);
+  e = hipGetLastError();
   if (e != hipSuccess) { set_error("feature conversion launch failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
   return CADA_OK;
 }
@@ -573,121 +758,105 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
   DevState s = c->s;
   s.k = c->k;
   hipStream_t st = c->stream;
-  const int L = P.L, M = P.M, B = P.B;
-  const int64_t R = P.R;
+  const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
+  const int64_t Rp = P.Rp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
-  const int64_t dw_stride = per_worker ? P.wb_total : 0;   // batch stride of the delta weights
-  float *innov = P.innov;
+  const int64_t dwt_stride = per_worker ? P.wt_total : 0, dwn_stride = per_worker ? P.wn_total : 0;
 
   prof_mark(c);
-  hipLaunchKernelGGL(k_rows, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, s, idx, P.grow);
-  for (int l = 0; l < L; ++l) {
+  hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp);
+  hipLaunchKernelGGL(k_gather_transpose, dim3((P.d[0] + 63) / 64, (B + 63) / 64, M), dim3(kBlock), 0, st,
+                     P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.d[0], B, Bp, Rp);
+  for (int l = 1; l <= L; ++l) {
     PrepArgs pa;
-    pa.s = s; pa.Wb = P.Wb; pa.Wl = P.Wl; pa.dWb = P.dWb; pa.offW = P.offW[l]; pa.wb_off = P.wb_off[l]; pa.wb_total = P.wb_total;
-    pa.din = P.d[l]; pa.dout = P.d[l + 1]; pa.ldw = P.ldw[l]; pa.nW = P.nW;
-    const int64_t n = (int64_t)pa.din * pa.dout;
-    hipLaunchKernelGGL(k_prep_weights, dim3((unsigned)((n + 255) / 256), P.nW + 1), dim3(256), 0, st, pa);
+    pa.s = s;
+    pa.WTh = P.WTh + P.wt_off[l - 1]; pa.WTl = P.WTl + P.wt_off[l - 1]; pa.dWT = P.dWT + P.wt_off[l - 1];
+    pa.WNh = P.WNh + P.wn_off[l - 1]; pa.WNl = P.WNl + P.wn_off[l - 1]; pa.dWN = P.dWN + P.wn_off[l - 1];
+    pa.offW = P.offW[l - 1]; pa.wt_total = P.wt_total; pa.wn_total = P.wn_total;
+    pa.din = P.d[l - 1]; pa.dout = P.d[l]; pa.ldt = P8(P.d[l - 1]); pa.ldn = P8(P.d[l]); pa.want_n = l >= 2;
+    hipLaunchKernelGGL(k_prep_weights, dim3((pa.dout + 63) / 64, (pa.din + 63) / 64, P.nW + 1), dim3(kBlock), 0, st, pa);
   }
 
-  // ---- forward.  All GEMMs are batched over the workers: rows [m*B, (m+1)*B).
+  // ---- forward: worker m owns padded rows [m*Bp, m*Bp + B)
   for (int l = 1; l <= L; ++l) {
     const int din = P.d[l - 1], dout = P.d[l];
-    const bf16_t *W = P.Wb + P.wb_off[l - 1];
-    const bf16_t *dW = P.dWb + P.wb_off[l - 1];
-    GemmArgs g{};
-    g.M = B; g.N = dout; g.ldc = dout; g.c_batch_stride = (int64_t)B * dout; g.sel = nullptr;
-    // Z_l = A_{l-1} W_l with split operands: hi*hi + hi*lo + lo*hi
-    const bf16_t *Wlo = P.Wl + P.wb_off[l - 1];
-    g.npairs = 3; g.K[0] = g.K[1] = g.K[2] = din; g.C = P.Z[l - 1];
-    const Operand ahi = (l == 1) ? op(P.Xb, P.ldx, 0, 1, P.grow, B) : op(P.A[l - 1], P.lda[l - 1], (int64_t)B * P.lda[l - 1], 1);
-    const Operand alo = (l == 1) ? op(P.Xl, P.ldx, 0, 1, P.grow, B) : op(P.Al[l - 1], P.lda[l - 1], (int64_t)B * P.lda[l - 1], 1);
-    g.A[0] = alo; g.B[0] = op(W, P.ldw[l - 1], 0, 0);          // small terms first
-    g.A[1] = ahi; g.B[1] = op(Wlo, P.ldw[l - 1], 0, 0);
-    g.A[2] = ahi; g.B[2] = op(W, P.ldw[l - 1], 0, 0);
-    launch_gemm(c, g, M);
-    // dZ_l = dA_{l-1} W_l + Aref_{l-1} dW_l   (layer 1: A_0 dW_1)
-    g.C = P.dZ[l - 1];
+    Mm5Args g = blank(s, P);
+    g.M = B; g.N = dout; g.K = din;
     if (l == 1) {
-      g.npairs = 1; g.K[0] = din;
-      g.A[0] = op(P.Xb, P.ldx, 0, 1, P.grow, B);
-      g.B[0] = op(dW, P.ldw[0], dw_stride, 0);
+      side_add(g.A, P.Xh, P.ldx, 0); side_add(g.A, P.Xl, P.ldx, 0);
+      g.gatherA = P.grow; g.gstride = Bp;
+      g.a_h = 0; g.a_l = 1; g.a_r = 0;                    // dZ_1 = A_0 dW_1
     } else {
-      g.npairs = 2; g.K[0] = din; g.K[1] = din;
-      g.A[0] = op(P.dA[l - 1], P.lda[l - 1], (int64_t)B * P.lda[l - 1], 1);
-      g.B[0] = op(W, P.ldw[l - 1], 0, 0);
-      g.A[1] = op(P.Aref[l - 1], P.lda[l - 1], (int64_t)B * P.lda[l - 1], 1);
-      g.B[1] = op(dW, P.ldw[l - 1], dw_stride, 0);
+      const int64_t bs = (int64_t)Bp * P.lda[l - 1];
+      side_add(g.A, P.Ah[l - 1], P.lda[l - 1], bs); side_add(g.A, P.Al[l - 1], P.lda[l - 1], bs);
+      side_add(g.A, P.dA[l - 1], P.lda[l - 1], bs); side_add(g.A, P.Aref[l - 1], P.lda[l - 1], bs);
+      g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 3;         // dZ_l = dA W + Aref dW
     }
-    launch_gemm(c, g, M);
+    const int64_t ldt = P8(din);
+    side_add(g.B, P.WTh + P.wt_off[l - 1], ldt, 0); side_add(g.B, P.WTl + P.wt_off[l - 1], ldt, 0);
+    side_add(g.B, P.dWT + P.wt_off[l - 1], ldt, dwt_stride);
+    g.b_h = 0; g.b_l = 1; g.b_x = 0; g.b_d = 2;
     if (l < L) {
-      FwdArgs fa;
-      fa.s = s; fa.Z = P.Z[l - 1]; fa.dZ = P.dZ[l - 1]; fa.A = P.A[l]; fa.Al = P.Al[l]; fa.dA = P.dA[l]; fa.Aref = P.Aref[l];
-      fa.offb = P.offb[l - 1]; fa.d = dout; fa.lda = P.lda[l];
-      const int64_t n = R * dout;
-      hipLaunchKernelGGL(k_hidden_fwd, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, fa);
+      g.offb = P.offb[l - 1]; g.ldo = P.lda[l];
+      g.o_h = P.Ah[l]; g.o_l = P.Al[l]; g.o_d = P.dA[l]; g.o_r = P.Aref[l];
+      g.t_h = P.AhT[l]; g.t_l = P.AlT[l]; g.t_d = P.dAT[l]; g.t_r = nullptr;
+      launch_mm5<EPI_FWD_HIDDEN>(c, g, M);
+    } else {
+      g.c1 = P.ZL; g.c2 = P.dZL;
+      launch_mm5<EPI_STORE2>(c, g, M);
     }
   }
   {
     LossArgs la;
-    la.s = s; la.Z = P.Z[L - 1]; la.dZ = P.dZ[L - 1]; la.G = P.G[L - 1]; la.Gl = P.Gl[L - 1]; la.dG = P.dG[L - 1]; la.Gref = P.Gref[L - 1];
-    la.grow = P.grow; la.offb = P.offb[L - 1]; la.C = P.d[L]; la.ldg = P.lda[L]; la.innov = innov;
+    la.s = s; la.Z = P.ZL; la.dZ = P.dZL;
+    la.Gh = P.Gh[L]; la.Gl = P.Gl[L]; la.dG = P.dG[L]; la.Gref = P.Gref[L];
+    la.GhT = P.GhT[L]; la.GlT = P.GlT[L]; la.dGT = P.dGT[L]; la.GrefT = P.GrefT[L];
+    la.grow = P.grow; la.offb = P.offb[L - 1]; la.Rp = Rp; la.C = P.d[L]; la.Bp = Bp; la.ldg = P.lda[L];
+    la.lhs_slot = P.lhs_b_slot[L - 1];
     hipLaunchKernelGGL(k_loss, dim3(M), dim3(kBlock), 0, st, la);
   }
 
   // ---- backward
-  const int64_t mp = (int64_t)s.M * s.p;
   for (int l = L; l >= 1; --l) {
     const int din = P.d[l - 1], dout = P.d[l];
-    const bf16_t *W = P.Wb + P.wb_off[l - 1];
-    const bf16_t *dW = P.dWb + P.wb_off[l - 1];
-    const int64_t gstride = (int64_t)B * P.lda[l];
-    // weight gradient of worker m: A_{l-1}[m]^T G_l[m] (split operands) -> fresh row of the gradient store
-    GemmArgs g{};
-    g.M = din; g.N = dout; g.ldc = dout; g.npairs = 3; g.K[0] = g.K[1] = g.K[2] = B;
-    const Operand athi = (l == 1) ? op(P.Xb, P.ldx, 0, 0, P.grow, B) : op(P.A[l - 1], P.lda[l - 1], (int64_t)B * P.lda[l - 1], 0);
-    const Operand atlo = (l == 1) ? op(P.Xl, P.ldx, 0, 0, P.grow, B) : op(P.Al[l - 1], P.lda[l - 1], (int64_t)B * P.lda[l - 1], 0);
-    g.A[0] = atlo; g.B[0] = op(P.G[l - 1], P.lda[l], gstride, 0);
-    g.A[1] = athi; g.B[1] = op(P.Gl[l - 1], P.lda[l], gstride, 0);
-    g.A[2] = athi; g.B[2] = op(P.G[l - 1], P.lda[l], gstride, 0);
-    g.C = s.gbuf + P.offW[l - 1]; g.c_batch_stride = s.p; g.sel = s.sel; g.c_sel_stride = mp;
-    launch_gemm(c, g, M);
-    // its innovation: A_{l-1}^T dG_l + dA_{l-1}^T Gref_l
-    g.npairs = 1;
-    g.A[0] = athi;
-    g.B[0] = op(P.dG[l - 1], P.lda[l], gstride, 0);
-    if (l > 1) {
-      g.npairs = 2; g.K[1] = B;
-      g.A[1] = op(P.dA[l - 1], P.lda[l - 1], (int64_t)B * P.lda[l - 1], 0);
-      g.B[1] = op(P.Gref[l - 1], P.lda[l], gstride, 0);
+    {   // weight gradient and its innovation: contraction over the worker's rows
+      Mm5Args g = blank(s, P);
+      g.M = din; g.N = dout; g.K = B;
+      if (l == 1) {
+        side_add(g.A, P.XTh, Rp, Bp); side_add(g.A, P.XTl, Rp, Bp);
+        g.a_h = 0; g.a_l = 1; g.a_r = 0;
+      } else {
+        side_add(g.A, P.AhT[l - 1], Rp, Bp); side_add(g.A, P.AlT[l - 1], Rp, Bp); side_add(g.A, P.dAT[l - 1], Rp, Bp);
+        g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 0;       // innov = A^T dG + dA^T Gref
+      }
+      side_add(g.B, P.GhT[l], Rp, Bp); side_add(g.B, P.GlT[l], Rp, Bp);
+      side_add(g.B, P.GrefT[l], Rp, Bp); side_add(g.B, P.dGT[l], Rp, Bp);
+      g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
+      g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1];
+      launch_mm5<EPI_DW>(c, g, M);
     }
-    if (P.rule == CADA_RULE_CADA1) { g.C = s.dtl + P.offW[l - 1]; g.sel = s.sel; g.c_sel_stride = mp; }
-    else { g.C = innov + P.offW[l - 1]; g.sel = nullptr; g.c_sel_stride = 0; }
-    launch_gemm(c, g, M);
-    if (l > 1) {
-      // gradient w.r.t. the activations of layer l-1 and its difference
-      GemmArgs h{};
-      h.M = B; h.N = din; h.ldc = din; h.c_batch_stride = (int64_t)B * din; h.sel = nullptr;
-      const bf16_t *Wlo = P.Wl + P.wb_off[l - 1];
-      h.npairs = 3; h.K[0] = h.K[1] = h.K[2] = dout; h.C = P.GA[l - 1];
-      h.A[0] = op(P.Gl[l - 1], P.lda[l], gstride, 1); h.B[0] = op(W, P.ldw[l - 1], 0, 1);
-      h.A[1] = op(P.G[l - 1], P.lda[l], gstride, 1);  h.B[1] = op(Wlo, P.ldw[l - 1], 0, 1);
-      h.A[2] = op(P.G[l - 1], P.lda[l], gstride, 1);  h.B[2] = op(W, P.ldw[l - 1], 0, 1);
-      launch_gemm(c, h, M);
-      h.npairs = 2; h.K[1] = dout; h.C = P.dGA[l - 1];
-      h.A[0] = op(P.dG[l - 1], P.lda[l], gstride, 1);
-      h.B[0] = op(W, P.ldw[l - 1], 0, 1);
-      h.A[1] = op(P.Gref[l - 1], P.lda[l], gstride, 1);
-      h.B[1] = op(dW, P.ldw[l - 1], dw_stride, 1);
-      launch_gemm(c, h, M);
-      BwdArgs ba;
-      ba.s = s; ba.GA = P.GA[l - 1]; ba.dGA = P.dGA[l - 1]; ba.A = P.A[l - 1]; ba.Aref = P.Aref[l - 1];
-      ba.G = P.G[l - 2]; ba.Gl = P.Gl[l - 2]; ba.dG = P.dG[l - 2]; ba.Gref = P.Gref[l - 2];
-      ba.offb = P.offb[l - 2]; ba.d = din; ba.lda = P.lda[l - 1]; ba.innov = innov;
-      hipLaunchKernelGGL(k_hidden_bwd, dim3((unsigned)((din + 63) / 64), M), dim3(kBlock), 0, st, ba);
+    if (l >= 2) {   // gradient w.r.t. the activations of layer l-1, masks, bias partials
+      Mm5Args g = blank(s, P);
+      g.M = B; g.N = din; g.K = dout;
+      const int64_t bs = (int64_t)Bp * P.lda[l];
+      side_add(g.A, P.Gh[l], P.lda[l], bs); side_add(g.A, P.Gl[l], P.lda[l], bs);
+      side_add(g.A, P.dG[l], P.lda[l], bs); side_add(g.A, P.Gref[l], P.lda[l], bs);
+      g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 3;         // dGA = dG W^T + Gref dW^T
+      const int64_t ldn = P8(dout);
+      side_add(g.B, P.WNh + P.wn_off[l - 1], ldn, 0); side_add(g.B, P.WNl + P.wn_off[l - 1], ldn, 0);
+      side_add(g.B, P.dWN + P.wn_off[l - 1], ldn, dwn_stride);
+      g.b_h = 0; g.b_l = 1; g.b_x = 0; g.b_d = 2;
+      const int q = l - 1;
+      g.offb = P.offb[q - 1]; g.ldo = P.lda[q];
+      g.o_h = P.Gh[q]; g.o_l = P.Gl[q]; g.o_d = P.dG[q]; g.o_r = P.Gref[q];     // null for q = 1
+      g.t_h = P.GhT[q]; g.t_l = P.GlT[q]; g.t_d = P.dGT[q]; g.t_r = P.GrefT[q];
+      g.m_on = P.Ah[q]; g.m_onref = P.Aref[q]; g.ldm = P.lda[q];
+      g.dbpart = P.dbpart; g.ddbpart = P.ddbpart;
+      launch_mm5<EPI_DA>(c, g, M);
+      hipLaunchKernelGGL(k_bias_finish, dim3((din + 255) / 256, M), dim3(kBlock), 0, st, s, P.dbpart, P.ddbpart, P.RT, din,
+                         P.offb[q - 1], P.lhs_b_slot[q - 1]);
     }
   }
-  prof_mark(c);
-  hipLaunchKernelGGL(k_mlp_lhs, dim3(s.n_lhs_part, M), dim3(kBlock), 0, st, s, innov);
   prof_mark(c);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
