@@ -388,6 +388,7 @@ struct MlpPlan {
   int nW;                                                 // delta-weight copies: 1 (CADA1) or M (CADA2)
   bf16_t *Xh, *Xl; int64_t ldx;
   bf16_t *XTh, *XTl;                                      // gathered minibatch, transposed [d0][Rp]
+  bf16_t *XGh, *XGl;                                      // gathered minibatch, row-major [Rp][ldx]
   int64_t *grow;
   bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;
   bf16_t *Ah[CADA_MAX_LAYERS], *Al[CADA_MAX_LAYERS], *dA[CADA_MAX_LAYERS], *Aref[CADA_MAX_LAYERS];   // hidden l, row-major
@@ -437,6 +438,8 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.Xl = w.take<bf16_t>((size_t)total_rows * P.ldx);
   P.XTh = w.take<bf16_t>((size_t)P.d[0] * Rp);
   P.XTl = w.take<bf16_t>((size_t)P.d[0] * Rp);
+  P.XGh = w.take<bf16_t>(Rp * P.ldx);
+  P.XGl = w.take<bf16_t>(Rp * P.ldx);
   P.grow = w.take<int64_t>(Rp);
   P.WTh = w.take<bf16_t>((size_t)wt); P.WTl = w.take<bf16_t>((size_t)wt); P.dWT = w.take<bf16_t>((size_t)wt * P.nW);
   P.WNh = w.take<bf16_t>((size_t)wn + 8); P.WNl = w.take<bf16_t>((size_t)wn + 8); P.dWN = w.take<bf16_t>((size_t)wn * P.nW + 8);
@@ -525,10 +528,13 @@ __global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow, int 
   grow[(int64_t)m * Bp + b] = s.row_off[m] + r;
 }
 
-// Transposed copy of the gathered minibatch: XT[c][m*Bp + b] = X[grow[m*Bp + b]][c].
-// grid (ceil(d0/64), ceil(B/64), M), block 256; 64 x 64 tile through LDS.
+// Compact copies of the gathered minibatch, so that the contractions read dense matrices
+// instead of 64-byte pieces of scattered rows: XG[m*Bp + b][c] = X[grow[m*Bp + b]][c] and
+// XT[c][m*Bp + b] = the same, transposed.  grid (ceil(d0/64), ceil(B/64), M), block 256;
+// 64 x 64 tile through LDS.
 __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, const bf16_t *Xl, int64_t ldx, const int64_t *grow,
-                                                             bf16_t *XTh, bf16_t *XTl, int d0, int B, int Bp, int64_t Rp) {
+                                                             bf16_t *XTh, bf16_t *XTl, bf16_t *XGh, bf16_t *XGl, int d0, int B, int Bp,
+                                                             int64_t Rp) {
   __shared__ bf16_t th[64][66], tl[64][66];
   const int m = blockIdx.z, c0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -538,6 +544,8 @@ __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, c
     if (b < B && c < d0) {
       const int64_t src = grow[(int64_t)m * Bp + b] * ldx + c;
       vh = Xh[src]; vl = Xl[src];
+      const int64_t dst = ((int64_t)m * Bp + b) * ldx + c;
+      XGh[dst] = vh; XGl[dst] = vl;
     }
     th[r][tx] = vh; tl[r][tx] = vl;
   }
@@ -766,7 +774,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
   prof_mark(c);
   hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp);
   hipLaunchKernelGGL(k_gather_transpose, dim3((P.d[0] + 63) / 64, (B + 63) / 64, M), dim3(kBlock), 0, st,
-                     P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.d[0], B, Bp, Rp);
+                     P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, Rp);
   for (int l = 1; l <= L; ++l) {
     PrepArgs pa;
     pa.s = s;
@@ -783,8 +791,8 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
     Mm5Args g = blank(s, P);
     g.M = B; g.N = dout; g.K = din;
     if (l == 1) {
-      side_add(g.A, P.Xh, P.ldx, 0); side_add(g.A, P.Xl, P.ldx, 0);
-      g.gatherA = P.grow; g.gstride = Bp;
+      const int64_t bs0 = (int64_t)Bp * P.ldx;
+      side_add(g.A, P.XGh, P.ldx, bs0); side_add(g.A, P.XGl, P.ldx, bs0);
       g.a_h = 0; g.a_l = 1; g.a_r = 0;                    // dZ_1 = A_0 dW_1
     } else {
       const int64_t bs = (int64_t)Bp * P.lda[l - 1];

@@ -40,10 +40,14 @@ __global__ __launch_bounds__(kBlock) void k_rule(const DevState s, const uint8_t
   __syncthreads();
   const double rhs = rhs_s;
   const bool tr = k < s.trace_steps;
-  for (int m = threadIdx.x; m < s.M; m += kBlock) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  for (int m = wv; m < s.M; m += kBlock / kWave) {     // one wavefront per worker
     double lhs = 0.0;
     const float *lp = s.lhs_part + (int64_t)m * s.n_lhs_part;
-    for (int t = 0; t < s.n_lhs_part; ++t) lhs += (double)lp[t];
+    for (int t = lane; t < s.n_lhs_part; t += kWave) lhs += (double)lp[t];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lhs += __shfl_xor(lhs, o, 64);   // fixed tree order
+    if (lane != 0) continue;
     const int32_t tau = s.tau[m];
     const bool own = (lhs > rhs) || (tau >= s.D);
     bool up = own;
