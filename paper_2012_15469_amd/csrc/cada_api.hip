@@ -55,6 +55,7 @@ struct Geometry {
   int n_col_chunks;
   int64_t chunk_cols;
   int n_lhs_part;
+  int lhs_cap;              // slots reserved per worker (the single-pass logistic kernel needs 4 per workgroup)
   int n_ring_part;
   int64_t total_rows;
 };
@@ -101,6 +102,8 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   g->n_lhs_part = (int)((cfg->p + per_block - 1) / per_block);
   g->n_ring_part = g->n_lhs_part;
   if (cfg->model == CADA_MODEL_MLP) g->n_lhs_part = mlp_lhs_slots(cfg);
+  const int fused_slots = 4 * (int)((cfg->p + 2047) / 2048);
+  g->lhs_cap = g->n_lhs_part > fused_slots ? g->n_lhs_part : fused_slots;
   return true;
 }
 
@@ -121,7 +124,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   }
   int32_t *tau = w.take<int32_t>(M), *sel = w.take<int32_t>(M);
   float *lhs = w.take<float>(M);
-  float *lhs_part = w.take<float>(M * (size_t)g.n_lhs_part);
+  float *lhs_part = w.take<float>(M * (size_t)g.lhs_cap);
   uint8_t *mask = w.take<uint8_t>(M);
   float *ring = w.take<float>((size_t)cfg->d_max);
   float *ring_part = w.take<float>((size_t)g.n_ring_part);
@@ -248,7 +251,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   s.omb1 = (float)(1.0 - cfg->beta1); s.omb2 = (float)(1.0 - cfg->beta2);
   s.eps = (float)cfg->eps; s.lam = (float)cfg->lambda_l2; s.c = cfg->c;
   if (cfg->model == CADA_MODEL_LOGREG) {
-    if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = c->fused_Q;
+    if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = 4 * c->fused_Q;
     c->n_phases = 4;
     c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad";
     c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";

@@ -3,309 +3,490 @@
 //
 // Both passes of the gradient (z = X_B theta, then g = X_B^T r / B) need the same B x p
 // rows, and a second pass over them costs as much as the first whether it is served by
-// HBM or by the memory-side cache.  Here a cluster of Q workgroups owns one worker at a
-// time; workgroup c of the cluster owns a fixed range of columns and streams the worker's
-// rows through its registers in slabs of RS rows.  For every slab it
-//   1. forms the partial dot products z_b, dz_b of its columns (from registers),
-//   2. publishes them to the cluster as 8-byte words {value, sequence tag},
-//   3. collects the Q partials of every row (polling the tags), sums them in a fixed tree
-//      order, and turns z_b, dz_b into the residual r_b and the residual difference dr_b,
-//   4. accumulates r_b x_b and dr_b x_b for its columns from the same registers.
-// The next slab's loads are in flight during steps 1-4.  After the last slab the column
-// range's gradient, innovation and squared-norm partial are written once.
+// HBM or by the memory-side cache (measured: re-reading a 64 MB window immediately runs at
+// the same 6 TB/s as HBM).  Here a cluster of Q workgroups owns one worker at a time;
+// workgroup c of the cluster owns a fixed range of columns (8 per thread) and streams the
+// worker's rows through its registers one row (slab) at a time.  For slab t it
+//   1. forms the partial dot products z, dz of its columns (from registers) and publishes
+//      them to the cluster as 8-byte words {value, sequence tag},
+//   2. parks the slab in an LDS ring of NL = 16 slabs (each thread parks and later re-reads
+//      only its own columns, so the ring itself needs no synchronisation),
+//   3. LAG = 15 slabs later, when the Q partials of the row have long arrived, sums them in
+//      a fixed tree order, turns z, dz into the residual r and the residual difference dr,
+//      and accumulates r x and dr x for its columns from the ring.
+// An exchange among workgroups takes 2 us idle and 3-4 us under load, far longer than a
+// slab takes to stream (0.35 us), so everything hinges on the exchange being off the critical
+// path: the 128 KB ring holds 5.5 us of stream per CU.
+//
+// Loads return in order within a wavefront, so waiting for a young load (a poll, an index,
+// a label) means waiting for every older one: a wavefront that keeps 8 slabs of bulk loads
+// in flight must issue no other load in its steady state.  The workgroup is therefore split
+// into roles, six wavefronts that meet at one LDS-only barrier per slab:
+//   wavefronts 0-3  stream: bulk loads (PD = 8 slabs in flight), partial dot products,
+//                   parking, accumulation; row addresses come from LDS;
+//   wavefront 4     exchange: publishes the workgroup's partials, polls the cluster's
+//                   (P polls in flight, first issued LAG-2-P slabs after publication),
+//                   sums them;
+//   wavefront 5     turns (z, dz, y) into (r, dr) one slab later, and every 64 slabs fetches
+//                   the row indices and labels of 64 slabs to come into LDS.
+// Every global memory operation of a steady-state iteration is executed by all lanes: the
+// compiler counts outstanding operations per path, and one that a branch may skip does not
+// count, which would turn every wait into a wait for the youngest load.
 //
 // Notation and formulas as in cada_logreg.hip (Algorithm 1, the workers' two gradient
 // evaluations on the same samples; conditions (workerrule1)/(workerrule2) for the norm).
 //
 // The cluster's workgroups wait for each other, so all of them must be resident: the
-// kernel is launched cooperatively with a grid no larger than what fits the device, and
-// every wait is bounded (a wait that exceeds the bound sets bit 1 of the error flags and
-// the workgroup stops waiting for the rest of the launch, so every wave always exits).
+// kernel is launched cooperatively, one workgroup per CU, and every wait is bounded (a wait
+// that exceeds the bound sets bit 1 of the error flags and the workgroup stops waiting for
+// the rest of the launch, so every wave always exits).
+#include <cstdlib>
+#include <type_traits>
+
 #include "cada_internal.h"
 
 namespace cada {
 
+constexpr int F_NL = 16;             // one-row slabs parked in LDS
+constexpr int F_LAG = F_NL - 1;      // a slab is consumed this many iterations after it was produced
+constexpr int F_PD = 8;              // slabs of loads in flight per thread (= unroll factor of the main loop)
+constexpr int F_P = 4;               // polls in flight in the exchange wavefront (divides F_PD)
+constexpr int F_NP = 32;             // publication buffers (>= LAG + 2)
+constexpr int F_V = 2;               // exchanged values per slab and workgroup: z and dz
+constexpr int F_STREAM = 256;        // streaming threads (4 wavefronts)
+constexpr int F_THREADS = F_STREAM + 128;   // + exchange wavefront + residual/feeder wavefront
+constexpr int F_QMAX = 32;
+constexpr int F_NE = 256;            // slabs whose row address and label are held in LDS (4 chunks of 64)
+constexpr size_t kFusedLds = (size_t)F_NL * 2 * F_STREAM * sizeof(float4);   // 128 KB (dynamic part)
+
 struct FusedArgs {
   DevState s;
   const int32_t *idx;            // [M][B]
-  unsigned long long *zpost;     // [n_clusters][4][2*RS][Q] words {hi: tag, lo: float bits}
+  unsigned long long *zpost;     // [n_clusters][F_NP][F_V][Q] words {hi: tag, lo: float bits}
   int Q, n_clusters;
-  int64_t cols_per_block;        // multiple of 4
-  uint32_t seq_base;             // tags of this launch are seq_base+1, seq_base+2, ...
+  int64_t cols_per_block;        // multiple of 4, <= 2048
+  uint32_t seq_base;             // tag of slab t of this launch is seq_base + 1 + t
   uint32_t spin_limit;
 };
 
-template <int N> struct Log2 { static constexpr int v = 1 + Log2<N / 2>::v; };
-template <> struct Log2<1> { static constexpr int v = 0; };
-
-// Sums V per-lane values over the 64 lanes of a wave with V-1+log2(64/V) shuffles.
-// Returns, in every lane, the wave-wide sum of value number bitreverse(lane mod V).
-template <int V, int H>
-__device__ __forceinline__ void reduce_scatter_step(float (&v)[V], const int lane) {
-  if constexpr (H >= 1) {
-    constexpr int o = V / (2 * H);      // exchange distance: 1, 2, 4, ...
-    const bool up = (lane & o) != 0;
-#pragma unroll
-    for (int i = 0; i < H; ++i) {
-      const float send = up ? v[i] : v[i + H];
-      const float keep = up ? v[i + H] : v[i];
-      v[i] = keep + __shfl_xor(send, o, 64);
-    }
-    reduce_scatter_step<V, H / 2>(v, lane);
-  }
-}
-
-template <int V>
-__device__ __forceinline__ float wave_reduce_scatter(float (&v)[V]) {
-  reduce_scatter_step<V, V / 2>(v, threadIdx.x & 63);
-  float r = v[0];
-#pragma unroll
-  for (int oo = V; oo < 64; oo <<= 1) r += __shfl_xor(r, oo, 64);
-  return r;
-}
-
 __device__ __forceinline__ float sigmoid_f(float a) { return 1.0f / (1.0f + expf(-a)); }
 
-template <int RS, int CPT4>
-struct Slab {
-  float4 x[RS][CPT4];
-  float y;          // label of row (slab*RS + tid), threads tid < RS only
-};
+template <int I> using ic = std::integral_constant<int, I>;
+template <bool B> using bc = std::integral_constant<bool, B>;
 
-template <int RS, int CPT4>
-__global__ __launch_bounds__(kBlock) void k_fused(const FusedArgs a) {
-  constexpr int V = 2 * RS;
-  constexpr int L = Log2<V>::v;
-  static_assert(V >= 4 && V <= 64 && (V & (V - 1)) == 0, "2*RS must be a power of two in [4, 64]");
+typedef float v4f __attribute__((ext_vector_type(4)));   // four consecutive registers
+
+// The bulk loads of the steady state and the waits for them are written out: the compiler
+// places a wait for a load from what it can prove about the loads issued since, and across
+// the back edge of the unrolled loop (and past the rarely taken blocks inside it) it proves
+// too little, so that it drains the whole prefetch pipeline once per trip.  A load issued here
+// is invisible to the compiler's bookkeeping; wait_slab() is what orders its use.
+__device__ __forceinline__ void issue_slab(v4f &a, v4f &b, const float *pa, const float *pb) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(a) : "v"(pa) : "memory");
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(b) : "v"(pb) : "memory");
+}
+// Waits until at most N vector memory operations issued after the two loads of (a, b) are
+// outstanding.  Operations complete in issue order, so (a, b) have then arrived.
+template <int N>
+__device__ __forceinline__ void wait_slab(v4f &a, v4f &b) {
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+
+// Workgroup barrier that orders LDS traffic only.  (__syncthreads() also fences global
+// memory, which makes every wavefront wait for all its outstanding loads and would drain the
+// prefetch pipeline each iteration; the wavefronts of a workgroup exchange data through LDS only.)
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// x + (x of another lane), the other lane chosen by a data-parallel-primitive control word:
+// quad_perm [1,0,3,2] = 0xB1 (lane ^ 1), quad_perm [2,3,0,1] = 0x4E (lane ^ 2),
+// row_ror:4 = 0x124, row_ror:8 = 0x128 (rotation within a row of 16 lanes).
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+// Sum over the lanes of the same parity within each row of 16 lanes (every lane gets it).
+__device__ __forceinline__ float row16_parity_sum(float v) {
+  v += dpp_get<0x4E>(v);
+  v += dpp_get<0x124>(v);
+  v += dpp_get<0x128>(v);
+  return v;
+}
+
+__global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   const DevState &s = a.s;
-  __shared__ float red[4][V];
-  __shared__ float zs[V];
-  __shared__ float r_s[RS], dr_s[RS];
-  __shared__ float red4[4];
+  extern __shared__ __align__(16) unsigned char fused_smem[];
+  v4f *ring = reinterpret_cast<v4f *>(fused_smem);            // [F_NL][2][F_STREAM]
+  __shared__ __align__(16) float red[2][F_V][16];             // [slab parity][z|dz][wavefront * 4 + row of 16 lanes]
+  __shared__ float zz_s[2][F_V];                              // cluster sums z, dz of a slab
+  __shared__ float r_s[2], dr_s[2];
+  __shared__ long long off_s[F_NE];                           // element offset of slab t's row in X, at t % NE
+  __shared__ float y_s[F_NE];                                 // label of slab t
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int Q = a.Q;
+  const int Q = a.Q, ncl = a.n_clusters;
   const int cluster = blockIdx.x / Q, cb = blockIdx.x % Q;
+  const int nslab = s.B;                                      // one row per slab
+  const int rounds = (s.M - cluster + ncl - 1) / ncl;         // workers of this cluster
+  const int S = rounds * nslab;                               // slabs of this cluster
+  const int total = S + F_LAG;                                // iterations (= barriers after the first) of every wavefront
+  unsigned long long *post_base = a.zpost + (int64_t)cluster * F_NP * F_V * Q;
+  // (worker, slab within worker) cursors advance one slab at a time
+  auto advance = [&](int &m, int &loc) __attribute__((always_inline)) { if (++loc == nslab) { loc = 0; m += ncl; } };
+
+  if (w == 5) {
+    // ================= residual / feeder wavefront =================
+    const float invB = 1.0f / (float)s.B;
+    // feeder registers (lane = slab 64 * chunk + lane): row index, first row and end of the
+    // worker's row range, label.  Three stages several iterations apart, so that no stage
+    // waits for a load it has just issued.
+    int64_t f_base = 0, f_end = 0, f_r = 0;
+    float f_y = 0.f;
+    auto feed_issue = [&](int chunk) __attribute__((always_inline)) {                 // stage 1: index and row range
+      const int t = chunk * 64 + lane;
+      const int tt = t < S ? t : S - 1;
+      const int m = cluster + (tt / nslab) * ncl;
+      f_base = s.row_off[m];
+      f_end = s.row_off[m + 1];
+      f_r = a.idx[(int64_t)m * s.B + tt % nslab];
+    };
+    auto feed_label = [&]() __attribute__((always_inline)) {                          // stage 2: range check, label
+      const int64_t n_m = f_end - f_base;
+      if (f_r < 0 || f_r >= n_m) { atomicOr(s.err, 1u); f_r = f_r < 0 ? 0 : n_m - 1; }
+      f_y = static_cast<const float *>(s.y)[f_base + f_r];
+    };
+    auto feed_write = [&](int chunk) __attribute__((always_inline)) {                 // stage 3
+      const int e = (chunk * 64 + lane) % F_NE;
+      off_s[e] = (f_base + f_r) * s.p;
+      y_s[e] = f_y;
+    };
+    feed_issue(0); feed_label(); feed_write(0);
+    lds_barrier();
+
+    auto math_iter = [&](auto ST, const int sl) __attribute__((always_inline)) {
+      constexpr bool st = decltype(ST)::value;
+      lds_barrier();
+      const int c1 = sl + 1 - F_LAG;                   // summed by the exchange wavefront last iteration
+      if (st || (c1 >= 0 && c1 < S)) {
+        const float z = zz_s[c1 & 1][0], dz = zz_s[c1 & 1][1];
+        const float y = y_s[c1 % F_NE];
+        const float aa = -y * z;
+        const float bb = aa + y * dz;
+        // lane 0 evaluates sigmoid(aa), the other lanes sigmoid(-bb): one evaluation for both
+        const float sg = sigmoid_f(lane == 0 ? aa : -bb);
+        const float sa = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sg), 0));
+        const float sb = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sg), 1));
+        const float em = expm1f(y * dz);
+        if (lane == 0) {
+          r_s[c1 & 1] = -y * sa * invB;
+          dr_s[c1 & 1] = y * sa * sb * em * invB;
+        }
+      }
+      // rows and labels of chunk sl / 64 + 1, first needed at iteration 64 (sl / 64 + 1) - PD
+      const int ph = sl & 63, chunk = (sl >> 6) + 1;
+      if (chunk * 64 < S) {
+        if (ph == 16) feed_issue(chunk);
+        else if (ph == 24) feed_label();
+        else if (ph == 32) feed_write(chunk);
+      }
+    };
+    // head, steady-state loop, tail: three loops of their own, so that the steady-state loop
+    // has a single body and its loop-carried registers stay in place
+    int s0 = 0;
+    for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD)
+      for (int i = 0; i < F_PD; ++i)
+        if (s0 + i < total) math_iter(bc<false>{}, s0 + i);
+    for (; s0 + 2 * F_PD < S; s0 += F_PD) {
+#pragma unroll
+      for (int i = 0; i < F_PD; ++i) math_iter(bc<true>{}, s0 + i);
+    }
+    for (; s0 < total; s0 += F_PD)
+      for (int i = 0; i < F_PD; ++i)
+        if (s0 + i < total) math_iter(bc<false>{}, s0 + i);
+    return;
+  }
+
+  if (w == 4) {
+    // ================= exchange wavefront =================
+    const int j = lane & 31, half = lane >> 5, par = lane & 1;
+    const bool jok = j < Q;
+    const int jc = jok ? j : Q - 1;
+    bool dead = false;
+    unsigned long long pw[F_P];
+#pragma unroll
+    for (int i = 0; i < F_P; ++i) pw[i] = 0ull;
+    lds_barrier();
+
+    auto comm_iter = [&](auto PI, auto ST, const int sl) __attribute__((always_inline)) {
+      constexpr int pi = decltype(PI)::value;
+      constexpr bool st = decltype(ST)::value;
+      lds_barrier();
+      // publish slab sl: lanes of equal parity compute and store the same word
+      if (st || sl < S) {
+        const float4 *rp = reinterpret_cast<const float4 *>(red[sl & 1][par]);
+        const float4 q0 = rp[0], q1 = rp[1], q2 = rp[2], q3 = rp[3];
+        const float tot = (((q0.x + q0.y) + (q0.z + q0.w)) + ((q1.x + q1.y) + (q1.z + q1.w))) +
+                          (((q2.x + q2.y) + (q2.z + q2.w)) + ((q3.x + q3.y) + (q3.z + q3.w)));
+        const uint32_t tag = a.seq_base + 1u + (uint32_t)sl;
+        const unsigned long long word = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(tot);
+        __hip_atomic_store(post_base + ((int64_t)(sl % F_NP) * F_V + par) * Q + cb, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      // sum the cluster's partials of slab c1 (first polled F_P iterations ago)
+      const int c1 = sl + 2 - F_LAG;
+      if (st || (c1 >= 0 && c1 < S)) {
+        const uint32_t tag = a.seq_base + 1u + (uint32_t)c1;
+        if ((uint32_t)(pw[pi] >> 32) != tag) {      // not there yet: rare
+          const unsigned long long *pp = post_base + ((int64_t)(c1 % F_NP) * F_V + half) * Q + jc;
+          uint32_t spins = 0;
+          while (!dead && (uint32_t)(pw[pi] >> 32) != tag) {
+            if (++spins > a.spin_limit) { dead = true; atomicOr(s.err, 2u); break; }
+            __builtin_amdgcn_s_sleep(1);
+            pw[pi] = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+        float v = jok ? __uint_as_float((uint32_t)pw[pi]) : 0.f;
+        v += dpp_get<0xB1>(v);
+        v = row16_parity_sum(v);                     // every lane: sum of its row of 16
+        const float z0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+        const float z1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+        const float d0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+        const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+        if (lane == 0) { zz_s[c1 & 1][0] = z0 + z1; zz_s[c1 & 1][1] = d0 + d1; }
+      }
+      // first poll of slab c2, summed F_P iterations from now
+      const int c2 = sl + 2 + F_P - F_LAG;
+      if (st || (c2 >= 0 && c2 < S))
+        pw[pi] = __hip_atomic_load(post_base + ((int64_t)(c2 % F_NP) * F_V + half) * Q + jc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+
+    auto comm_generic = [&](const int s0) __attribute__((always_inline)) {
+      comm_iter(ic<0>{}, bc<false>{}, s0);
+      if (s0 + 1 < total) comm_iter(ic<1>{}, bc<false>{}, s0 + 1);
+      if (s0 + 2 < total) comm_iter(ic<2>{}, bc<false>{}, s0 + 2);
+      if (s0 + 3 < total) comm_iter(ic<3>{}, bc<false>{}, s0 + 3);
+      if (s0 + 4 < total) comm_iter(ic<0>{}, bc<false>{}, s0 + 4);
+      if (s0 + 5 < total) comm_iter(ic<1>{}, bc<false>{}, s0 + 5);
+      if (s0 + 6 < total) comm_iter(ic<2>{}, bc<false>{}, s0 + 6);
+      if (s0 + 7 < total) comm_iter(ic<3>{}, bc<false>{}, s0 + 7);
+    };
+    int s0 = 0;
+    for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD) comm_generic(s0);
+    for (; s0 + 2 * F_PD < S; s0 += F_PD) {
+      comm_iter(ic<0>{}, bc<true>{}, s0);     comm_iter(ic<1>{}, bc<true>{}, s0 + 1);
+      comm_iter(ic<2>{}, bc<true>{}, s0 + 2); comm_iter(ic<3>{}, bc<true>{}, s0 + 3);
+      comm_iter(ic<0>{}, bc<true>{}, s0 + 4); comm_iter(ic<1>{}, bc<true>{}, s0 + 5);
+      comm_iter(ic<2>{}, bc<true>{}, s0 + 6); comm_iter(ic<3>{}, bc<true>{}, s0 + 7);
+    }
+    for (; s0 < total; s0 += F_PD) comm_generic(s0);
+    return;
+  }
+
+  // ================= streaming wavefronts =================
   const int64_t colbase = (int64_t)cb * a.cols_per_block;
   const int64_t colend = min(s.p, colbase + a.cols_per_block);
-  int64_t col[CPT4];
-  bool cv[CPT4];
+  int64_t col[2];
+  bool cv[2];
 #pragma unroll
-  for (int q = 0; q < CPT4; ++q) {
-    col[q] = colbase + ((int64_t)q * kBlock + tid) * 4;
+  for (int q = 0; q < 2; ++q) {
+    col[q] = colbase + ((int64_t)q * F_STREAM + tid) * 4;
     cv[q] = col[q] < colend;
     if (!cv[q]) col[q] = 0;            // a valid address; the value is discarded
   }
-  const float *yv = static_cast<const float *>(s.y);
-  const float invB = 1.0f / (float)s.B;
-  const int nslab = (s.B + RS - 1) / RS;
   const int64_t mp = (int64_t)s.M * s.p;
-  unsigned long long *post_base = a.zpost + (int64_t)cluster * 4 * V * Q;
-  uint32_t seq = a.seq_base;
-  bool dead = false;
-  // value index this lane holds after wave_reduce_scatter
-  const int my_v = (int)(__brev((unsigned)lane) >> (32 - L)) & (V - 1);
-
-  for (int m = cluster; m < s.M; m += a.n_clusters) {
-    const int32_t *idx = a.idx + (int64_t)m * s.B;
-    const int64_t n_m = s.row_off[m + 1] - s.row_off[m];
+  // first element of the row of slab t (wavefront-uniform, from the feeder's table)
+  auto row_ptr = [&](int t) __attribute__((always_inline)) -> const float * {
+    const long long o = off_s[t % F_NE];
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)o);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((unsigned long long)o >> 32));
+    return s.X + (int64_t)(((unsigned long long)hi << 32) | lo);
+  };
+  auto load_theta = [&](int m, float4 (&t)[2], float4 (&d)[2]) {
     const RefPtr ref = theta_ref(s, m, s.k);
-    float4 th[CPT4], dd[CPT4], g[CPT4], iv[CPT4];
 #pragma unroll
-    for (int q = 0; q < CPT4; ++q) {
-      const float4 t = *reinterpret_cast<const float4 *>(s.theta + col[q]);
+    for (int q = 0; q < 2; ++q) {
+      const float4 tt = *reinterpret_cast<const float4 *>(s.theta + col[q]);
       const float4 tl = *reinterpret_cast<const float4 *>(s.theta_lo + col[q]);
       const float4 rh = *reinterpret_cast<const float4 *>(ref.hi + col[q]);
       const float4 rl = *reinterpret_cast<const float4 *>(ref.lo + col[q]);
-      th[q] = cv[q] ? t : make_float4(0.f, 0.f, 0.f, 0.f);
-      dd[q] = cv[q] ? make_float4((t.x - rh.x) + (tl.x - rl.x), (t.y - rh.y) + (tl.y - rl.y),
-                                  (t.z - rh.z) + (tl.z - rl.z), (t.w - rh.w) + (tl.w - rl.w))
-                    : make_float4(0.f, 0.f, 0.f, 0.f);
-      g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-      iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      t[q] = cv[q] ? tt : make_float4(0.f, 0.f, 0.f, 0.f);
+      d[q] = cv[q] ? make_float4((tt.x - rh.x) + (tl.x - rl.x), (tt.y - rh.y) + (tl.y - rl.y),
+                                 (tt.z - rh.z) + (tl.z - rl.z), (tt.w - rh.w) + (tl.w - rl.w))
+                   : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+  };
 
-    // row of slab sl, slot r (clamped into the worker's range; slots past B reuse row B-1)
-    auto row_of = [&](int sl, int r, bool *bad) -> int64_t {
-      const int b = min(sl * RS + r, s.B - 1);
-      int64_t loc = idx[b];
-      if (loc < 0) { loc = 0; *bad = true; }
-      if (loc >= n_m) { loc = n_m - 1; *bad = true; }
-      return s.row_off[m] + loc;
-    };
-    auto load_slab = [&](Slab<RS, CPT4> &sb, int sl) {
-      bool bad = false;
+  v4f xb[F_PD][2];
+  float4 th[2], dd[2], g[2], iv[2];
 #pragma unroll
-      for (int r = 0; r < RS; ++r) {
-        const float *rowp = s.X + row_of(sl, r, &bad) * s.p;
-#pragma unroll
-        for (int q = 0; q < CPT4; ++q) sb.x[r][q] = *reinterpret_cast<const float4 *>(rowp + col[q]);
-      }
-      sb.y = (tid < RS) ? yv[row_of(sl, tid, &bad)] : 0.f;
-      if (bad && tid == 0) atomicOr(s.err, 1u);
-    };
+  for (int q = 0; q < 2; ++q) th[q] = dd[q] = g[q] = iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-    auto process = [&](const Slab<RS, CPT4> &sb, int sl) {
-      seq += 1;
-      // 1. partial dot products of this block's columns
-      float pv[V];
+  int pm = cluster, ploc = 0;           // slab produced (dot products, parked) this iteration
+  int cm = cluster, cloc = 0;           // slab consumed this iteration (valid once sl >= LAG)
+  lds_barrier();                        // the feeder's first chunk is in LDS
+  // prologue: loads of slabs 0 .. PD-1
 #pragma unroll
-      for (int r = 0; r < RS; ++r) {
-        float z = 0.f, dz = 0.f;
+  for (int i = 0; i < F_PD; ++i) {
+    if (i < S) {
+      const float *rp = row_ptr(i);
 #pragma unroll
-        for (int q = 0; q < CPT4; ++q) {
-          const float4 x = sb.x[r][q];
-          z = fmaf(x.x, th[q].x, z); z = fmaf(x.y, th[q].y, z); z = fmaf(x.z, th[q].z, z); z = fmaf(x.w, th[q].w, z);
-          dz = fmaf(x.x, dd[q].x, dz); dz = fmaf(x.y, dd[q].y, dz); dz = fmaf(x.z, dd[q].z, dz); dz = fmaf(x.w, dd[q].w, dz);
-        }
-        pv[2 * r] = z;
-        pv[2 * r + 1] = dz;
-      }
-      const float mine = wave_reduce_scatter<V>(pv);
-      if (lane < V) red[w][my_v] = mine;
-      __syncthreads();
-      // 2. publish {value, tag}
-      unsigned long long *post = post_base + (int64_t)(seq & 3u) * V * Q;
-      if (tid < V) {
-        const float tot = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
-        const unsigned long long word = ((unsigned long long)seq << 32) | (unsigned long long)__float_as_uint(tot);
-        __hip_atomic_store(post + (int64_t)tid * Q + cb, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      // 3. collect: wave w gathers values v = w, w+4, ...; lane j reads workgroup j's word
-      constexpr int NV = V / 4;
-      unsigned long long wd[NV];
-      if (lane < Q) {
-        uint32_t spins = 0;
-        for (;;) {
-          bool ok = true;
-#pragma unroll
-          for (int i = 0; i < NV; ++i) {
-            wd[i] = __hip_atomic_load(post + (int64_t)(w + 4 * i) * Q + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = ok && ((uint32_t)(wd[i] >> 32) == seq);
-          }
-          if (ok || dead) break;
-          if (++spins > a.spin_limit) {
-            dead = true;
-            atomicOr(s.err, 2u);
-            break;
-          }
-          __builtin_amdgcn_s_sleep(2);
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) wd[i] = 0ull;
-      }
-#pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const float tot = wave_sum(__uint_as_float((uint32_t)wd[i]));
-        if (lane == 0) zs[w + 4 * i] = tot;
-      }
-      __syncthreads();
-      if (tid < RS) {
-        const int b = sl * RS + tid;
-        float r = 0.f, dr = 0.f;
-        if (b < s.B) {
-          const float y = sb.y;
-          const float z = zs[2 * tid], dz = zs[2 * tid + 1];
-          const float aa = -y * z;
-          const float bb = aa + y * dz;
-          const float sa = sigmoid_f(aa);
-          r = -y * sa * invB;
-          dr = y * sa * sigmoid_f(-bb) * expm1f(y * dz) * invB;
-        }
-        r_s[tid] = r;
-        dr_s[tid] = dr;
-      }
-      __syncthreads();
-      // 4. accumulate the gradient and the innovation from the same registers
-#pragma unroll
-      for (int r = 0; r < RS; ++r) {
-        const float rr = r_s[r], dr = dr_s[r];
-#pragma unroll
-        for (int q = 0; q < CPT4; ++q) {
-          const float4 x = sb.x[r][q];
-          g[q].x = fmaf(rr, x.x, g[q].x); g[q].y = fmaf(rr, x.y, g[q].y);
-          g[q].z = fmaf(rr, x.z, g[q].z); g[q].w = fmaf(rr, x.w, g[q].w);
-          iv[q].x = fmaf(dr, x.x, iv[q].x); iv[q].y = fmaf(dr, x.y, iv[q].y);
-          iv[q].z = fmaf(dr, x.z, iv[q].z); iv[q].w = fmaf(dr, x.w, iv[q].w);
-        }
-      }
-    };
-
-    Slab<RS, CPT4> sa, sb;
-    load_slab(sa, 0);
-    for (int sl = 0; sl < nslab; sl += 2) {
-      if (sl + 1 < nslab) load_slab(sb, sl + 1);
-      process(sa, sl);
-      if (sl + 1 < nslab) {
-        if (sl + 2 < nslab) load_slab(sa, sl + 2);
-        process(sb, sl + 1);
-      }
+      for (int q = 0; q < 2; ++q) xb[i][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
     }
-
-    // epilogue: regulariser, stores, squared norm of the rule's left-hand side
-    const int cur = s.sel[m];
-    float sq = 0.f;
-#pragma unroll
-    for (int q = 0; q < CPT4; ++q) {
-      if (cv[q]) {
-        float4 gg = g[q], ii = iv[q];
-        gg.x = fmaf(s.lam, th[q].x, gg.x); gg.y = fmaf(s.lam, th[q].y, gg.y);
-        gg.z = fmaf(s.lam, th[q].z, gg.z); gg.w = fmaf(s.lam, th[q].w, gg.w);
-        ii.x = fmaf(s.lam, dd[q].x, ii.x); ii.y = fmaf(s.lam, dd[q].y, ii.y);
-        ii.z = fmaf(s.lam, dd[q].z, ii.z); ii.w = fmaf(s.lam, dd[q].w, ii.w);
-        *reinterpret_cast<float4 *>(s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = gg;
-        if (s.rule == CADA_RULE_CADA1) {
-          const float4 st = *reinterpret_cast<const float4 *>(s.dtl + (int64_t)cur * mp + (int64_t)m * s.p + col[q]);
-          *reinterpret_cast<float4 *>(s.dtl + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = ii;
-          ii.x -= st.x; ii.y -= st.y; ii.z -= st.z; ii.w -= st.w;
-        }
-        sq = fmaf(ii.x, ii.x, sq); sq = fmaf(ii.y, ii.y, sq); sq = fmaf(ii.z, ii.z, sq); sq = fmaf(ii.w, ii.w, sq);
-      }
-    }
-    const float tot = block_sum(sq, red4);
-    if (tid == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + cb] = tot;
   }
+
+  auto stream_iter = [&](auto BI, auto ST, const int sl) __attribute__((always_inline)) {
+    constexpr int bi = decltype(BI)::value;
+    constexpr bool st = decltype(ST)::value;
+    if (st || sl < S) {
+      if (ploc == 0) load_theta(pm, th, dd);
+      if constexpr (st) wait_slab<2 * (F_PD - 1)>(xb[bi][0], xb[bi][1]);
+      // 1. partial dot products of this thread's columns
+      float z = 0.f, dz = 0.f;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const v4f x = xb[bi][q];
+        z = fmaf(x.x, th[q].x, z); z = fmaf(x.y, th[q].y, z); z = fmaf(x.z, th[q].z, z); z = fmaf(x.w, th[q].w, z);
+        dz = fmaf(x.x, dd[q].x, dz); dz = fmaf(x.y, dd[q].y, dz); dz = fmaf(x.z, dd[q].z, dz); dz = fmaf(x.w, dd[q].w, dz);
+      }
+      // even lanes carry the sum of z, odd lanes of dz, over each row of 16 lanes (fixed tree)
+      const bool up = (lane & 1) != 0;
+      float v = (up ? dz : z) + dpp_get<0xB1>(up ? z : dz);
+      v = row16_parity_sum(v);
+      if ((lane & 15) < F_V) red[sl & 1][lane & 1][w * 4 + (lane >> 4)] = v;
+      // 2. park the slab; the registers are free for the slab F_PD ahead
+      v4f *slot = ring + (size_t)(sl % F_NL) * 2 * F_STREAM;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) slot[q * F_STREAM + tid] = xb[bi][q];
+      advance(pm, ploc);
+      if constexpr (st) {
+        const float *rp = row_ptr(sl + F_PD);
+        issue_slab(xb[bi][0], xb[bi][1], rp + col[0], rp + col[1]);
+      } else if (sl + F_PD < S) {
+        const float *rp = row_ptr(sl + F_PD);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) xb[bi][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
+      }
+    }
+    // 3. consume slab c0 = sl - LAG; its ring entries are this thread's own (no wait needed),
+    //    its residuals are valid after the barrier
+    const bool cons = st || (sl >= F_LAG && sl - F_LAG < S);
+    const int c0 = sl - F_LAG;
+    v4f xr[2];
+    if (cons) {
+      const v4f *slot = ring + (size_t)(c0 % F_NL) * 2 * F_STREAM;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) xr[q] = slot[q * F_STREAM + tid];
+    }
+    lds_barrier();
+    if (cons) {
+      const float rr = r_s[c0 & 1], dr = dr_s[c0 & 1];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const v4f x = xr[q];
+        g[q].x = fmaf(rr, x.x, g[q].x); g[q].y = fmaf(rr, x.y, g[q].y);
+        g[q].z = fmaf(rr, x.z, g[q].z); g[q].w = fmaf(rr, x.w, g[q].w);
+        iv[q].x = fmaf(dr, x.x, iv[q].x); iv[q].y = fmaf(dr, x.y, iv[q].y);
+        iv[q].z = fmaf(dr, x.z, iv[q].z); iv[q].w = fmaf(dr, x.w, iv[q].w);
+      }
+      if (cloc == nslab - 1) {
+        // last slab of worker cm: regulariser, stores, squared norm of the rule's left-hand side
+        const int m = cm;
+        float4 tm[2], dm[2];
+        load_theta(m, tm, dm);
+        const int cur = s.sel[m];
+        float sq = 0.f;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          if (cv[q]) {
+            float4 gg = g[q], ii = iv[q];
+            gg.x = fmaf(s.lam, tm[q].x, gg.x); gg.y = fmaf(s.lam, tm[q].y, gg.y);
+            gg.z = fmaf(s.lam, tm[q].z, gg.z); gg.w = fmaf(s.lam, tm[q].w, gg.w);
+            ii.x = fmaf(s.lam, dm[q].x, ii.x); ii.y = fmaf(s.lam, dm[q].y, ii.y);
+            ii.z = fmaf(s.lam, dm[q].z, ii.z); ii.w = fmaf(s.lam, dm[q].w, ii.w);
+            *reinterpret_cast<float4 *>(s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = gg;
+            if (s.rule == CADA_RULE_CADA1) {
+              const float4 stv = *reinterpret_cast<const float4 *>(s.dtl + (int64_t)cur * mp + (int64_t)m * s.p + col[q]);
+              *reinterpret_cast<float4 *>(s.dtl + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = ii;
+              ii.x -= stv.x; ii.y -= stv.y; ii.z -= stv.z; ii.w -= stv.w;
+            }
+            sq = fmaf(ii.x, ii.x, sq); sq = fmaf(ii.y, ii.y, sq); sq = fmaf(ii.z, ii.z, sq); sq = fmaf(ii.w, ii.w, sq);
+          }
+          g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+          iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        const float tot = wave_sum(sq);
+        if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + cb * 4 + w] = tot;
+      }
+      advance(cm, cloc);
+    }
+  };
+
+  auto stream_generic = [&](const int s0) __attribute__((always_inline)) {
+    stream_iter(ic<0>{}, bc<false>{}, s0);
+    if (s0 + 1 < total) stream_iter(ic<1>{}, bc<false>{}, s0 + 1);
+    if (s0 + 2 < total) stream_iter(ic<2>{}, bc<false>{}, s0 + 2);
+    if (s0 + 3 < total) stream_iter(ic<3>{}, bc<false>{}, s0 + 3);
+    if (s0 + 4 < total) stream_iter(ic<4>{}, bc<false>{}, s0 + 4);
+    if (s0 + 5 < total) stream_iter(ic<5>{}, bc<false>{}, s0 + 5);
+    if (s0 + 6 < total) stream_iter(ic<6>{}, bc<false>{}, s0 + 6);
+    if (s0 + 7 < total) stream_iter(ic<7>{}, bc<false>{}, s0 + 7);
+  };
+  int s0 = 0;
+  for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD) stream_generic(s0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): nothing the compiler tracks is in flight from here on
+  for (; s0 + 2 * F_PD < S; s0 += F_PD) {
+    stream_iter(ic<0>{}, bc<true>{}, s0);     stream_iter(ic<1>{}, bc<true>{}, s0 + 1);
+    stream_iter(ic<2>{}, bc<true>{}, s0 + 2); stream_iter(ic<3>{}, bc<true>{}, s0 + 3);
+    stream_iter(ic<4>{}, bc<true>{}, s0 + 4); stream_iter(ic<5>{}, bc<true>{}, s0 + 5);
+    stream_iter(ic<6>{}, bc<true>{}, s0 + 6); stream_iter(ic<7>{}, bc<true>{}, s0 + 7);
+  }
+  // the loads of the last trip are still in flight and unknown to the compiler
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(xb[0][0]), "+v"(xb[0][1]), "+v"(xb[1][0]), "+v"(xb[1][1]), "+v"(xb[2][0]), "+v"(xb[2][1]),
+                 "+v"(xb[3][0]), "+v"(xb[3][1]), "+v"(xb[4][0]), "+v"(xb[4][1]), "+v"(xb[5][0]), "+v"(xb[5][1]),
+                 "+v"(xb[6][0]), "+v"(xb[6][1]), "+v"(xb[7][0]), "+v"(xb[7][1]));
+  for (; s0 < total; s0 += F_PD) stream_generic(s0);
 }
 
-// Chooses the cluster geometry; returns false if the fused path does not apply.
+// Chooses the cluster geometry; returns false if the single-pass path does not apply.
 bool fused_plan(Ctx *c, int64_t p, int B, int M) {
   c->fused = 0;
-  // Off unless asked for: with one exchange per slab the workgroups spend longer waiting for
-  // each other's partial sums (2 us idle, 4+ us under load per exchange) than the slab takes
-  // to stream, so the two-pass path is faster.  Kept parity-tested as the basis of a deeper
-  // pipeline that parks slabs in LDS while their exchange completes.
   const char *on = getenv("CADA_FUSED");
-  if (!on || atoi(on) == 0) return false;
+  if (on && atoi(on) == 0) return false;
   if (c->vec != 4 || p < 8192) return false;
   int dev = 0, coop = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return false;
-  // columns one workgroup can own: 256 threads x 4 columns x CPT4
-  int cpt4 = 2;
-  int64_t per_block = (int64_t)kBlock * 4 * cpt4;
+  const int64_t per_block = (int64_t)F_STREAM * 4 * 2;           // 2048 columns per workgroup
   int Q = (int)((p + per_block - 1) / per_block);
-  if (const char *e = getenv("CADA_FUSED_Q")) Q = max(Q, atoi(e));
-  if (Q > 64) return false;
+  if (Q > F_QMAX || Q > cus) return false;
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
   int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<8, 2>, kBlock, 0) != hipSuccess || per_cu < 1) return false;
-  if (const char *e = getenv("CADA_FUSED_BLOCKS_PER_CU")) per_cu = min(per_cu, max(1, atoi(e)));
-  else per_cu = 1;
-  int ncl = (cus * per_cu) / Q;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused, F_THREADS, kFusedLds) != hipSuccess || per_cu < 1) {
+    (void)hipGetLastError();
+    return false;
+  }
+  int ncl = cus / Q;                       // one workgroup per CU
   if (ncl < 1) return false;
   ncl = min(ncl, M);
+  if (const char *e = getenv("CADA_FUSED_CLUSTERS")) {     // tuning / test knob: fewer, longer-lived clusters
+    const int want = atoi(e);
+    if (want >= 1 && want < ncl) ncl = want;
+  }
+  if ((size_t)ncl * F_NP * F_V * Q > kFusedPostWords) return false;
   c->fused = 1;
   c->fused_Q = Q;
   c->fused_clusters = ncl;
   c->fused_cols = ((p + Q - 1) / Q + 3) / 4 * 4;
-  c->fused_rs = 8;
-  const int nslab = (B + 8 - 1) / 8;
+  c->fused_rs = 1;
+  const int nslab = B;
   c->fused_seq_per_step = (uint32_t)(((M + ncl - 1) / ncl) * nslab);
   return true;
 }
-
-size_t fused_post_words(int Q, int n_clusters) { return (size_t)n_clusters * 4 * 16 * (size_t)Q; }
 
 int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
   FusedArgs a;
@@ -317,12 +498,12 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
   a.n_clusters = c->fused_clusters;
   a.cols_per_block = c->fused_cols;
   a.seq_base = c->fused_seq;
-  a.spin_limit = 4000000u;
+  a.spin_limit = 2000000u;
   c->fused_seq += c->fused_seq_per_step;
   void *args[] = {&a};
   prof_mark(c);
-  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_fused<8, 2>),
-                                                  dim3((unsigned)(a.Q * a.n_clusters)), dim3(kBlock), args, 0, c->stream);
+  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_fused), dim3((unsigned)(a.Q * a.n_clusters)),
+                                                  dim3(F_THREADS), args, (unsigned)kFusedLds, c->stream);
   prof_mark(c);
   prof_mark(c);
   if (e != hipSuccess) {

@@ -58,6 +58,25 @@ def test_cfg3_reduced_ragged(p, rule, fused, monkeypatch):
     assert 0.1 < tr["mask"][free].mean() < 0.9, "the case must mix rule-driven uploads and skips"
 
 
+@pytest.mark.parametrize("rule,B,clusters", [(2, 48, 0), (1, 48, 0), (2, 100, 2), (1, 72, 2), (2, 200, 1)])
+def test_single_pass_kernel_steady_state(rule, B, clusters, monkeypatch):
+    """The single-pass kernel's unrolled steady-state loop only runs once a cluster of
+    workgroups streams more than 40 rows: longer minibatches, and fewer clusters than workers
+    so that a cluster changes worker (reference point, gradient store) in mid-stream."""
+    monkeypatch.setenv("CADA_FUSED", "1")
+    if clusters:
+        monkeypatch.setenv("CADA_FUSED_CLUSTERS", str(clusters))
+    # K = 30: later the left-hand sides are differences of nearly converged iterates, and both
+    # logistic paths lose digits there alike (the cancellation, not the kernel, sets the error)
+    cfg = configs.CFG3.scaled(layer_dims=(8200,), M=5, N_m=256, B=B, K=30, D=10, rule=rule, alpha=0.02, c=1e-4)
+    prob = generators.make_problem(cfg)
+    Xs, ys = zip(*(prob.rows(m, np.arange(cfg.N_m)) for m in range(cfg.M)))
+    prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
+    sched = generators.make_schedule(cfg)
+    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4)
+    print(rule, B, clusters, stats)
+
+
 def test_special_cases_c0_and_huge_c():
     cfg = configs.CFG1.scaled(c=0.0, K=50)
     prob, dev, sched = _case(cfg)
