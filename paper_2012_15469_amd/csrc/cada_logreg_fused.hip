@@ -57,6 +57,7 @@ constexpr int F_STREAM = 256;        // streaming threads (4 wavefronts)
 constexpr int F_THREADS = F_STREAM + 128;   // + exchange wavefront + residual/feeder wavefront
 constexpr int F_QMAX = 32;
 constexpr int F_NE = 256;            // slabs whose row address and label are held in LDS (4 chunks of 64)
+static_assert(F_PD % F_P == 0 && F_NP >= F_LAG + 2 && F_NE % 64 == 0, "pipeline constants");
 constexpr size_t kFusedLds = (size_t)F_NL * 2 * F_STREAM * sizeof(float4);   // 128 KB (dynamic part)
 
 struct FusedArgs {
@@ -73,6 +74,12 @@ __device__ __forceinline__ float sigmoid_f(float a) { return 1.0f / (1.0f + expf
 
 template <int I> using ic = std::integral_constant<int, I>;
 template <bool B> using bc = std::integral_constant<bool, B>;
+
+// f(ic<0>{}), f(ic<1>{}), ..., f(ic<N-1>{}) written out
+template <class F, int... I>
+__device__ __forceinline__ void unrolled(F &&f, std::integer_sequence<int, I...>) { (f(ic<I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void unrolled(F &&f) { unrolled(static_cast<F &&>(f), std::make_integer_sequence<int, N>{}); }
 
 typedef float v4f __attribute__((ext_vector_type(4)));   // four consecutive registers
 
@@ -260,25 +267,17 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
         pw[pi] = __hip_atomic_load(post_base + ((int64_t)(c2 % F_NP) * F_V + half) * Q + jc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
 
-    auto comm_generic = [&](const int s0) __attribute__((always_inline)) {
-      comm_iter(ic<0>{}, bc<false>{}, s0);
-      if (s0 + 1 < total) comm_iter(ic<1>{}, bc<false>{}, s0 + 1);
-      if (s0 + 2 < total) comm_iter(ic<2>{}, bc<false>{}, s0 + 2);
-      if (s0 + 3 < total) comm_iter(ic<3>{}, bc<false>{}, s0 + 3);
-      if (s0 + 4 < total) comm_iter(ic<0>{}, bc<false>{}, s0 + 4);
-      if (s0 + 5 < total) comm_iter(ic<1>{}, bc<false>{}, s0 + 5);
-      if (s0 + 6 < total) comm_iter(ic<2>{}, bc<false>{}, s0 + 6);
-      if (s0 + 7 < total) comm_iter(ic<3>{}, bc<false>{}, s0 + 7);
-    };
     int s0 = 0;
-    for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD) comm_generic(s0);
-    for (; s0 + 2 * F_PD < S; s0 += F_PD) {
-      comm_iter(ic<0>{}, bc<true>{}, s0);     comm_iter(ic<1>{}, bc<true>{}, s0 + 1);
-      comm_iter(ic<2>{}, bc<true>{}, s0 + 2); comm_iter(ic<3>{}, bc<true>{}, s0 + 3);
-      comm_iter(ic<0>{}, bc<true>{}, s0 + 4); comm_iter(ic<1>{}, bc<true>{}, s0 + 5);
-      comm_iter(ic<2>{}, bc<true>{}, s0 + 6); comm_iter(ic<3>{}, bc<true>{}, s0 + 7);
-    }
-    for (; s0 < total; s0 += F_PD) comm_generic(s0);
+    for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD)
+      unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
+        if (s0 + I.value < total) comm_iter(ic<I.value % F_P>{}, bc<false>{}, s0 + I.value);
+      });
+    for (; s0 + 2 * F_PD < S; s0 += F_PD)
+      unrolled<F_PD>([&](auto I) __attribute__((always_inline)) { comm_iter(ic<I.value % F_P>{}, bc<true>{}, s0 + I.value); });
+    for (; s0 < total; s0 += F_PD)
+      unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
+        if (s0 + I.value < total) comm_iter(ic<I.value % F_P>{}, bc<false>{}, s0 + I.value);
+      });
     return;
   }
 
@@ -314,6 +313,9 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
                                  (tt.z - rh.z) + (tl.z - rl.z), (tt.w - rh.w) + (tl.w - rl.w))
                    : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    // a rarely taken block must leave no load the compiler still tracks in flight: a wait for
+    // it on the main path would be a wait for nearly all the bulk loads issued since
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   };
 
   v4f xb[F_PD][2];
@@ -334,12 +336,89 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     }
   }
 
+  // Accumulation of a consumed slab, deferred by one iteration: its residuals are read from
+  // LDS right after the barrier but first used here, after the next slab's dot products, so
+  // that the wavefront never waits for that read.
+  v4f xr[2];                            // the consumed slab's columns, from the ring
+  float rr = 0.f, dr = 0.f;             // its residual and residual difference
+  bool pending = false;
+  auto accumulate = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const v4f x = xr[q];
+      g[q].x = fmaf(rr, x.x, g[q].x); g[q].y = fmaf(rr, x.y, g[q].y);
+      g[q].z = fmaf(rr, x.z, g[q].z); g[q].w = fmaf(rr, x.w, g[q].w);
+      iv[q].x = fmaf(dr, x.x, iv[q].x); iv[q].y = fmaf(dr, x.y, iv[q].y);
+      iv[q].z = fmaf(dr, x.z, iv[q].z); iv[q].w = fmaf(dr, x.w, iv[q].w);
+    }
+    if (cloc == nslab - 1) {
+      // last slab of worker cm: regulariser, stores, squared norm of the rule's left-hand side
+      const int m = cm;
+      float4 tm[2], dm[2];
+      load_theta(m, tm, dm);
+      const int cur = s.sel[m];
+      float sq = 0.f;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        if (cv[q]) {
+          float4 gg = g[q], ii = iv[q];
+          gg.x = fmaf(s.lam, tm[q].x, gg.x); gg.y = fmaf(s.lam, tm[q].y, gg.y);
+          gg.z = fmaf(s.lam, tm[q].z, gg.z); gg.w = fmaf(s.lam, tm[q].w, gg.w);
+          ii.x = fmaf(s.lam, dm[q].x, ii.x); ii.y = fmaf(s.lam, dm[q].y, ii.y);
+          ii.z = fmaf(s.lam, dm[q].z, ii.z); ii.w = fmaf(s.lam, dm[q].w, ii.w);
+          *reinterpret_cast<float4 *>(s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = gg;
+          if (s.rule == CADA_RULE_CADA1) {
+            const float4 stv = *reinterpret_cast<const float4 *>(s.dtl + (int64_t)cur * mp + (int64_t)m * s.p + col[q]);
+            *reinterpret_cast<float4 *>(s.dtl + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = ii;
+            ii.x -= stv.x; ii.y -= stv.y; ii.z -= stv.z; ii.w -= stv.w;
+          }
+          sq = fmaf(ii.x, ii.x, sq); sq = fmaf(ii.y, ii.y, sq); sq = fmaf(ii.z, ii.z, sq); sq = fmaf(ii.w, ii.w, sq);
+        }
+        g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      const float tot = wave_sum(sq);
+      if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + cb * 4 + w] = tot;
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), see load_theta
+    }
+    advance(cm, cloc);
+  };
+
+  // LDS word of the row address of slab sl + F_PD, read one iteration before its use
+  long long off_q = (F_PD < S) ? off_s[F_PD % F_NE] : 0;
+  auto to_row = [&](long long o) __attribute__((always_inline)) -> const float * {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)o);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((unsigned long long)o >> 32));
+    return s.X + (int64_t)(((unsigned long long)hi << 32) | lo);
+  };
+
+  // One iteration.  The LDS reads whose results are needed later are issued first, and the
+  // only LDS operation the barrier has to wait for (the partial sums) is followed by the
+  // previous slab's accumulation, so that no LDS latency is exposed.
   auto stream_iter = [&](auto BI, auto ST, const int sl) __attribute__((always_inline)) {
     constexpr int bi = decltype(BI)::value;
     constexpr bool st = decltype(ST)::value;
-    if (st || sl < S) {
+    const bool prod = st || sl < S;
+    const bool more = st || sl + F_PD < S;
+    const float *rp = to_row(off_q);
+    if (st || sl + F_PD + 1 < S) off_q = off_s[(sl + F_PD + 1) % F_NE];
+    // 3a. ring entries of slab c0 = sl - LAG, consumed after the barrier (this thread's own
+    //     columns: no synchronisation needed)
+    const bool cons = st || (sl >= F_LAG && sl - F_LAG < S);
+    const int c0 = sl - F_LAG;
+    v4f xn[2];
+    if (cons) {
+      const v4f *slot = ring + (size_t)(c0 % F_NL) * 2 * F_STREAM;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) xn[q] = slot[q * F_STREAM + tid];
+    }
+    if (prod) {
       if (ploc == 0) load_theta(pm, th, dd);
       if constexpr (st) wait_slab<2 * (F_PD - 1)>(xb[bi][0], xb[bi][1]);
+      // 2. park the slab
+      v4f *slot = ring + (size_t)(sl % F_NL) * 2 * F_STREAM;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) slot[q * F_STREAM + tid] = xb[bi][q];
       // 1. partial dot products of this thread's columns
       float z = 0.f, dz = 0.f;
 #pragma unroll
@@ -353,99 +432,40 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       float v = (up ? dz : z) + dpp_get<0xB1>(up ? z : dz);
       v = row16_parity_sum(v);
       if ((lane & 15) < F_V) red[sl & 1][lane & 1][w * 4 + (lane >> 4)] = v;
-      // 2. park the slab; the registers are free for the slab F_PD ahead
-      v4f *slot = ring + (size_t)(sl % F_NL) * 2 * F_STREAM;
-#pragma unroll
-      for (int q = 0; q < 2; ++q) slot[q * F_STREAM + tid] = xb[bi][q];
       advance(pm, ploc);
+      // the registers are free for the slab F_PD ahead
       if constexpr (st) {
-        const float *rp = row_ptr(sl + F_PD);
         issue_slab(xb[bi][0], xb[bi][1], rp + col[0], rp + col[1]);
-      } else if (sl + F_PD < S) {
-        const float *rp = row_ptr(sl + F_PD);
+      } else if (more) {
 #pragma unroll
         for (int q = 0; q < 2; ++q) xb[bi][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
       }
     }
-    // 3. consume slab c0 = sl - LAG; its ring entries are this thread's own (no wait needed),
-    //    its residuals are valid after the barrier
-    const bool cons = st || (sl >= F_LAG && sl - F_LAG < S);
-    const int c0 = sl - F_LAG;
-    v4f xr[2];
-    if (cons) {
-      const v4f *slot = ring + (size_t)(c0 % F_NL) * 2 * F_STREAM;
-#pragma unroll
-      for (int q = 0; q < 2; ++q) xr[q] = slot[q * F_STREAM + tid];
-    }
+    // 3b. accumulate the slab consumed in the previous iteration
+    if (st || pending) accumulate();
     lds_barrier();
+    pending = cons;
     if (cons) {
-      const float rr = r_s[c0 & 1], dr = dr_s[c0 & 1];
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const v4f x = xr[q];
-        g[q].x = fmaf(rr, x.x, g[q].x); g[q].y = fmaf(rr, x.y, g[q].y);
-        g[q].z = fmaf(rr, x.z, g[q].z); g[q].w = fmaf(rr, x.w, g[q].w);
-        iv[q].x = fmaf(dr, x.x, iv[q].x); iv[q].y = fmaf(dr, x.y, iv[q].y);
-        iv[q].z = fmaf(dr, x.z, iv[q].z); iv[q].w = fmaf(dr, x.w, iv[q].w);
-      }
-      if (cloc == nslab - 1) {
-        // last slab of worker cm: regulariser, stores, squared norm of the rule's left-hand side
-        const int m = cm;
-        float4 tm[2], dm[2];
-        load_theta(m, tm, dm);
-        const int cur = s.sel[m];
-        float sq = 0.f;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          if (cv[q]) {
-            float4 gg = g[q], ii = iv[q];
-            gg.x = fmaf(s.lam, tm[q].x, gg.x); gg.y = fmaf(s.lam, tm[q].y, gg.y);
-            gg.z = fmaf(s.lam, tm[q].z, gg.z); gg.w = fmaf(s.lam, tm[q].w, gg.w);
-            ii.x = fmaf(s.lam, dm[q].x, ii.x); ii.y = fmaf(s.lam, dm[q].y, ii.y);
-            ii.z = fmaf(s.lam, dm[q].z, ii.z); ii.w = fmaf(s.lam, dm[q].w, ii.w);
-            *reinterpret_cast<float4 *>(s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = gg;
-            if (s.rule == CADA_RULE_CADA1) {
-              const float4 stv = *reinterpret_cast<const float4 *>(s.dtl + (int64_t)cur * mp + (int64_t)m * s.p + col[q]);
-              *reinterpret_cast<float4 *>(s.dtl + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = ii;
-              ii.x -= stv.x; ii.y -= stv.y; ii.z -= stv.z; ii.w -= stv.w;
-            }
-            sq = fmaf(ii.x, ii.x, sq); sq = fmaf(ii.y, ii.y, sq); sq = fmaf(ii.z, ii.z, sq); sq = fmaf(ii.w, ii.w, sq);
-          }
-          g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-          iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-        const float tot = wave_sum(sq);
-        if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + cb * 4 + w] = tot;
-      }
-      advance(cm, cloc);
+      rr = r_s[c0 & 1]; dr = dr_s[c0 & 1];
+      xr[0] = xn[0]; xr[1] = xn[1];
     }
   };
 
-  auto stream_generic = [&](const int s0) __attribute__((always_inline)) {
-    stream_iter(ic<0>{}, bc<false>{}, s0);
-    if (s0 + 1 < total) stream_iter(ic<1>{}, bc<false>{}, s0 + 1);
-    if (s0 + 2 < total) stream_iter(ic<2>{}, bc<false>{}, s0 + 2);
-    if (s0 + 3 < total) stream_iter(ic<3>{}, bc<false>{}, s0 + 3);
-    if (s0 + 4 < total) stream_iter(ic<4>{}, bc<false>{}, s0 + 4);
-    if (s0 + 5 < total) stream_iter(ic<5>{}, bc<false>{}, s0 + 5);
-    if (s0 + 6 < total) stream_iter(ic<6>{}, bc<false>{}, s0 + 6);
-    if (s0 + 7 < total) stream_iter(ic<7>{}, bc<false>{}, s0 + 7);
-  };
   int s0 = 0;
-  for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD) stream_generic(s0);
+  for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD)
+    unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
+      if (s0 + I.value < total) stream_iter(I, bc<false>{}, s0 + I.value);
+    });
   __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): nothing the compiler tracks is in flight from here on
-  for (; s0 + 2 * F_PD < S; s0 += F_PD) {
-    stream_iter(ic<0>{}, bc<true>{}, s0);     stream_iter(ic<1>{}, bc<true>{}, s0 + 1);
-    stream_iter(ic<2>{}, bc<true>{}, s0 + 2); stream_iter(ic<3>{}, bc<true>{}, s0 + 3);
-    stream_iter(ic<4>{}, bc<true>{}, s0 + 4); stream_iter(ic<5>{}, bc<true>{}, s0 + 5);
-    stream_iter(ic<6>{}, bc<true>{}, s0 + 6); stream_iter(ic<7>{}, bc<true>{}, s0 + 7);
-  }
+  for (; s0 + 2 * F_PD < S; s0 += F_PD)
+    unrolled<F_PD>([&](auto I) __attribute__((always_inline)) { stream_iter(I, bc<true>{}, s0 + I.value); });
   // the loads of the last trip are still in flight and unknown to the compiler
-  asm volatile("s_waitcnt vmcnt(0)"
-               : "+v"(xb[0][0]), "+v"(xb[0][1]), "+v"(xb[1][0]), "+v"(xb[1][1]), "+v"(xb[2][0]), "+v"(xb[2][1]),
-                 "+v"(xb[3][0]), "+v"(xb[3][1]), "+v"(xb[4][0]), "+v"(xb[4][1]), "+v"(xb[5][0]), "+v"(xb[5][1]),
-                 "+v"(xb[6][0]), "+v"(xb[6][1]), "+v"(xb[7][0]), "+v"(xb[7][1]));
-  for (; s0 < total; s0 += F_PD) stream_generic(s0);
+  unrolled<F_PD>([&](auto I) __attribute__((always_inline)) { wait_slab<0>(xb[I.value][0], xb[I.value][1]); });
+  for (; s0 < total; s0 += F_PD)
+    unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
+      if (s0 + I.value < total) stream_iter(I, bc<false>{}, s0 + I.value);
+    });
+  if (pending) accumulate();
 }
 
 // Chooses the cluster geometry; returns false if the single-pass path does not apply.
