@@ -3,7 +3,7 @@
 
 Calls only the CPU oracle (oracle/) and the seeded input generators (cada_synth/); nothing
 here touches the GPU library.  Each .npz holds the oracle's trace (mask, lhs, rhs, tau),
-the final iterate (all of it up to 2^17 coordinates, else every `stride`-th coordinate plus
+the final iterate (all of it up to 2^16 coordinates, else every `stride`-th coordinate plus
 its norm) and a fingerprint of the inputs so that a test can tell a stale file.
 
     python tests/golden/make_goldens.py [case ...]
@@ -27,6 +27,11 @@ from oracle.driver import oracle_for        # noqa: E402
 CASES = {
     "cfg3_full_c0.3": (configs.CFG3, 3),
     "cfg3_full_c1e-4": (configs.CFG3.scaled(c=1e-4), 4),
+    "cfg4_full": (configs.CFG4, 12),
+    "cfg5_full": (configs.CFG5, 8),
+    # larger c than the workloads' 0.5, with which every worker uploads in the first steps
+    "cfg4_full_c3": (configs.CFG4.scaled(c=3.0), 12),
+    "cfg5_full_c20": (configs.CFG5.scaled(c=20.0), 8),
 }
 
 
@@ -41,7 +46,7 @@ def fingerprint(cfg, prob, sched) -> int:
 
 
 def theta_sample(theta):
-    stride = 1 if theta.size <= (1 << 17) else int(np.ceil(theta.size / (1 << 17)))
+    stride = 1 if theta.size <= (1 << 16) else int(np.ceil(theta.size / (1 << 16)))
     return theta[::stride].copy(), stride
 
 
@@ -51,13 +56,22 @@ def make(name):
     prob = generators.make_problem(cfg)
     sched = generators.make_schedule(cfg, K)
     o = oracle_for(cfg, prob)
+    first = {}
     for k in range(K):
         o.step(sched[k])
+        if k == 0:   # every worker uploads at step 0: the stored gradients are the gradients at theta0
+            first = dict(G0_first=theta_sample(o.G[0])[0], G0_last=theta_sample(o.G[-1])[0],
+                         G0_norms=np.linalg.norm(o.G, axis=1))
         print("  %s step %d/%d  %.0fs" % (name, k + 1, K, time.time() - t0), flush=True)
     tr = o.trace_arrays()
     th, stride = theta_sample(o.theta)
+    # stored gradient of the first and the last worker, sampled like the iterate, and every
+    # worker's stored-gradient norm: a direct check of the gradient kernels at full size
+    G_first, _ = theta_sample(o.G[0])
+    G_last, _ = theta_sample(o.G[-1])
     np.savez_compressed(os.path.join(HERE, name + ".npz"), mask=tr["mask"], own_mask=tr["own_mask"], lhs=tr["lhs"],
                         rhs=tr["rhs"], tau=tr["tau"], tau_final=o.tau, theta=th, theta_stride=stride,
+                        G_first=G_first, G_last=G_last, G_norms=np.linalg.norm(o.G, axis=1), **first,
                         theta_norm=np.linalg.norm(o.theta), h_norm=np.linalg.norm(o.h),
                         vhat_norm=np.linalg.norm(o.vhat), ring=o.ring, uploads_total=o.uploads_total,
                         fingerprint=fingerprint(cfg, prob, sched), K=K)

@@ -1,0 +1,73 @@
+"""The two MLP workloads at their full size (784-512-10 with 64 workers of 128 rows;
+3072-1024-1024-10 with 16 workers of 256 rows), in the launch configuration bench.py times,
+against stored fp64 oracle results written by tests/golden/make_goldens.py.  The library
+replays the oracle's upload decisions (so that both follow one trajectory) and its own
+decisions are compared with the oracle's where the rule's margin exceeds the accuracy of
+the bf16 contractions."""
+import os
+
+import numpy as np
+import pytest
+
+from cada_synth import configs, generators
+
+from common import run_library, upload, rel_l2
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+BF16_TOL = 2e-2
+
+CASES = {
+    "cfg4_full": configs.CFG4,
+    "cfg4_full_c3": configs.CFG4.scaled(c=3.0),
+    "cfg5_full": configs.CFG5,
+    "cfg5_full_c20": configs.CFG5.scaled(c=20.0),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_full_size_mlp_steps_match_stored_oracle(name):
+    from tests_golden_fingerprint import fingerprint
+    cfg = CASES[name]
+    g = np.load(os.path.join(GOLD, name + ".npz"))
+    K = int(g["K"])
+    prob = generators.make_problem(cfg)
+    sched = generators.make_schedule(cfg, K)
+    assert fingerprint(cfg, prob, sched) == int(g["fingerprint"]), "stored oracle results are stale: rerun make_goldens.py"
+    dev = upload(prob)
+    stride = int(g["theta_stride"])
+    # step 0 alone: every worker uploads, so the stored gradients are the gradients at theta0,
+    # the same point in both implementations -- the accuracy of the contractions themselves
+    one = run_library(cfg, dev, sched[:1])
+    assert one["error_flags"][0] == 0 and one["trace_mask"].all()
+    g0 = {"G0_first": rel_l2(one["stored"][0][::stride], g["G0_first"]),
+          "G0_last": rel_l2(one["stored"][-1][::stride], g["G0_last"]),
+          "G0_norms": float(np.abs(np.linalg.norm(one["stored"].astype(np.float64), axis=1) / g["G0_norms"] - 1).max())}
+    print(name, g0)
+    assert max(g0.values()) < 1e-3, g0
+    out = run_library(cfg, dev, sched, replay=g["mask"])
+    assert out["error_flags"][0] == 0
+    assert np.array_equal(out["trace_mask"], g["mask"]) and np.array_equal(out["trace_tau"], g["tau"])
+    assert np.array_equal(out["tau"], g["tau_final"]) and out["uploads_total"][0] == int(g["uploads_total"])
+    stats = {
+        "theta": rel_l2(out["theta64"][::stride], g["theta"]),
+        "G_first": rel_l2(out["stored"][0][::stride], g["G_first"]),
+        "G_last": rel_l2(out["stored"][-1][::stride], g["G_last"]),
+        "G_norms": float(np.abs(np.linalg.norm(out["stored"].astype(np.float64), axis=1) / g["G_norms"] - 1).max()),
+        "theta_norm": abs(np.linalg.norm(out["theta64"]) / float(g["theta_norm"]) - 1),
+    }
+    big = g["lhs"] > 1e-9 * g["lhs"].max()
+    rel = np.abs(out["trace_lhs"] - g["lhs"])[big] / g["lhs"][big]
+    stats["lhs_rel_median"], stats["lhs_rel_max"] = float(np.median(rel)), float(rel.max())
+    margin = np.abs(g["lhs"] - g["rhs"][:, None]) / np.maximum(g["rhs"][:, None], 1e-300)
+    own_diff = out["trace_own_mask"] != g["own_mask"]
+    stats["own_disagreements"] = int(own_diff.sum())
+    stats["own_disagreements_outside_margin"] = int((own_diff & (margin > 0.05)).sum())
+    print(name, stats)
+    # after K steps the two iterates differ (by `theta`), and a gradient is far more sensitive
+    # to the point it is taken at than the point is to a gradient: G is held to 1e-1 only
+    assert stats["theta"] < BF16_TOL and stats["G_first"] < 1e-1 and stats["G_last"] < 1e-1
+    assert stats["G_norms"] < BF16_TOL and stats["theta_norm"] < 1e-3
+    assert stats["lhs_rel_median"] < 1e-2 and stats["lhs_rel_max"] < 0.2
+    assert stats["own_disagreements_outside_margin"] == 0
+    np.testing.assert_allclose(out["trace_rhs"], g["rhs"], rtol=BF16_TOL)
