@@ -45,6 +45,22 @@ def algorithmic_flops_per_step(cfg) -> float:
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
+def stored_traffic(workload: str):
+    """HBM bytes per launch of the single-pass kernel from the committed rocprofv3 --pmc
+    summary, or None when there is none or the kernel's source changed since it was taken."""
+    import hashlib
+    here = os.path.dirname(os.path.abspath(__file__))
+    path = os.path.join(here, "profiles", "k_fused_%s_traffic.json" % workload)
+    src = os.path.join(here, "paper_2012_15469_amd", "csrc", "cada_logreg_fused.hip")
+    try:
+        rec = json.load(open(path))
+        if rec["kernel_source_sha256"] != hashlib.sha256(open(src, "rb").read()).hexdigest():
+            return None
+        return rec["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +68,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the HBM-bound logistic workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plain-launch", action="store_true",
+                    help="launch the single-pass kernel without the cooperative-launch API (rocprofv3 on this "
+                         "image crashes at exit after tracing a cooperative dispatch); same grid, same kernel")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one elementwise pass over 1 GiB (reads 1 GiB, writes 1 GiB): the kernel of known "
+                         "size that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: every box here has one, and the path uses no collectives "
@@ -64,6 +86,8 @@ def main() -> int:
     from paper_2012_15469_amd import binding
     from paper_2012_15469_amd.binding import Cada
 
+    if args.plain_launch:
+        os.environ["CADA_FUSED_PLAIN_LAUNCH"] = "1"
     cfg = configs.ALL[args.config]
     dev = torch.device("cuda:0")
     K, W = args.steps, args.warmup
@@ -109,13 +133,16 @@ def main() -> int:
            "kernel_ms": {k: v for k, v in prof.items() if k != "steps"}}
 
     if cfg.model == "logreg":
-        # the two streaming passes over the gathered rows together form the gradient phase;
-        # its algorithmic bytes are those of the whole step (rows counted once)
-        grad_ms = prof["logreg_dots"] + prof["logreg_grad"]
+        # the gradient phase is one launch of the single-pass kernel (p >= 8192) or the two
+        # streaming passes over the gathered rows; its algorithmic bytes are those of the whole
+        # step (rows counted once)
+        single = "logreg_single_pass" in prof
+        grad_ms = sum(v for k, v in prof.items() if k.startswith("logreg_"))
         alg = algorithmic_bytes_per_step(cfg)
         achieved = alg / (grad_ms * 1e-3) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "logreg_dots+logreg_grad", "achieved": achieved,
-                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+        out["roofline"] = {"bound": "hbm", "kernel": "k_fused" if single else "k_dots+k_grad", "achieved": achieved,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": stored_traffic(cfg.name) if single else None,
                            "algorithmic_bytes_per_launch": alg, "avg_launch_ms": grad_ms}
 
     if cfg.model == "mlp":
@@ -126,6 +153,13 @@ def main() -> int:
                            "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                            "algorithmic_flops_per_launch": fl, "avg_launch_ms": ms}
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_cpu_baseline:
         from oracle.driver import oracle_for

@@ -100,7 +100,8 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   g->n_col_chunks = (int)((cfg->p + g->chunk_cols - 1) / g->chunk_cols);
   const int64_t per_block = (int64_t)kBlock * g->vec;
   g->n_lhs_part = (int)((cfg->p + per_block - 1) / per_block);
-  g->n_ring_part = g->n_lhs_part;
+  // server kernel: one block per 256 coordinates, see cada_server.hip
+  g->n_ring_part = (int)((cfg->p + 255) / 256);
   if (cfg->model == CADA_MODEL_MLP) g->n_lhs_part = mlp_lhs_slots(cfg);
   const int fused_slots = 4 * (int)((cfg->p + 2047) / 2048);
   g->lhs_cap = g->n_lhs_part > fused_slots ? g->n_lhs_part : fused_slots;
@@ -253,7 +254,8 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   if (cfg->model == CADA_MODEL_LOGREG) {
     if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = 4 * c->fused_Q;
     c->n_phases = 4;
-    c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad";
+    if (c->fused) { c->phase_names[0] = "logreg_single_pass"; c->phase_names[1] = "logreg_unused"; }
+    else { c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad"; }
     c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
   }
   if (cfg->model == CADA_MODEL_MLP) {

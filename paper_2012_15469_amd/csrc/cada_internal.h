@@ -97,7 +97,7 @@ struct Ctx {
   float *zpart;              // [M][B][n_col_chunks][2]
   int n_server_blocks;
   // single-pass (register-resident) logistic path, cada_logreg_fused.hip
-  int fused, fused_Q, fused_clusters, fused_rs;
+  int fused, fused_Q, fused_clusters, fused_rs, fused_plain_launch;
   int64_t fused_cols;
   uint32_t fused_seq, fused_seq_per_step;
   unsigned long long *fused_post;

@@ -503,6 +503,8 @@ bool fused_plan(Ctx *c, int64_t p, int B, int M) {
   c->fused_clusters = ncl;
   c->fused_cols = ((p + Q - 1) / Q + 3) / 4 * 4;
   c->fused_rs = 1;
+  const char *plain = getenv("CADA_FUSED_PLAIN_LAUNCH");
+  c->fused_plain_launch = (plain && atoi(plain) != 0) ? 1 : 0;
   const int nslab = B;
   c->fused_seq_per_step = (uint32_t)(((M + ncl - 1) / ncl) * nslab);
   return true;
@@ -522,8 +524,17 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
   c->fused_seq += c->fused_seq_per_step;
   void *args[] = {&a};
   prof_mark(c);
-  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_fused), dim3((unsigned)(a.Q * a.n_clusters)),
-                                                  dim3(F_THREADS), args, (unsigned)kFusedLds, c->stream);
+  hipError_t e;
+  if (c->fused_plain_launch) {
+    // Same grid without the cooperative-launch guarantee: one workgroup per CU is resident at once
+    // on an otherwise idle device, and every wait in the kernel is bounded.  For profilers that
+    // cannot trace cooperative dispatches.
+    hipLaunchKernelGGL(k_fused, dim3((unsigned)(a.Q * a.n_clusters)), dim3(F_THREADS), kFusedLds, c->stream, a);
+    e = hipGetLastError();
+  } else {
+    e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_fused), dim3((unsigned)(a.Q * a.n_clusters)),
+                                   dim3(F_THREADS), args, (unsigned)kFusedLds, c->stream);
+  }
   prof_mark(c);
   prof_mark(c);
   if (e != hipSuccess) {

@@ -8,10 +8,9 @@
 
 namespace cada {
 
-// Folds the per-block partial sums of the squared step of iteration k-1 into
-// ring[(k-1) mod d_max].  Called by the whole block; fixed summation order.
-__device__ void finalize_ring(const DevState &s, int64_t k, double *red /* [kBlock] LDS */) {
-  if (k <= 0) return;
+// Sum of the per-block partial sums of the squared step of iteration k-1 (the value of
+// ring[(k-1) mod d_max]), in a fixed order; called by the whole block, valid in every thread.
+__device__ float last_step_sq(const DevState &s, double *red /* [kBlock] LDS */) {
   double acc = 0.0;
   for (int i = threadIdx.x; i < s.n_ring_part; i += kBlock) acc += (double)s.ring_part[i];
   red[threadIdx.x] = acc;
@@ -20,137 +19,165 @@ __device__ void finalize_ring(const DevState &s, int64_t k, double *red /* [kBlo
     if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
     __syncthreads();
   }
-  if (threadIdx.x == 0) s.ring[(k - 1) % s.d_max] = (float)red[0];
+  const float r = (float)red[0];
   __syncthreads();
+  return r;
 }
 
-// One block.  S3 of the step: RHS, per-worker decision, tau, pointer swap, trace.
+// S3 of the step: RHS, per-worker decision, tau, pointer swap, trace.  One wavefront per
+// worker, four workers per block; every block forms the RHS itself (same operations, same
+// value), block 0 records it.
 __global__ __launch_bounds__(kBlock) void k_rule(const DevState s, const uint8_t *replay) {
   __shared__ double red[kBlock];
-  __shared__ double rhs_s;
   __shared__ unsigned int cnt;
   const int64_t k = s.k;
-  finalize_ring(s, k, red);
-  if (threadIdx.x == 0) {
-    double sum = 0.0;
-    for (int j = 0; j < s.d_max; ++j) sum += (double)s.ring[j];
-    rhs_s = (s.c / (double)s.d_max) * sum;
-    cnt = 0;
-  }
+  const int last = k > 0 ? (int)((k - 1) % s.d_max) : -1;
+  const float newest = k > 0 ? last_step_sq(s, red) : 0.f;
+  double sum = 0.0;
+  for (int j = 0; j < s.d_max; ++j) sum += (double)(j == last ? newest : s.ring[j]);
+  const double rhs = (s.c / (double)s.d_max) * sum;
+  if (threadIdx.x == 0) cnt = 0;
   __syncthreads();
-  const double rhs = rhs_s;
   const bool tr = k < s.trace_steps;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  for (int m = wv; m < s.M; m += kBlock / kWave) {     // one wavefront per worker
+  const int m = blockIdx.x * (kBlock / kWave) + wv;
+  if (m < s.M) {
     double lhs = 0.0;
     const float *lp = s.lhs_part + (int64_t)m * s.n_lhs_part;
     for (int t = lane; t < s.n_lhs_part; t += kWave) lhs += (double)lp[t];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) lhs += __shfl_xor(lhs, o, 64);   // fixed tree order
-    if (lane != 0) continue;
-    const int32_t tau = s.tau[m];
-    const bool own = (lhs > rhs) || (tau >= s.D);
-    bool up = own;
-    if (replay != nullptr && replay[m] != CADA_REPLAY_FREE) up = replay[m] != 0;
-    if (tr) {
-      const int64_t o = k * s.M + m;
-      s.t_mask[o] = up ? 1 : 0;
-      s.t_own[o] = own ? 1 : 0;
-      s.t_lhs[o] = (float)lhs;
-      s.t_tau[o] = tau;
-    }
-    s.lhs[m] = (float)lhs;
-    s.mask[m] = up ? 1 : 0;
-    if (up) {
-      s.tau[m] = 1;
-      s.sel[m] ^= 1;       // the fresh row becomes the stored one
-      atomicAdd(&cnt, 1u);
-    } else {
-      s.tau[m] = tau + 1;
+    if (lane == 0) {
+      const int32_t tau = s.tau[m];
+      const bool own = (lhs > rhs) || (tau >= s.D);
+      bool up = own;
+      if (replay != nullptr && replay[m] != CADA_REPLAY_FREE) up = replay[m] != 0;
+      if (tr) {
+        const int64_t o = k * s.M + m;
+        s.t_mask[o] = up ? 1 : 0;
+        s.t_own[o] = own ? 1 : 0;
+        s.t_lhs[o] = (float)lhs;
+        s.t_tau[o] = tau;
+      }
+      s.lhs[m] = (float)lhs;
+      s.mask[m] = up ? 1 : 0;
+      if (up) {
+        s.tau[m] = 1;
+        s.sel[m] ^= 1;       // the fresh row becomes the stored one
+        atomicAdd(&cnt, 1u);
+      } else {
+        s.tau[m] = tau + 1;
+      }
     }
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    *s.uploads += cnt;
-    if (tr) s.t_rhs[k] = (float)rhs;
+    if (cnt) atomicAdd(reinterpret_cast<unsigned long long *>(s.uploads), (unsigned long long)cnt);
+    if (blockIdx.x == 0) {
+      if (last >= 0) s.ring[last] = newest;
+      if (tr) s.t_rhs[k] = (float)rhs;
+    }
   }
 }
 
 // One block; used when the state is read out after the last step.
 __global__ __launch_bounds__(kBlock) void k_ring_finalize(const DevState s) {
   __shared__ double red[kBlock];
-  finalize_ring(s, s.k, red);
+  if (s.k <= 0) return;
+  const float newest = last_step_sq(s, red);
+  if (threadIdx.x == 0) s.ring[(s.k - 1) % s.d_max] = newest;
 }
 
-// S5-S7.  grid = n_ring_part blocks, one (VEC-wide) coordinate group per thread.
+// S5-S7.  A block owns 256 coordinates, four per lane: consecutive ones read as one 16-byte
+// access when every row start is 16-byte aligned (VEC == 4), else the coordinates lane,
+// lane + 64, lane + 128, lane + 192 of the block's range (VEC == 1, coalesced scalar accesses).
+// Wavefront w sums the stored gradients of workers w, w+4, w+8, ... for them, the four sums
+// are combined through LDS in a fixed order, and wavefront 0 applies the update.
+// grid = n_ring_part = ceil(p / 256) blocks.
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
-  __shared__ float red[4];
-  const int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+  __shared__ float part[4][4][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int64_t base = (int64_t)blockIdx.x * 256;
   const int64_t mp = (int64_t)s.M * s.p;
-  float sq = 0.f;
-  if (j < s.p) {
-    float nab[VEC];
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) nab[v] = 0.f;
-    for (int m = 0; m < s.M; ++m) {
-      const float *row = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p + j;
-      if constexpr (VEC == 4) {
-        const float4 t = *reinterpret_cast<const float4 *>(row);
-        nab[0] += t.x; nab[1] += t.y; nab[2] += t.z; nab[3] += t.w;
-      } else {
-        nab[0] += *row;
+  // coordinate of this lane's v-th value, and whether it exists
+  auto coord = [&](int v) -> int64_t { return VEC == 4 ? base + lane * 4 + v : base + lane + 64 * v; };
+  auto get = [&](const float *x, float (&o)[4]) {
+    if constexpr (VEC == 4) {
+      if (coord(0) < s.p) {
+        const float4 t = *reinterpret_cast<const float4 *>(x + coord(0));
+        o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w;
       }
-    }
-    const float fM = (float)s.M;
-    float th[VEC], tl[VEC], hh[VEC], vv[VEC], vh[VEC];
+    } else {
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      const int64_t i = j + v;
-      nab[v] = nab[v] / fM;
-      // beta*x + (1-beta)*y written as x + (1-beta)*(y - x): float32(0.999) is off by 1.3e-8
-      // relative, which compounds to 1e-5 over the ~1000-step memory of vhat, whereas
-      // float32(1-beta) enters only linearly
-      const float ho = s.h[i];
-      hh[v] = fmaf(s.omb1, nab[v] - ho, ho);
-      const float vo = s.vhat[i];
-      vv[v] = fmaf(s.omb2, nab[v] * nab[v] - vo, vo);
-      vh[v] = fmaxf(vv[v], vo);
-      const float step = s.alpha * hh[v] / sqrtf(s.eps + vh[v]);
-      // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
-      const float a = s.theta[i], ms = -step;
-      const float sum = a + ms;
-      const float bb = sum - a;
-      const float err = (a - (sum - bb)) + (ms - bb);
-      const float lo = s.theta_lo[i] + err;
-      th[v] = sum + lo;
-      tl[v] = lo - (th[v] - sum);
-      sq = fmaf(step, step, sq);
+      for (int v = 0; v < 4; ++v)
+        if (coord(v) < s.p) o[v] = x[coord(v)];
     }
-    const bool snap = (s.rule == CADA_RULE_CADA1) && ((s.k + 1) % s.D == 0);
-    float *hs = (s.rule == CADA_RULE_CADA2) ? s.hist + ((s.k + 1) % s.R) * s.p : nullptr;
-    float *hl = (s.rule == CADA_RULE_CADA2) ? s.hist_lo + ((s.k + 1) % s.R) * s.p : nullptr;
+  };
+  auto put = [&](float *x, const float (&o)[4]) {
+    if constexpr (VEC == 4) {
+      if (coord(0) < s.p) *reinterpret_cast<float4 *>(x + coord(0)) = make_float4(o[0], o[1], o[2], o[3]);
+    } else {
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      const int64_t i = j + v;
-      s.nabla[i] = nab[v];
-      s.h[i] = hh[v];
-      s.v[i] = vv[v];
-      s.vhat[i] = vh[v];
-      s.theta[i] = th[v];
-      s.theta_lo[i] = tl[v];
-      if (hs) { hs[i] = th[v]; hl[i] = tl[v]; }
-      if (snap) { s.snap[i] = th[v]; s.snap_lo[i] = tl[v]; }
+      for (int v = 0; v < 4; ++v)
+        if (coord(v) < s.p) x[coord(v)] = o[v];
     }
+  };
+  float nab[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int m = w; m < s.M; m += 4) {
+    float t[4] = {0.f, 0.f, 0.f, 0.f};
+    get(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p, t);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) nab[v] += t[v];
   }
-  const float tot = block_sum(sq, red);
-  if (threadIdx.x == 0) s.ring_part[blockIdx.x] = tot;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[w][v][lane] = nab[v];
+  __syncthreads();
+  if (w != 0) return;
+  float sq = 0.f;
+  const float fM = (float)s.M;
+  float th[4] = {0.f, 0.f, 0.f, 0.f}, tl[4] = {0.f, 0.f, 0.f, 0.f}, hh[4] = {0.f, 0.f, 0.f, 0.f};
+  float vv[4], vh[4] = {0.f, 0.f, 0.f, 0.f};
+  get(s.h, hh); get(s.vhat, vh); get(s.theta, th); get(s.theta_lo, tl);
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    nab[v] = ((part[0][v][lane] + part[1][v][lane]) + (part[2][v][lane] + part[3][v][lane])) / fM;
+    // beta*x + (1-beta)*y written as x + (1-beta)*(y - x): float32(0.999) is off by 1.3e-8
+    // relative, which compounds to 1e-5 over the ~1000-step memory of vhat, whereas
+    // float32(1-beta) enters only linearly
+    const float ho = hh[v];
+    hh[v] = fmaf(s.omb1, nab[v] - ho, ho);
+    const float vo = vh[v];
+    vv[v] = fmaf(s.omb2, nab[v] * nab[v] - vo, vo);
+    vh[v] = fmaxf(vv[v], vo);
+    const float step = s.alpha * hh[v] / sqrtf(s.eps + vh[v]);
+    // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
+    const float a = th[v], ms = -step;
+    const float sum = a + ms;
+    const float bb = sum - a;
+    const float err = (a - (sum - bb)) + (ms - bb);
+    const float lo = tl[v] + err;
+    th[v] = sum + lo;
+    tl[v] = lo - (th[v] - sum);
+    if (coord(v) < s.p) sq = fmaf(step, step, sq);
+  }
+  put(s.nabla, nab); put(s.h, hh); put(s.v, vv); put(s.vhat, vh); put(s.theta, th); put(s.theta_lo, tl);
+  if (s.rule == CADA_RULE_CADA2) {
+    put(s.hist + ((s.k + 1) % s.R) * s.p, th);
+    put(s.hist_lo + ((s.k + 1) % s.R) * s.p, tl);
+  } else if (s.rule == CADA_RULE_CADA1 && (s.k + 1) % s.D == 0) {
+    put(s.snap, th);
+    put(s.snap_lo, tl);
+  }
+  const float tot = wave_sum(sq);
+  if (lane == 0) s.ring_part[blockIdx.x] = tot;
 }
 
 int rule_and_server(Ctx *c, const uint8_t *replay) {
   DevState s = c->s;
   s.k = c->k;
-  hipLaunchKernelGGL(k_rule, dim3(1), dim3(kBlock), 0, c->stream, s, replay);
+  hipLaunchKernelGGL(k_rule, dim3((unsigned)((s.M + 3) / 4)), dim3(kBlock), 0, c->stream, s, replay);
   prof_mark(c);
   if (c->vec == 4)
     hipLaunchKernelGGL(k_server<4>, dim3(s.n_ring_part), dim3(kBlock), 0, c->stream, s);
