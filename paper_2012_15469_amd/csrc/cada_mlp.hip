@@ -48,6 +48,8 @@ namespace cada {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef uint16_t bf16_t;   // storage type
+struct ic0 { static constexpr int value = 0; };
+struct ic1 { static constexpr int value = 1; };
 
 __device__ __forceinline__ bf16_t f2bf(float f) {
   uint32_t u = __float_as_uint(f);
@@ -62,7 +64,8 @@ static inline int64_t P8(int64_t x) { return (x + 7) / 8 * 8; }
 constexpr int BM = 128, BN = 128, BK = 32, PITCH = BK + 8;
 constexpr int TILE = 128 * PITCH;                 // bf16 elements of one staged tile
 constexpr int kMaxSlots = 4;
-constexpr size_t kMm5Lds = (size_t)2 * kMaxSlots * TILE * sizeof(bf16_t);   // 80 KB
+constexpr int kStages = 2;                        // LDS tile sets: one being multiplied, one being filled
+constexpr size_t mm5_lds_bytes(int n_slots) { return (size_t)kStages * n_slots * TILE * sizeof(bf16_t); }   // <= 140 KB for 7 tensors
 
 enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
 
@@ -110,11 +113,19 @@ __device__ __forceinline__ uint2 pack4(const bf16_t (&v)[4]) {
   return make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
 }
 
-template <int EPI>
+// NA, NB: tensors on the A and the B side (compile-time, so that every load of the main loop is
+// unconditional: the compiler places a wait for a load from the number of loads it can prove
+// were issued after it, and a load that a branch may skip counts for nothing).  HAS_D: the
+// product Ad Bx^T is present.
+//
+// Main loop: tile step h is multiplied from LDS stage h%2 while step h+1 moves from registers to
+// the other stage and the loads of step h+3 are issued into the registers that frees: a load has
+// two tile steps (about 2 x 0.6 us) to arrive, and there is one barrier per step.
+template <int EPI, int NA, int NB, bool HAS_D>
 __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = reinterpret_cast<bf16_t *>(smem_raw);
-  bf16_t *ldsA = lds, *ldsB = lds + kMaxSlots * TILE;
+  constexpr int NS = NA + NB;
   const DevState &s = g.s;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int wy = w >> 1, wx = w & 1;
@@ -130,57 +141,55 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) { acc1[i][j][r] = 0.f; acc2[i][j][r] = 0.f; }
 
-  // this thread's two 16-byte chunks of a 128 x 32 tile: rows (t>>2) and (t>>2)+64, k offset (t&3)*8
+  // this thread's two 16-byte chunks of a 128 x 32 tile: rows (t>>2) and (t>>2)+64, k offset (t&3)*8.
+  // Rows beyond the extent are read from the last valid row and zeroed on the way to LDS.
   const int crow = t >> 2, ck = (t & 3) * 8;
-  uint4 ra[kMaxSlots][2], rb[kMaxSlots][2];
-  auto load_tiles = [&](int k0) {
-    const int k = k0 + ck;
+  const bf16_t *pa[NA][2], *pb[NB][2];
+  bool oka[2], okb[2];
 #pragma unroll
-    for (int sl = 0; sl < kMaxSlots; ++sl) {
-      if (sl < g.A.n) {
-        const bf16_t *base = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl];
+  for (int c = 0; c < 2; ++c) {
+    const int ra = m0 + crow + c * 64, rb = n0 + crow + c * 64;
+    oka[c] = ra < g.M; okb[c] = rb < g.N;
+    const int rac = oka[c] ? ra : g.M - 1, rbc = okb[c] ? rb : g.N - 1;
+    const int64_t src = gat ? gat[rac] : (int64_t)rac;
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const int row = m0 + crow + c * 64;
-          uint4 v = make_uint4(0u, 0u, 0u, 0u);
-          if (row < g.M && k < g.K) {
-            const int64_t src = gat ? gat[row] : (int64_t)row;
-            v = *reinterpret_cast<const uint4 *>(base + src * g.A.ld[sl] + k);
-          }
-          ra[sl][c] = v;
-        }
-      }
-      if (sl < g.B.n) {
-        const bf16_t *base = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl];
+    for (int sl = 0; sl < NA; ++sl) pa[sl][c] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + src * g.A.ld[sl] + ck;
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const int row = n0 + crow + c * 64;
-          uint4 v = make_uint4(0u, 0u, 0u, 0u);
-          if (row < g.N && k < g.K) v = *reinterpret_cast<const uint4 *>(base + (int64_t)row * g.B.ld[sl] + k);
-          rb[sl][c] = v;
-        }
-      }
-    }
+    for (int sl = 0; sl < NB; ++sl) pb[sl][c] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl] + (int64_t)rbc * g.B.ld[sl] + ck;
+  }
+  uint4 R[2][NS][2];          // two register sets of tile chunks in flight
+  bool kin[2];                // whether the chunk's k offset lies inside the contraction
+  auto issue = [&](auto BUF, int step) __attribute__((always_inline)) {
+    constexpr int bu = decltype(BUF)::value;
+    const int k = step * BK;
+    kin[bu] = k + ck < g.K;
+    const int koff = kin[bu] ? k : 0;          // always a valid address
+#pragma unroll
+    for (int sl = 0; sl < NA; ++sl)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) R[bu][sl][c] = *reinterpret_cast<const uint4 *>(pa[sl][c] + koff);
+#pragma unroll
+    for (int sl = 0; sl < NB; ++sl)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) R[bu][NA + sl][c] = *reinterpret_cast<const uint4 *>(pb[sl][c] + koff);
   };
-  auto store_tiles = [&]() {
+  auto stash = [&](auto BUF, int stage) __attribute__((always_inline)) {
+    constexpr int bu = decltype(BUF)::value;
+    bf16_t *base = lds + (size_t)stage * NS * TILE + (crow * PITCH + ck);
 #pragma unroll
-    for (int sl = 0; sl < kMaxSlots; ++sl) {
+    for (int sl = 0; sl < NS; ++sl)
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        if (sl < g.A.n) *reinterpret_cast<uint4 *>(ldsA + sl * TILE + (crow + c * 64) * PITCH + ck) = ra[sl][c];
-        if (sl < g.B.n) *reinterpret_cast<uint4 *>(ldsB + sl * TILE + (crow + c * 64) * PITCH + ck) = rb[sl][c];
+        const bool ok = kin[bu] && (sl < NA ? oka[c] : okb[c]);
+        uint4 v = R[bu][sl][c];
+        v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+        *reinterpret_cast<uint4 *>(base + sl * TILE + c * 64 * PITCH) = v;
       }
-    }
   };
 
-  const bool has_lo = g.a_l >= 0, has_d = g.a_d >= 0, has_r = g.a_r >= 0;
   const int fro = (lane & 31) * PITCH + (lane >> 5) * 8;   // fragment offset of this lane inside a 32-row band
-  load_tiles(0);
-  for (int k0 = 0; k0 < g.K; k0 += BK) {
-    __syncthreads();
-    store_tiles();
-    __syncthreads();
-    if (k0 + BK < g.K) load_tiles(k0 + BK);
+  auto multiply = [&](int stage) __attribute__((always_inline)) {
+    const bf16_t *ldsA = lds + (size_t)stage * NS * TILE, *ldsB = ldsA + NA * TILE;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       bf16x8 ah[2], al[2], ad[2], ar[2], bh[2], bl[2], bx[2], bd[2];
@@ -188,32 +197,61 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
       for (int i = 0; i < 2; ++i) {
         const int o = (wy * 64 + i * 32) * PITCH + fro + ks;
         ah[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_h * TILE + o);
-        if (has_lo) al[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_l * TILE + o);
-        if (has_d) ad[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_d * TILE + o);
-        if (has_r) ar[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_r * TILE + o);
+        al[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_l * TILE + o);
+        if constexpr (HAS_D) ad[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_d * TILE + o);
+        // with fewer than four A tensors the reference operand is the hi part itself
+        if constexpr (NA == 4) ar[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_r * TILE + o);
+        else ar[i] = ah[i];
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int o = (wx * 64 + j * 32) * PITCH + fro + ks;
         bh[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_h * TILE + o);
-        if (has_lo) bl[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_l * TILE + o);
-        if (has_d) bx[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_x * TILE + o);
-        if (has_r) bd[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_d * TILE + o);
+        bl[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_l * TILE + o);
+        // with fewer than four B tensors the single-bf16 operand is the hi part itself
+        if constexpr (HAS_D) {
+          if constexpr (NB == 4) bx[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_x * TILE + o);
+          else bx[j] = bh[j];
+        }
+        bd[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_d * TILE + o);
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          if (has_lo) {
-            acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc1[i][j], 0, 0, 0);
-            acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc1[i][j], 0, 0, 0);
-          }
+          acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc1[i][j], 0, 0, 0);
+          acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc1[i][j], 0, 0, 0);
           acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc1[i][j], 0, 0, 0);
-          if (has_d) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad[i], bx[j], acc2[i][j], 0, 0, 0);
-          if (has_r) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ar[i], bd[j], acc2[i][j], 0, 0, 0);
+          if constexpr (HAS_D) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad[i], bx[j], acc2[i][j], 0, 0, 0);
+          acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ar[i], bd[j], acc2[i][j], 0, 0, 0);
         }
     }
+  };
+
+  // steps are taken in pairs (the two register sets alternate); an odd count gets one step of
+  // zeros, and the loads issued for steps beyond the end re-read the first step and are dropped
+  const int nk = (g.K + BK - 1) / BK, nk2 = (nk + 1) & ~1;
+  issue(ic0{}, 0);
+  issue(ic1{}, 1);
+  stash(ic0{}, 0);
+  issue(ic0{}, 2);
+  __syncthreads();
+  // The instruction scheduler is fenced at the phase boundaries: left alone it sinks the loads to
+  // the end of a step and hoists the zeroing selects of the *next* step's chunks (and with them
+  // the wait for loads issued only one step earlier) into the current step's multiply phase.
+  for (int h = 0; h < nk2; h += 2) {
+    __builtin_amdgcn_sched_barrier(0);
+    stash(ic1{}, 1);  issue(ic1{}, h + 3);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    stash(ic0{}, 0);  issue(ic0{}, h + 4);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(1);
+    __syncthreads();
   }
+  __builtin_amdgcn_sched_barrier(0);
   __syncthreads();   // LDS is free for the epilogue
 
   // accumulator element (i, j, r) is output (row, col):
@@ -730,9 +768,28 @@ void side_add(Side &sd, const bf16_t *p, int64_t ld, int64_t bstride) {
   sd.ptr[sd.n] = p; sd.ld[sd.n] = ld; sd.bstride[sd.n] = bstride; sd.n += 1;
 }
 
-template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
+// The (tensor count, product set) combinations the layers use.
+template <int EPI, int NA, int NB, bool HAS_D> hipError_t mm5_allow_lds() {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)mm5_lds_bytes(NA + NB));
+}
+template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const Mm5Args &g, int workers) {
   const dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, workers);
-  hipLaunchKernelGGL(k_mm5<EPI>, grid, dim3(kBlock), kMm5Lds, c->stream, g);
+  hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D>), grid, dim3(kBlock), mm5_lds_bytes(NA + NB), c->stream, g);
+}
+// first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
+template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
+  const bool has_d = g.a_d >= 0;
+  if constexpr (EPI == EPI_DW) {
+    if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g, workers);
+    if (has_d && g.A.n == 3 && g.B.n == 4) return launch_mm5_as<EPI, 3, 4, true>(c, g, workers);
+  } else if constexpr (EPI == EPI_DA) {
+    if (has_d && g.A.n == 4 && g.B.n == 3) return launch_mm5_as<EPI, 4, 3, true>(c, g, workers);
+  } else {
+    if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g, workers);
+    if (has_d && g.A.n == 4 && g.B.n == 3) return launch_mm5_as<EPI, 4, 3, true>(c, g, workers);
+  }
+  set_error("internal: no MFMA kernel variant for %d + %d tensors", g.A.n, g.B.n);
 }
 
 Mm5Args blank(const DevState &s, const MlpPlan &P) {
@@ -749,10 +806,13 @@ Mm5Args blank(const DevState &s, const MlpPlan &P) {
 int mlp_init_state(Ctx *c, const float *) {
   MlpPlan &P = *static_cast<MlpPlan *>(c->mlp);
   hipError_t e = hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_FWD_HIDDEN>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_STORE2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_DW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI_DA>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMm5Lds);
+  e = mm5_allow_lds<EPI_FWD_HIDDEN, 2, 3, false>();
+  if (e == hipSuccess) e = mm5_allow_lds<EPI_FWD_HIDDEN, 4, 3, true>();
+  if (e == hipSuccess) e = mm5_allow_lds<EPI_STORE2, 2, 3, false>();
+  if (e == hipSuccess) e = mm5_allow_lds<EPI_STORE2, 4, 3, true>();
+  if (e == hipSuccess) e = mm5_allow_lds<EPI_DW, 2, 3, false>();
+  if (e == hipSuccess) e = mm5_allow_lds<EPI_DW, 3, 4, true>();
+  if (e == hipSuccess) e = mm5_allow_lds<EPI_DA, 4, 3, true>();
   if (e != hipSuccess) { set_error("hipFuncSetAttribute(LDS size) failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
   const int64_t n = P.total_rows * P.ldx;
   hipLaunchKernelGGL(k_x_to_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->s.X, P.Xh, P.Xl, P.total_rows, P.d[0], P.ldx);
@@ -838,8 +898,13 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
         g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 0;       // innov = A^T dG + dA^T Gref
       }
       side_add(g.B, P.GhT[l], Rp, Bp); side_add(g.B, P.GlT[l], Rp, Bp);
-      side_add(g.B, P.GrefT[l], Rp, Bp); side_add(g.B, P.dGT[l], Rp, Bp);
-      g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
+      if (l == 1) {     // no dA^T Gref term in the first layer
+        side_add(g.B, P.dGT[l], Rp, Bp);
+        g.b_h = 0; g.b_l = 1; g.b_d = 2;
+      } else {
+        side_add(g.B, P.GrefT[l], Rp, Bp); side_add(g.B, P.dGT[l], Rp, Bp);
+        g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
+      }
       g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1];
       launch_mm5<EPI_DW>(c, g, M);
     }

@@ -124,12 +124,22 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
     }
   };
   float nab[4] = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (VEC == 4) {
+    if (coord(0) < s.p) {
+#pragma unroll 5
+      for (int m = w; m < s.M; m += 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p + coord(0));
+        nab[0] += t.x; nab[1] += t.y; nab[2] += t.z; nab[3] += t.w;
+      }
+    }
+  } else {
 #pragma unroll 4
-  for (int m = w; m < s.M; m += 4) {
-    float t[4] = {0.f, 0.f, 0.f, 0.f};
-    get(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p, t);
+    for (int m = w; m < s.M; m += 4) {
+      float t[4] = {0.f, 0.f, 0.f, 0.f};
+      get(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p, t);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) nab[v] += t[v];
+      for (int v = 0; v < 4; ++v) nab[v] += t[v];
+    }
   }
 #pragma unroll
   for (int v = 0; v < 4; ++v) part[w][v][lane] = nab[v];
