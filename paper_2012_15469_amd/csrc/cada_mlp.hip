@@ -65,7 +65,7 @@ constexpr int BM = 128, BN = 128, BK = 32, PITCH = BK + 8;
 constexpr int TILE = 128 * PITCH;                 // bf16 elements of one staged tile
 constexpr int kMaxSlots = 4;
 constexpr int kStages = 2;                        // LDS tile sets: one being multiplied, one being filled
-constexpr size_t mm5_lds_bytes(int n_slots) { return (size_t)kStages * n_slots * TILE * sizeof(bf16_t); }   // <= 140 KB for 7 tensors
+constexpr size_t mm5_lds_bytes(int n_slots, bool deep) { return (size_t)(deep ? kStages : 1) * n_slots * TILE * sizeof(bf16_t); }   // <= 140 KB for 7 tensors
 
 enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
 
@@ -100,6 +100,7 @@ struct Mm5Args {
   // EPI_DW
   int64_t offW;
   int lhs_slot0;
+  int by_worker;                        // 1-D grid, tiles renumbered per XCD (see k_mm5)
 };
 
 __device__ __forceinline__ float delta_theta(const DevState &s, const RefPtr &ref, int64_t i) {
@@ -121,16 +122,31 @@ __device__ __forceinline__ uint2 pack4(const bf16_t (&v)[4]) {
 // Main loop: tile step h is multiplied from LDS stage h%2 while step h+1 moves from registers to
 // the other stage and the loads of step h+3 are issued into the registers that frees: a load has
 // two tile steps (about 2 x 0.6 us) to arrive, and there is one barrier per step.
-template <int EPI, int NA, int NB, bool HAS_D>
-__global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
+//
+// DEEP = false is the shallow variant for contractions over few tile steps with a heavy epilogue
+// (the weight gradients: K = B rows, then 128 x 128 floats stored per tile): one LDS stage and one
+// register set, so that two workgroups fit a CU and one's epilogue overlaps the other's loop.
+template <int EPI, int NA, int NB, bool HAS_D, bool DEEP>
+__global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = reinterpret_cast<bf16_t *>(smem_raw);
   constexpr int NS = NA + NB;
   const DevState &s = g.s;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int wy = w >> 1, wx = w & 1;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int wk = blockIdx.z;                         // worker
+  // Tile of this workgroup.  Workgroups are dealt to the 8 XCDs (each with an L2 of its own) in
+  // turn, so consecutive workgroups never share an L2.  With g.by_worker the tiles are renumbered
+  // so that an XCD works through whole workers: the operands of a weight-gradient contraction
+  // (a few MB per worker) are then read from HBM once instead of once per XCD.
+  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  if (g.by_worker) {
+    const int gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
+    const int lin = blockIdx.x, total = gridDim.x, per = total / 8;
+    const int tix = lin < per * 8 ? (lin % 8) * per + lin / 8 : lin;
+    bx = tix % gx; by = (tix / gx) % gy; bz = tix / (gx * gy);
+  }
+  const int m0 = by * BM, n0 = bx * BN;
+  const int wk = bz;                                 // worker
   const int64_t *gat = g.gatherA ? g.gatherA + (int64_t)wk * g.gstride : nullptr;
 
   f32x16 acc1[2][2], acc2[2][2];
@@ -144,7 +160,13 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
   // this thread's two 16-byte chunks of a 128 x 32 tile: rows (t>>2) and (t>>2)+64, k offset (t&3)*8.
   // Rows beyond the extent are read from the last valid row and zeroed on the way to LDS.
   const int crow = t >> 2, ck = (t & 3) * 8;
-  const bf16_t *pa[NA][2], *pb[NB][2];
+  // (all tensors of a side share the leading dimension, so one element offset per chunk serves them)
+  const bf16_t *basea[NA], *baseb[NB];
+#pragma unroll
+  for (int sl = 0; sl < NA; ++sl) basea[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl];
+#pragma unroll
+  for (int sl = 0; sl < NB; ++sl) baseb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl];
+  int64_t offa[2], offb[2];
   bool oka[2], okb[2];
 #pragma unroll
   for (int c = 0; c < 2; ++c) {
@@ -152,12 +174,10 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
     oka[c] = ra < g.M; okb[c] = rb < g.N;
     const int rac = oka[c] ? ra : g.M - 1, rbc = okb[c] ? rb : g.N - 1;
     const int64_t src = gat ? gat[rac] : (int64_t)rac;
-#pragma unroll
-    for (int sl = 0; sl < NA; ++sl) pa[sl][c] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + src * g.A.ld[sl] + ck;
-#pragma unroll
-    for (int sl = 0; sl < NB; ++sl) pb[sl][c] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl] + (int64_t)rbc * g.B.ld[sl] + ck;
+    offa[c] = src * g.A.ld[0] + ck;
+    offb[c] = (int64_t)rbc * g.B.ld[0] + ck;
   }
-  uint4 R[2][NS][2];          // two register sets of tile chunks in flight
+  uint4 R[DEEP ? 2 : 1][NS][2];   // register sets of tile chunks in flight
   bool kin[2];                // whether the chunk's k offset lies inside the contraction
   auto issue = [&](auto BUF, int step) __attribute__((always_inline)) {
     constexpr int bu = decltype(BUF)::value;
@@ -167,11 +187,11 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
 #pragma unroll
     for (int sl = 0; sl < NA; ++sl)
 #pragma unroll
-      for (int c = 0; c < 2; ++c) R[bu][sl][c] = *reinterpret_cast<const uint4 *>(pa[sl][c] + koff);
+      for (int c = 0; c < 2; ++c) R[bu][sl][c] = *reinterpret_cast<const uint4 *>(basea[sl] + offa[c] + koff);
 #pragma unroll
     for (int sl = 0; sl < NB; ++sl)
 #pragma unroll
-      for (int c = 0; c < 2; ++c) R[bu][NA + sl][c] = *reinterpret_cast<const uint4 *>(pb[sl][c] + koff);
+      for (int c = 0; c < 2; ++c) R[bu][NA + sl][c] = *reinterpret_cast<const uint4 *>(baseb[sl] + offb[c] + koff);
   };
   auto stash = [&](auto BUF, int stage) __attribute__((always_inline)) {
     constexpr int bu = decltype(BUF)::value;
@@ -231,27 +251,40 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
   // steps are taken in pairs (the two register sets alternate); an odd count gets one step of
   // zeros, and the loads issued for steps beyond the end re-read the first step and are dropped
   const int nk = (g.K + BK - 1) / BK, nk2 = (nk + 1) & ~1;
-  issue(ic0{}, 0);
-  issue(ic1{}, 1);
-  stash(ic0{}, 0);
-  issue(ic0{}, 2);
-  __syncthreads();
-  // The instruction scheduler is fenced at the phase boundaries: left alone it sinks the loads to
-  // the end of a step and hoists the zeroing selects of the *next* step's chunks (and with them
-  // the wait for loads issued only one step earlier) into the current step's multiply phase.
-  for (int h = 0; h < nk2; h += 2) {
-    __builtin_amdgcn_sched_barrier(0);
-    stash(ic1{}, 1);  issue(ic1{}, h + 3);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(0);
+  if constexpr (DEEP) {
+    issue(ic0{}, 0);
+    issue(ic1{}, 1);
+    stash(ic0{}, 0);
+    issue(ic0{}, 2);
     __syncthreads();
+    // The instruction scheduler is fenced at the phase boundaries: left alone it sinks the loads to
+    // the end of a step and hoists the zeroing selects of the *next* step's chunks (and with them
+    // the wait for loads issued only one step earlier) into the current step's multiply phase.
+    for (int h = 0; h < nk2; h += 2) {
+      __builtin_amdgcn_sched_barrier(0);
+      stash(ic1{}, 1);  issue(ic1{}, h + 3);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(0);
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      stash(ic0{}, 0);  issue(ic0{}, h + 4);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(1);
+      __syncthreads();
+    }
     __builtin_amdgcn_sched_barrier(0);
-    stash(ic0{}, 0);  issue(ic0{}, h + 4);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(1);
-    __syncthreads();
+  } else {
+    issue(ic0{}, 0);
+    for (int h = 0; h < nk; ++h) {
+      __builtin_amdgcn_sched_barrier(0);
+      stash(ic0{}, 0);
+      __syncthreads();
+      issue(ic0{}, h + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(0);
+      __syncthreads();
+    }
   }
-  __builtin_amdgcn_sched_barrier(0);
   __syncthreads();   // LDS is free for the epilogue
 
   // accumulator element (i, j, r) is output (row, col):
@@ -376,7 +409,7 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
     }
     __syncthreads();
     if (t < 128 && n0 + t < g.N) {
-      const int64_t o = ((int64_t)wk * gridDim.y + blockIdx.y) * g.N + n0 + t;
+      const int64_t o = ((int64_t)wk * ((g.M + BM - 1) / BM) + by) * g.N + n0 + t;
       g.dbpart[o] = red[t * 2] + red[(128 + t) * 2];
       g.ddbpart[o] = red[t * 2 + 1] + red[(128 + t) * 2 + 1];
     }
@@ -387,6 +420,22 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
     const int cur = s.sel[wk];
     float *ivf = cada1 ? s.dtl + ((int64_t)(1 - cur) * s.M + wk) * s.p + g.offW : nullptr;
     const float *ivs = cada1 ? s.dtl + ((int64_t)cur * s.M + wk) * s.p + g.offW : nullptr;
+    // CADA1: the stored innovations of the tile, all loads issued before anything waits for one
+    // (addresses clamped into the matrix so that no load sits under a branch)
+    float old[2][2][16];
+    if (cada1) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int col = min(cbase + j * 32, g.N - 1);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = min(rbase + i * 32 + 8 * (r >> 2) + (r & 3), g.M - 1);
+            old[i][j][r] = ivs[(int64_t)row * g.N + col];
+          }
+        }
+    }
     float sq = 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -400,13 +449,13 @@ __global__ __launch_bounds__(kBlock) void k_mm5(const Mm5Args g) {
             const int64_t o = (int64_t)row * g.N + col;
             gf[o] = acc1[i][j][r];
             float iv = acc2[i][j][r];
-            if (cada1) { ivf[o] = iv; iv -= ivs[o]; }
+            if (cada1) { ivf[o] = iv; iv -= old[i][j][r]; }
             sq = fmaf(iv, iv, sq);
           }
         }
       }
     const float tot = block_sum(sq, red);
-    if (t == 0) s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + blockIdx.y * gridDim.x + blockIdx.x] = tot;
+    if (t == 0) s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + by * ((g.N + BN - 1) / BN) + bx] = tot;
   }
 }
 
@@ -769,17 +818,24 @@ void side_add(Side &sd, const bf16_t *p, int64_t ld, int64_t bstride) {
 }
 
 // The (tensor count, product set) combinations the layers use.
+template <int EPI> constexpr bool mm5_deep() { return EPI != EPI_DW; }
 template <int EPI, int NA, int NB, bool HAS_D> hipError_t mm5_allow_lds() {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)mm5_lds_bytes(NA + NB));
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI, NA, NB, HAS_D, mm5_deep<EPI>()>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)mm5_lds_bytes(NA + NB, mm5_deep<EPI>()));
 }
 template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const Mm5Args &g, int workers) {
-  const dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, workers);
-  hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D>), grid, dim3(kBlock), mm5_lds_bytes(NA + NB), c->stream, g);
+  const unsigned gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
+  const dim3 grid = g.by_worker ? dim3(gx * gy * workers) : dim3(gx, gy, workers);
+  hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D, mm5_deep<EPI>()>), grid, dim3(kBlock), mm5_lds_bytes(NA + NB, mm5_deep<EPI>()),
+                     c->stream, g);
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
 template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
   const bool has_d = g.a_d >= 0;
+  for (int i = 1; i < g.A.n; ++i)
+    if (g.A.ld[i] != g.A.ld[0]) { set_error("internal: A tensors with different leading dimensions"); return; }
+  for (int i = 1; i < g.B.n; ++i)
+    if (g.B.ld[i] != g.B.ld[0]) { set_error("internal: B tensors with different leading dimensions"); return; }
   if constexpr (EPI == EPI_DW) {
     if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g, workers);
     if (has_d && g.A.n == 3 && g.B.n == 4) return launch_mm5_as<EPI, 3, 4, true>(c, g, workers);
@@ -905,7 +961,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
         side_add(g.B, P.GrefT[l], Rp, Bp); side_add(g.B, P.dGT[l], Rp, Bp);
         g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
       }
-      g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1];
+      g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1]; g.by_worker = 1;
       launch_mm5<EPI_DW>(c, g, M);
     }
     if (l >= 2) {   // gradient w.r.t. the activations of layer l-1, masks, bias partials
