@@ -17,8 +17,12 @@ import dataclasses
 from dataclasses import dataclass
 from typing import Tuple
 
+RULE_ALWAYS = 0   # every worker uploads every iteration (distributed Adam/AMSGrad baseline, Section 4)
 RULE_CADA1 = 1
 RULE_CADA2 = 2
+RULE_LAG = 3      # stochastic LAG, condition (LAGrule) of Section 2.1
+SERVER_AMSGRAD = 0
+SERVER_SGD = 1    # theta <- theta - alpha * nabla, the update stochastic LAG follows
 
 
 @dataclass(frozen=True)
@@ -30,7 +34,7 @@ class CadaConfig:
     N_m: int                      # samples per worker (uniform)
     B: int                        # minibatch rows per worker per step
     K: int                        # iterations
-    rule: int                     # RULE_CADA1 | RULE_CADA2
+    rule: int                     # RULE_*
     D: int                        # max delay / CADA1 snapshot period
     d_max: int = 10
     c: float = 0.5
@@ -42,6 +46,7 @@ class CadaConfig:
     gemm_dtype: str = "fp32"      # "fp32" | "bf16" (MLP contractions)
     seed: int = 0
     data: str = ""                # name of the input recipe in generators.py
+    server: int = SERVER_AMSGRAD  # SERVER_*
 
     @property
     def p(self) -> int:

@@ -40,8 +40,12 @@ from typing import Callable, Optional, Sequence
 import numpy as np
 from scipy.special import expit, logsumexp
 
+RULE_ALWAYS = 0      # every worker uploads at every iteration (the distributed Adam/AMSGrad baseline of Section 4)
 RULE_CADA1 = 1
 RULE_CADA2 = 2
+RULE_LAG = 3         # stochastic LAG, condition (LAGrule) of Section 2.1: fresh gradient against the stored one
+SERVER_AMSGRAD = 0   # equations (CADA-1)-(CADA-3)
+SERVER_SGD = 1       # theta <- theta - alpha * nabla (the update stochastic LAG follows, Section 2.1)
 REPLAY_FREE = 255
 
 
@@ -129,8 +133,10 @@ class CadaOracle:
 
     def __init__(self, *, model: str, layer_dims: Sequence[int], M: int, rule: int, D: int,
                  d_max: int, c: float, alpha: float, beta1: float, beta2: float, eps: float,
-                 lam: float, theta0, rows: Callable):
-        assert rule in (RULE_CADA1, RULE_CADA2)
+                 lam: float, theta0, rows: Callable, server: int = SERVER_AMSGRAD):
+        assert rule in (RULE_ALWAYS, RULE_CADA1, RULE_CADA2, RULE_LAG)
+        assert server in (SERVER_AMSGRAD, SERVER_SGD)
+        self.server = server
         self.model, self.dims, self.M, self.rule = model, tuple(layer_dims), M, rule
         self.D, self.d_max, self.c = D, d_max, c
         self.alpha, self.beta1, self.beta2, self.eps, self.lam = alpha, beta1, beta2, eps, lam
@@ -149,7 +155,7 @@ class CadaOracle:
         self.uploads_total = 0
         if rule == RULE_CADA2:
             self.theta_hat = np.tile(self.theta, (M, 1))      # theta^{k - tau_m^k}
-        else:
+        elif rule == RULE_CADA1:
             self.theta_snap = self.theta.copy()               # snapshot theta-tilde
             self.delta_stored = np.zeros((M, p))              # stored delta-tilde_m^{k-tau}
         self.trace = {"mask": [], "own_mask": [], "lhs": [], "rhs": [], "tau": []}
@@ -174,12 +180,18 @@ class CadaOracle:
             g[m] = self.grad(self.theta, X, y)
             if self.rule == RULE_CADA2:
                 diff = g[m] - self.grad(self.theta_hat[m], X, y)
-            else:
+            elif self.rule == RULE_CADA1:
                 delta_t[m] = g[m] - self.grad(self.theta_snap, X, y)
                 diff = delta_t[m] - self.delta_stored[m]
+            else:
+                # (LAGrule): the stored gradient was taken at theta^{k-tau} on the samples of that
+                # iteration.  RULE_ALWAYS records the same quantity but does not use it.
+                diff = g[m] - self.G[m]
             lhs[m] = diff @ diff
         rhs = (self.c / self.d_max) * float(np.sum(self.ring))
         own = (lhs > rhs) | (self.tau >= self.D)
+        if self.rule == RULE_ALWAYS:
+            own = np.ones(M, dtype=bool)
         mask = own.copy()
         if replay is not None:
             rp = np.asarray(replay)
@@ -196,7 +208,7 @@ class CadaOracle:
                 self.tau[m] = 1
                 if self.rule == RULE_CADA2:
                     self.theta_hat[m] = self.theta
-                else:
+                elif self.rule == RULE_CADA1:
                     self.delta_stored[m] = delta_t[m]
             else:
                 self.tau[m] += 1
@@ -208,6 +220,13 @@ class CadaOracle:
         """Equations (CADA-1)-(CADA-3) with the aggregate ``nabla``; records
         |theta^{k+1}-theta^k|^2 for the rules' right-hand side and advances k."""
         self.nabla = np.asarray(nabla, dtype=np.float64)
+        if self.server == SERVER_SGD:
+            theta_new = self.theta - self.alpha * self.nabla
+            dtheta = theta_new - self.theta
+            self.ring[self.k % self.d_max] = dtheta @ dtheta
+            self.theta = theta_new
+            self.k += 1
+            return
         self.h = self.beta1 * self.h + (1.0 - self.beta1) * self.nabla
         self.v = self.beta2 * self.vhat + (1.0 - self.beta2) * self.nabla * self.nabla
         self.vhat = np.maximum(self.v, self.vhat)

@@ -309,17 +309,22 @@ def brute_force(cfg, prob, sched, K):
             tau = k - u[m]
             if cfg.rule == configs.RULE_CADA2:
                 diff = grad_at(k, m, k) - grad_at(k - tau, m, k)
-            else:
+            elif cfg.rule == configs.RULE_CADA1:
                 diff = dtilde(k, m) - dtilde(u[m], m)
+            else:                             # (LAGrule): other iterate AND other samples
+                diff = grad_at(k, m, k) - stored_grad(m)
             lhs.append(float(diff @ diff))
-            mask.append(lhs[-1] > rhs or tau >= D)
+            mask.append(lhs[-1] > rhs or tau >= D or cfg.rule == configs.RULE_ALWAYS)
         for m in range(M):
             if mask[m]:
                 u[m] = k
         nab = sum(stored_grad(m) for m in range(M)) / M
-        h = cfg.beta1 * h + (1 - cfg.beta1) * nab
-        vh = np.maximum(cfg.beta2 * vh + (1 - cfg.beta2) * nab * nab, vh)
-        thetas.append(thetas[-1] - cfg.alpha * h / np.sqrt(cfg.eps + vh))
+        if cfg.server == configs.SERVER_SGD:
+            thetas.append(thetas[-1] - cfg.alpha * nab)
+        else:
+            h = cfg.beta1 * h + (1 - cfg.beta1) * nab
+            vh = np.maximum(cfg.beta2 * vh + (1 - cfg.beta2) * nab * nab, vh)
+            thetas.append(thetas[-1] - cfg.alpha * h / np.sqrt(cfg.eps + vh))
         masks.append(mask); lhss.append(lhs); rhss.append(rhs)
     return thetas, np.array(masks), np.array(lhss), np.array(rhss)
 
@@ -337,6 +342,52 @@ def test_brute_force_history_transcription(rule):
     np.testing.assert_allclose(t["lhs"], lhss, rtol=1e-9, atol=1e-22)
     np.testing.assert_allclose(t["rhs"], rhss, rtol=1e-11, atol=0)
     np.testing.assert_allclose(o.theta, thetas[-1], rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------- rule variants: always-upload, stochastic LAG
+@pytest.mark.parametrize("server,c", [(configs.SERVER_SGD, 400.0), (configs.SERVER_AMSGRAD, 10.0)])
+def test_lag_rule_brute_force_history_transcription(server, c):
+    """Condition (LAGrule) of Section 2.1 with the SGD update it is stated for, and with the
+    server update of (CADA-1)-(CADA-3), against the history-based transcription."""
+    cfg = TINY_LOG.scaled(rule=configs.RULE_LAG, server=server, M=3, layer_dims=(3,), B=2, N_m=12, K=30, D=5, d_max=3,
+                          c=c, alpha=0.05 if server == configs.SERVER_SGD else 0.01, seed=22)
+    prob, sched, o = setup(cfg)
+    o.run(sched)
+    thetas, masks, lhss, rhss = brute_force(cfg, prob, sched, cfg.K)
+    t = o.trace_arrays()
+    assert (t["mask"] == masks).all()
+    forced = t["tau"] >= cfg.D
+    assert 0 < masks[~forced].sum() < (~forced).sum(), "rule decisions must mix uploads and skips"
+    np.testing.assert_allclose(t["lhs"], lhss, rtol=1e-9, atol=1e-22)
+    np.testing.assert_allclose(t["rhs"], rhss, rtol=1e-11, atol=0)
+    np.testing.assert_allclose(o.theta, thetas[-1], rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("cfg", [TINY_LOG, TINY_MLP], ids=lambda c: c.name)
+def test_always_rule_is_distributed_amsgrad_for_any_c(cfg):
+    cfg = cfg.scaled(rule=configs.RULE_ALWAYS, c=1e30)
+    prob, sched, o = setup(cfg)
+    o.run(sched)
+    assert o.trace_arrays()["mask"].all() and o.uploads_total == cfg.M * cfg.K
+    ref = distributed_amsgrad(cfg, prob, sched, cfg.K, grad_fn_for(cfg))
+    np.testing.assert_allclose(o.theta, ref, rtol=1e-12, atol=1e-15)
+
+
+def test_lag_sgd_with_c_zero_is_distributed_sgd_and_huge_c_uploads_every_D():
+    cfg = TINY_LOG.scaled(rule=configs.RULE_LAG, server=configs.SERVER_SGD, c=0.0, alpha=0.05)
+    prob, sched, o = setup(cfg)
+    o.run(sched)
+    assert o.trace_arrays()["mask"].all()
+    th = prob.theta0.astype(np.float64)
+    for k in range(cfg.K):                    # plain distributed minibatch SGD
+        nab = sum(co.logreg_grad(th, *prob.rows(m, sched[k, m]), cfg.lam) for m in range(cfg.M)) / cfg.M
+        th = th - cfg.alpha * nab
+    np.testing.assert_allclose(o.theta, th, rtol=1e-12, atol=1e-15)
+    prob, sched, o = setup(cfg.scaled(c=1e30))
+    o.run(sched)
+    m = o.trace_arrays()["mask"]
+    for k in range(cfg.K):
+        assert m[k].all() == (k % cfg.D == 0) and m[k].any() == (k % cfg.D == 0)
 
 
 # ------------------------------------------------------------------ replay
