@@ -43,7 +43,18 @@ extern "C" {
 
 typedef struct cada_ctx cada_ctx; /* opaque, host memory owned by the library */
 
-enum { CADA_RULE_CADA1 = 1, CADA_RULE_CADA2 = 2 };   /* Section 2.2 */
+enum {
+  CADA_RULE_ALWAYS = 0, /* every worker uploads every iteration: the distributed Adam/AMSGrad baseline (Section 4) */
+  CADA_RULE_CADA1 = 1,  /* condition (workerrule1), Section 2.2 */
+  CADA_RULE_CADA2 = 2,  /* condition (workerrule2), Section 2.2 */
+  CADA_RULE_LAG = 3     /* stochastic LAG, condition (LAGrule), Section 2.1: left-hand side
+                           |fresh gradient - stored gradient|^2, one gradient evaluation per iteration */
+};
+enum {
+  CADA_SERVER_AMSGRAD = 0, /* equations (CADA-1)-(CADA-3) */
+  CADA_SERVER_SGD = 1      /* theta <- theta - alpha * nabla, the update stochastic LAG follows (Section 2.1);
+                              h, v, vhat stay at their initial zeros */
+};
 enum { CADA_MODEL_LOGREG = 0, CADA_MODEL_MLP = 1 };
 enum { CADA_GEMM_FP32 = 0, CADA_GEMM_BF16 = 1 };
 
@@ -82,6 +93,7 @@ typedef struct cada_config {
   int32_t D;                 /* max delay (forced upload) and CADA1 snapshot period */
   int32_t rule;              /* CADA_RULE_* */
   int32_t gemm_dtype;        /* MLP contractions: CADA_GEMM_* (LOGREG ignores it) */
+  int32_t server;            /* CADA_SERVER_* */
   int64_t trace_steps;       /* steps of per-step trace to keep (0 = none) */
   void *workspace;           /* DEVICE, 256-byte aligned, caller-owned */
   size_t workspace_bytes;

@@ -70,7 +70,8 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   if (!(cfg->c >= 0.0)) { set_error("c must be >= 0"); return false; }
   if (!(cfg->beta1 >= 0.0 && cfg->beta1 < 1.0 && cfg->beta2 >= 0.0 && cfg->beta2 < 1.0)) { set_error("beta1, beta2 must be in [0, 1)"); return false; }
   if (!(cfg->eps >= 0.0)) { set_error("eps must be >= 0"); return false; }
-  if (cfg->rule != CADA_RULE_CADA1 && cfg->rule != CADA_RULE_CADA2) { set_error("rule must be CADA_RULE_CADA1 or CADA_RULE_CADA2"); return false; }
+  if (cfg->rule < CADA_RULE_ALWAYS || cfg->rule > CADA_RULE_LAG) { set_error("rule must be one of CADA_RULE_* (got %d)", cfg->rule); return false; }
+  if (cfg->server != CADA_SERVER_AMSGRAD && cfg->server != CADA_SERVER_SGD) { set_error("server must be one of CADA_SERVER_* (got %d)", cfg->server); return false; }
   if (cfg->model != CADA_MODEL_LOGREG && cfg->model != CADA_MODEL_MLP) { set_error("unknown model %d", cfg->model); return false; }
   if (!cfg->layer_dims) { set_error("layer_dims is NULL"); return false; }
   if (!cfg->n_samples) { set_error("n_samples is NULL"); return false; }
@@ -118,7 +119,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   if (cfg->rule == CADA_RULE_CADA2) {
     hist = w.take<float>((size_t)(cfg->D + 1) * p);
     hist_lo = w.take<float>((size_t)(cfg->D + 1) * p);
-  } else {
+  } else if (cfg->rule == CADA_RULE_CADA1) {
     snap = w.take<float>(p);
     snap_lo = w.take<float>(p);
     dtl = w.take<float>(2 * M * p);
@@ -245,7 +246,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   Carver w{static_cast<char *>(cfg->workspace)};
   carve_common(w, cfg, g, &s, c);
   s.X = cfg->X; s.y = cfg->y;
-  s.M = cfg->M; s.B = cfg->B; s.d_max = cfg->d_max; s.D = cfg->D; s.R = cfg->D + 1; s.rule = cfg->rule;
+  s.M = cfg->M; s.B = cfg->B; s.d_max = cfg->d_max; s.D = cfg->D; s.R = cfg->D + 1; s.rule = cfg->rule; s.server_sgd = cfg->server == CADA_SERVER_SGD;
   s.n_lhs_part = g.n_lhs_part; s.n_ring_part = g.n_ring_part;
   s.p = cfg->p; s.k = 0;
   s.alpha = (float)cfg->alpha; s.beta1 = (float)cfg->beta1; s.beta2 = (float)cfg->beta2;
@@ -286,7 +287,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   const unsigned pb = (unsigned)((p + tb - 1) / tb);
   if (s.rule == CADA_RULE_CADA2)
     hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.hist, theta0, (int64_t)p, (int64_t)s.R);
-  else
+  else if (s.rule == CADA_RULE_CADA1)
     hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.snap, theta0, (int64_t)p, (int64_t)1);
   if ((e = hipGetLastError()) != hipSuccess) return fail(e, "init kernels");
   if (cfg->model == CADA_MODEL_MLP) {

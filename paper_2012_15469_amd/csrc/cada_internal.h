@@ -46,7 +46,7 @@ struct DevState {
   const float *X;
   const void *y;
   const int64_t *row_off;   // device [M+1], prefix sums of N_m
-  int32_t M, B, d_max, D, R, rule, n_lhs_part, n_ring_part;
+  int32_t M, B, d_max, D, R, rule, server_sgd, n_lhs_part, n_ring_part;
   int64_t p;
   int64_t k;                // iteration of the launch this copy is passed to
   float alpha, beta1, beta2, omb1, omb2, eps, lam;   // omb = 1 - beta, rounded once from double
@@ -54,10 +54,13 @@ struct DevState {
 };
 
 // Reference point of worker m at iteration k (Algorithm 1: theta-tilde for CADA1,
-// theta^{k - tau_m^k} for CADA2).
+// theta^{k - tau_m^k} for CADA2).  The always-upload and the stochastic LAG rules evaluate no
+// second gradient: their reference point is the iterate itself, so every difference the
+// gradient kernels carry is exactly zero.
 struct RefPtr { const float *hi, *lo; };
 __device__ __forceinline__ RefPtr theta_ref(const DevState &s, int m, int64_t k) {
   if (s.rule == CADA_RULE_CADA1) return RefPtr{s.snap, s.snap_lo};
+  if (s.rule != CADA_RULE_CADA2) return RefPtr{s.theta, s.theta_lo};
   int64_t j = k - (int64_t)min(s.tau[m], s.D);   // tau <= D unless a replay kept m silent longer
   int64_t slot = j % s.R;
   if (slot < 0) slot += s.R;

@@ -24,6 +24,27 @@ __device__ float last_step_sq(const DevState &s, double *red /* [kBlock] LDS */)
   return r;
 }
 
+// Left-hand side of condition (LAGrule), Section 2.1: |fresh gradient - stored gradient|^2 per
+// worker (the stored one was taken at another iterate on other samples).  grid (blocks, M);
+// block b of worker m writes lhs_part[m][b]; the remaining slots are cleared.
+__global__ __launch_bounds__(kBlock) void k_lag_lhs(const DevState s) {
+  __shared__ float red[4];
+  const int m = blockIdx.y;
+  const int64_t mp = (int64_t)s.M * s.p;
+  const float *gs = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p;
+  const float *gf = s.gbuf + (int64_t)(1 - s.sel[m]) * mp + (int64_t)m * s.p;
+  float sq = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
+    const float d = gf[i] - gs[i];
+    sq = fmaf(d, d, sq);
+  }
+  const float tot = block_sum(sq, red);
+  float *lp = s.lhs_part + (int64_t)m * s.n_lhs_part;
+  if (threadIdx.x == 0) lp[blockIdx.x] = tot;
+  if (blockIdx.x == 0)
+    for (int t = gridDim.x + threadIdx.x; t < s.n_lhs_part; t += kBlock) lp[t] = 0.f;
+}
+
 // S3 of the step: RHS, per-worker decision, tau, pointer swap, trace.  One wavefront per
 // worker, four workers per block; every block forms the RHS itself (same operations, same
 // value), block 0 records it.
@@ -49,7 +70,7 @@ __global__ __launch_bounds__(kBlock) void k_rule(const DevState s, const uint8_t
     for (int o = 32; o > 0; o >>= 1) lhs += __shfl_xor(lhs, o, 64);   // fixed tree order
     if (lane == 0) {
       const int32_t tau = s.tau[m];
-      const bool own = (lhs > rhs) || (tau >= s.D);
+      const bool own = (s.rule == CADA_RULE_ALWAYS) || (lhs > rhs) || (tau >= s.D);
       bool up = own;
       if (replay != nullptr && replay[m] != CADA_REPLAY_FREE) up = replay[m] != 0;
       if (tr) {
@@ -157,11 +178,17 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
     // relative, which compounds to 1e-5 over the ~1000-step memory of vhat, whereas
     // float32(1-beta) enters only linearly
     const float ho = hh[v];
-    hh[v] = fmaf(s.omb1, nab[v] - ho, ho);
     const float vo = vh[v];
-    vv[v] = fmaf(s.omb2, nab[v] * nab[v] - vo, vo);
-    vh[v] = fmaxf(vv[v], vo);
-    const float step = s.alpha * hh[v] / sqrtf(s.eps + vh[v]);
+    float step;
+    if (s.server_sgd) {          // theta <- theta - alpha * nabla; h, v, vhat keep their zeros
+      vv[v] = vo;
+      step = s.alpha * nab[v];
+    } else {
+      hh[v] = fmaf(s.omb1, nab[v] - ho, ho);
+      vv[v] = fmaf(s.omb2, nab[v] * nab[v] - vo, vo);
+      vh[v] = fmaxf(vv[v], vo);
+      step = s.alpha * hh[v] / sqrtf(s.eps + vh[v]);
+    }
     // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
     const float a = th[v], ms = -step;
     const float sum = a + ms;
@@ -187,6 +214,10 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
 int rule_and_server(Ctx *c, const uint8_t *replay) {
   DevState s = c->s;
   s.k = c->k;
+  if (s.rule == CADA_RULE_LAG || s.rule == CADA_RULE_ALWAYS) {   // (the always-upload rule only records it)
+    const int nb = (int)min((int64_t)s.n_lhs_part, (s.p + 4 * kBlock - 1) / (4 * kBlock));
+    hipLaunchKernelGGL(k_lag_lhs, dim3((unsigned)max(nb, 1), (unsigned)s.M), dim3(kBlock), 0, c->stream, s);
+  }
   hipLaunchKernelGGL(k_rule, dim3((unsigned)((s.M + 3) / 4)), dim3(kBlock), 0, c->stream, s, replay);
   prof_mark(c);
   if (c->vec == 4)
