@@ -47,18 +47,25 @@
 
 namespace cada {
 
-constexpr int F_NL = 16;             // one-row slabs parked in LDS
-constexpr int F_LAG = F_NL - 1;      // a slab is consumed this many iterations after it was produced
-constexpr int F_PD = 8;              // slabs of loads in flight per thread (= unroll factor of the main loop)
-constexpr int F_P = 4;               // polls in flight in the exchange wavefront (divides F_PD)
-constexpr int F_NP = 32;             // publication buffers (>= LAG + 2)
+// R = rows (slabs) a workgroup takes per iteration, i.e. per barrier: 2 when the minibatch size is
+// even (the per-iteration costs -- barrier, cursor updates, address and residual reads, branches --
+// are paid once per two rows), else 1.
+constexpr int F_PD = 8;              // slabs of loads in flight per thread
+constexpr int F_NP = 32;             // publication buffers, in slabs
 constexpr int F_V = 2;               // exchanged values per slab and workgroup: z and dz
 constexpr int F_STREAM = 256;        // streaming threads (4 wavefronts)
 constexpr int F_THREADS = F_STREAM + 128;   // + exchange wavefront + residual/feeder wavefront
 constexpr int F_QMAX = 32;
 constexpr int F_NE = 256;            // slabs whose row address and label are held in LDS (4 chunks of 64)
-static_assert(F_PD % F_P == 0 && F_NP >= F_LAG + 2 && F_NE % 64 == 0, "pipeline constants");
-constexpr size_t kFusedLds = (size_t)F_NL * 2 * F_STREAM * sizeof(float4);   // 128 KB (dynamic part)
+template <int R> struct FusedGeom {
+  static constexpr int NL = 16 + 2 * (R - 1);     // one-row slabs parked in LDS (128 KB, 144 KB)
+  static constexpr int LAGI = NL / R - 1;         // iterations between producing and consuming a slab
+  static constexpr int PDI = F_PD / R;            // iterations of loads in flight = unroll factor of the loops
+  static constexpr int P = 4 / R;                 // iterations of polls in flight in the exchange wavefront
+  static constexpr int IPC = 64 / R;              // iterations per feeder chunk of 64 slabs
+  static constexpr size_t lds = (size_t)NL * 2 * F_STREAM * sizeof(float4);   // dynamic part
+  static_assert(PDI % P == 0 && F_NP >= (LAGI + 2) * R && F_NE % 64 == 0 && NL % R == 0, "pipeline constants");
+};
 
 struct FusedArgs {
   DevState s;
@@ -92,13 +99,6 @@ __device__ __forceinline__ void issue_slab(v4f &a, v4f &b, const float *pa, cons
   asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(a) : "v"(pa) : "memory");
   asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(b) : "v"(pb) : "memory");
 }
-// Waits until at most N vector memory operations issued after the two loads of (a, b) are
-// outstanding.  Operations complete in issue order, so (a, b) have then arrived.
-template <int N>
-__device__ __forceinline__ void wait_slab(v4f &a, v4f &b) {
-  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
-}
-
 // Workgroup barrier that orders LDS traffic only.  (__syncthreads() also fences global
 // memory, which makes every wavefront wait for all its outstanding loads and would drain the
 // prefetch pipeline each iteration; the wavefronts of a workgroup exchange data through LDS only.)
@@ -121,26 +121,39 @@ __device__ __forceinline__ float row16_parity_sum(float v) {
   return v;
 }
 
+// Waits until at most N vector memory operations issued after the loads of x are outstanding.
+template <int N, int R>
+__device__ __forceinline__ void wait_rows(v4f (&x)[R][2]) {
+  if constexpr (R == 1) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(x[0][0]), "+v"(x[0][1]) : "n"(N));
+  else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[1][0]), "+v"(x[1][1]) : "n"(N));
+}
+
+template <int R>
 __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
+  using G = FusedGeom<R>;
+  constexpr int NL = G::NL, LAGI = G::LAGI, PDI = G::PDI, P = G::P, IPC = G::IPC;
+  // iterations before the steady-state loop: it assumes that the previous iteration consumed rows
+  constexpr int HEAD = (LAGI + 1 + PDI - 1) / PDI * PDI;
   const DevState &s = a.s;
   extern __shared__ __align__(16) unsigned char fused_smem[];
-  v4f *ring = reinterpret_cast<v4f *>(fused_smem);            // [F_NL][2][F_STREAM]
-  __shared__ __align__(16) float red[2][F_V][16];             // [slab parity][z|dz][wavefront * 4 + row of 16 lanes]
-  __shared__ float zz_s[2][F_V];                              // cluster sums z, dz of a slab
-  __shared__ float r_s[2], dr_s[2];
-  __shared__ long long off_s[F_NE];                           // element offset of slab t's row in X, at t % NE
+  v4f *ring = reinterpret_cast<v4f *>(fused_smem);            // [NL][2][F_STREAM]
+  __shared__ __align__(16) float red[2][R][F_V][16];          // [iteration parity][row][z|dz][wavefront * 4 + row of 16 lanes]
+  __shared__ float zz_s[2][R][F_V];                           // cluster sums z, dz
+  __shared__ float r_s[2][R], dr_s[2][R];
+  __shared__ __align__(16) long long off_s[F_NE];             // element offset of slab t's row in X, at t % NE
   __shared__ float y_s[F_NE];                                 // label of slab t
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int Q = a.Q, ncl = a.n_clusters;
   const int cluster = blockIdx.x / Q, cb = blockIdx.x % Q;
-  const int nslab = s.B;                                      // one row per slab
+  const int nslab = s.B;                                      // one row per slab; a multiple of R
   const int rounds = (s.M - cluster + ncl - 1) / ncl;         // workers of this cluster
   const int S = rounds * nslab;                               // slabs of this cluster
-  const int total = S + F_LAG;                                // iterations (= barriers after the first) of every wavefront
+  const int IS = S / R;                                       // iterations that produce
+  const int total = IS + LAGI;                                // iterations (= barriers after the first) of every wavefront
   unsigned long long *post_base = a.zpost + (int64_t)cluster * F_NP * F_V * Q;
-  // (worker, slab within worker) cursors advance one slab at a time
-  auto advance = [&](int &m, int &loc) __attribute__((always_inline)) { if (++loc == nslab) { loc = 0; m += ncl; } };
+  // (worker, slab within worker) cursors advance one iteration (R slabs) at a time
+  auto advance = [&](int &m, int &loc) __attribute__((always_inline)) { loc += R; if (loc == nslab) { loc = 0; m += ncl; } };
 
   if (w == 5) {
     // ================= residual / feeder wavefront =================
@@ -171,112 +184,124 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     feed_issue(0); feed_label(); feed_write(0);
     lds_barrier();
 
-    auto math_iter = [&](auto ST, const int sl) __attribute__((always_inline)) {
+    // lanes 2r, 2r+1 work on row r of the iteration: the even lane evaluates sigmoid(aa), the
+    // odd lane sigmoid(-bb) (one evaluation for both)
+    const int mr = (lane >> 1) & (R - 1);
+    auto math_iter = [&](auto ST, const int it) __attribute__((always_inline)) {
       constexpr bool st = decltype(ST)::value;
       lds_barrier();
-      const int c1 = sl + 1 - F_LAG;                   // summed by the exchange wavefront last iteration
-      if (st || (c1 >= 0 && c1 < S)) {
-        const float z = zz_s[c1 & 1][0], dz = zz_s[c1 & 1][1];
-        const float y = y_s[c1 % F_NE];
+      const int c1 = it + 1 - LAGI;                    // summed by the exchange wavefront last iteration
+      if (st || (c1 >= 0 && c1 < IS)) {
+        const float z = zz_s[c1 & 1][mr][0], dz = zz_s[c1 & 1][mr][1];
+        const float y = y_s[(c1 * R + mr) % F_NE];
         const float aa = -y * z;
         const float bb = aa + y * dz;
-        // lane 0 evaluates sigmoid(aa), the other lanes sigmoid(-bb): one evaluation for both
-        const float sg = sigmoid_f(lane == 0 ? aa : -bb);
-        const float sa = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sg), 0));
-        const float sb = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sg), 1));
+        const float sg = sigmoid_f((lane & 1) ? -bb : aa);
+        const float sb = dpp_get<0xB1>(sg);            // the neighbour's value
         const float em = expm1f(y * dz);
-        if (lane == 0) {
-          r_s[c1 & 1] = -y * sa * invB;
-          dr_s[c1 & 1] = y * sa * sb * em * invB;
+        if ((lane & 1) == 0 && lane < 2 * R) {
+          r_s[c1 & 1][mr] = -y * sg * invB;
+          dr_s[c1 & 1][mr] = y * sg * sb * em * invB;
         }
       }
-      // rows and labels of chunk sl / 64 + 1, first needed at iteration 64 (sl / 64 + 1) - PD
-      const int ph = sl & 63, chunk = (sl >> 6) + 1;
+      // rows and labels of chunk it / IPC + 1, first needed PDI + 1 iterations before its first slab
+      const int ph = it % IPC, chunk = it / IPC + 1;
       if (chunk * 64 < S) {
-        if (ph == 16) feed_issue(chunk);
-        else if (ph == 24) feed_label();
-        else if (ph == 32) feed_write(chunk);
+        if (ph == IPC / 4) feed_issue(chunk);
+        else if (ph == IPC * 3 / 8) feed_label();
+        else if (ph == IPC / 2) feed_write(chunk);
       }
     };
     // head, steady-state loop, tail: three loops of their own, so that the steady-state loop
     // has a single body and its loop-carried registers stay in place
     int s0 = 0;
-    for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD)
-      for (int i = 0; i < F_PD; ++i)
+    for (; s0 < HEAD && s0 < total; s0 += PDI)
+      for (int i = 0; i < PDI; ++i)
         if (s0 + i < total) math_iter(bc<false>{}, s0 + i);
-    for (; s0 + 2 * F_PD < S; s0 += F_PD) {
+    for (; s0 + 2 * PDI < IS; s0 += PDI) {
 #pragma unroll
-      for (int i = 0; i < F_PD; ++i) math_iter(bc<true>{}, s0 + i);
+      for (int i = 0; i < PDI; ++i) math_iter(bc<true>{}, s0 + i);
     }
-    for (; s0 < total; s0 += F_PD)
-      for (int i = 0; i < F_PD; ++i)
+    for (; s0 < total; s0 += PDI)
+      for (int i = 0; i < PDI; ++i)
         if (s0 + i < total) math_iter(bc<false>{}, s0 + i);
     return;
   }
 
   if (w == 4) {
     // ================= exchange wavefront =================
-    const int j = lane & 31, half = lane >> 5, par = lane & 1;
+    const int j = lane & 31, half = lane >> 5, par = lane & 1, pr = (lane >> 1) & (R - 1);
     const bool jok = j < Q;
     const int jc = jok ? j : Q - 1;
     bool dead = false;
-    unsigned long long pw[F_P];
+    unsigned long long pw[P][R];
 #pragma unroll
-    for (int i = 0; i < F_P; ++i) pw[i] = 0ull;
+    for (int i = 0; i < P; ++i)
+#pragma unroll
+      for (int r = 0; r < R; ++r) pw[i][r] = 0ull;
     lds_barrier();
 
-    auto comm_iter = [&](auto PI, auto ST, const int sl) __attribute__((always_inline)) {
+    auto comm_iter = [&](auto PI, auto ST, const int it) __attribute__((always_inline)) {
       constexpr int pi = decltype(PI)::value;
       constexpr bool st = decltype(ST)::value;
       lds_barrier();
-      // publish slab sl: lanes of equal parity compute and store the same word
-      if (st || sl < S) {
-        const float4 *rp = reinterpret_cast<const float4 *>(red[sl & 1][par]);
+      // publish the rows of iteration it: lanes of equal (parity, row) compute and store the same word
+      if (st || it < IS) {
+        const float4 *rp = reinterpret_cast<const float4 *>(red[it & 1][pr][par]);
         const float4 q0 = rp[0], q1 = rp[1], q2 = rp[2], q3 = rp[3];
         const float tot = (((q0.x + q0.y) + (q0.z + q0.w)) + ((q1.x + q1.y) + (q1.z + q1.w))) +
                           (((q2.x + q2.y) + (q2.z + q2.w)) + ((q3.x + q3.y) + (q3.z + q3.w)));
-        const uint32_t tag = a.seq_base + 1u + (uint32_t)sl;
+        const int t = it * R + pr;
+        const uint32_t tag = a.seq_base + 1u + (uint32_t)t;
         const unsigned long long word = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(tot);
-        __hip_atomic_store(post_base + ((int64_t)(sl % F_NP) * F_V + par) * Q + cb, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(post_base + ((int64_t)(t % F_NP) * F_V + par) * Q + cb, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      // sum the cluster's partials of slab c1 (first polled F_P iterations ago)
-      const int c1 = sl + 2 - F_LAG;
-      if (st || (c1 >= 0 && c1 < S)) {
-        const uint32_t tag = a.seq_base + 1u + (uint32_t)c1;
-        if ((uint32_t)(pw[pi] >> 32) != tag) {      // not there yet: rare
-          const unsigned long long *pp = post_base + ((int64_t)(c1 % F_NP) * F_V + half) * Q + jc;
-          uint32_t spins = 0;
-          while (!dead && (uint32_t)(pw[pi] >> 32) != tag) {
-            if (++spins > a.spin_limit) { dead = true; atomicOr(s.err, 2u); break; }
-            __builtin_amdgcn_s_sleep(1);
-            pw[pi] = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // sum the cluster's partials of the rows of iteration c1 (first polled P iterations ago)
+      const int c1 = it + 2 - LAGI;
+      if (st || (c1 >= 0 && c1 < IS)) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const int t = c1 * R + r;
+          const uint32_t tag = a.seq_base + 1u + (uint32_t)t;
+          if ((uint32_t)(pw[pi][r] >> 32) != tag) {      // not there yet: rare
+            const unsigned long long *pp = post_base + ((int64_t)(t % F_NP) * F_V + half) * Q + jc;
+            uint32_t spins = 0;
+            while (!dead && (uint32_t)(pw[pi][r] >> 32) != tag) {
+              if (++spins > a.spin_limit) { dead = true; atomicOr(s.err, 2u); break; }
+              __builtin_amdgcn_s_sleep(1);
+              pw[pi][r] = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
           }
+          float v = jok ? __uint_as_float((uint32_t)pw[pi][r]) : 0.f;
+          v += dpp_get<0xB1>(v);
+          v = row16_parity_sum(v);                     // every lane: sum of its row of 16
+          const float z0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+          const float z1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+          const float d0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+          const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+          if (lane == 0) { zz_s[c1 & 1][r][0] = z0 + z1; zz_s[c1 & 1][r][1] = d0 + d1; }
         }
-        float v = jok ? __uint_as_float((uint32_t)pw[pi]) : 0.f;
-        v += dpp_get<0xB1>(v);
-        v = row16_parity_sum(v);                     // every lane: sum of its row of 16
-        const float z0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-        const float z1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-        const float d0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-        const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-        if (lane == 0) { zz_s[c1 & 1][0] = z0 + z1; zz_s[c1 & 1][1] = d0 + d1; }
       }
-      // first poll of slab c2, summed F_P iterations from now
-      const int c2 = sl + 2 + F_P - F_LAG;
-      if (st || (c2 >= 0 && c2 < S))
-        pw[pi] = __hip_atomic_load(post_base + ((int64_t)(c2 % F_NP) * F_V + half) * Q + jc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // first poll of the rows of iteration c2, summed P iterations from now
+      const int c2 = it + 2 + P - LAGI;
+      if (st || (c2 >= 0 && c2 < IS)) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+          pw[pi][r] = __hip_atomic_load(post_base + ((int64_t)((c2 * R + r) % F_NP) * F_V + half) * Q + jc, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);
+      }
     };
 
     int s0 = 0;
-    for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD)
-      unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
-        if (s0 + I.value < total) comm_iter(ic<I.value % F_P>{}, bc<false>{}, s0 + I.value);
+    for (; s0 < HEAD && s0 < total; s0 += PDI)
+      unrolled<PDI>([&](auto I) __attribute__((always_inline)) {
+        if (s0 + I.value < total) comm_iter(ic<I.value % P>{}, bc<false>{}, s0 + I.value);
       });
-    for (; s0 + 2 * F_PD < S; s0 += F_PD)
-      unrolled<F_PD>([&](auto I) __attribute__((always_inline)) { comm_iter(ic<I.value % F_P>{}, bc<true>{}, s0 + I.value); });
-    for (; s0 < total; s0 += F_PD)
-      unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
-        if (s0 + I.value < total) comm_iter(ic<I.value % F_P>{}, bc<false>{}, s0 + I.value);
+    for (; s0 + 2 * PDI < IS; s0 += PDI)
+      unrolled<PDI>([&](auto I) __attribute__((always_inline)) { comm_iter(ic<I.value % P>{}, bc<true>{}, s0 + I.value); });
+    for (; s0 < total; s0 += PDI)
+      unrolled<PDI>([&](auto I) __attribute__((always_inline)) {
+        if (s0 + I.value < total) comm_iter(ic<I.value % P>{}, bc<false>{}, s0 + I.value);
       });
     return;
   }
@@ -293,9 +318,8 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     if (!cv[q]) col[q] = 0;            // a valid address; the value is discarded
   }
   const int64_t mp = (int64_t)s.M * s.p;
-  // first element of the row of slab t (wavefront-uniform, from the feeder's table)
-  auto row_ptr = [&](int t) __attribute__((always_inline)) -> const float * {
-    const long long o = off_s[t % F_NE];
+  // first element of a row from its LDS word (wavefront-uniform, from the feeder's table)
+  auto to_row = [&](long long o) __attribute__((always_inline)) -> const float * {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)o);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((unsigned long long)o >> 32));
     return s.X + (int64_t)(((unsigned long long)hi << 32) | lo);
@@ -318,41 +342,46 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   };
 
-  v4f xb[F_PD][2];
+  v4f xb[PDI][R][2];
   float4 th[2], dd[2], g[2], iv[2];
 #pragma unroll
   for (int q = 0; q < 2; ++q) th[q] = dd[q] = g[q] = iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-  int pm = cluster, ploc = 0;           // slab produced (dot products, parked) this iteration
-  int cm = cluster, cloc = 0;           // slab consumed this iteration (valid once sl >= LAG)
+  int pm = cluster, ploc = 0;           // first slab produced (dot products, parked) this iteration
+  int cm = cluster, cloc = 0;           // first slab accumulated this iteration
   lds_barrier();                        // the feeder's first chunk is in LDS
-  // prologue: loads of slabs 0 .. PD-1
+  // prologue: loads of the first PDI iterations
 #pragma unroll
-  for (int i = 0; i < F_PD; ++i) {
-    if (i < S) {
-      const float *rp = row_ptr(i);
+  for (int i = 0; i < PDI; ++i)
 #pragma unroll
-      for (int q = 0; q < 2; ++q) xb[i][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
-    }
-  }
+    for (int r = 0; r < R; ++r)
+      if (i * R + r < S) {
+        const float *rp = to_row(off_s[(i * R + r) % F_NE]);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) xb[i][r][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
+      }
 
-  // Accumulation of a consumed slab, deferred by one iteration: its residuals are read from
-  // LDS right after the barrier but first used here, after the next slab's dot products, so
+  // Accumulation of the consumed rows, deferred by one iteration: their residuals are read from
+  // LDS right after the barrier but first used here, after the next rows' dot products, so
   // that the wavefront never waits for that read.
-  v4f xr[2];                            // the consumed slab's columns, from the ring
-  float rr = 0.f, dr = 0.f;             // its residual and residual difference
+  v4f xr[R][2];                         // the consumed rows' columns, from the ring
+  float rr[R], dr[R];                   // their residuals and residual differences
+#pragma unroll
+  for (int r = 0; r < R; ++r) rr[r] = dr[r] = 0.f;
   bool pending = false;
   auto accumulate = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const v4f x = xr[q];
-      g[q].x = fmaf(rr, x.x, g[q].x); g[q].y = fmaf(rr, x.y, g[q].y);
-      g[q].z = fmaf(rr, x.z, g[q].z); g[q].w = fmaf(rr, x.w, g[q].w);
-      iv[q].x = fmaf(dr, x.x, iv[q].x); iv[q].y = fmaf(dr, x.y, iv[q].y);
-      iv[q].z = fmaf(dr, x.z, iv[q].z); iv[q].w = fmaf(dr, x.w, iv[q].w);
-    }
-    if (cloc == nslab - 1) {
-      // last slab of worker cm: regulariser, stores, squared norm of the rule's left-hand side
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const v4f x = xr[r][q];
+        g[q].x = fmaf(rr[r], x.x, g[q].x); g[q].y = fmaf(rr[r], x.y, g[q].y);
+        g[q].z = fmaf(rr[r], x.z, g[q].z); g[q].w = fmaf(rr[r], x.w, g[q].w);
+        iv[q].x = fmaf(dr[r], x.x, iv[q].x); iv[q].y = fmaf(dr[r], x.y, iv[q].y);
+        iv[q].z = fmaf(dr[r], x.z, iv[q].z); iv[q].w = fmaf(dr[r], x.w, iv[q].w);
+      }
+    if (cloc + R == nslab) {
+      // last rows of worker cm: regulariser, stores, squared norm of the rule's left-hand side
       const int m = cm;
       float4 tm[2], dm[2];
       load_theta(m, tm, dm);
@@ -384,85 +413,99 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     advance(cm, cloc);
   };
 
-  // LDS word of the row address of slab sl + F_PD, read one iteration before its use
-  long long off_q = (F_PD < S) ? off_s[F_PD % F_NE] : 0;
-  auto to_row = [&](long long o) __attribute__((always_inline)) -> const float * {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)o);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((unsigned long long)o >> 32));
-    return s.X + (int64_t)(((unsigned long long)hi << 32) | lo);
-  };
+  // LDS words of the row addresses of iteration it + PDI, read one iteration before their use
+  long long off_q[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) off_q[r] = (PDI < IS) ? off_s[(PDI * R + r) % F_NE] : 0;
 
   // One iteration.  The LDS reads whose results are needed later are issued first, and the
   // only LDS operation the barrier has to wait for (the partial sums) is followed by the
-  // previous slab's accumulation, so that no LDS latency is exposed.
-  auto stream_iter = [&](auto BI, auto ST, const int sl) __attribute__((always_inline)) {
+  // previous rows' accumulation, so that no LDS latency is exposed.
+  auto stream_iter = [&](auto BI, auto ST, const int it) __attribute__((always_inline)) {
     constexpr int bi = decltype(BI)::value;
     constexpr bool st = decltype(ST)::value;
-    const bool prod = st || sl < S;
-    const bool more = st || sl + F_PD < S;
-    const float *rp = to_row(off_q);
-    if (st || sl + F_PD + 1 < S) off_q = off_s[(sl + F_PD + 1) % F_NE];
-    // 3a. ring entries of slab c0 = sl - LAG, consumed after the barrier (this thread's own
-    //     columns: no synchronisation needed)
-    const bool cons = st || (sl >= F_LAG && sl - F_LAG < S);
-    const int c0 = sl - F_LAG;
-    v4f xn[2];
-    if (cons) {
-      const v4f *slot = ring + (size_t)(c0 % F_NL) * 2 * F_STREAM;
+    const bool prod = st || it < IS;
+    const bool more = st || it + PDI < IS;
+    const float *rp[R];
 #pragma unroll
-      for (int q = 0; q < 2; ++q) xn[q] = slot[q * F_STREAM + tid];
+    for (int r = 0; r < R; ++r) rp[r] = to_row(off_q[r]);
+    if (st || it + PDI + 1 < IS) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) off_q[r] = off_s[((it + PDI + 1) * R + r) % F_NE];
+    }
+    // 3a. ring entries of the rows of iteration c0 = it - LAGI, consumed after the barrier (this
+    //     thread's own columns: no synchronisation needed)
+    const bool cons = st || (it >= LAGI && it - LAGI < IS);
+    const int c0 = it - LAGI;
+    v4f xn[R][2];
+    if (cons) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const v4f *slot = ring + (size_t)((c0 * R + r) % NL) * 2 * F_STREAM;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) xn[r][q] = slot[q * F_STREAM + tid];
+      }
     }
     if (prod) {
       if (ploc == 0) load_theta(pm, th, dd);
-      if constexpr (st) wait_slab<2 * (F_PD - 1)>(xb[bi][0], xb[bi][1]);
-      // 2. park the slab
-      v4f *slot = ring + (size_t)(sl % F_NL) * 2 * F_STREAM;
+      if constexpr (st) wait_rows<(PDI - 1) * 2 * R, R>(xb[bi]);
 #pragma unroll
-      for (int q = 0; q < 2; ++q) slot[q * F_STREAM + tid] = xb[bi][q];
-      // 1. partial dot products of this thread's columns
-      float z = 0.f, dz = 0.f;
+      for (int r = 0; r < R; ++r) {
+        // 2. park the row
+        v4f *slot = ring + (size_t)((it * R + r) % NL) * 2 * F_STREAM;
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const v4f x = xb[bi][q];
-        z = fmaf(x.x, th[q].x, z); z = fmaf(x.y, th[q].y, z); z = fmaf(x.z, th[q].z, z); z = fmaf(x.w, th[q].w, z);
-        dz = fmaf(x.x, dd[q].x, dz); dz = fmaf(x.y, dd[q].y, dz); dz = fmaf(x.z, dd[q].z, dz); dz = fmaf(x.w, dd[q].w, dz);
+        for (int q = 0; q < 2; ++q) slot[q * F_STREAM + tid] = xb[bi][r][q];
+        // 1. partial dot products of this thread's columns
+        float z = 0.f, dz = 0.f;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const v4f x = xb[bi][r][q];
+          z = fmaf(x.x, th[q].x, z); z = fmaf(x.y, th[q].y, z); z = fmaf(x.z, th[q].z, z); z = fmaf(x.w, th[q].w, z);
+          dz = fmaf(x.x, dd[q].x, dz); dz = fmaf(x.y, dd[q].y, dz); dz = fmaf(x.z, dd[q].z, dz); dz = fmaf(x.w, dd[q].w, dz);
+        }
+        // even lanes carry the sum of z, odd lanes of dz, over each row of 16 lanes (fixed tree)
+        const bool up = (lane & 1) != 0;
+        float v = (up ? dz : z) + dpp_get<0xB1>(up ? z : dz);
+        v = row16_parity_sum(v);
+        if ((lane & 15) < F_V) red[it & 1][r][lane & 1][w * 4 + (lane >> 4)] = v;
       }
-      // even lanes carry the sum of z, odd lanes of dz, over each row of 16 lanes (fixed tree)
-      const bool up = (lane & 1) != 0;
-      float v = (up ? dz : z) + dpp_get<0xB1>(up ? z : dz);
-      v = row16_parity_sum(v);
-      if ((lane & 15) < F_V) red[sl & 1][lane & 1][w * 4 + (lane >> 4)] = v;
       advance(pm, ploc);
-      // the registers are free for the slab F_PD ahead
+      // the registers are free for the rows PDI iterations ahead
       if constexpr (st) {
-        issue_slab(xb[bi][0], xb[bi][1], rp + col[0], rp + col[1]);
+#pragma unroll
+        for (int r = 0; r < R; ++r) issue_slab(xb[bi][r][0], xb[bi][r][1], rp[r] + col[0], rp[r] + col[1]);
       } else if (more) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) xb[bi][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) xb[bi][r][q] = *reinterpret_cast<const v4f *>(rp[r] + col[q]);
       }
     }
-    // 3b. accumulate the slab consumed in the previous iteration
+    // 3b. accumulate the rows consumed in the previous iteration
     if (st || pending) accumulate();
     lds_barrier();
     pending = cons;
     if (cons) {
-      rr = r_s[c0 & 1]; dr = dr_s[c0 & 1];
-      xr[0] = xn[0]; xr[1] = xn[1];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        rr[r] = r_s[c0 & 1][r]; dr[r] = dr_s[c0 & 1][r];
+        xr[r][0] = xn[r][0]; xr[r][1] = xn[r][1];
+      }
     }
   };
 
   int s0 = 0;
-  for (; s0 < 2 * F_PD && s0 < total; s0 += F_PD)
-    unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
+  for (; s0 < HEAD && s0 < total; s0 += PDI)
+    unrolled<PDI>([&](auto I) __attribute__((always_inline)) {
       if (s0 + I.value < total) stream_iter(I, bc<false>{}, s0 + I.value);
     });
   __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): nothing the compiler tracks is in flight from here on
-  for (; s0 + 2 * F_PD < S; s0 += F_PD)
-    unrolled<F_PD>([&](auto I) __attribute__((always_inline)) { stream_iter(I, bc<true>{}, s0 + I.value); });
+  for (; s0 + 2 * PDI < IS; s0 += PDI)
+    unrolled<PDI>([&](auto I) __attribute__((always_inline)) { stream_iter(I, bc<true>{}, s0 + I.value); });
   // the loads of the last trip are still in flight and unknown to the compiler
-  unrolled<F_PD>([&](auto I) __attribute__((always_inline)) { wait_slab<0>(xb[I.value][0], xb[I.value][1]); });
-  for (; s0 < total; s0 += F_PD)
-    unrolled<F_PD>([&](auto I) __attribute__((always_inline)) {
+  unrolled<PDI>([&](auto I) __attribute__((always_inline)) { wait_rows<0, R>(xb[I.value]); });
+  for (; s0 < total; s0 += PDI)
+    unrolled<PDI>([&](auto I) __attribute__((always_inline)) {
       if (s0 + I.value < total) stream_iter(I, bc<false>{}, s0 + I.value);
     });
   if (pending) accumulate();
@@ -481,12 +524,20 @@ bool fused_plan(Ctx *c, int64_t p, int B, int M) {
   const int64_t per_block = (int64_t)F_STREAM * 4 * 2;           // 2048 columns per workgroup
   int Q = (int)((p + per_block - 1) / per_block);
   if (Q > F_QMAX || Q > cus) return false;
-  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds) != hipSuccess) {
+  int R = (B % 2 == 0) ? 2 : 1;                            // rows per iteration
+  if (const char *e = getenv("CADA_FUSED_ROWS")) {         // tuning / test knob
+    if (atoi(e) == 1) R = 1;
+  }
+  const void *fn = R == 2 ? reinterpret_cast<const void *>(k_fused<2>) : reinterpret_cast<const void *>(k_fused<1>);
+  const size_t lds = R == 2 ? FusedGeom<2>::lds : FusedGeom<1>::lds;
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return false;
   }
   int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused, F_THREADS, kFusedLds) != hipSuccess || per_cu < 1) {
+  const hipError_t oe = R == 2 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<2>, F_THREADS, lds)
+                               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<1>, F_THREADS, lds);
+  if (oe != hipSuccess || per_cu < 1) {
     (void)hipGetLastError();
     return false;
   }
@@ -502,7 +553,7 @@ bool fused_plan(Ctx *c, int64_t p, int B, int M) {
   c->fused_Q = Q;
   c->fused_clusters = ncl;
   c->fused_cols = ((p + Q - 1) / Q + 3) / 4 * 4;
-  c->fused_rs = 1;
+  c->fused_rs = R;
   const char *plain = getenv("CADA_FUSED_PLAIN_LAUNCH");
   c->fused_plain_launch = (plain && atoi(plain) != 0) ? 1 : 0;
   const int nslab = B;
@@ -525,15 +576,19 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
   void *args[] = {&a};
   prof_mark(c);
   hipError_t e;
+  const dim3 grid((unsigned)(a.Q * a.n_clusters)), block(F_THREADS);
+  const bool two = c->fused_rs == 2;
+  const size_t lds = two ? FusedGeom<2>::lds : FusedGeom<1>::lds;
   if (c->fused_plain_launch) {
     // Same grid without the cooperative-launch guarantee: one workgroup per CU is resident at once
     // on an otherwise idle device, and every wait in the kernel is bounded.  For profilers that
     // cannot trace cooperative dispatches.
-    hipLaunchKernelGGL(k_fused, dim3((unsigned)(a.Q * a.n_clusters)), dim3(F_THREADS), kFusedLds, c->stream, a);
+    if (two) hipLaunchKernelGGL(k_fused<2>, grid, block, lds, c->stream, a);
+    else hipLaunchKernelGGL(k_fused<1>, grid, block, lds, c->stream, a);
     e = hipGetLastError();
   } else {
-    e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_fused), dim3((unsigned)(a.Q * a.n_clusters)),
-                                   dim3(F_THREADS), args, (unsigned)kFusedLds, c->stream);
+    const void *fn = two ? reinterpret_cast<const void *>(k_fused<2>) : reinterpret_cast<const void *>(k_fused<1>);
+    e = hipLaunchCooperativeKernel(fn, grid, block, args, (unsigned)lds, c->stream);
   }
   prof_mark(c);
   prof_mark(c);
