@@ -152,6 +152,19 @@ int cada_get_state(cada_ctx *ctx, cada_state *out);
  * worker, into out (DEVICE float32 [M, p]). */
 int cada_copy_stored_gradients(cada_ctx *ctx, float *out);
 
+/* Checkpoint / resume.  A checkpoint is the whole workspace (iterate, moments, stored
+ * gradients, reference points, delays, ring, trace, ...) plus the host-side counters, as one
+ * opaque block of cada_checkpoint_bytes(ctx) bytes of DEVICE memory owned by the caller.
+ * cada_checkpoint_save enqueues the copy on the context's stream and then waits for it (this
+ * call synchronises the stream).  cada_checkpoint_load validates the block against the
+ * context (same configuration: shapes, rule, model, workspace size), restores the state and
+ * the step counter, and also waits for the stream; on a mismatch it returns CADA_EINVAL and
+ * changes nothing.  A block saved by one context can be loaded into another context created
+ * with an equal configuration (the data X, y are not part of it). */
+size_t cada_checkpoint_bytes(cada_ctx *ctx);
+int cada_checkpoint_save(cada_ctx *ctx, void *dst);
+int cada_checkpoint_load(cada_ctx *ctx, const void *src);
+
 /* Measurement hooks (not part of the method).  cada_profile_begin creates HIP events
  * for up to max_steps steps; while profiling, every step records an event on the
  * context's stream before and after each of its phases (a phase is one kernel, or one

@@ -56,6 +56,12 @@ _lib.cada_get_state.restype = C.c_int
 _lib.cada_get_state.argtypes = [C.c_void_p, C.POINTER(cada_state)]
 _lib.cada_copy_stored_gradients.restype = C.c_int
 _lib.cada_copy_stored_gradients.argtypes = [C.c_void_p, C.c_void_p]
+_lib.cada_checkpoint_bytes.restype = C.c_size_t
+_lib.cada_checkpoint_bytes.argtypes = [C.c_void_p]
+_lib.cada_checkpoint_save.restype = C.c_int
+_lib.cada_checkpoint_save.argtypes = [C.c_void_p, C.c_void_p]
+_lib.cada_checkpoint_load.restype = C.c_int
+_lib.cada_checkpoint_load.argtypes = [C.c_void_p, C.c_void_p]
 _lib.cada_profile_phases.restype = C.c_int
 _lib.cada_profile_phases.argtypes = [C.c_void_p]
 _lib.cada_profile_phase_name.restype = C.c_char_p
@@ -116,6 +122,18 @@ def cada_copy_stored_gradients(ctx: int, out_ptr: int):
 
 def cada_profile_begin(ctx: int, max_steps: int):
     _check(_lib.cada_profile_begin(ctx, max_steps))
+
+
+def cada_checkpoint_bytes(ctx: int) -> int:
+    return int(_lib.cada_checkpoint_bytes(ctx))
+
+
+def cada_checkpoint_save(ctx: int, dst_ptr: int):
+    _check(_lib.cada_checkpoint_save(ctx, dst_ptr))
+
+
+def cada_checkpoint_load(ctx: int, src_ptr: int):
+    _check(_lib.cada_checkpoint_load(ctx, src_ptr))
 
 
 def cada_profile_end(ctx: int) -> dict:
@@ -226,6 +244,20 @@ class Cada:
         out = torch.empty(self.M, self.p, dtype=torch.float32, device=self.workspace.device)
         cada_copy_stored_gradients(self.ctx, out.data_ptr())
         return out
+
+    def checkpoint(self) -> torch.Tensor:
+        """The whole state as one opaque device block (see cada_checkpoint_save)."""
+        out = torch.empty(cada_checkpoint_bytes(self.ctx), dtype=torch.uint8, device=self.workspace.device)
+        cada_checkpoint_save(self.ctx, out.data_ptr())
+        return out
+
+    def restore(self, block: torch.Tensor):
+        assert block.is_cuda and block.dtype == torch.uint8 and block.is_contiguous()
+        assert block.numel() == cada_checkpoint_bytes(self.ctx)
+        cada_checkpoint_load(self.ctx, block.data_ptr())
+        st = cada_state()
+        _check(_lib.cada_get_state(self.ctx, C.byref(st)))
+        self.k = int(st.k)
 
     def close(self):
         if self.ctx:

@@ -242,6 +242,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   c->n_col_chunks = g.n_col_chunks;
   c->chunk_cols = g.chunk_cols;
   c->ws_bytes = need;
+  c->ws_base = cfg->workspace;
   if (const char *e = getenv("CADA_LOGREG_GROUP")) c->logreg_group = atoi(e);   // tuning knob
   Carver w{static_cast<char *>(cfg->workspace)};
   carve_common(w, cfg, g, &s, c);
@@ -344,6 +345,58 @@ int cada_copy_stored_gradients(cada_ctx *ctx, float *out) {
   const int tb = 256;
   hipLaunchKernelGGL(k_gather_stored, dim3((unsigned)((c->s.p + tb - 1) / tb), c->s.M), dim3(tb), 0, c->stream, c->s, out);
   HIP_TRY(hipGetLastError());
+  return CADA_OK;
+}
+
+namespace {
+struct CheckpointHeader {          // 64 bytes in front of the workspace image
+  uint64_t magic, ws_bytes;
+  int64_t k, p;
+  int32_t M, B, rule, model, D, d_max, server_sgd;
+  uint32_t fused_seq;
+};
+static_assert(sizeof(CheckpointHeader) <= 64, "checkpoint header");
+constexpr uint64_t kCheckpointMagic = 0x43414441434b5031ull;   // "CADACKP1"
+constexpr size_t kCheckpointHeaderBytes = 64;
+
+CheckpointHeader header_of(const Ctx *c) {
+  CheckpointHeader h{};
+  h.magic = kCheckpointMagic; h.ws_bytes = c->ws_bytes; h.k = c->k; h.p = c->s.p;
+  h.M = c->s.M; h.B = c->s.B; h.rule = c->s.rule; h.model = c->model; h.D = c->s.D; h.d_max = c->s.d_max;
+  h.server_sgd = c->s.server_sgd; h.fused_seq = c->fused_seq;
+  return h;
+}
+}  // namespace
+
+size_t cada_checkpoint_bytes(cada_ctx *ctx) { return ctx ? kCheckpointHeaderBytes + ctx->c.ws_bytes : 0; }
+
+int cada_checkpoint_save(cada_ctx *ctx, void *dst) {
+  if (!ctx || !dst) { set_error("ctx/dst is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  const CheckpointHeader h = header_of(c);
+  HIP_TRY(hipMemcpyAsync(static_cast<char *>(dst) + kCheckpointHeaderBytes, c->ws_base, c->ws_bytes, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(dst, &h, sizeof(h), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));     // h lives on this frame
+  return CADA_OK;
+}
+
+int cada_checkpoint_load(cada_ctx *ctx, const void *src) {
+  if (!ctx || !src) { set_error("ctx/src is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  CheckpointHeader h{};
+  HIP_TRY(hipMemcpyAsync(&h, src, sizeof(h), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  const CheckpointHeader mine = header_of(c);
+  if (h.magic != kCheckpointMagic) { set_error("not a checkpoint block"); return CADA_EINVAL; }
+  if (h.ws_bytes != mine.ws_bytes || h.p != mine.p || h.M != mine.M || h.B != mine.B || h.rule != mine.rule ||
+      h.model != mine.model || h.D != mine.D || h.d_max != mine.d_max || h.server_sgd != mine.server_sgd) {
+    set_error("checkpoint was saved with a different configuration");
+    return CADA_EINVAL;
+  }
+  HIP_TRY(hipMemcpyAsync(c->ws_base, static_cast<const char *>(src) + kCheckpointHeaderBytes, c->ws_bytes, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  c->k = h.k;
+  c->fused_seq = h.fused_seq;
   return CADA_OK;
 }
 

@@ -93,6 +93,7 @@ struct Ctx {
   int32_t model, gemm_dtype, n_layers;
   int32_t dims[CADA_MAX_LAYERS + 1];
   size_t ws_bytes;
+  void *ws_base;             // the caller's workspace
   // logistic launch geometry
   int vec;                   // 4 if rows can be read as float4, else 1
   int n_col_chunks;          // column chunks of the dot-product kernel
