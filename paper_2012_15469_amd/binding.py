@@ -136,6 +136,10 @@ def cada_checkpoint_load(ctx: int, src_ptr: int):
     _check(_lib.cada_checkpoint_load(ctx, src_ptr))
 
 
+def cada_profile_phase_names(ctx: int) -> list:
+    return [_lib.cada_profile_phase_name(ctx, i).decode() for i in range(_lib.cada_profile_phases(ctx))]
+
+
 def cada_profile_end(ctx: int) -> dict:
     """{phase name: mean milliseconds per step} over the profiled steps, plus "steps"."""
     n = _lib.cada_profile_phases(ctx)

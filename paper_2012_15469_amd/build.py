@@ -13,7 +13,8 @@ HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
 
 LIBCADA = os.path.join(HERE, "libcada.so")
 LIBCADA_SRC = [os.path.join(HERE, "csrc", f) for f in
-               ("cada_api.hip", "cada_logreg.hip", "cada_logreg_fused.hip", "cada_server.hip", "cada_mlp.hip")]
+               ("cada_api.hip", "cada_logreg.hip", "cada_logreg_fused.hip", "cada_logreg_small.hip", "cada_server.hip",
+                "cada_mlp.hip")]
 
 
 def _run(cmd):

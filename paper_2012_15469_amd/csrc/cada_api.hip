@@ -56,7 +56,7 @@ struct Geometry {
   int64_t chunk_cols;
   int n_lhs_part;
   int lhs_cap;              // slots reserved per worker (the single-pass logistic kernel needs 4 per workgroup)
-  int n_ring_part;
+  int n_ring_part, ring_cap;
   int64_t total_rows;
 };
 
@@ -101,8 +101,10 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   g->n_col_chunks = (int)((cfg->p + g->chunk_cols - 1) / g->chunk_cols);
   const int64_t per_block = (int64_t)kBlock * g->vec;
   g->n_lhs_part = (int)((cfg->p + per_block - 1) / per_block);
-  // server kernel: one block per 256 coordinates, see cada_server.hip
+  // server kernel: one block per 256 coordinates, see cada_server.hip (the multi-step kernel of
+  // cada_logreg_small.hip writes one partial per worker instead: room for either)
   g->n_ring_part = (int)((cfg->p + 255) / 256);
+  g->ring_cap = g->n_ring_part > cfg->M ? g->n_ring_part : cfg->M;
   if (cfg->model == CADA_MODEL_MLP) g->n_lhs_part = mlp_lhs_slots(cfg);
   const int fused_slots = 4 * (int)((cfg->p + 2047) / 2048);
   g->lhs_cap = g->n_lhs_part > fused_slots ? g->n_lhs_part : fused_slots;
@@ -129,7 +131,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   float *lhs_part = w.take<float>(M * (size_t)g.lhs_cap);
   uint8_t *mask = w.take<uint8_t>(M);
   float *ring = w.take<float>((size_t)cfg->d_max);
-  float *ring_part = w.take<float>((size_t)g.n_ring_part);
+  float *ring_part = w.take<float>((size_t)g.ring_cap);
   uint64_t *uploads = w.take<uint64_t>(1);
   uint32_t *err = w.take<uint32_t>(1);
   int64_t *row_off = w.take<int64_t>(M + 1);
@@ -139,12 +141,15 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   int32_t *t_tau = w.take<int32_t>(T * M);
   float *zpart = nullptr;
   unsigned long long *post = nullptr;
+  uint32_t *small_bar = nullptr;
   if (cfg->model == CADA_MODEL_LOGREG) {
     zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
     post = w.take<unsigned long long>(kFusedPostWords);
+    small_bar = w.take<uint32_t>(64);
   }
   if (!s) return;
   c->fused_post = post;
+  c->small_bar = small_bar;
   s->theta = theta; s->theta_lo = theta_lo; s->hist_lo = hist_lo; s->snap_lo = snap_lo; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
   s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl;
   s->tau = tau; s->sel = sel; s->lhs = lhs; s->lhs_part = lhs_part; s->mask = mask;
@@ -255,9 +260,11 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   s.eps = (float)cfg->eps; s.lam = (float)cfg->lambda_l2; s.c = cfg->c;
   if (cfg->model == CADA_MODEL_LOGREG) {
     if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = 4 * c->fused_Q;
+    else if (small_plan(c, cfg->p, cfg->B, cfg->M)) s.n_ring_part = cfg->M;
     c->n_phases = 4;
     if (c->fused) { c->phase_names[0] = "logreg_single_pass"; c->phase_names[1] = "logreg_unused"; }
     else { c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad"; }
+    if (c->small) { c->n_phases = 1; c->phase_names[0] = "logreg_whole_steps"; }
     c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
   }
   if (cfg->model == CADA_MODEL_MLP) {
@@ -303,6 +310,11 @@ int cada_step(cada_ctx *ctx, const int32_t *idx, const uint8_t *replay) {
   if (!ctx) { set_error("ctx is NULL"); return CADA_EINVAL; }
   if (!idx) { set_error("idx is NULL"); return CADA_EINVAL; }
   Ctx *c = &ctx->c;
+  if (c->small) {
+    const int rs = small_steps(c, idx, replay, 1);
+    if (rs == CADA_OK) c->k += 1;
+    return rs;
+  }
   int rc = (c->model != CADA_MODEL_LOGREG) ? mlp_gradients(c, idx)
            : (c->fused ? logreg_gradients_fused(c, idx) : logreg_gradients(c, idx));
   if (rc != CADA_OK) return rc;
@@ -317,6 +329,11 @@ int cada_run(cada_ctx *ctx, const int32_t *idx_sched, const uint8_t *replay_sche
   if (n_steps < 0) { set_error("n_steps must be >= 0"); return CADA_EINVAL; }
   if (n_steps > 0 && !idx_sched) { set_error("idx_sched is NULL"); return CADA_EINVAL; }
   const int64_t M = ctx->c.s.M, B = ctx->c.s.B;
+  if (ctx->c.small && n_steps > 0) {      // all n_steps iterations in one launch
+    const int rs = small_steps(&ctx->c, idx_sched, replay_sched, n_steps);
+    if (rs == CADA_OK) ctx->c.k += n_steps;
+    return rs;
+  }
   for (int64_t i = 0; i < n_steps; ++i) {
     const int rc = cada_step(ctx, idx_sched + i * M * B, replay_sched ? replay_sched + i * M : nullptr);
     if (rc != CADA_OK) return rc;
@@ -349,21 +366,21 @@ int cada_copy_stored_gradients(cada_ctx *ctx, float *out) {
 }
 
 namespace {
-struct CheckpointHeader {          // 64 bytes in front of the workspace image
+struct CheckpointHeader {          // in front of the workspace image
   uint64_t magic, ws_bytes;
   int64_t k, p;
   int32_t M, B, rule, model, D, d_max, server_sgd;
-  uint32_t fused_seq;
+  uint32_t fused_seq, small_seq;
 };
-static_assert(sizeof(CheckpointHeader) <= 64, "checkpoint header");
+static_assert(sizeof(CheckpointHeader) <= 128, "checkpoint header");
 constexpr uint64_t kCheckpointMagic = 0x43414441434b5031ull;   // "CADACKP1"
-constexpr size_t kCheckpointHeaderBytes = 64;
+constexpr size_t kCheckpointHeaderBytes = 128;
 
 CheckpointHeader header_of(const Ctx *c) {
   CheckpointHeader h{};
   h.magic = kCheckpointMagic; h.ws_bytes = c->ws_bytes; h.k = c->k; h.p = c->s.p;
   h.M = c->s.M; h.B = c->s.B; h.rule = c->s.rule; h.model = c->model; h.D = c->s.D; h.d_max = c->s.d_max;
-  h.server_sgd = c->s.server_sgd; h.fused_seq = c->fused_seq;
+  h.server_sgd = c->s.server_sgd; h.fused_seq = c->fused_seq; h.small_seq = c->small_seq;
   return h;
 }
 }  // namespace
@@ -397,6 +414,7 @@ int cada_checkpoint_load(cada_ctx *ctx, const void *src) {
   HIP_TRY(hipStreamSynchronize(c->stream));
   c->k = h.k;
   c->fused_seq = h.fused_seq;
+  c->small_seq = h.small_seq;
   return CADA_OK;
 }
 

@@ -105,6 +105,11 @@ struct Ctx {
   int64_t fused_cols;
   uint32_t fused_seq, fused_seq_per_step;
   unsigned long long *fused_post;
+  // whole iterations in one launch for small logistic workloads, cada_logreg_small.hip
+  int small;
+  size_t small_lds;
+  uint32_t *small_bar;       // grid barrier counter in the workspace
+  uint32_t small_seq;        // its value after everything enqueued so far
   int logreg_group;          // workers per launch pair of the logistic gradient kernels (0 = all)
   void *mlp;                 // MLP plan (cada_mlp.hip), or nullptr
   void *prof;                // profiling events (cada_api.hip), or nullptr
@@ -120,6 +125,8 @@ void prof_mark(Ctx *c);
 int logreg_gradients(Ctx *c, const int32_t *idx);
 bool fused_plan(Ctx *c, int64_t p, int B, int M);
 int logreg_gradients_fused(Ctx *c, const int32_t *idx);
+bool small_plan(Ctx *c, int64_t p, int B, int M);
+int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps);
 constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgroups x 4 buffers x 16 values
 // S1+S2 for the MLP.
 int mlp_gradients(Ctx *c, const int32_t *idx);

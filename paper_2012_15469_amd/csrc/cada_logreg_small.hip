@@ -1,0 +1,277 @@
+// Whole iterations of Algorithm 1 in one kernel launch, for logistic workloads so small that a
+// step is bound by launch and dependency latency rather than by memory (tens of workers, a few
+// hundred coordinates): four dependent launches per step cost 35-40 us, the arithmetic well
+// under one.  One workgroup per worker, launched cooperatively; n_steps iterations per launch
+// with two grid-wide barriers each:
+//   phase A (workgroup m = worker m): both minibatch gradients in the difference form of
+//     cada_logreg.hip, the rule's left-hand side, the right-hand side from the ring, the
+//     decision, tau, the stored/fresh pointer swap, the trace           [S1-S4 of the step]
+//   -- barrier --
+//   phase B (coordinates dealt to the workgroups): aggregate of the stored gradients, the server
+//     update, the reference-point history, the squared step             [S5-S7]
+//   -- barrier --
+// A barrier is an agent-scope counter in the workspace; arrivals release (write back) and
+// departures acquire (invalidate) the XCD-local caches.  Every wait is bounded: a wait that
+// exceeds the bound sets bit 1 of the error flags and the workgroup stops waiting.
+#include <cstdlib>
+
+#include "cada_internal.h"
+
+namespace cada {
+
+struct SmallArgs {
+  DevState s;
+  const int32_t *idx;        // [n_steps][M][B]
+  const uint8_t *replay;     // [n_steps][M] or nullptr
+  int64_t n_steps;
+  uint32_t *bar;             // barrier counter (monotone over the life of the context)
+  uint32_t bar_base;         // its value when this launch starts
+  uint32_t spin_limit;
+};
+
+__device__ __forceinline__ float sigmoid_s(float a) { return 1.0f / (1.0f + expf(-a)); }
+
+// All workgroups arrive; `target` is the counter value that means everyone has.
+__device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target, bool &dead) {
+  __threadfence();                      // release: this workgroup's writes are visible device-wide
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t spins = 0;
+    // (difference compared as signed so that the counter may wrap)
+    while (!dead && (int32_t)(__hip_atomic_load(a.bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+      if (++spins > a.spin_limit) { dead = true; atomicOr(a.s.err, 2u); break; }
+      __builtin_amdgcn_s_sleep(2);
+    }
+  }
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // acquire: drop stale cached lines
+}
+
+// grid = M workgroups of kBlock threads; dynamic LDS: theta, d (2 p floats), r, dr, row offsets
+// (B each) and the worker's whole minibatch (B p floats): the rows are fetched once, with every
+// load independent of the others, and both passes over them run from LDS
+__global__ __launch_bounds__(kBlock) void k_small(const SmallArgs a) {
+  extern __shared__ __align__(16) unsigned char small_smem[];
+  DevState s = a.s;
+  const int p = (int)s.p, B = s.B, M = s.M;
+  float *th_s = reinterpret_cast<float *>(small_smem);     // [p] theta (hi part + lo part rounded once)
+  float *d_s = th_s + p;                                   // [p] theta - theta_ref
+  float *r_s = d_s + p;                                    // [B]
+  float *dr_s = r_s + B;                                   // [B]
+  long long *row_s = reinterpret_cast<long long *>(dr_s + B + ((2 * p + 2 * B) & 1));   // [B], 8-byte aligned
+  float *x_s = reinterpret_cast<float *>(row_s + B);       // [B][p] the minibatch
+  __shared__ float red[4];
+  __shared__ double redd[kBlock];
+  __shared__ float bcast[2];
+
+  const int m = blockIdx.x, nb = gridDim.x;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t mp = (int64_t)M * s.p;
+  const float invB = 1.0f / (float)B;
+  bool dead = false;
+  uint32_t bar_target = a.bar_base;
+
+  for (int64_t step = 0; step < a.n_steps; ++step) {
+    const int64_t k = s.k + step;
+    // ------------------------------------------------------------ phase A
+    const RefPtr ref = theta_ref(s, m, k);
+    for (int j = tid; j < p; j += kBlock) {
+      th_s[j] = s.theta[j];
+      d_s[j] = (s.theta[j] - ref.hi[j]) + (s.theta_lo[j] - ref.lo[j]);
+    }
+    const int32_t *idx = a.idx + (step * M + m) * (int64_t)B;
+    const int64_t base = s.row_off[m], n_m = s.row_off[m + 1] - base;
+    for (int b = tid; b < B; b += kBlock) {
+      int64_t r = idx[b];
+      if (r < 0 || r >= n_m) { atomicOr(s.err, 1u); r = r < 0 ? 0 : n_m - 1; }
+      row_s[b] = (base + r) * s.p;
+    }
+    __syncthreads();
+    for (int e = tid; e < B * p; e += kBlock) {
+      const int b = e / p, j = e - b * p;
+      x_s[e] = s.X[row_s[b] + j];
+    }
+    if (tid < B) r_s[tid] = static_cast<const float *>(s.y)[row_s[tid] / s.p];     // the labels, for now
+    for (int b = kBlock + tid; b < B; b += kBlock) r_s[b] = static_cast<const float *>(s.y)[row_s[b] / s.p];
+    __syncthreads();
+    // rows over the wavefronts: z = x.theta, dz = x.d, then the residual and its difference
+    for (int b = w; b < B; b += kBlock / kWave) {
+      const float *x = x_s + b * p;
+      float z = 0.f, dz = 0.f;
+      for (int j = lane; j < p; j += kWave) {
+        const float xv = x[j];
+        z = fmaf(xv, th_s[j], z);
+        dz = fmaf(xv, d_s[j], dz);
+      }
+      z = wave_sum(z);
+      dz = wave_sum(dz);
+      if (lane == 0) {
+        const float y = r_s[b];
+        const float aa = -y * z, bb = aa + y * dz;
+        const float sa = sigmoid_s(aa);
+        r_s[b] = -y * sa * invB;
+        dr_s[b] = y * sa * sigmoid_s(-bb) * expm1f(y * dz) * invB;
+      }
+    }
+    __syncthreads();
+    // columns over the threads: fresh gradient, innovation, the rule's left-hand side
+    const int cur = s.sel[m];
+    float *gf = s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p;
+    const float *gs = s.gbuf + (int64_t)cur * mp + (int64_t)m * s.p;
+    float sq = 0.f;
+    for (int j = tid; j < p; j += kBlock) {
+      float g = 0.f, iv = 0.f;
+      for (int b = 0; b < B; ++b) {
+        const float xv = x_s[b * p + j];
+        g = fmaf(r_s[b], xv, g);
+        iv = fmaf(dr_s[b], xv, iv);
+      }
+      g = fmaf(s.lam, th_s[j], g);
+      iv = fmaf(s.lam, d_s[j], iv);
+      float lhs_term = iv;
+      if (s.rule == CADA_RULE_CADA1) {
+        const int64_t o = (int64_t)m * s.p + j;
+        s.dtl[(int64_t)(1 - cur) * mp + o] = iv;
+        lhs_term = iv - s.dtl[(int64_t)cur * mp + o];
+      } else if (s.rule != CADA_RULE_CADA2) {
+        lhs_term = g - gs[j];                 // condition (LAGrule): against the stored gradient
+      }
+      gf[j] = g;
+      sq = fmaf(lhs_term, lhs_term, sq);
+    }
+    const float lhs = block_sum(sq, red);
+    // right-hand side: the squared step of iteration k-1 from the per-workgroup partial sums
+    double acc = 0.0;
+    if (k > 0)
+      for (int i = tid; i < s.n_ring_part; i += kBlock) acc += (double)s.ring_part[i];
+    redd[tid] = acc;
+    __syncthreads();
+    for (int o = kBlock / 2; o > 0; o >>= 1) {
+      if (tid < o) redd[tid] += redd[tid + o];
+      __syncthreads();
+    }
+    if (tid == 0) {
+      const int last = k > 0 ? (int)((k - 1) % s.d_max) : -1;
+      const float newest = (float)redd[0];
+      double sum = 0.0;
+      for (int j = 0; j < s.d_max; ++j) sum += (double)(j == last ? newest : s.ring[j]);
+      const double rhs = (s.c / (double)s.d_max) * sum;
+      const int32_t tau = s.tau[m];
+      const bool own = (s.rule == CADA_RULE_ALWAYS) || ((double)lhs > rhs) || (tau >= s.D);
+      bool up = own;
+      const uint8_t *replay = a.replay ? a.replay + step * M : nullptr;
+      if (replay != nullptr && replay[m] != CADA_REPLAY_FREE) up = replay[m] != 0;
+      if (k < s.trace_steps) {
+        const int64_t o = k * M + m;
+        s.t_mask[o] = up ? 1 : 0;
+        s.t_own[o] = own ? 1 : 0;
+        s.t_lhs[o] = lhs;
+        s.t_tau[o] = tau;
+        if (m == 0) s.t_rhs[k] = (float)rhs;
+      }
+      s.lhs[m] = lhs;
+      s.mask[m] = up ? 1 : 0;
+      if (up) {
+        s.tau[m] = 1;
+        s.sel[m] = cur ^ 1;
+        atomicAdd(reinterpret_cast<unsigned long long *>(s.uploads), 1ull);
+      } else {
+        s.tau[m] = tau + 1;
+      }
+      bcast[0] = newest;
+    }
+    __syncthreads();
+    bar_target += (uint32_t)nb;
+    grid_barrier(a, bar_target, dead);
+    // ------------------------------------------------------------ phase B
+    if (m == 0 && tid == 0 && k > 0) s.ring[(k - 1) % s.d_max] = bcast[0];   // nobody reads this slot before the next barrier
+    float sqs = 0.f;
+    for (int64_t j = (int64_t)m * kBlock + tid; j < s.p; j += (int64_t)nb * kBlock) {
+      float nab = 0.f;
+#pragma unroll 8
+      for (int mm = 0; mm < M; ++mm) nab += s.gbuf[(int64_t)s.sel[mm] * mp + (int64_t)mm * s.p + j];
+      nab = nab / (float)M;
+      float hh = s.h[j], vh = s.vhat[j], vv = vh, stp;
+      if (s.server_sgd) {
+        stp = s.alpha * nab;
+      } else {
+        hh = fmaf(s.omb1, nab - hh, hh);
+        vv = fmaf(s.omb2, nab * nab - vh, vh);
+        vh = fmaxf(vv, vh);
+        stp = s.alpha * hh / sqrtf(s.eps + vh);
+      }
+      // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
+      const float t0 = s.theta[j], ms = -stp;
+      const float sum = t0 + ms;
+      const float bb = sum - t0;
+      const float er = (t0 - (sum - bb)) + (ms - bb);
+      const float lo = s.theta_lo[j] + er;
+      const float th = sum + lo, tl = lo - (th - sum);
+      s.nabla[j] = nab; s.h[j] = hh; s.v[j] = vv; s.vhat[j] = vh; s.theta[j] = th; s.theta_lo[j] = tl;
+      if (s.rule == CADA_RULE_CADA2) {
+        s.hist[((k + 1) % s.R) * s.p + j] = th;
+        s.hist_lo[((k + 1) % s.R) * s.p + j] = tl;
+      } else if (s.rule == CADA_RULE_CADA1 && (k + 1) % s.D == 0) {
+        s.snap[j] = th;
+        s.snap_lo[j] = tl;
+      }
+      sqs = fmaf(stp, stp, sqs);
+    }
+    const float part = block_sum(sqs, red);
+    if (tid == 0) s.ring_part[m] = part;
+    bar_target += (uint32_t)nb;
+    grid_barrier(a, bar_target, dead);
+  }
+}
+
+// Whether the multi-step kernel serves this configuration; sets the ring-partial count it uses.
+bool small_plan(Ctx *c, int64_t p, int B, int M) {
+  c->small = 0;
+  const char *on = getenv("CADA_SMALL");
+  if (on && atoi(on) == 0) return false;
+  if (p >= 8192) return false;
+  // Measured: 16 us per step against 36 us for M = 10, B = 10, p = 54, but 73 us against 39 us for
+  // M = 20, B = 32, p = 784 (20 workgroups cannot hide the latency of their dependent loads, and
+  // each barrier invalidates the XCD's L2): only the tiny problems take this path unless asked to.
+  const char *force = getenv("CADA_SMALL");
+  if (!(force && atoi(force) == 1) && (int64_t)M * B * p > 32768) return false;
+  int dev = 0, coop = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return false;
+  if (M > cus) return false;
+  c->small_lds = (size_t)(2 * p + 2 * B + 1) * sizeof(float) + (size_t)B * sizeof(long long) + (size_t)B * p * sizeof(float);
+  if (c->small_lds > 150 * 1024) return false;      // the minibatch of a worker must fit in LDS
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_small), hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->small_lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  c->small = 1;
+  return true;
+}
+
+int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps) {
+  SmallArgs a;
+  a.s = c->s;
+  a.s.k = c->k;
+  a.idx = idx;
+  a.replay = replay;
+  a.n_steps = n_steps;
+  a.bar = c->small_bar;
+  a.bar_base = c->small_seq;
+  a.spin_limit = 4000000u;
+  c->small_seq += (uint32_t)(2 * n_steps * c->s.M);
+  void *args[] = {&a};
+  prof_mark(c);
+  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_small), dim3((unsigned)c->s.M), dim3(kBlock), args,
+                                                  (unsigned)c->small_lds, c->stream);
+  prof_mark(c);
+  if (e != hipSuccess) {
+    set_error("multi-step logistic launch failed: %s", hipGetErrorString(e));
+    return CADA_EHIP;
+  }
+  return CADA_OK;
+}
+
+}  // namespace cada

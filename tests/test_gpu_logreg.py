@@ -17,7 +17,10 @@ def _case(cfg):
     return prob, upload(prob), generators.make_schedule(cfg)
 
 
-def test_cfg1_full():
+# small: 1 = whole iterations in one launch (cada_logreg_small.hip), 0 = one launch per kernel
+@pytest.mark.parametrize("small", [1, 0])
+def test_cfg1_full(small, monkeypatch):
+    monkeypatch.setenv("CADA_SMALL", str(small))
     cfg = configs.CFG1
     prob, dev, sched = _case(cfg)
     stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
@@ -26,7 +29,9 @@ def test_cfg1_full():
     assert stats["stored_rel_l2"] < 1e-5
 
 
-def test_cfg2_full():
+@pytest.mark.parametrize("small", [1, 0])
+def test_cfg2_full(small, monkeypatch):
+    monkeypatch.setenv("CADA_SMALL", str(small))
     cfg = configs.CFG2
     prob, dev, sched = _case(cfg)
     stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
@@ -34,12 +39,16 @@ def test_cfg2_full():
     assert stats["stored_rel_l2"] < 1e-5
 
 
-@pytest.mark.parametrize("p,rule,fused", [(8200, 2, 0), (8200, 1, 0), (4099, 2, 0), (4099, 1, 0), (8200, 2, 1), (8200, 1, 1)])
+@pytest.mark.parametrize("p,rule,fused", [(8200, 2, 0), (8200, 1, 0), (4099, 2, 0), (4099, 1, 0), (8200, 2, 1), (8200, 1, 1),
+                                          (4099, 2, -1), (4099, 1, -1)])
 def test_cfg3_reduced_ragged(p, rule, fused, monkeypatch):
     """The high-dimensional recipe at reduced size: several column chunks with a ragged
     tail (p = 8200 = 8192 + 8), a row count that is no multiple of the row group (B = 20)
     and the scalar-load path (p = 4099 is not a multiple of 4)."""
-    monkeypatch.setenv("CADA_FUSED", str(fused))     # 1: the single-pass register-resident kernel
+    # fused 1: the single-pass register-resident kernel; 0: the two streaming passes;
+    # -1: the multi-step kernel for small problems (p < 8192)
+    monkeypatch.setenv("CADA_FUSED", str(max(fused, 0)))
+    monkeypatch.setenv("CADA_SMALL", "1" if fused < 0 else "0")
     # c is lowered from the workload's 0.3: a minibatch spans only B of the p directions, so
     # with c = 0.3 the rule never fires at this size and only forced uploads would be tested
     cfg = configs.CFG3.scaled(layer_dims=(p,), M=5, N_m=64, B=20, K=60, D=10, rule=rule, alpha=0.02, c=1e-4)
