@@ -261,11 +261,14 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   if (cfg->model == CADA_MODEL_LOGREG) {
     if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = 4 * c->fused_Q;
     else if (small_plan(c, cfg->p, cfg->B, cfg->M)) s.n_ring_part = cfg->M;
-    c->n_phases = 4;
-    if (c->fused) { c->phase_names[0] = "logreg_single_pass"; c->phase_names[1] = "logreg_unused"; }
-    else { c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad"; }
-    if (c->small) { c->n_phases = 1; c->phase_names[0] = "logreg_whole_steps"; }
-    c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
+    if (c->small) {
+      c->n_phases = 1; c->phase_names[0] = "logreg_whole_steps";
+    } else if (c->fused) {
+      c->n_phases = 3; c->phase_names[0] = "logreg_single_pass"; c->phase_names[1] = "rule"; c->phase_names[2] = "server_update";
+    } else {
+      c->n_phases = 4; c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad";
+      c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
+    }
   }
   if (cfg->model == CADA_MODEL_MLP) {
     size_t off = w.off;

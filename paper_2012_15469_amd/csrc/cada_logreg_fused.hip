@@ -591,7 +591,6 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
     e = hipLaunchCooperativeKernel(fn, grid, block, args, (unsigned)lds, c->stream);
   }
   prof_mark(c);
-  prof_mark(c);
   if (e != hipSuccess) {
     set_error("fused logistic gradient launch failed: %s", hipGetErrorString(e));
     return CADA_EHIP;
