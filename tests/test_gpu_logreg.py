@@ -67,7 +67,8 @@ def test_cfg3_reduced_ragged(p, rule, fused, monkeypatch):
     assert 0.1 < tr["mask"][free].mean() < 0.9, "the case must mix rule-driven uploads and skips"
 
 
-@pytest.mark.parametrize("rule,B,clusters", [(2, 48, 0), (1, 48, 0), (2, 100, 2), (1, 72, 2), (2, 200, 1)])
+# even B: two rows per iteration; odd B: one row per iteration
+@pytest.mark.parametrize("rule,B,clusters", [(2, 48, 0), (1, 48, 0), (2, 100, 2), (1, 72, 2), (2, 200, 1), (2, 51, 0), (1, 75, 2)])
 def test_single_pass_kernel_steady_state(rule, B, clusters, monkeypatch):
     """The single-pass kernel's unrolled steady-state loop only runs once a cluster of
     workgroups streams more than 40 rows: longer minibatches, and fewer clusters than workers
