@@ -152,6 +152,16 @@ int cada_get_state(cada_ctx *ctx, cada_state *out);
  * worker, into out (DEVICE float32 [M, p]). */
 int cada_copy_stored_gradients(cada_ctx *ctx, float *out);
 
+/* Evaluation on all the data at the current iterate (the y-axes of the figures of Section 4):
+ * out[0] = L(theta) = (1/M) sum_m L_m(theta), L_m the mean loss over worker m's N_m samples
+ * (problem (1), Section 1; plus (lambda/2)|theta|^2 for the logistic model), out[1] = the
+ * fraction of correctly classified samples, averaged over the workers in the same way.
+ * out: DEVICE double[2], written by kernels enqueued on the context's stream (no host
+ * synchronisation).  Not part of an iteration: the optimiser state is not touched; the MLP
+ * variant runs the forward contractions in chunks of B rows per worker and overwrites the
+ * activation buffers of the last step. */
+int cada_eval(cada_ctx *ctx, double *out);
+
 /* Checkpoint / resume.  A checkpoint is the whole workspace (iterate, moments, stored
  * gradients, reference points, delays, ring, trace, ...) plus the host-side counters, as one
  * opaque block of cada_checkpoint_bytes(ctx) bytes of DEVICE memory owned by the caller.

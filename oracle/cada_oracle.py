@@ -83,8 +83,7 @@ def mlp_unpack(theta, dims: Sequence[int]):
     return out
 
 
-def mlp_loss(theta, X, y, dims):
-    """Mean softmax cross-entropy of a ReLU MLP."""
+def mlp_logits(theta, X, dims):
     theta = np.asarray(theta, dtype=np.float64)
     a = np.asarray(X, dtype=np.float64)
     layers = mlp_unpack(theta, dims)
@@ -92,6 +91,12 @@ def mlp_loss(theta, X, y, dims):
         a = a @ W + b
         if i + 1 < len(layers):
             a = np.maximum(a, 0.0)
+    return a
+
+
+def mlp_loss(theta, X, y, dims):
+    """Mean softmax cross-entropy of a ReLU MLP."""
+    a = mlp_logits(theta, X, dims)
     lse = logsumexp(a, axis=1)
     return float(np.mean(lse - a[np.arange(a.shape[0]), np.asarray(y, dtype=np.int64)]))
 
@@ -235,6 +240,23 @@ class CadaOracle:
         self.ring[self.k % self.d_max] = dtheta @ dtheta
         self.theta = theta_new
         self.k += 1
+
+    def evaluate(self, n_samples: Sequence[int]):
+        """(L(theta), accuracy) on all the data: the objective of problem (1), Section 1,
+        L = (1/M) sum_m L_m with L_m the mean loss over worker m's samples (plus the
+        regulariser for the logistic model), and the fraction of correctly classified samples
+        averaged over the workers in the same way (the y-axes of the figures of Section 4)."""
+        loss = acc = 0.0
+        for m in range(self.M):
+            X, y = self.rows(m, np.arange(int(n_samples[m])))
+            if self.model == "logreg":
+                loss += logreg_loss(self.theta, X, y, self.lam)
+                z = np.asarray(X, dtype=np.float64) @ self.theta
+                acc += float(np.mean(np.asarray(y, dtype=np.float64) * z > 0.0))
+            else:
+                loss += mlp_loss(self.theta, X, y, self.dims)
+                acc += float(np.mean(np.argmax(mlp_logits(self.theta, X, self.dims), axis=1) == np.asarray(y)))
+        return loss / self.M, acc / self.M
 
     def run(self, schedule, replay_schedule=None):
         for k in range(len(schedule)):

@@ -56,6 +56,8 @@ _lib.cada_get_state.restype = C.c_int
 _lib.cada_get_state.argtypes = [C.c_void_p, C.POINTER(cada_state)]
 _lib.cada_copy_stored_gradients.restype = C.c_int
 _lib.cada_copy_stored_gradients.argtypes = [C.c_void_p, C.c_void_p]
+_lib.cada_eval.restype = C.c_int
+_lib.cada_eval.argtypes = [C.c_void_p, C.c_void_p]
 _lib.cada_checkpoint_bytes.restype = C.c_size_t
 _lib.cada_checkpoint_bytes.argtypes = [C.c_void_p]
 _lib.cada_checkpoint_save.restype = C.c_int
@@ -122,6 +124,10 @@ def cada_copy_stored_gradients(ctx: int, out_ptr: int):
 
 def cada_profile_begin(ctx: int, max_steps: int):
     _check(_lib.cada_profile_begin(ctx, max_steps))
+
+
+def cada_eval(ctx: int, out_ptr: int):
+    _check(_lib.cada_eval(ctx, out_ptr))
 
 
 def cada_checkpoint_bytes(ctx: int) -> int:
@@ -247,6 +253,12 @@ class Cada:
     def stored_gradients(self) -> torch.Tensor:
         out = torch.empty(self.M, self.p, dtype=torch.float32, device=self.workspace.device)
         cada_copy_stored_gradients(self.ctx, out.data_ptr())
+        return out
+
+    def evaluate(self) -> torch.Tensor:
+        """DEVICE float64 [2]: objective L(theta) and accuracy on all the data (see cada_eval)."""
+        out = torch.empty(2, dtype=torch.float64, device=self.workspace.device)
+        cada_eval(self.ctx, out.data_ptr())
         return out
 
     def checkpoint(self) -> torch.Tensor:

@@ -139,6 +139,8 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   uint8_t *t_mask = w.take<uint8_t>(T * M), *t_own = w.take<uint8_t>(T * M);
   float *t_lhs = w.take<float>(T * M), *t_rhs = w.take<float>(T);
   int32_t *t_tau = w.take<int32_t>(T * M);
+  double *eval_part = w.take<double>(M * (size_t)kEvalBlocks * 2), *eval_acc = w.take<double>(M * 2);
+  int32_t *eval_idx = w.take<int32_t>(M * (size_t)cfg->B);
   float *zpart = nullptr;
   unsigned long long *post = nullptr;
   uint32_t *small_bar = nullptr;
@@ -149,6 +151,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   }
   if (!s) return;
   c->fused_post = post;
+  c->eval_part = eval_part; c->eval_acc = eval_acc; c->eval_idx = eval_idx;
   c->small_bar = small_bar;
   s->theta = theta; s->theta_lo = theta_lo; s->hist_lo = hist_lo; s->snap_lo = snap_lo; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
   s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl;
@@ -366,6 +369,12 @@ int cada_copy_stored_gradients(cada_ctx *ctx, float *out) {
   hipLaunchKernelGGL(k_gather_stored, dim3((unsigned)((c->s.p + tb - 1) / tb), c->s.M), dim3(tb), 0, c->stream, c->s, out);
   HIP_TRY(hipGetLastError());
   return CADA_OK;
+}
+
+int cada_eval(cada_ctx *ctx, double *out) {
+  if (!ctx || !out) { set_error("ctx/out is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  return c->model == CADA_MODEL_LOGREG ? logreg_eval(c, out) : mlp_eval(c, out);
 }
 
 namespace {

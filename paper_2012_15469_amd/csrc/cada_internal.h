@@ -110,6 +110,10 @@ struct Ctx {
   size_t small_lds;
   uint32_t *small_bar;       // grid barrier counter in the workspace
   uint32_t small_seq;        // its value after everything enqueued so far
+  // full-data evaluation scratch (cada_eval)
+  double *eval_part;         // [M][kEvalBlocks][2] per-block sums of (loss, correct)
+  double *eval_acc;          // [M][2]
+  int32_t *eval_idx;         // [M][B] row ids of one evaluation chunk (MLP)
   int logreg_group;          // workers per launch pair of the logistic gradient kernels (0 = all)
   void *mlp;                 // MLP plan (cada_mlp.hip), or nullptr
   void *prof;                // profiling events (cada_api.hip), or nullptr
@@ -131,6 +135,10 @@ constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgro
 // S1+S2 for the MLP.
 int mlp_gradients(Ctx *c, const int32_t *idx);
 int mlp_lhs_slots(const cada_config *cfg);
+int mlp_eval(Ctx *c, double *out);
+int logreg_eval(Ctx *c, double *out);
+void eval_finish(Ctx *c, double *out, int with_reg);   // out = mean over the workers of eval_acc (+ regulariser)
+constexpr int kEvalBlocks = 512;      // blocks per worker of the logistic evaluation kernel
 size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows);
 int mlp_plan(Ctx *c, const cada_config *cfg, char *base, size_t *offset, int64_t total_rows);
 int mlp_init_state(Ctx *c, const float *theta0);

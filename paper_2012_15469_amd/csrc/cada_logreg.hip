@@ -256,4 +256,93 @@ int logreg_gradients(Ctx *c, const int32_t *idx) {
   return CADA_OK;
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Evaluation on all the data (not part of an iteration): logistic loss and accuracy per worker.
+// grid (kEvalBlocks, M); a wavefront takes one row at a time, the block strides over the
+// worker's rows; per-block sums in a fixed order, then one block per worker adds them up.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_eval_rows(const DevState s, double *part) {
+  __shared__ double red[4][2];
+  const int m = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int64_t r0 = s.row_off[m], n = s.row_off[m + 1] - r0;
+  double loss = 0.0, hits = 0.0;
+  for (int64_t r = (int64_t)blockIdx.x * 4 + w; r < n; r += (int64_t)gridDim.x * 4) {
+    const float *x = s.X + (r0 + r) * s.p;
+    float z = 0.f;
+    for (int64_t j = (int64_t)lane * VEC; j < s.p; j += (int64_t)kWave * VEC) {
+      float xv[VEC], tv[VEC], tl[VEC];
+      load_vec<VEC>(x + j, xv);
+      load_vec<VEC>(s.theta + j, tv);
+      load_vec<VEC>(s.theta_lo + j, tl);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) z = fmaf(xv[v], tv[v] + tl[v], z);
+    }
+    z = wave_sum(z);
+    const float mg = static_cast<const float *>(s.y)[r0 + r] * z;       // margin y x.theta
+    // log(1 + exp(-mg)) without overflow
+    loss += (double)(fmaxf(-mg, 0.f) + log1pf(expf(-fabsf(mg))));
+    hits += mg > 0.f ? 1.0 : 0.0;
+  }
+  if (lane == 0) { red[w][0] = loss; red[w][1] = hits; }
+  __syncthreads();
+  if (threadIdx.x < 2) {
+    const int q = threadIdx.x;
+    part[((int64_t)m * gridDim.x + blockIdx.x) * 2 + q] = (red[0][q] + red[1][q]) + (red[2][q] + red[3][q]);
+  }
+}
+
+// acc[m] = (mean loss, mean accuracy) of worker m from its per-block sums.  grid M, one wavefront.
+__global__ void k_eval_worker(const DevState s, const double *part, int nparts, double *acc) {
+  const int m = blockIdx.x, lane = threadIdx.x;
+  double a0 = 0.0, a1 = 0.0;
+  for (int i = lane; i < nparts; i += kWave) { a0 += part[((int64_t)m * nparts + i) * 2]; a1 += part[((int64_t)m * nparts + i) * 2 + 1]; }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { a0 += __shfl_xor(a0, o, 64); a1 += __shfl_xor(a1, o, 64); }
+  if (lane == 0) {
+    const double n = (double)(s.row_off[m + 1] - s.row_off[m]);
+    acc[2 * m] = a0 / n;
+    acc[2 * m + 1] = a1 / n;
+  }
+}
+
+// out = mean over the workers (+ the regulariser's (lambda/2)|theta|^2 when lam != 0).  One block.
+__global__ __launch_bounds__(kBlock) void k_eval_finish(const DevState s, const double *acc, double *out, int with_reg) {
+  __shared__ double red[kBlock];
+  double sq = 0.0;
+  if (with_reg)
+    for (int64_t j = threadIdx.x; j < s.p; j += kBlock) {
+      const double t = (double)s.theta[j] + (double)s.theta_lo[j];
+      sq += t * t;
+    }
+  red[threadIdx.x] = sq;
+  __syncthreads();
+  for (int o = kBlock / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    double l = 0.0, a = 0.0;
+    for (int m = 0; m < s.M; ++m) { l += acc[2 * m]; a += acc[2 * m + 1]; }
+    out[0] = l / (double)s.M + (with_reg ? 0.5 * (double)s.lam * red[0] : 0.0);
+    out[1] = a / (double)s.M;
+  }
+}
+
+void eval_finish(Ctx *c, double *out, int with_reg) {
+  hipLaunchKernelGGL(k_eval_finish, dim3(1), dim3(kBlock), 0, c->stream, c->s, c->eval_acc, out, with_reg);
+}
+
+int logreg_eval(Ctx *c, double *out) {
+  const DevState &s = c->s;
+  const dim3 grid(kEvalBlocks, (unsigned)s.M);
+  if (c->vec == 4) hipLaunchKernelGGL(k_eval_rows<4>, grid, dim3(kBlock), 0, c->stream, s, c->eval_part);
+  else hipLaunchKernelGGL(k_eval_rows<1>, grid, dim3(kBlock), 0, c->stream, s, c->eval_part);
+  hipLaunchKernelGGL(k_eval_worker, dim3((unsigned)s.M), dim3(kWave), 0, c->stream, s, c->eval_part, kEvalBlocks, c->eval_acc);
+  eval_finish(c, out, 1);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_error("evaluation launch failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
+  return CADA_OK;
+}
+
 }  // namespace cada

@@ -466,6 +466,7 @@ struct MlpPlan {
   int L, M, B, Bp, rule, RT;
   int64_t Rp;                     // M * Bp padded rows per step
   int64_t total_rows;             // rows of X
+  int64_t max_rows_per_worker;
   int d[CADA_MAX_LAYERS + 1];
   int64_t offW[CADA_MAX_LAYERS], offb[CADA_MAX_LAYERS];   // offsets into theta, index l-1
   int64_t lda[CADA_MAX_LAYERS + 1];                       // P8(d_l)
@@ -505,6 +506,9 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.RT = tiles128(cfg->B);
   P.Rp = (int64_t)cfg->M * P.Bp;
   P.total_rows = total_rows;
+  P.max_rows_per_worker = 0;
+  for (int m = 0; m < cfg->M; ++m)
+    if (cfg->n_samples[m] > P.max_rows_per_worker) P.max_rows_per_worker = cfg->n_samples[m];
   for (int l = 0; l <= P.L; ++l) { P.d[l] = cfg->layer_dims[l]; P.lda[l] = P8(P.d[l]); }
   int64_t o = 0, wt = 0, wn = 0;
   int slot = 0, maxh = 1;
@@ -877,17 +881,14 @@ int mlp_init_state(Ctx *c, const float *) {
   return CADA_OK;
 }
 
-int mlp_gradients(Ctx *c, const int32_t *idx) {
-  MlpPlan &P = *static_cast<MlpPlan *>(c->mlp);
-  DevState s = c->s;
-  s.k = c->k;
+// Gathers the minibatch rows, prepares the bf16 weights and runs the forward contractions:
+// leaves the activations of every layer and the logits (without bias) of the last one.
+static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx) {
   hipStream_t st = c->stream;
   const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
   const int64_t Rp = P.Rp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
-  const int64_t dwt_stride = per_worker ? P.wt_total : 0, dwn_stride = per_worker ? P.wn_total : 0;
-
-  prof_mark(c);
+  const int64_t dwt_stride = per_worker ? P.wt_total : 0;
   hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp);
   hipLaunchKernelGGL(k_gather_transpose, dim3((P.d[0] + 63) / 64, (B + 63) / 64, M), dim3(kBlock), 0, st,
                      P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, Rp);
@@ -930,6 +931,20 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
       launch_mm5<EPI_STORE2>(c, g, M);
     }
   }
+}
+
+int mlp_gradients(Ctx *c, const int32_t *idx) {
+  MlpPlan &P = *static_cast<MlpPlan *>(c->mlp);
+  DevState s = c->s;
+  s.k = c->k;
+  hipStream_t st = c->stream;
+  const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
+  const int64_t Rp = P.Rp;
+  const bool per_worker = (P.rule == CADA_RULE_CADA2);
+  const int64_t dwn_stride = per_worker ? P.wn_total : 0;
+
+  prof_mark(c);
+  mlp_forward(c, P, s, idx);
   {
     LossArgs la;
     la.s = s; la.Z = P.ZL; la.dZ = P.dZL;
@@ -992,6 +1007,91 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
     set_error("MLP gradient launch failed: %s", hipGetErrorString(e));
     return CADA_EHIP;
   }
+  return CADA_OK;
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Evaluation on all the data (not part of an iteration).
+// idx[m][b] = min(chunk*B + b, N_m - 1): the rows of one evaluation chunk (the tail repeats the
+// last row; those copies are not counted)
+__global__ void k_eval_idx(const DevState s, int32_t *idx, int chunk) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)s.M * s.B) return;
+  const int m = (int)(i / s.B), b = (int)(i % s.B);
+  const int64_t n = s.row_off[m + 1] - s.row_off[m];
+  const int64_t r = (int64_t)chunk * s.B + b;
+  idx[i] = (int32_t)(r < n ? r : n - 1);
+}
+
+// Softmax cross-entropy and top-1 hits of the chunk's valid rows, added to acc[m] (sums, not yet
+// means).  One block per worker, so consecutive chunks add in a fixed order.
+__global__ __launch_bounds__(kBlock) void k_eval_chunk(const DevState s, const float *Z, const int64_t *grow, int64_t offb, int C, int Bp,
+                                                      int chunk, double *acc) {
+  constexpr int MAXC = 32;
+  __shared__ double red[kBlock][2];
+  const int m = blockIdx.x;
+  const int64_t n = s.row_off[m + 1] - s.row_off[m];
+  const int64_t left = n - (int64_t)chunk * s.B;
+  const int valid = (int)(left < 0 ? 0 : (left > s.B ? s.B : left));
+  const int32_t *yv = static_cast<const int32_t *>(s.y);
+  double loss = 0.0, hits = 0.0;
+  for (int b = threadIdx.x; b < valid; b += kBlock) {
+    const int64_t r = (int64_t)m * Bp + b;
+    const int label = yv[grow[r]];
+    float zmax = -INFINITY, zl = 0.f;
+    int arg = 0;
+    float z[MAXC];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+      if (c < C) {
+        z[c] = Z[r * C + c] + s.theta[offb + c];
+        if (z[c] > zmax) { zmax = z[c]; arg = c; }
+        if (c == label) zl = z[c];
+      }
+    float den = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) if (c < C) den += expf(z[c] - zmax);
+    loss += (double)(zmax + logf(den) - zl);
+    hits += arg == label ? 1.0 : 0.0;
+  }
+  red[threadIdx.x][0] = loss; red[threadIdx.x][1] = hits;
+  __syncthreads();
+  for (int o = kBlock / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) { red[threadIdx.x][0] += red[threadIdx.x + o][0]; red[threadIdx.x][1] += red[threadIdx.x + o][1]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { acc[2 * m] += red[0][0]; acc[2 * m + 1] += red[0][1]; }
+}
+
+__global__ void k_eval_means(const DevState s, double *acc) {
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m >= s.M) return;
+  const double n = (double)(s.row_off[m + 1] - s.row_off[m]);
+  acc[2 * m] /= n;
+  acc[2 * m + 1] /= n;
+}
+
+int mlp_eval(Ctx *c, double *out) {
+  MlpPlan &P = *static_cast<MlpPlan *>(c->mlp);
+  DevState s = c->s;
+  s.k = c->k;
+  hipStream_t st = c->stream;
+  if (P.d[P.L] > 32) { set_error("evaluation supports at most 32 classes"); return CADA_EINVAL; }
+  hipError_t e = hipMemsetAsync(c->eval_acc, 0, (size_t)P.M * 2 * sizeof(double), st);
+  if (e != hipSuccess) { set_error("hipMemsetAsync failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
+  const int64_t nmax = P.max_rows_per_worker;
+  const int chunks = (int)((nmax + P.B - 1) / P.B);
+  const unsigned nb = (unsigned)(((int64_t)P.M * P.B + 255) / 256);
+  for (int ch = 0; ch < chunks; ++ch) {
+    hipLaunchKernelGGL(k_eval_idx, dim3(nb), dim3(256), 0, st, s, c->eval_idx, ch);
+    mlp_forward(c, P, s, c->eval_idx);
+    hipLaunchKernelGGL(k_eval_chunk, dim3((unsigned)P.M), dim3(kBlock), 0, st, s, P.ZL, P.grow, P.offb[P.L - 1], P.d[P.L], P.Bp, ch, c->eval_acc);
+  }
+  hipLaunchKernelGGL(k_eval_means, dim3((unsigned)((P.M + 63) / 64)), dim3(64), 0, st, s, c->eval_acc);
+  eval_finish(c, out, 0);
+  e = hipGetLastError();
+  if (e != hipSuccess) { set_error("evaluation launch failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
   return CADA_OK;
 }
 

@@ -390,6 +390,33 @@ def test_lag_sgd_with_c_zero_is_distributed_sgd_and_huge_c_uploads_every_D():
         assert m[k].all() == (k % cfg.D == 0) and m[k].any() == (k % cfg.D == 0)
 
 
+# -------------------------------------------------------------- evaluation
+def test_evaluate_closed_forms_and_direct_sum():
+    """At theta = 0 the logistic objective is ln 2 and the C-class cross-entropy ln C; at a
+    generic point it is the per-sample Python-loop mean, averaged over the workers."""
+    for cfg, want in ((TINY_LOG, math.log(2.0)), (TINY_MLP, math.log(3.0))):
+        prob = generators.make_problem(cfg)
+        o = oracle_for(cfg, prob, theta0=np.zeros(cfg.p))
+        loss, acc = o.evaluate([cfg.N_m] * cfg.M)
+        assert loss == pytest.approx(want, rel=1e-14)
+    cfg = TINY_LOG
+    prob, sched, o = setup(cfg)
+    o.run(sched[:5])
+    loss, acc = o.evaluate([cfg.N_m] * cfg.M)
+    tot = hits = 0.0
+    for m in range(cfg.M):
+        X, y = prob.rows(m, np.arange(cfg.N_m))
+        lm = hm = 0.0
+        for b in range(cfg.N_m):
+            z = sum(float(X[b][j]) * o.theta[j] for j in range(cfg.p))
+            lm += math.log1p(math.exp(-float(y[b]) * z))
+            hm += 1.0 if float(y[b]) * z > 0 else 0.0
+        tot += lm / cfg.N_m + 0.5 * cfg.lam * float(o.theta @ o.theta)
+        hits += hm / cfg.N_m
+    assert loss == pytest.approx(tot / cfg.M, rel=1e-12) and acc == pytest.approx(hits / cfg.M, rel=1e-12)
+    assert acc > 0.5, "five steps of training beat chance on the planted direction"
+
+
 # ------------------------------------------------------------------ replay
 @pytest.mark.parametrize("cfg", [TINY_LOG, TINY_MLP1], ids=lambda c: c.name)
 def test_replay_reproduces_and_overrides(cfg):
