@@ -47,6 +47,7 @@ class CadaConfig:
     seed: int = 0
     data: str = ""                # name of the input recipe in generators.py
     server: int = SERVER_AMSGRAD  # SERVER_*
+    alpha_K0: int = 0             # 0: constant stepsize; else alpha_k = alpha K0/(k+K0) (Theorem 2)
 
     @property
     def p(self) -> int:

@@ -94,6 +94,8 @@ typedef struct cada_config {
   int32_t rule;              /* CADA_RULE_* */
   int32_t gemm_dtype;        /* MLP contractions: CADA_GEMM_* (LOGREG ignores it) */
   int32_t server;            /* CADA_SERVER_* */
+  int64_t alpha_K0;          /* 0: constant stepsize alpha; K0 > 0: alpha_k = alpha K0/(k + K0), the
+                                decaying stepsize 2/(mu (k + K0)) of Theorem 2 with alpha = 2/(mu K0) */
   int64_t trace_steps;       /* steps of per-step trace to keep (0 = none) */
   void *workspace;           /* DEVICE, 256-byte aligned, caller-owned */
   size_t workspace_bytes;

@@ -138,10 +138,11 @@ class CadaOracle:
 
     def __init__(self, *, model: str, layer_dims: Sequence[int], M: int, rule: int, D: int,
                  d_max: int, c: float, alpha: float, beta1: float, beta2: float, eps: float,
-                 lam: float, theta0, rows: Callable, server: int = SERVER_AMSGRAD):
+                 lam: float, theta0, rows: Callable, server: int = SERVER_AMSGRAD, alpha_K0: int = 0):
         assert rule in (RULE_ALWAYS, RULE_CADA1, RULE_CADA2, RULE_LAG)
         assert server in (SERVER_AMSGRAD, SERVER_SGD)
         self.server = server
+        self.alpha_K0 = alpha_K0      # 0: constant stepsize; else alpha_k = alpha K0/(k+K0) (Theorem 2's 2/(mu(k+K0)))
         self.model, self.dims, self.M, self.rule = model, tuple(layer_dims), M, rule
         self.D, self.d_max, self.c = D, d_max, c
         self.alpha, self.beta1, self.beta2, self.eps, self.lam = alpha, beta1, beta2, eps, lam
@@ -225,8 +226,9 @@ class CadaOracle:
         """Equations (CADA-1)-(CADA-3) with the aggregate ``nabla``; records
         |theta^{k+1}-theta^k|^2 for the rules' right-hand side and advances k."""
         self.nabla = np.asarray(nabla, dtype=np.float64)
+        alpha = self.alpha if self.alpha_K0 <= 0 else self.alpha * self.alpha_K0 / (self.k + self.alpha_K0)
         if self.server == SERVER_SGD:
-            theta_new = self.theta - self.alpha * self.nabla
+            theta_new = self.theta - alpha * self.nabla
             dtheta = theta_new - self.theta
             self.ring[self.k % self.d_max] = dtheta @ dtheta
             self.theta = theta_new
@@ -235,7 +237,7 @@ class CadaOracle:
         self.h = self.beta1 * self.h + (1.0 - self.beta1) * self.nabla
         self.v = self.beta2 * self.vhat + (1.0 - self.beta2) * self.nabla * self.nabla
         self.vhat = np.maximum(self.v, self.vhat)
-        theta_new = self.theta - self.alpha * self.h / np.sqrt(self.eps + self.vhat)
+        theta_new = self.theta - alpha * self.h / np.sqrt(self.eps + self.vhat)
         dtheta = theta_new - self.theta
         self.ring[self.k % self.d_max] = dtheta @ dtheta
         self.theta = theta_new

@@ -10,6 +10,6 @@ def oracle_for(cfg, problem, **override) -> CadaOracle:
     kw = dict(model=cfg.model, layer_dims=cfg.layer_dims, M=cfg.M, rule=cfg.rule, D=cfg.D,
               d_max=cfg.d_max, c=cfg.c, alpha=cfg.alpha, beta1=cfg.beta1, beta2=cfg.beta2,
               eps=cfg.eps, lam=cfg.lam, theta0=problem.theta0, rows=problem.rows,
-              server=getattr(cfg, "server", 0))
+              server=getattr(cfg, "server", 0), alpha_K0=getattr(cfg, "alpha_K0", 0))
     kw.update(override)
     return CadaOracle(**kw)

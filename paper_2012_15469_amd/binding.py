@@ -33,7 +33,7 @@ class cada_config(C.Structure):
                 ("n_samples", C.POINTER(C.c_int64)), ("X", C.c_void_p), ("y", C.c_void_p),
                 ("alpha", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
                 ("lambda_l2", C.c_double), ("c", C.c_double), ("d_max", C.c_int32), ("D", C.c_int32),
-                ("rule", C.c_int32), ("gemm_dtype", C.c_int32), ("server", C.c_int32), ("trace_steps", C.c_int64),
+                ("rule", C.c_int32), ("gemm_dtype", C.c_int32), ("server", C.c_int32), ("alpha_K0", C.c_int64), ("trace_steps", C.c_int64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
@@ -168,7 +168,7 @@ class Cada:
                  X: torch.Tensor, y: torch.Tensor, theta0: torch.Tensor, rule: int, D: int, d_max: int,
                  c: float, alpha: float, beta1: float, beta2: float, eps: float, lam: float = 0.0,
                  gemm_dtype: str = "fp32", trace_steps: int = 0, stream: Optional[torch.cuda.Stream] = None,
-                 server: int = 0):
+                 server: int = 0, alpha_K0: int = 0):
         assert X.is_cuda and y.is_cuda and theta0.is_cuda
         assert X.dtype == torch.float32 and X.is_contiguous() and theta0.dtype == torch.float32
         assert y.dtype == (torch.float32 if model == "logreg" else torch.int32) and y.is_contiguous()
@@ -188,6 +188,7 @@ class Cada:
         cfg.d_max, cfg.D, cfg.rule = d_max, D, rule
         cfg.gemm_dtype = GEMM_BF16 if gemm_dtype == "bf16" else GEMM_FP32
         cfg.server = server
+        cfg.alpha_K0 = alpha_K0
         cfg.trace_steps = trace_steps
         cfg.stream = self.stream.cuda_stream
         nbytes = cada_workspace_bytes(cfg)
@@ -204,7 +205,7 @@ class Cada:
         args = dict(model=cfg.model, layer_dims=cfg.layer_dims, M=cfg.M, B=cfg.B, n_samples=[cfg.N_m] * cfg.M,
                     X=X, y=y, theta0=theta0, rule=cfg.rule, D=cfg.D, d_max=cfg.d_max, c=cfg.c, alpha=cfg.alpha,
                     beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, lam=cfg.lam, gemm_dtype=cfg.gemm_dtype,
-                    server=getattr(cfg, "server", 0))
+                    server=getattr(cfg, "server", 0), alpha_K0=getattr(cfg, "alpha_K0", 0))
         args.update(kw)
         return cls(**args)
 

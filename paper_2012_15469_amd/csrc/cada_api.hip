@@ -70,6 +70,7 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   if (!(cfg->c >= 0.0)) { set_error("c must be >= 0"); return false; }
   if (!(cfg->beta1 >= 0.0 && cfg->beta1 < 1.0 && cfg->beta2 >= 0.0 && cfg->beta2 < 1.0)) { set_error("beta1, beta2 must be in [0, 1)"); return false; }
   if (!(cfg->eps >= 0.0)) { set_error("eps must be >= 0"); return false; }
+  if (cfg->alpha_K0 < 0) { set_error("alpha_K0 must be >= 0"); return false; }
   if (cfg->rule < CADA_RULE_ALWAYS || cfg->rule > CADA_RULE_LAG) { set_error("rule must be one of CADA_RULE_* (got %d)", cfg->rule); return false; }
   if (cfg->server != CADA_SERVER_AMSGRAD && cfg->server != CADA_SERVER_SGD) { set_error("server must be one of CADA_SERVER_* (got %d)", cfg->server); return false; }
   if (cfg->model != CADA_MODEL_LOGREG && cfg->model != CADA_MODEL_MLP) { set_error("unknown model %d", cfg->model); return false; }
@@ -258,6 +259,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   s.M = cfg->M; s.B = cfg->B; s.d_max = cfg->d_max; s.D = cfg->D; s.R = cfg->D + 1; s.rule = cfg->rule; s.server_sgd = cfg->server == CADA_SERVER_SGD;
   s.n_lhs_part = g.n_lhs_part; s.n_ring_part = g.n_ring_part;
   s.p = cfg->p; s.k = 0;
+  s.alpha0 = cfg->alpha; s.alpha_K0 = cfg->alpha_K0;
   s.alpha = (float)cfg->alpha; s.beta1 = (float)cfg->beta1; s.beta2 = (float)cfg->beta2;
   s.omb1 = (float)(1.0 - cfg->beta1); s.omb2 = (float)(1.0 - cfg->beta2);
   s.eps = (float)cfg->eps; s.lam = (float)cfg->lambda_l2; s.c = cfg->c;

@@ -51,6 +51,8 @@ struct DevState {
   int64_t k;                // iteration of the launch this copy is passed to
   float alpha, beta1, beta2, omb1, omb2, eps, lam;   // omb = 1 - beta, rounded once from double
   double c;
+  double alpha0;            // stepsize constant; alpha above is the stepsize of iteration k
+  int64_t alpha_K0;         // 0: constant; else alpha_k = alpha0 K0 / (k + K0)
 };
 
 // Reference point of worker m at iteration k (Algorithm 1: theta-tilde for CADA1,
@@ -65,6 +67,11 @@ __device__ __forceinline__ RefPtr theta_ref(const DevState &s, int m, int64_t k)
   int64_t slot = j % s.R;
   if (slot < 0) slot += s.R;
   return RefPtr{s.hist + slot * s.p, s.hist_lo + slot * s.p};
+}
+
+// Stepsize of iteration k (constant, or the decaying 2/(mu(k+K0)) of Theorem 2).
+__host__ __device__ __forceinline__ float stepsize(const DevState &s, int64_t k) {
+  return s.alpha_K0 <= 0 ? (float)s.alpha0 : (float)(s.alpha0 * (double)s.alpha_K0 / (double)(k + s.alpha_K0));
 }
 
 __device__ __forceinline__ float wave_sum(float x) {

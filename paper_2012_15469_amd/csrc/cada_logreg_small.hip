@@ -187,6 +187,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallArgs a) {
     // ------------------------------------------------------------ phase B
     if (m == 0 && tid == 0 && k > 0) s.ring[(k - 1) % s.d_max] = bcast[0];   // nobody reads this slot before the next barrier
     float sqs = 0.f;
+    const float alpha = stepsize(s, k);
     for (int64_t j = (int64_t)m * kBlock + tid; j < s.p; j += (int64_t)nb * kBlock) {
       float nab = 0.f;
 #pragma unroll 8
@@ -194,12 +195,12 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallArgs a) {
       nab = nab / (float)M;
       float hh = s.h[j], vh = s.vhat[j], vv = vh, stp;
       if (s.server_sgd) {
-        stp = s.alpha * nab;
+        stp = alpha * nab;
       } else {
         hh = fmaf(s.omb1, nab - hh, hh);
         vv = fmaf(s.omb2, nab * nab - vh, vh);
         vh = fmaxf(vv, vh);
-        stp = s.alpha * hh / sqrtf(s.eps + vh);
+        stp = alpha * hh / sqrtf(s.eps + vh);
       }
       // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
       const float t0 = s.theta[j], ms = -stp;

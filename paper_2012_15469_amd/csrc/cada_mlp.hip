@@ -568,7 +568,6 @@ int mlp_lhs_slots(const cada_config *cfg) {
 
 size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows) {
   if (cfg->gemm_dtype != CADA_GEMM_BF16) { set_error("the MLP model computes its contractions in bf16 (gemm_dtype must be CADA_GEMM_BF16)"); return 0; }
-  if (cfg->n_layers < 2) { set_error("the MLP model needs at least 2 layers"); return 0; }
   if (cfg->layer_dims[cfg->n_layers] > 32) { set_error("at most 32 classes"); return 0; }
   MlpPlan P;
   Carve w{nullptr, 0};
@@ -750,7 +749,7 @@ __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
         const float dg = z[c] * (S - dz[c]) / (1.0f + S) * invB;
         const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
         const int64_t o = r * a.ldg + c, ot = (int64_t)c * a.Rp + r;
-        a.Gh[o] = hi; a.Gl[o] = lo; a.dG[o] = bd; a.Gref[o] = br;
+        if (a.Gh) { a.Gh[o] = hi; a.Gl[o] = lo; a.dG[o] = bd; a.Gref[o] = br; }   // (a single-layer network has no layer below to pass them to)
         a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
         sumG[c] += gl;
         sumD[c] += dg;

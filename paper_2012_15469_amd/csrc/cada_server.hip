@@ -214,6 +214,7 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
 int rule_and_server(Ctx *c, const uint8_t *replay) {
   DevState s = c->s;
   s.k = c->k;
+  s.alpha = stepsize(s, s.k);
   if (s.rule == CADA_RULE_LAG || s.rule == CADA_RULE_ALWAYS) {   // (the always-upload rule only records it)
     const int nb = (int)min((int64_t)s.n_lhs_part, (s.p + 4 * kBlock - 1) / (4 * kBlock));
     hipLaunchKernelGGL(k_lag_lhs, dim3((unsigned)max(nb, 1), (unsigned)s.M), dim3(kBlock), 0, c->stream, s);

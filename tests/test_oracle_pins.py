@@ -390,6 +390,30 @@ def test_lag_sgd_with_c_zero_is_distributed_sgd_and_huge_c_uploads_every_D():
         assert m[k].all() == (k % cfg.D == 0) and m[k].any() == (k % cfg.D == 0)
 
 
+def test_decaying_stepsize_is_the_plain_loop():
+    """alpha_k = alpha K0/(k+K0) (Theorem 2's 2/(mu(k+K0))): always-upload + SGD server is
+    distributed SGD with that schedule; with the AMSGrad server the schedule multiplies the
+    same h/sqrt(eps+vhat) direction."""
+    cfg = TINY_LOG.scaled(rule=configs.RULE_ALWAYS, server=configs.SERVER_SGD, alpha=0.2, alpha_K0=7)
+    prob, sched, o = setup(cfg)
+    o.run(sched)
+    th = prob.theta0.astype(np.float64)
+    for k in range(cfg.K):
+        nab = sum(co.logreg_grad(th, *prob.rows(m, sched[k, m]), cfg.lam) for m in range(cfg.M)) / cfg.M
+        th = th - (0.2 * 7.0 / (k + 7.0)) * nab
+    np.testing.assert_allclose(o.theta, th, rtol=1e-12, atol=1e-15)
+    cfg = TINY_LOG.scaled(rule=configs.RULE_ALWAYS, alpha=0.05, alpha_K0=5)
+    prob, sched, o = setup(cfg)
+    o.run(sched)
+    th = prob.theta0.astype(np.float64); h = np.zeros_like(th); vh = np.zeros_like(th)
+    for k in range(cfg.K):
+        nab = sum(co.logreg_grad(th, *prob.rows(m, sched[k, m]), cfg.lam) for m in range(cfg.M)) / cfg.M
+        h = cfg.beta1 * h + (1 - cfg.beta1) * nab
+        vh = np.maximum(cfg.beta2 * vh + (1 - cfg.beta2) * nab ** 2, vh)
+        th = th - (0.05 * 5.0 / (k + 5.0)) * h / np.sqrt(cfg.eps + vh)
+    np.testing.assert_allclose(o.theta, th, rtol=1e-12, atol=1e-15)
+
+
 # -------------------------------------------------------------- evaluation
 def test_evaluate_closed_forms_and_direct_sum():
     """At theta = 0 the logistic objective is ln 2 and the C-class cross-entropy ln C; at a
