@@ -353,6 +353,22 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
   } else if constexpr (EPI == EPI_DA) {
     // ReLU masks of the layer below, hi/lo split of the signal, bias-gradient partial sums
     float *red = reinterpret_cast<float *>(smem_raw);          // [2 (wy)][128 cols][2]
+    // the activations whose sign is the ReLU mask, all loads issued before anything waits for one
+    // (addresses clamped into the matrix so that no load sits under a branch)
+    bf16_t mon[2][2][16], mref[2][2][16];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int colc = min(cbase + j * 32, g.N - 1);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int rowc = min(rbase + i * 32 + 8 * (r >> 2) + (r & 3), g.M - 1);
+          const int64_t om = (rp0 + rowc) * g.ldm + colc;
+          mon[i][j][r] = g.m_on[om];
+          mref[i][j][r] = g.m_onref[om];
+        }
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = cbase + j * 32;
@@ -369,10 +385,9 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
             const int row = row0 + e;
             float gl = 0.f, gref = 0.f;
             if (cok && row < g.M) {
-              const int64_t om = (rp0 + row) * g.ldm + col;
               const float ga = acc1[i][j][4 * q + e], dga = acc2[i][j][4 * q + e];
-              gl = bf2f(g.m_on[om]) > 0.f ? ga : 0.f;
-              gref = bf2f(g.m_onref[om]) > 0.f ? (ga - dga) : 0.f;
+              gl = bf2f(mon[i][j][4 * q + e]) > 0.f ? ga : 0.f;
+              gref = bf2f(mref[i][j][4 * q + e]) > 0.f ? (ga - dga) : 0.f;
             }
             const float dg = gl - gref;
             const bf16_t hi = f2bf(gl);
