@@ -48,8 +48,7 @@ namespace cada {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef uint16_t bf16_t;   // storage type
-struct ic0 { static constexpr int value = 0; };
-struct ic1 { static constexpr int value = 1; };
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes in flight (a native vector: stays in registers)
 
 __device__ __forceinline__ bf16_t f2bf(float f) {
   uint32_t u = __float_as_uint(f);
@@ -61,18 +60,43 @@ __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32
 
 static inline int64_t P8(int64_t x) { return (x + 7) / 8 * 8; }
 
-constexpr int BM = 128, BN = 128, BK = 32, PITCH = BK + 8;
-constexpr int TILE = 128 * PITCH;                 // bf16 elements of one staged tile
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int TILE = 128 * BK;                    // bf16 elements of one chunk (8 KB)
 constexpr int kMaxSlots = 4;
-constexpr int kStages = 2;                        // LDS tile sets: one being multiplied, one being filled
-constexpr size_t mm5_lds_bytes(int n_slots, bool deep) { return (size_t)(deep ? kStages : 1) * n_slots * TILE * sizeof(bf16_t); }   // <= 140 KB for 7 tensors
+
+// Operand layout.  Every bf16 tensor a contraction reads is stored in chunks of 128 rows x 32
+// contraction indices, each chunk 8 KB of consecutive memory, the chunks of a 128-row tile one
+// after the other: element (r, k) of a tensor with kt chunks per row tile lies at
+//     ((r / 128) * kt + k / 32) * 4096 + (r % 128) * 32 + k % 32.
+// A tile step of the contraction then reads whole 128-byte lines only.  With rows stored one
+// after the other a step reads a 64-byte piece of each of 128 rows, and the vector L1, which
+// works line by line, delivers those at half the rate (measured from L2: 27 against 51 B/clk
+// per CU), which made the loads, not the MFMAs, the longest phase of a step.  Rows and indices
+// beyond a tensor's extent, up to whole chunks, exist in memory and stay zero: nothing is
+// clamped or masked on the way in.
+__host__ __device__ __forceinline__ int64_t tm(int64_t r, int64_t k, int64_t kt) {
+  return (((r >> 7) * kt + (k >> 5)) << 12) + ((r & 127) << 5) + (k & 31);
+}
+static inline int tiles128(int64_t x) { return (int)((x + 127) / 128); }
+static inline int chunks32(int64_t x) { return (int)((x + 31) / 32); }
+
+// In LDS a chunk keeps its 8 KB (row r at byte 64 r, no padding); the four 16-byte pieces of a row
+// are stored in the order q ^ ((r >> 1) & 3), so that the 16-byte fragment reads of eight
+// consecutive rows fall into eight different groups of four banks.
+__device__ __forceinline__ int lds_piece(int piece) {   // piece = 4 row + q  ->  position (16-byte units)
+  return piece ^ ((piece >> 3) & 3);
+}
+
+// LDS stages of the deep variant: as many as fit (three for five tensors, two for seven)
+constexpr int mm5_stages(int n_slots) { return n_slots <= 5 ? 3 : 2; }
+constexpr size_t mm5_lds_bytes(int n_slots, bool deep) { return (size_t)(deep ? mm5_stages(n_slots) : 1) * n_slots * TILE * sizeof(bf16_t); }
 
 enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
 
 // Up to four tensors that share the row index of one side of the product.
 struct Side {
   const bf16_t *ptr[kMaxSlots];
-  int64_t ld[kMaxSlots];        // elements between consecutive rows (multiple of 8)
+  int64_t kt[kMaxSlots];        // chunks per 128-row tile
   int64_t bstride[kMaxSlots];   // elements added per worker
   int n;
 };
@@ -80,20 +104,17 @@ struct Side {
 struct Mm5Args {
   DevState s;
   Side A, B;
-  const int64_t *gatherA;       // optional: A row r of worker m is source row gatherA[m*gstride + r]
-  int64_t gstride;
   int a_h, a_l, a_d, a_r;       // role -> slot of A (-1: absent)
   int b_h, b_l, b_x, b_d;       // role -> slot of B
   int M, N, K;                  // extents of the tile index spaces and of the contraction
-  int Bp;                       // padded rows per worker
-  int64_t Rp;                   // M_workers * Bp
+  int Bp;                       // padded rows per worker (multiple of 128)
+  int64_t ktT;                  // chunks per tile of the transposed tensors = M_workers * Bp / 32
   // EPI_FWD_HIDDEN / EPI_DA: bias offset, row-major and transposed outputs
   int64_t offb;
-  bf16_t *o_h, *o_l, *o_d, *o_r;        // row-major [Rp][ldo]
-  bf16_t *t_h, *t_l, *t_d, *t_r;        // transposed [N][Rp]
-  int64_t ldo;
-  const bf16_t *m_on, *m_onref;         // EPI_DA: activations whose sign is the ReLU mask, [Rp][ldm]
-  int64_t ldm;
+  bf16_t *o_h, *o_l, *o_d, *o_r;        // (padded row, column), kto chunks per tile
+  bf16_t *t_h, *t_l, *t_d, *t_r;        // transposed: (column, padded row), ktT chunks per tile
+  int64_t kto;
+  const bf16_t *m_on, *m_onref;         // EPI_DA: activations whose sign is the ReLU mask, laid out like o_h
   float *dbpart, *ddbpart;              // EPI_DA: [M_workers][row tiles][N]
   // EPI_STORE2
   float *c1, *c2;                       // [Rp][N]
@@ -114,25 +135,30 @@ __device__ __forceinline__ uint2 pack4(const bf16_t (&v)[4]) {
   return make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
 }
 
-// NA, NB: tensors on the A and the B side (compile-time, so that every load of the main loop is
-// unconditional: the compiler places a wait for a load from the number of loads it can prove
-// were issued after it, and a load that a branch may skip counts for nothing).  HAS_D: the
-// product Ad Bx^T is present.
+// NA, NB: tensors on the A and the B side (compile-time, so that the loads of a tile step are a
+// fixed number of instructions and the waits can count them).  HAS_D: the product Ad Bx^T is present.
 //
-// Main loop: tile step h is multiplied from LDS stage h%2 while step h+1 moves from registers to
-// the other stage and the loads of step h+3 are issued into the registers that frees: a load has
-// two tile steps (about 2 x 0.6 us) to arrive, and there is one barrier per step.
+// DEEP = true: the workgroup has eight wavefronts in two roles.  Wavefronts 4-7 move chunks from
+// global memory straight into LDS (16-byte LDS-direct loads: no registers, no second pass through
+// the LDS write port), a ring of mm5_stages() stages ahead of wavefronts 0-3, which read
+// fragments and issue MFMAs and, once the movers have left, run the epilogue.  One barrier per
+// tile step: it tells the multipliers that step h has landed and the movers that the stage of
+// step h-1 is free.  (With four wavefronts doing load, LDS write and multiply in turn, the three
+// phases of a step, each near 1000 cycles, ran one after the other.)
 //
 // DEEP = false is the shallow variant for contractions over few tile steps with a heavy epilogue
-// (the weight gradients: K = B rows, then 128 x 128 floats stored per tile): one LDS stage and one
-// register set, so that two workgroups fit a CU and one's epilogue overlaps the other's loop.
+// (the weight gradients: K = B rows, then 128 x 128 floats stored per tile): four wavefronts, one
+// LDS stage and one register set, so that two workgroups fit a CU and one's epilogue overlaps
+// the other's loop.
 template <int EPI, int NA, int NB, bool HAS_D, bool DEEP>
-__global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
+__global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = reinterpret_cast<bf16_t *>(smem_raw);
   constexpr int NS = NA + NB;
+  constexpr int NST = DEEP ? mm5_stages(NS) : 1;
   const DevState &s = g.s;
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const bool mover = DEEP && __builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kBlock;   // uniform per wavefront
+  const int t = threadIdx.x & (kBlock - 1), lane = t & 63, w = t >> 6;
   const int wy = w >> 1, wx = w & 1;
   // Tile of this workgroup.  Workgroups are dealt to the 8 XCDs (each with an L2 of its own) in
   // turn, so consecutive workgroups never share an L2.  With g.by_worker the tiles are renumbered
@@ -147,7 +173,47 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
   }
   const int m0 = by * BM, n0 = bx * BN;
   const int wk = bz;                                 // worker
-  const int64_t *gat = g.gatherA ? g.gatherA + (int64_t)wk * g.gstride : nullptr;
+
+  // first chunk of this tile's rows in every tensor; tile step h reads the chunk 4096 h elements on
+  const bf16_t *basea[NA], *baseb[NB];
+#pragma unroll
+  for (int sl = 0; sl < NA; ++sl) basea[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + (((int64_t)by * g.A.kt[sl]) << 12);
+#pragma unroll
+  for (int sl = 0; sl < NB; ++sl) baseb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl] + (((int64_t)bx * g.B.kt[sl]) << 12);
+  const int nk = (g.K + BK - 1) / BK;
+
+  if constexpr (DEEP) {
+    if (mover) {
+      // Instruction c of wavefront w fills the 64 pieces from position 64 (2 w + c) on of every
+      // tensor's chunk; the lane at position P fetches the piece that the LDS order puts there.
+      const int lw = __builtin_amdgcn_readfirstlane(w);
+      int goff[2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c) goff[c] = lds_piece((2 * lw + c) * 64 + lane) * 8;      // (the order is its own inverse)
+      auto fill = [&](int step, int stage) __attribute__((always_inline)) {
+        const int64_t k = (int64_t)min(step, nk - 1) << 12;         // steps past the end re-read the last chunk into a stage nobody reads
+        bf16_t *dst = lds + ((size_t)stage * NS << 12) + (2 * lw << 9);
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl)
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const bf16_t *src = (sl < NA ? basea[sl < NA ? sl : 0] : baseb[sl < NA ? 0 : sl - NA]) + k + goff[c];
+            __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)(dst + (sl << 12) + (c << 9)), 16, 0, 0);
+          }
+      };
+#pragma unroll
+      for (int h = 0; h < NST - 1; ++h) fill(h, h);
+      for (int h = 0; h < nk; ++h) {
+        // own loads of step h have landed when at most the later steps' (NST - 2 of them) are outstanding
+        if constexpr (NST == 3) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(2 * NS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        const int hn = h + NST - 1;
+        fill(hn, hn % NST);                           // into the stage of step h - 1, which the barrier has freed
+      }
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");     // nothing may land after the epilogue has taken over the LDS
+      return;        // the barriers of the epilogue count the remaining wavefronts only
+    }
+  }
 
   f32x16 acc1[2][2], acc2[2][2];
 #pragma unroll
@@ -157,65 +223,16 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) { acc1[i][j][r] = 0.f; acc2[i][j][r] = 0.f; }
 
-  // this thread's two 16-byte chunks of a 128 x 32 tile: rows (t>>2) and (t>>2)+64, k offset (t&3)*8.
-  // Rows beyond the extent are read from the last valid row and zeroed on the way to LDS.
-  const int crow = t >> 2, ck = (t & 3) * 8;
-  // (all tensors of a side share the leading dimension, so one element offset per chunk serves them)
-  const bf16_t *basea[NA], *baseb[NB];
-#pragma unroll
-  for (int sl = 0; sl < NA; ++sl) basea[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl];
-#pragma unroll
-  for (int sl = 0; sl < NB; ++sl) baseb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl];
-  int64_t offa[2], offb[2];
-  bool oka[2], okb[2];
-#pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    const int ra = m0 + crow + c * 64, rb = n0 + crow + c * 64;
-    oka[c] = ra < g.M; okb[c] = rb < g.N;
-    const int rac = oka[c] ? ra : g.M - 1, rbc = okb[c] ? rb : g.N - 1;
-    const int64_t src = gat ? gat[rac] : (int64_t)rac;
-    offa[c] = src * g.A.ld[0] + ck;
-    offb[c] = (int64_t)rbc * g.B.ld[0] + ck;
-  }
-  uint4 R[DEEP ? 2 : 1][NS][2];   // register sets of tile chunks in flight
-  bool kin[2];                // whether the chunk's k offset lies inside the contraction
-  auto issue = [&](auto BUF, int step) __attribute__((always_inline)) {
-    constexpr int bu = decltype(BUF)::value;
-    const int k = step * BK;
-    kin[bu] = k + ck < g.K;
-    const int koff = kin[bu] ? k : 0;          // always a valid address
-#pragma unroll
-    for (int sl = 0; sl < NA; ++sl)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) R[bu][sl][c] = *reinterpret_cast<const uint4 *>(basea[sl] + offa[c] + koff);
-#pragma unroll
-    for (int sl = 0; sl < NB; ++sl)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) R[bu][NA + sl][c] = *reinterpret_cast<const uint4 *>(baseb[sl] + offb[c] + koff);
-  };
-  auto stash = [&](auto BUF, int stage) __attribute__((always_inline)) {
-    constexpr int bu = decltype(BUF)::value;
-    bf16_t *base = lds + (size_t)stage * NS * TILE + (crow * PITCH + ck);
-#pragma unroll
-    for (int sl = 0; sl < NS; ++sl)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const bool ok = kin[bu] && (sl < NA ? oka[c] : okb[c]);
-        uint4 v = R[bu][sl][c];
-        v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
-        *reinterpret_cast<uint4 *>(base + sl * TILE + c * 64 * PITCH) = v;
-      }
-  };
-
-  const int fro = (lane & 31) * PITCH + (lane >> 5) * 8;   // fragment offset of this lane inside a 32-row band
+  // fragment of this lane inside a 32-row band: row lane % 32, piece lane / 32 (+ 2 in the second half step)
+  const int fro = lds_piece((lane & 31) * 4 + (lane >> 5)) * 8;
   auto multiply = [&](int stage) __attribute__((always_inline)) {
-    const bf16_t *ldsA = lds + (size_t)stage * NS * TILE, *ldsB = ldsA + NA * TILE;
+    const bf16_t *ldsA = lds + ((size_t)stage * NS << 12), *ldsB = ldsA + NA * TILE;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       bf16x8 ah[2], al[2], ad[2], ar[2], bh[2], bl[2], bx[2], bd[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int o = (wy * 64 + i * 32) * PITCH + fro + ks;
+        const int o = (wy * 64 + i * 32) * BK + (fro ^ ks);
         ah[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_h * TILE + o);
         al[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_l * TILE + o);
         if constexpr (HAS_D) ad[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_d * TILE + o);
@@ -225,7 +242,7 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const int o = (wx * 64 + j * 32) * PITCH + fro + ks;
+        const int o = (wx * 64 + j * 32) * BK + (fro ^ ks);
         bh[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_h * TILE + o);
         bl[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_l * TILE + o);
         // with fewer than four B tensors the single-bf16 operand is the hi part itself
@@ -248,38 +265,42 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
     }
   };
 
-  // steps are taken in pairs (the two register sets alternate); an odd count gets one step of
-  // zeros, and the loads issued for steps beyond the end re-read the first step and are dropped
-  const int nk = (g.K + BK - 1) / BK, nk2 = (nk + 1) & ~1;
   if constexpr (DEEP) {
-    issue(ic0{}, 0);
-    issue(ic1{}, 1);
-    stash(ic0{}, 0);
-    issue(ic0{}, 2);
-    __syncthreads();
-    // The instruction scheduler is fenced at the phase boundaries: left alone it sinks the loads to
-    // the end of a step and hoists the zeroing selects of the *next* step's chunks (and with them
-    // the wait for loads issued only one step earlier) into the current step's multiply phase.
-    for (int h = 0; h < nk2; h += 2) {
-      __builtin_amdgcn_sched_barrier(0);
-      stash(ic1{}, 1);  issue(ic1{}, h + 3);
-      __builtin_amdgcn_sched_barrier(0);
-      multiply(0);
-      __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);
-      stash(ic0{}, 0);  issue(ic0{}, h + 4);
-      __builtin_amdgcn_sched_barrier(0);
-      multiply(1);
-      __syncthreads();
+    // the same number of barriers as the movers' loop
+    for (int h = 0; h < nk; ++h) {
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      multiply(h % NST);
     }
-    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   } else {
-    issue(ic0{}, 0);
+    // this thread's two 16-byte pieces of a chunk: t and t + 256, stored at their LDS positions
+    u32x4 R[NS][2];
+    auto issue = [&](int step) __attribute__((always_inline)) {
+      const int64_t k = ((int64_t)min(step, nk - 1) << 12) + t * 8;       // the load past the end re-reads the last chunk and is dropped
+#pragma unroll
+      for (int sl = 0; sl < NA; ++sl)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) R[sl][c] = *reinterpret_cast<const u32x4 *>(basea[sl] + k + c * 2048);
+#pragma unroll
+      for (int sl = 0; sl < NB; ++sl)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) R[NA + sl][c] = *reinterpret_cast<const u32x4 *>(baseb[sl] + k + c * 2048);
+    };
+    const int pos = lds_piece(t) * 8;          // (piece t + 256 lands 2048 elements on: the order only touches the low bits)
+    auto stash = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4 *>(lds + sl * TILE + pos + c * 2048) = R[sl][c];
+    };
+    // The instruction scheduler is fenced at the phase boundaries: left alone it sinks the loads to
+    // the end of a step.
+    issue(0);
     for (int h = 0; h < nk; ++h) {
       __builtin_amdgcn_sched_barrier(0);
-      stash(ic0{}, 0);
+      stash();
       __syncthreads();
-      issue(ic0{}, h + 1);
+      issue(h + 1);
       __builtin_amdgcn_sched_barrier(0);
       multiply(0);
       __syncthreads();
@@ -292,6 +313,13 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
   const int rbase = m0 + wy * 64 + 4 * (lane >> 5);
   const int cbase = n0 + wx * 64 + (lane & 31);
   const int64_t rp0 = (int64_t)wk * g.Bp;            // first padded row of this worker
+  // Places of the accumulator elements in chunked outputs.  The 32 rows of band i lie in one
+  // 128-row tile and in one 32-row chunk, the 32 columns of band j in one chunk and one tile, so
+  // element (i, j, r) is 32 (8 (r>>2) + (r&3)) elements past orow(i, j) in a (row, column) tensor
+  // and 8 (r>>2) + (r&3) elements past ocol(i, j) in a (column, row) tensor: one address per
+  // band pair, the rest are constants of the instruction.
+  auto orow = [&](int i, int j) __attribute__((always_inline)) { return tm(rp0 + rbase + i * 32, cbase + j * 32, g.kto); };
+  auto ocol = [&](int i, int j) __attribute__((always_inline)) { return tm(cbase + j * 32, rp0 + rbase + i * 32, g.ktT); };
 
   if constexpr (EPI == EPI_STORE2) {
 #pragma unroll
@@ -318,6 +346,7 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
       const float db = cok ? delta_theta(s, ref, g.offb + col) : 0.f;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
+        const int64_t o0 = orow(i, j), ot0 = ocol(i, j);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {        // four groups of four consecutive rows
           const int row0 = rbase + i * 32 + 8 * q;
@@ -331,12 +360,12 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
             const bf16_t hi = f2bf(act);
             vh[e] = hi; vl[e] = f2bf(act - bf2f(hi)); vd[e] = f2bf(act - aref);
             if (cok && row < g.M) {
-              const int64_t o = (rp0 + row) * g.ldo + col;
+              const int64_t o = o0 + 32 * (8 * q + e);
               g.o_h[o] = hi; g.o_l[o] = vl[e]; g.o_d[o] = vd[e]; g.o_r[o] = f2bf(aref);
             }
           }
           if (cok) {
-            const int64_t ot = (int64_t)col * g.Rp + rp0 + row0;
+            const int64_t ot = ot0 + 8 * q;
             if (row0 + 3 < g.M) {
               *reinterpret_cast<uint2 *>(g.t_h + ot) = pack4(vh);
               *reinterpret_cast<uint2 *>(g.t_l + ot) = pack4(vl);
@@ -353,29 +382,32 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
   } else if constexpr (EPI == EPI_DA) {
     // ReLU masks of the layer below, hi/lo split of the signal, bias-gradient partial sums
     float *red = reinterpret_cast<float *>(smem_raw);          // [2 (wy)][128 cols][2]
-    // the activations whose sign is the ReLU mask, all loads issued before anything waits for one
-    // (addresses clamped into the matrix so that no load sits under a branch)
-    bf16_t mon[2][2][16], mref[2][2][16];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int colc = min(cbase + j * 32, g.N - 1);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int rowc = min(rbase + i * 32 + 8 * (r >> 2) + (r & 3), g.M - 1);
-          const int64_t om = (rp0 + rowc) * g.ldm + colc;
-          mon[i][j][r] = g.m_on[om];
-          mref[i][j][r] = g.m_onref[om];
-        }
-    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = cbase + j * 32;
       const bool cok = col < g.N;
       float sg = 0.f, sd = 0.f;
+      // the activations whose sign is the ReLU mask: all loads of this half of the columns are
+      // issued before anything waits for one (one half at a time keeps the wavefront within 256
+      // registers)
+      bf16_t mon[2][16], mref[2][16];
+      {
+        // (rows beyond the extent exist in the chunked tensors and hold zeros; whole chunks of columns may not)
+        const int colc = min(col, g.N - 1);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int64_t om = tm(rp0 + rbase + i * 32, colc, g.kto);
+          const bf16_t *pon = g.m_on + om, *pref = g.m_onref + om;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            mon[i][r] = pon[32 * (8 * (r >> 2) + (r & 3))];
+            mref[i][r] = pref[32 * (8 * (r >> 2) + (r & 3))];
+          }
+        }
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
+        const int64_t o0 = orow(i, j), ot0 = ocol(i, j);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int row0 = rbase + i * 32 + 8 * q;
@@ -386,20 +418,20 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
             float gl = 0.f, gref = 0.f;
             if (cok && row < g.M) {
               const float ga = acc1[i][j][4 * q + e], dga = acc2[i][j][4 * q + e];
-              gl = bf2f(mon[i][j][4 * q + e]) > 0.f ? ga : 0.f;
-              gref = bf2f(mref[i][j][4 * q + e]) > 0.f ? (ga - dga) : 0.f;
+              gl = bf2f(mon[i][4 * q + e]) > 0.f ? ga : 0.f;
+              gref = bf2f(mref[i][4 * q + e]) > 0.f ? (ga - dga) : 0.f;
             }
             const float dg = gl - gref;
             const bf16_t hi = f2bf(gl);
             vh[e] = hi; vl[e] = f2bf(gl - bf2f(hi)); vd[e] = f2bf(dg); vr[e] = f2bf(gref);
             sg += gl; sd += dg;
             if (g.o_h && cok && row < g.M) {
-              const int64_t o = (rp0 + row) * g.ldo + col;
+              const int64_t o = o0 + 32 * (8 * q + e);
               g.o_h[o] = hi; g.o_l[o] = vl[e]; g.o_d[o] = vd[e]; g.o_r[o] = vr[e];
             }
           }
           if (cok) {
-            const int64_t ot = (int64_t)col * g.Rp + rp0 + row0;
+            const int64_t ot = ot0 + 8 * q;
             if (row0 + 3 < g.M) {
               *reinterpret_cast<uint2 *>(g.t_h + ot) = pack4(vh);
               *reinterpret_cast<uint2 *>(g.t_l + ot) = pack4(vl);
@@ -479,25 +511,26 @@ __global__ __launch_bounds__(kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
 // ------------------------------------------------------------------------------------------
 struct MlpPlan {
   int L, M, B, Bp, rule, RT;
-  int64_t Rp;                     // M * Bp padded rows per step
+  int64_t Rp;                     // M * Bp padded rows per step (Bp a multiple of 128: a worker's rows start a tile)
+  int64_t ktT;                    // Rp / 32: chunks per tile of the transposed tensors
   int64_t total_rows;             // rows of X
   int64_t max_rows_per_worker;
   int d[CADA_MAX_LAYERS + 1];
   int64_t offW[CADA_MAX_LAYERS], offb[CADA_MAX_LAYERS];   // offsets into theta, index l-1
-  int64_t lda[CADA_MAX_LAYERS + 1];                       // P8(d_l)
-  int64_t wt_off[CADA_MAX_LAYERS], wt_total;              // W_l^T [d_l][P8(d_{l-1})], index l-1
-  int64_t wn_off[CADA_MAX_LAYERS], wn_total;              // W_l   [d_{l-1}][P8(d_l)], l >= 2
+  int64_t kta[CADA_MAX_LAYERS + 1];                       // chunks32(d_l): chunks per tile of (row, d_l) tensors
+  int64_t wt_off[CADA_MAX_LAYERS], wt_total;              // W_l^T (d_l, d_{l-1}), index l-1
+  int64_t wn_off[CADA_MAX_LAYERS], wn_total;              // W_l   (d_{l-1}, d_l), l >= 2
   int lhs_w_slot[CADA_MAX_LAYERS], lhs_b_slot[CADA_MAX_LAYERS];
   int nW;                                                 // delta-weight copies: 1 (CADA1) or M (CADA2)
-  bf16_t *Xh, *Xl; int64_t ldx;
-  bf16_t *XTh, *XTl;                                      // gathered minibatch, transposed [d0][Rp]
-  bf16_t *XGh, *XGl;                                      // gathered minibatch, row-major [Rp][ldx]
+  bf16_t *Xh, *Xl; int64_t ldx;                           // all features, rows one after the other [total_rows][ldx]
+  bf16_t *XTh, *XTl;                                      // gathered minibatch, (feature, padded row)
+  bf16_t *XGh, *XGl;                                      // gathered minibatch, (padded row, feature)
   int64_t *grow;
   bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;
-  bf16_t *Ah[CADA_MAX_LAYERS], *Al[CADA_MAX_LAYERS], *dA[CADA_MAX_LAYERS], *Aref[CADA_MAX_LAYERS];   // hidden l, row-major
-  bf16_t *AhT[CADA_MAX_LAYERS], *AlT[CADA_MAX_LAYERS], *dAT[CADA_MAX_LAYERS];                        // hidden l, transposed
-  bf16_t *Gh[CADA_MAX_LAYERS + 1], *Gl[CADA_MAX_LAYERS + 1], *dG[CADA_MAX_LAYERS + 1], *Gref[CADA_MAX_LAYERS + 1];       // layer l >= 2, row-major
-  bf16_t *GhT[CADA_MAX_LAYERS + 1], *GlT[CADA_MAX_LAYERS + 1], *dGT[CADA_MAX_LAYERS + 1], *GrefT[CADA_MAX_LAYERS + 1];   // layer l, transposed
+  bf16_t *Ah[CADA_MAX_LAYERS], *Al[CADA_MAX_LAYERS], *dA[CADA_MAX_LAYERS], *Aref[CADA_MAX_LAYERS];   // hidden l, (row, unit)
+  bf16_t *AhT[CADA_MAX_LAYERS], *AlT[CADA_MAX_LAYERS], *dAT[CADA_MAX_LAYERS];                        // hidden l, (unit, row)
+  bf16_t *Gh[CADA_MAX_LAYERS + 1], *Gl[CADA_MAX_LAYERS + 1], *dG[CADA_MAX_LAYERS + 1], *Gref[CADA_MAX_LAYERS + 1];       // layer l >= 2, (row, unit)
+  bf16_t *GhT[CADA_MAX_LAYERS + 1], *GlT[CADA_MAX_LAYERS + 1], *dGT[CADA_MAX_LAYERS + 1], *GrefT[CADA_MAX_LAYERS + 1];   // layer l, (unit, row)
   float *ZL, *dZL;                                        // logits [Rp][C]
   float *dbpart, *ddbpart;                                // [M][RT][max hidden width]
 };
@@ -513,25 +546,27 @@ struct Carve {
   }
 };
 
-int tiles128(int x) { return (x + 127) / 128; }
+// elements of a chunked tensor of r rows and k contraction indices (whole chunks)
+size_t tm_elems(int64_t r, int64_t k) { return (size_t)tiles128(r) * chunks32(k) * TILE; }
 
 void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.L = cfg->n_layers; P.M = cfg->M; P.B = cfg->B; P.rule = cfg->rule;
-  P.Bp = (int)P8(cfg->B);
   P.RT = tiles128(cfg->B);
+  P.Bp = P.RT * 128;
   P.Rp = (int64_t)cfg->M * P.Bp;
+  P.ktT = P.Rp / 32;
   P.total_rows = total_rows;
   P.max_rows_per_worker = 0;
   for (int m = 0; m < cfg->M; ++m)
     if (cfg->n_samples[m] > P.max_rows_per_worker) P.max_rows_per_worker = cfg->n_samples[m];
-  for (int l = 0; l <= P.L; ++l) { P.d[l] = cfg->layer_dims[l]; P.lda[l] = P8(P.d[l]); }
+  for (int l = 0; l <= P.L; ++l) { P.d[l] = cfg->layer_dims[l]; P.kta[l] = chunks32(P.d[l]); }
   int64_t o = 0, wt = 0, wn = 0;
   int slot = 0, maxh = 1;
   for (int l = 1; l <= P.L; ++l) {
     P.offW[l - 1] = o; o += (int64_t)P.d[l - 1] * P.d[l];
     P.offb[l - 1] = o; o += P.d[l];
-    P.wt_off[l - 1] = wt; wt += (int64_t)P.d[l] * P8(P.d[l - 1]);
-    P.wn_off[l - 1] = wn; if (l >= 2) wn += (int64_t)P.d[l - 1] * P8(P.d[l]);
+    P.wt_off[l - 1] = wt; wt += (int64_t)tm_elems(P.d[l], P.d[l - 1]);
+    P.wn_off[l - 1] = wn; if (l >= 2) wn += (int64_t)tm_elems(P.d[l - 1], P.d[l]);
     P.lhs_w_slot[l - 1] = slot; slot += tiles128(P.d[l - 1]) * tiles128(P.d[l]);
     P.lhs_b_slot[l - 1] = slot; slot += (P.d[l] + 255) / 256;
     if (l < P.L && P.d[l] > maxh) maxh = P.d[l];
@@ -542,25 +577,23 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   const size_t Rp = (size_t)P.Rp;
   P.Xh = w.take<bf16_t>((size_t)total_rows * P.ldx);
   P.Xl = w.take<bf16_t>((size_t)total_rows * P.ldx);
-  P.XTh = w.take<bf16_t>((size_t)P.d[0] * Rp);
-  P.XTl = w.take<bf16_t>((size_t)P.d[0] * Rp);
-  P.XGh = w.take<bf16_t>(Rp * P.ldx);
-  P.XGl = w.take<bf16_t>(Rp * P.ldx);
+  P.XTh = w.take<bf16_t>(tm_elems(P.d[0], Rp));
+  P.XTl = w.take<bf16_t>(tm_elems(P.d[0], Rp));
+  P.XGh = w.take<bf16_t>(tm_elems(Rp, P.d[0]));
+  P.XGl = w.take<bf16_t>(tm_elems(Rp, P.d[0]));
   P.grow = w.take<int64_t>(Rp);
   P.WTh = w.take<bf16_t>((size_t)wt); P.WTl = w.take<bf16_t>((size_t)wt); P.dWT = w.take<bf16_t>((size_t)wt * P.nW);
   P.WNh = w.take<bf16_t>((size_t)wn + 8); P.WNl = w.take<bf16_t>((size_t)wn + 8); P.dWN = w.take<bf16_t>((size_t)wn * P.nW + 8);
   for (int l = 1; l < P.L; ++l) {
-    P.Ah[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Al[l] = w.take<bf16_t>(Rp * P.lda[l]);
-    P.dA[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Aref[l] = w.take<bf16_t>(Rp * P.lda[l]);
-    P.AhT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp); P.AlT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
-    P.dAT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
+    const size_t n = tm_elems(Rp, P.d[l]), nt = tm_elems(P.d[l], Rp);
+    P.Ah[l] = w.take<bf16_t>(n); P.Al[l] = w.take<bf16_t>(n); P.dA[l] = w.take<bf16_t>(n); P.Aref[l] = w.take<bf16_t>(n);
+    P.AhT[l] = w.take<bf16_t>(nt); P.AlT[l] = w.take<bf16_t>(nt); P.dAT[l] = w.take<bf16_t>(nt);
   }
   for (int l = 1; l <= P.L; ++l) {
-    P.GhT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp); P.GlT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
-    P.dGT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp); P.GrefT[l] = w.take<bf16_t>((size_t)P.d[l] * Rp);
+    const size_t n = tm_elems(Rp, P.d[l]), nt = tm_elems(P.d[l], Rp);
+    P.GhT[l] = w.take<bf16_t>(nt); P.GlT[l] = w.take<bf16_t>(nt); P.dGT[l] = w.take<bf16_t>(nt); P.GrefT[l] = w.take<bf16_t>(nt);
     if (l >= 2) {
-      P.Gh[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Gl[l] = w.take<bf16_t>(Rp * P.lda[l]);
-      P.dG[l] = w.take<bf16_t>(Rp * P.lda[l]); P.Gref[l] = w.take<bf16_t>(Rp * P.lda[l]);
+      P.Gh[l] = w.take<bf16_t>(n); P.Gl[l] = w.take<bf16_t>(n); P.dG[l] = w.take<bf16_t>(n); P.Gref[l] = w.take<bf16_t>(n);
     } else {
       P.Gh[l] = P.Gl[l] = P.dG[l] = P.Gref[l] = nullptr;
     }
@@ -584,6 +617,8 @@ int mlp_lhs_slots(const cada_config *cfg) {
 size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows) {
   if (cfg->gemm_dtype != CADA_GEMM_BF16) { set_error("the MLP model computes its contractions in bf16 (gemm_dtype must be CADA_GEMM_BF16)"); return 0; }
   if (cfg->layer_dims[cfg->n_layers] > 32) { set_error("at most 32 classes"); return 0; }
+  for (int l = 0; l <= cfg->n_layers; ++l)    // the kernels index one worker's activations with 32 bits
+    if (((int64_t)cfg->B + 128) * (cfg->layer_dims[l] + 32) >= (1ll << 31)) { set_error("B x layer width must stay below 2^31"); return 0; }
   MlpPlan P;
   Carve w{nullptr, 0};
   layout(P, cfg, total_rows, w);
@@ -633,13 +668,12 @@ __global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow, int 
   grow[(int64_t)m * Bp + b] = s.row_off[m] + r;
 }
 
-// Compact copies of the gathered minibatch, so that the contractions read dense matrices
-// instead of 64-byte pieces of scattered rows: XG[m*Bp + b][c] = X[grow[m*Bp + b]][c] and
-// XT[c][m*Bp + b] = the same, transposed.  grid (ceil(d0/64), ceil(B/64), M), block 256;
+// Chunked copies of the gathered minibatch in both orientations:
+// XG(m*Bp + b, c) = X[grow[m*Bp + b]][c] and XT(c, m*Bp + b) = the same.  grid (ceil(d0/64), ceil(B/64), M), block 256;
 // 64 x 64 tile through LDS.
 __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, const bf16_t *Xl, int64_t ldx, const int64_t *grow,
                                                              bf16_t *XTh, bf16_t *XTl, bf16_t *XGh, bf16_t *XGl, int d0, int B, int Bp,
-                                                             int64_t Rp) {
+                                                             int64_t ktx, int64_t ktT) {
   __shared__ bf16_t th[64][66], tl[64][66];
   const int m = blockIdx.z, c0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -649,7 +683,7 @@ __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, c
     if (b < B && c < d0) {
       const int64_t src = grow[(int64_t)m * Bp + b] * ldx + c;
       vh = Xh[src]; vl = Xl[src];
-      const int64_t dst = ((int64_t)m * Bp + b) * ldx + c;
+      const int64_t dst = tm((int64_t)m * Bp + b, c, ktx);
       XGh[dst] = vh; XGl[dst] = vl;
     }
     th[r][tx] = vh; tl[r][tx] = vl;
@@ -658,7 +692,7 @@ __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, c
   for (int r = ty; r < 64; r += 4) {
     const int c = c0 + r, b = b0 + tx;
     if (c < d0 && b < B) {
-      const int64_t o = (int64_t)c * Rp + (int64_t)m * Bp + b;
+      const int64_t o = tm(c, (int64_t)m * Bp + b, ktT);
       XTh[o] = th[tx][r]; XTl[o] = tl[tx][r];
     }
   }
@@ -669,7 +703,7 @@ struct PrepArgs {
   bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;   // already offset to this layer
   int64_t offW, wt_total, wn_total;
   int din, dout;
-  int64_t ldt, ldn;      // P8(din), P8(dout)
+  int64_t ktt, ktn;      // chunks32(din), chunks32(dout)
   int want_n;            // also write the [in][out] orientation (layers >= 2)
 };
 
@@ -691,7 +725,7 @@ __global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
       const int64_t src = a.offW + (int64_t)i * a.dout + o;
       v = is_w ? s.theta[src] : delta_theta(s, ref, src);
       if (a.want_n) {
-        const int64_t dn = (int64_t)i * a.ldn + o;
+        const int64_t dn = tm(i, o, a.ktn);
         if (is_w) { const bf16_t hi = f2bf(v); a.WNh[dn] = hi; a.WNl[dn] = f2bf(v - bf2f(hi)); }
         else a.dWN[(int64_t)m * a.wn_total + dn] = f2bf(v);
       }
@@ -703,7 +737,7 @@ __global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
     const int o = o0 + r, i = i0 + tx;
     if (o < a.dout && i < a.din) {
       const float v = tile[tx][r];
-      const int64_t dt = (int64_t)o * a.ldt + i;
+      const int64_t dt = tm(o, i, a.ktt);
       if (is_w) { const bf16_t hi = f2bf(v); a.WTh[dt] = hi; a.WTl[dt] = f2bf(v - bf2f(hi)); }
       else a.dWT[(int64_t)m * a.wt_total + dt] = f2bf(v);
     }
@@ -713,11 +747,11 @@ __global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
 struct LossArgs {
   DevState s;
   const float *Z, *dZ;            // logits without bias [Rp][C]
-  bf16_t *Gh, *Gl, *dG, *Gref;    // row-major [Rp][ldg]
-  bf16_t *GhT, *GlT, *dGT, *GrefT;   // transposed [C][Rp]
+  bf16_t *Gh, *Gl, *dG, *Gref;    // (padded row, class), ktg chunks per tile
+  bf16_t *GhT, *GlT, *dGT, *GrefT;   // (class, padded row), ktT chunks per tile
   const int64_t *grow;
-  int64_t offb, Rp;
-  int C, Bp; int64_t ldg;
+  int64_t offb, ktT;
+  int C, Bp; int64_t ktg;
   int lhs_slot;
 };
 
@@ -763,7 +797,7 @@ __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
         const float gl = (z[c] - (c == label ? 1.f : 0.f)) * invB;
         const float dg = z[c] * (S - dz[c]) / (1.0f + S) * invB;
         const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
-        const int64_t o = r * a.ldg + c, ot = (int64_t)c * a.Rp + r;
+        const int64_t o = tm(r, c, a.ktg), ot = tm(c, r, a.ktT);
         if (a.Gh) { a.Gh[o] = hi; a.Gl[o] = lo; a.dG[o] = bd; a.Gref[o] = br; }   // (a single-layer network has no layer below to pass them to)
         a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
         sumG[c] += gl;
@@ -831,8 +865,8 @@ __global__ __launch_bounds__(kBlock) void k_bias_finish(const DevState s, const 
 // ------------------------------------------------------------------------------------------
 namespace {
 
-void side_add(Side &sd, const bf16_t *p, int64_t ld, int64_t bstride) {
-  sd.ptr[sd.n] = p; sd.ld[sd.n] = ld; sd.bstride[sd.n] = bstride; sd.n += 1;
+void side_add(Side &sd, const bf16_t *p, int64_t kt, int64_t bstride) {
+  sd.ptr[sd.n] = p; sd.kt[sd.n] = kt; sd.bstride[sd.n] = bstride; sd.n += 1;
 }
 
 // The (tensor count, product set) combinations the layers use.
@@ -844,16 +878,17 @@ template <int EPI, int NA, int NB, bool HAS_D> hipError_t mm5_allow_lds() {
 template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const Mm5Args &g, int workers) {
   const unsigned gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
   const dim3 grid = g.by_worker ? dim3(gx * gy * workers) : dim3(gx, gy, workers);
-  hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D, mm5_deep<EPI>()>), grid, dim3(kBlock), mm5_lds_bytes(NA + NB, mm5_deep<EPI>()),
-                     c->stream, g);
+  hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D, mm5_deep<EPI>()>), grid, dim3(mm5_deep<EPI>() ? 2 * kBlock : kBlock),
+                     mm5_lds_bytes(NA + NB, mm5_deep<EPI>()), c->stream, g);
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
 template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
   const bool has_d = g.a_d >= 0;
-  for (int i = 1; i < g.A.n; ++i)
-    if (g.A.ld[i] != g.A.ld[0]) { set_error("internal: A tensors with different leading dimensions"); return; }
-  for (int i = 1; i < g.B.n; ++i)
-    if (g.B.ld[i] != g.B.ld[0]) { set_error("internal: B tensors with different leading dimensions"); return; }
+  // every tensor must hold the chunks the tile steps walk through
+  for (int i = 0; i < g.A.n; ++i)
+    if (g.A.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: A tensor with fewer chunks than tile steps"); return; }
+  for (int i = 0; i < g.B.n; ++i)
+    if (g.B.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: B tensor with fewer chunks than tile steps"); return; }
   if constexpr (EPI == EPI_DW) {
     if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g, workers);
     if (has_d && g.A.n == 3 && g.B.n == 4) return launch_mm5_as<EPI, 3, 4, true>(c, g, workers);
@@ -868,7 +903,7 @@ template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
 
 Mm5Args blank(const DevState &s, const MlpPlan &P) {
   Mm5Args g{};
-  g.s = s; g.Bp = P.Bp; g.Rp = P.Rp;
+  g.s = s; g.Bp = P.Bp; g.ktT = P.ktT;
   g.a_h = g.a_l = g.a_d = g.a_r = -1;
   g.b_h = g.b_l = g.b_x = g.b_d = -1;
   return g;
@@ -900,19 +935,18 @@ int mlp_init_state(Ctx *c, const float *) {
 static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx) {
   hipStream_t st = c->stream;
   const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
-  const int64_t Rp = P.Rp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
   const int64_t dwt_stride = per_worker ? P.wt_total : 0;
   hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp);
   hipLaunchKernelGGL(k_gather_transpose, dim3((P.d[0] + 63) / 64, (B + 63) / 64, M), dim3(kBlock), 0, st,
-                     P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, Rp);
+                     P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, P.kta[0], P.ktT);
   for (int l = 1; l <= L; ++l) {
     PrepArgs pa;
     pa.s = s;
     pa.WTh = P.WTh + P.wt_off[l - 1]; pa.WTl = P.WTl + P.wt_off[l - 1]; pa.dWT = P.dWT + P.wt_off[l - 1];
     pa.WNh = P.WNh + P.wn_off[l - 1]; pa.WNl = P.WNl + P.wn_off[l - 1]; pa.dWN = P.dWN + P.wn_off[l - 1];
     pa.offW = P.offW[l - 1]; pa.wt_total = P.wt_total; pa.wn_total = P.wn_total;
-    pa.din = P.d[l - 1]; pa.dout = P.d[l]; pa.ldt = P8(P.d[l - 1]); pa.ldn = P8(P.d[l]); pa.want_n = l >= 2;
+    pa.din = P.d[l - 1]; pa.dout = P.d[l]; pa.ktt = P.kta[l - 1]; pa.ktn = P.kta[l]; pa.want_n = l >= 2;
     hipLaunchKernelGGL(k_prep_weights, dim3((pa.dout + 63) / 64, (pa.din + 63) / 64, P.nW + 1), dim3(kBlock), 0, st, pa);
   }
 
@@ -922,21 +956,21 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
     Mm5Args g = blank(s, P);
     g.M = B; g.N = dout; g.K = din;
     if (l == 1) {
-      const int64_t bs0 = (int64_t)Bp * P.ldx;
-      side_add(g.A, P.XGh, P.ldx, bs0); side_add(g.A, P.XGl, P.ldx, bs0);
+      const int64_t bs0 = (int64_t)Bp * P.kta[0] * 32;     // a worker's Bp / 128 row tiles
+      side_add(g.A, P.XGh, P.kta[0], bs0); side_add(g.A, P.XGl, P.kta[0], bs0);
       g.a_h = 0; g.a_l = 1; g.a_r = 0;                    // dZ_1 = A_0 dW_1
     } else {
-      const int64_t bs = (int64_t)Bp * P.lda[l - 1];
-      side_add(g.A, P.Ah[l - 1], P.lda[l - 1], bs); side_add(g.A, P.Al[l - 1], P.lda[l - 1], bs);
-      side_add(g.A, P.dA[l - 1], P.lda[l - 1], bs); side_add(g.A, P.Aref[l - 1], P.lda[l - 1], bs);
+      const int64_t bs = (int64_t)Bp * P.kta[l - 1] * 32;
+      side_add(g.A, P.Ah[l - 1], P.kta[l - 1], bs); side_add(g.A, P.Al[l - 1], P.kta[l - 1], bs);
+      side_add(g.A, P.dA[l - 1], P.kta[l - 1], bs); side_add(g.A, P.Aref[l - 1], P.kta[l - 1], bs);
       g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 3;         // dZ_l = dA W + Aref dW
     }
-    const int64_t ldt = P8(din);
-    side_add(g.B, P.WTh + P.wt_off[l - 1], ldt, 0); side_add(g.B, P.WTl + P.wt_off[l - 1], ldt, 0);
-    side_add(g.B, P.dWT + P.wt_off[l - 1], ldt, dwt_stride);
+    const int64_t ktt = P.kta[l - 1];
+    side_add(g.B, P.WTh + P.wt_off[l - 1], ktt, 0); side_add(g.B, P.WTl + P.wt_off[l - 1], ktt, 0);
+    side_add(g.B, P.dWT + P.wt_off[l - 1], ktt, dwt_stride);
     g.b_h = 0; g.b_l = 1; g.b_x = 0; g.b_d = 2;
     if (l < L) {
-      g.offb = P.offb[l - 1]; g.ldo = P.lda[l];
+      g.offb = P.offb[l - 1]; g.kto = P.kta[l];
       g.o_h = P.Ah[l]; g.o_l = P.Al[l]; g.o_d = P.dA[l]; g.o_r = P.Aref[l];
       g.t_h = P.AhT[l]; g.t_l = P.AlT[l]; g.t_d = P.dAT[l]; g.t_r = nullptr;
       launch_mm5<EPI_FWD_HIDDEN>(c, g, M);
@@ -953,7 +987,6 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
   s.k = c->k;
   hipStream_t st = c->stream;
   const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
-  const int64_t Rp = P.Rp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
   const int64_t dwn_stride = per_worker ? P.wn_total : 0;
 
@@ -964,7 +997,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
     la.s = s; la.Z = P.ZL; la.dZ = P.dZL;
     la.Gh = P.Gh[L]; la.Gl = P.Gl[L]; la.dG = P.dG[L]; la.Gref = P.Gref[L];
     la.GhT = P.GhT[L]; la.GlT = P.GlT[L]; la.dGT = P.dGT[L]; la.GrefT = P.GrefT[L];
-    la.grow = P.grow; la.offb = P.offb[L - 1]; la.Rp = Rp; la.C = P.d[L]; la.Bp = Bp; la.ldg = P.lda[L];
+    la.grow = P.grow; la.offb = P.offb[L - 1]; la.ktT = P.ktT; la.C = P.d[L]; la.Bp = Bp; la.ktg = P.kta[L];
     la.lhs_slot = P.lhs_b_slot[L - 1];
     hipLaunchKernelGGL(k_loss, dim3(M), dim3(kBlock), 0, st, la);
   }
@@ -975,19 +1008,20 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
     {   // weight gradient and its innovation: contraction over the worker's rows
       Mm5Args g = blank(s, P);
       g.M = din; g.N = dout; g.K = B;
+      const int64_t bsT = (int64_t)Bp * 128;              // a worker's Bp / 32 chunks of every row tile
       if (l == 1) {
-        side_add(g.A, P.XTh, Rp, Bp); side_add(g.A, P.XTl, Rp, Bp);
+        side_add(g.A, P.XTh, P.ktT, bsT); side_add(g.A, P.XTl, P.ktT, bsT);
         g.a_h = 0; g.a_l = 1; g.a_r = 0;
       } else {
-        side_add(g.A, P.AhT[l - 1], Rp, Bp); side_add(g.A, P.AlT[l - 1], Rp, Bp); side_add(g.A, P.dAT[l - 1], Rp, Bp);
+        side_add(g.A, P.AhT[l - 1], P.ktT, bsT); side_add(g.A, P.AlT[l - 1], P.ktT, bsT); side_add(g.A, P.dAT[l - 1], P.ktT, bsT);
         g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 0;       // innov = A^T dG + dA^T Gref
       }
-      side_add(g.B, P.GhT[l], Rp, Bp); side_add(g.B, P.GlT[l], Rp, Bp);
+      side_add(g.B, P.GhT[l], P.ktT, bsT); side_add(g.B, P.GlT[l], P.ktT, bsT);
       if (l == 1) {     // no dA^T Gref term in the first layer
-        side_add(g.B, P.dGT[l], Rp, Bp);
+        side_add(g.B, P.dGT[l], P.ktT, bsT);
         g.b_h = 0; g.b_l = 1; g.b_d = 2;
       } else {
-        side_add(g.B, P.GrefT[l], Rp, Bp); side_add(g.B, P.dGT[l], Rp, Bp);
+        side_add(g.B, P.GrefT[l], P.ktT, bsT); side_add(g.B, P.dGT[l], P.ktT, bsT);
         g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
       }
       g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1]; g.by_worker = 1;
@@ -996,19 +1030,19 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
     if (l >= 2) {   // gradient w.r.t. the activations of layer l-1, masks, bias partials
       Mm5Args g = blank(s, P);
       g.M = B; g.N = din; g.K = dout;
-      const int64_t bs = (int64_t)Bp * P.lda[l];
-      side_add(g.A, P.Gh[l], P.lda[l], bs); side_add(g.A, P.Gl[l], P.lda[l], bs);
-      side_add(g.A, P.dG[l], P.lda[l], bs); side_add(g.A, P.Gref[l], P.lda[l], bs);
+      const int64_t bs = (int64_t)Bp * P.kta[l] * 32;
+      side_add(g.A, P.Gh[l], P.kta[l], bs); side_add(g.A, P.Gl[l], P.kta[l], bs);
+      side_add(g.A, P.dG[l], P.kta[l], bs); side_add(g.A, P.Gref[l], P.kta[l], bs);
       g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 3;         // dGA = dG W^T + Gref dW^T
-      const int64_t ldn = P8(dout);
-      side_add(g.B, P.WNh + P.wn_off[l - 1], ldn, 0); side_add(g.B, P.WNl + P.wn_off[l - 1], ldn, 0);
-      side_add(g.B, P.dWN + P.wn_off[l - 1], ldn, dwn_stride);
+      const int64_t ktn = P.kta[l];
+      side_add(g.B, P.WNh + P.wn_off[l - 1], ktn, 0); side_add(g.B, P.WNl + P.wn_off[l - 1], ktn, 0);
+      side_add(g.B, P.dWN + P.wn_off[l - 1], ktn, dwn_stride);
       g.b_h = 0; g.b_l = 1; g.b_x = 0; g.b_d = 2;
       const int q = l - 1;
-      g.offb = P.offb[q - 1]; g.ldo = P.lda[q];
+      g.offb = P.offb[q - 1]; g.kto = P.kta[q];
       g.o_h = P.Gh[q]; g.o_l = P.Gl[q]; g.o_d = P.dG[q]; g.o_r = P.Gref[q];     // null for q = 1
       g.t_h = P.GhT[q]; g.t_l = P.GlT[q]; g.t_d = P.dGT[q]; g.t_r = P.GrefT[q];
-      g.m_on = P.Ah[q]; g.m_onref = P.Aref[q]; g.ldm = P.lda[q];
+      g.m_on = P.Ah[q]; g.m_onref = P.Aref[q];
       g.dbpart = P.dbpart; g.ddbpart = P.ddbpart;
       launch_mm5<EPI_DA>(c, g, M);
       hipLaunchKernelGGL(k_bias_finish, dim3((din + 255) / 256, M), dim3(kBlock), 0, st, s, P.dbpart, P.ddbpart, P.RT, din,
