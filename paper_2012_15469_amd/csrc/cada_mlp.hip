@@ -48,6 +48,7 @@ namespace cada {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef uint16_t bf16_t;   // storage type
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));   // four floats at any 4-byte aligned address
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes in flight (a native vector: stays in registers)
 
 __device__ __forceinline__ bf16_t f2bf(float f) {
@@ -89,7 +90,12 @@ __device__ __forceinline__ int lds_piece(int piece) {   // piece = 4 row + q  ->
 
 // LDS stages of the deep variant: as many as fit (three for five tensors, two for seven)
 constexpr int mm5_stages(int n_slots) { return n_slots <= 5 ? 3 : 2; }
-constexpr size_t mm5_lds_bytes(int n_slots, bool deep) { return (size_t)(deep ? mm5_stages(n_slots) : 1) * n_slots * TILE * sizeof(bf16_t); }
+// the shallow variant (weight gradients) also stages its 128 x 128 float tile in LDS on the way out; the row pitch of 136
+// floats puts the two half-wavefronts of an accumulator store (rows 4 apart) into different halves of the banks
+constexpr int kDwPitch = 136;
+constexpr size_t mm5_lds_bytes(int n_slots, bool deep) {
+  return deep ? (size_t)mm5_stages(n_slots) * n_slots * TILE * sizeof(bf16_t) : (size_t)BM * kDwPitch * sizeof(float);
+}
 
 enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
 
@@ -121,7 +127,6 @@ struct Mm5Args {
   // EPI_DW
   int64_t offW;
   int lhs_slot0;
-  int by_worker;                        // 1-D grid, tiles renumbered per XCD (see k_mm5)
 };
 
 __device__ __forceinline__ float delta_theta(const DevState &s, const RefPtr &ref, int64_t i) {
@@ -160,17 +165,16 @@ __global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm
   const bool mover = DEEP && __builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kBlock;   // uniform per wavefront
   const int t = threadIdx.x & (kBlock - 1), lane = t & 63, w = t >> 6;
   const int wy = w >> 1, wx = w & 1;
-  // Tile of this workgroup.  Workgroups are dealt to the 8 XCDs (each with an L2 of its own) in
-  // turn, so consecutive workgroups never share an L2.  With g.by_worker the tiles are renumbered
-  // so that an XCD works through whole workers: the operands of a weight-gradient contraction
-  // (a few MB per worker) are then read from HBM once instead of once per XCD.
-  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
-  if (g.by_worker) {
-    const int gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
-    const int lin = blockIdx.x, total = gridDim.x, per = total / 8;
-    const int tix = lin < per * 8 ? (lin % 8) * per + lin / 8 : lin;
-    bx = tix % gx; by = (tix / gx) % gy; bz = tix / (gx * gy);
-  }
+  // Tile of this workgroup (1-D grid).  Workgroups are dealt to the 8 XCDs (each with an L2 of its
+  // own) in turn, so consecutive workgroups never share an L2.  The tiles are renumbered so that an
+  // XCD works through a contiguous run of tiles, columns fastest: whole workers, or a few row
+  // tiles of one worker with all their column tiles.  Its L2 then fetches those rows' operands
+  // once and the other side's once per XCD; dealt in turn, every XCD would stream every worker's
+  // operands (8 x the traffic to HBM, which bounded the first layer's forward contraction).
+  const int gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
+  const int lin = blockIdx.x, per = gridDim.x / 8;
+  const int tix = lin < per * 8 ? (lin % 8) * per + lin / 8 : lin;
+  const int bx = tix % gx, by = (tix / gx) % gy, bz = tix / (gx * gy);
   const int m0 = by * BM, n0 = bx * BN;
   const int wk = bz;                                 // worker
 
@@ -461,47 +465,86 @@ __global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm
       g.ddbpart[o] = red[t * 2 + 1] + red[(128 + t) * 2 + 1];
     }
   } else {   // EPI_DW
-    float *red = reinterpret_cast<float *>(smem_raw);
+    // A lane's accumulators are one column and 16 rows of the tile: stored from there, an
+    // instruction moves 4 bytes per lane, and the 192 such instructions of a wavefront kept the
+    // CU's address unit busy for longer than the contraction took.  The tile goes through LDS
+    // instead and leaves row by row, 16 bytes per lane, 512 bytes per row.
+    constexpr int CP = kDwPitch;
+    float *ct = reinterpret_cast<float *>(smem_raw);           // [128][CP]
     float *gf = fresh_grad(s, wk) + g.offW;
     const bool cada1 = s.rule == CADA_RULE_CADA1;
     const int cur = s.sel[wk];
     float *ivf = cada1 ? s.dtl + ((int64_t)(1 - cur) * s.M + wk) * s.p + g.offW : nullptr;
     const float *ivs = cada1 ? s.dtl + ((int64_t)cur * s.M + wk) * s.p + g.offW : nullptr;
-    // CADA1: the stored innovations of the tile, all loads issued before anything waits for one
-    // (addresses clamped into the matrix so that no load sits under a branch)
-    float old[2][2][16];
-    if (cada1) {
+    // row-wise pass: this thread has columns c4 .. c4+3 of the rows r0 + 8 it, it = 0..15
+    const int c4 = (t & 31) * 4, r0 = t >> 5;
+    const bool wide = n0 + BN <= g.N;       // every column of the tile exists: 16-byte accesses (4-byte aligned)
+    auto put_tile = [&](const f32x16 (&acc)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int col = min(cbase + j * 32, g.N - 1);
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = min(rbase + i * 32 + 8 * (r >> 2) + (r & 3), g.M - 1);
-            old[i][j][r] = ivs[(int64_t)row * g.N + col];
-          }
-        }
+          for (int r = 0; r < 16; ++r)
+            ct[(wy * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * CP + wx * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
+    };
+    // CADA1: the stored innovations of the tile, all loads issued before anything waits for one
+    // (rows clamped into the matrix so that no load sits under a branch)
+    f32x4u old[16];
+    if (cada1 && wide) {
+#pragma unroll
+      for (int it = 0; it < 16; ++it) {
+        const int row = min(m0 + r0 + 8 * it, g.M - 1);
+        old[it] = *reinterpret_cast<const f32x4u *>(ivs + (int64_t)row * g.N + n0 + c4);
+      }
     }
     float sq = 0.f;
+    put_tile(acc1);
+    __syncthreads();
+    if (wide) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int it = 0; it < 16; ++it) {
+        const int rl = r0 + 8 * it;
+        const f32x4u v = *reinterpret_cast<const f32x4u *>(ct + rl * CP + c4);
+        if (m0 + rl < g.M) *reinterpret_cast<f32x4u *>(gf + (int64_t)(m0 + rl) * g.N + n0 + c4) = v;
+      }
+    } else if (n0 + c4 < g.N) {              // a tile that overhangs the matrix: element by element
+      for (int it = 0; it < 16; ++it) {
+        const int rl = r0 + 8 * it;
+        if (m0 + rl >= g.M) break;
+        for (int e = 0; e < 4 && n0 + c4 + e < g.N; ++e) gf[(int64_t)(m0 + rl) * g.N + n0 + c4 + e] = ct[rl * CP + c4 + e];
+      }
+    }
+    __syncthreads();
+    put_tile(acc2);
+    __syncthreads();
+    if (wide) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = cbase + j * 32;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
-          if (row < g.M && col < g.N) {
-            const int64_t o = (int64_t)row * g.N + col;
-            gf[o] = acc1[i][j][r];
-            float iv = acc2[i][j][r];
-            if (cada1) { ivf[o] = iv; iv -= old[i][j][r]; }
-            sq = fmaf(iv, iv, sq);
+      for (int it = 0; it < 16; ++it) {
+        const int rl = r0 + 8 * it;
+        f32x4u v = *reinterpret_cast<const f32x4u *>(ct + rl * CP + c4);
+        if (m0 + rl < g.M) {
+          if (cada1) {
+            *reinterpret_cast<f32x4u *>(ivf + (int64_t)(m0 + rl) * g.N + n0 + c4) = v;
+            v -= old[it];
           }
+          sq = fmaf(v.x, v.x, sq); sq = fmaf(v.y, v.y, sq); sq = fmaf(v.z, v.z, sq); sq = fmaf(v.w, v.w, sq);
         }
       }
-    const float tot = block_sum(sq, red);
+    } else if (n0 + c4 < g.N) {
+      for (int it = 0; it < 16; ++it) {
+        const int rl = r0 + 8 * it;
+        if (m0 + rl >= g.M) break;
+        for (int e = 0; e < 4 && n0 + c4 + e < g.N; ++e) {
+          const int64_t o = (int64_t)(m0 + rl) * g.N + n0 + c4 + e;
+          float iv = ct[rl * CP + c4 + e];
+          if (cada1) { ivf[o] = iv; iv -= ivs[o]; }
+          sq = fmaf(iv, iv, sq);
+        }
+      }
+    }
+    __syncthreads();
+    const float tot = block_sum(sq, ct);
     if (t == 0) s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + by * ((g.N + BN - 1) / BN) + bx] = tot;
   }
 }
@@ -877,7 +920,7 @@ template <int EPI, int NA, int NB, bool HAS_D> hipError_t mm5_allow_lds() {
 }
 template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const Mm5Args &g, int workers) {
   const unsigned gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
-  const dim3 grid = g.by_worker ? dim3(gx * gy * workers) : dim3(gx, gy, workers);
+  const dim3 grid(gx * gy * workers);
   hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D, mm5_deep<EPI>()>), grid, dim3(mm5_deep<EPI>() ? 2 * kBlock : kBlock),
                      mm5_lds_bytes(NA + NB, mm5_deep<EPI>()), c->stream, g);
 }
@@ -1024,7 +1067,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
         side_add(g.B, P.GrefT[l], P.ktT, bsT); side_add(g.B, P.dGT[l], P.ktT, bsT);
         g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
       }
-      g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1]; g.by_worker = 1;
+      g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1];
       launch_mm5<EPI_DW>(c, g, M);
     }
     if (l >= 2) {   // gradient w.r.t. the activations of layer l-1, masks, bias partials
