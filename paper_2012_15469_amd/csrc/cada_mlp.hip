@@ -88,16 +88,17 @@ __device__ __forceinline__ int lds_piece(int piece) {   // piece = 4 row + q  ->
   return piece ^ ((piece >> 3) & 3);
 }
 
-// LDS stages of the deep variant: as many as fit (three for five tensors, two for seven)
-constexpr int mm5_stages(int n_slots) { return n_slots <= 5 ? 3 : 2; }
-// the shallow variant (weight gradients) also stages its 128 x 128 float tile in LDS on the way out; the row pitch of 136
-// floats puts the two half-wavefronts of an accumulator store (rows 4 apart) into different halves of the banks
-constexpr int kDwPitch = 136;
-constexpr size_t mm5_lds_bytes(int n_slots, bool deep) {
-  return deep ? (size_t)mm5_stages(n_slots) * n_slots * TILE * sizeof(bf16_t) : (size_t)BM * kDwPitch * sizeof(float);
-}
-
 enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
+
+// LDS: a ring of 8 KB slots (one chunk each); the weight-gradient variant keeps, behind a shorter
+// ring, a buffer of 32 rows x 64 floats per multiplying wavefront for the way out.  The pitch of
+// 72 floats puts the two half-wavefronts of an accumulator store (rows 4 apart) into different
+// halves of the banks.
+constexpr int kDwPitch = 72;
+constexpr int mm5_slots(int epi) { return epi == EPI_DW ? 15 : 19; }
+constexpr size_t mm5_lds_bytes(int epi) {
+  return (size_t)mm5_slots(epi) * TILE * sizeof(bf16_t) + (epi == EPI_DW ? 4 * 32 * kDwPitch * sizeof(float) : 0);
+}
 
 // Up to four tensors that share the row index of one side of the product.
 struct Side {
@@ -113,6 +114,7 @@ struct Mm5Args {
   int a_h, a_l, a_d, a_r;       // role -> slot of A (-1: absent)
   int b_h, b_l, b_x, b_d;       // role -> slot of B
   int M, N, K;                  // extents of the tile index spaces and of the contraction
+  int workers;
   int Bp;                       // padded rows per worker (multiple of 128)
   int64_t ktT;                  // chunks per tile of the transposed tensors = M_workers * Bp / 32
   // EPI_FWD_HIDDEN / EPI_DA: bias offset, row-major and transposed outputs
@@ -121,7 +123,7 @@ struct Mm5Args {
   bf16_t *t_h, *t_l, *t_d, *t_r;        // transposed: (column, padded row), ktT chunks per tile
   int64_t kto;
   const bf16_t *m_on, *m_onref;         // EPI_DA: activations whose sign is the ReLU mask, laid out like o_h
-  float *dbpart, *ddbpart;              // EPI_DA: [M_workers][row tiles][N]
+  float *dbpart, *ddbpart;              // EPI_DA: [M_workers][2 x row tiles][N], one partial sum per 64-row band
   // EPI_STORE2
   float *c1, *c2;                       // [Rp][N]
   // EPI_DW
@@ -143,81 +145,100 @@ __device__ __forceinline__ uint2 pack4(const bf16_t (&v)[4]) {
 // NA, NB: tensors on the A and the B side (compile-time, so that the loads of a tile step are a
 // fixed number of instructions and the waits can count them).  HAS_D: the product Ad Bx^T is present.
 //
-// DEEP = true: the workgroup has eight wavefronts in two roles.  Wavefronts 4-7 move chunks from
-// global memory straight into LDS (16-byte LDS-direct loads: no registers, no second pass through
-// the LDS write port), a ring of mm5_stages() stages ahead of wavefronts 0-3, which read
-// fragments and issue MFMAs and, once the movers have left, run the epilogue.  One barrier per
-// tile step: it tells the multipliers that step h has landed and the movers that the stage of
-// step h-1 is free.  (With four wavefronts doing load, LDS write and multiply in turn, the three
-// phases of a step, each near 1000 cycles, ran one after the other.)
-//
-// DEEP = false is the shallow variant for contractions over few tile steps with a heavy epilogue
-// (the weight gradients: K = B rows, then 128 x 128 floats stored per tile): four wavefronts, one
-// LDS stage and one register set, so that two workgroups fit a CU and one's epilogue overlaps
-// the other's loop.
-template <int EPI, int NA, int NB, bool HAS_D, bool DEEP>
-__global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm5(const Mm5Args g) {
+// A workgroup has eight wavefronts in two roles and works through several tiles.  Wavefronts 4-7
+// move chunks from global memory straight into LDS (16-byte LDS-direct loads: no registers, no
+// second pass through the LDS write port); wavefronts 0-3 read fragments, issue MFMAs and run the
+// epilogue of each tile.  LDS is a ring of 8 KB slots, one chunk each, filled tensor by tensor in
+// the order the tile steps read them, across tile boundaries: while the multipliers write one
+// tile out, the first steps of the next are already landing.  One barrier per tile step: it
+// tells the multipliers that the step has landed, and the movers that the slots of the step before
+// are free (NS more loads may go out).  The epilogues use no workgroup barrier, so both roles
+// execute the same number of them.  (With four wavefronts doing load, LDS write and multiply in
+// turn, the three phases of a step, each near 1000 cycles, ran one after the other.)
+template <int EPI, int NA, int NB, bool HAS_D>
+__global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = reinterpret_cast<bf16_t *>(smem_raw);
-  constexpr int NS = NA + NB;
-  constexpr int NST = DEEP ? mm5_stages(NS) : 1;
+  constexpr int NS = NA + NB, NSLOT = mm5_slots(EPI);
+  static_assert(NSLOT >= 2 * NS, "the ring must hold two tile steps");
   const DevState &s = g.s;
-  const bool mover = DEEP && __builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kBlock;   // uniform per wavefront
+  const bool mover = __builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kBlock;   // uniform per wavefront
   const int t = threadIdx.x & (kBlock - 1), lane = t & 63, w = t >> 6;
   const int wy = w >> 1, wx = w & 1;
-  // Tile of this workgroup (1-D grid).  Workgroups are dealt to the 8 XCDs (each with an L2 of its
-  // own) in turn, so consecutive workgroups never share an L2.  The tiles are renumbered so that an
-  // XCD works through a contiguous run of tiles, columns fastest: whole workers, or a few row
-  // tiles of one worker with all their column tiles.  Its L2 then fetches those rows' operands
-  // once and the other side's once per XCD; dealt in turn, every XCD would stream every worker's
-  // operands (8 x the traffic to HBM, which bounded the first layer's forward contraction).
+  // Tiles of this workgroup.  Workgroups are dealt to the 8 XCDs (each with an L2 of its own) in
+  // turn; XCD x takes the x-th eighth of the tiles (columns fastest, then rows, then workers), its
+  // workgroups every nbx-th of those: an XCD's L2 then sees whole workers, or a few row tiles of
+  // one worker with all their column tiles, instead of every worker's operands.
   const int gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
-  const int lin = blockIdx.x, per = gridDim.x / 8;
-  const int tix = lin < per * 8 ? (lin % 8) * per + lin / 8 : lin;
-  const int bx = tix % gx, by = (tix / gx) % gy, bz = tix / (gx * gy);
-  const int m0 = by * BM, n0 = bx * BN;
-  const int wk = bz;                                 // worker
-
-  // first chunk of this tile's rows in every tensor; tile step h reads the chunk 4096 h elements on
-  const bf16_t *basea[NA], *baseb[NB];
-#pragma unroll
-  for (int sl = 0; sl < NA; ++sl) basea[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + (((int64_t)by * g.A.kt[sl]) << 12);
-#pragma unroll
-  for (int sl = 0; sl < NB; ++sl) baseb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl] + (((int64_t)bx * g.B.kt[sl]) << 12);
+  const int total = gx * gy * g.workers, per = (total + 7) / 8;
+  const int nbx = gridDim.x >> 3;
+  const int t_first = (blockIdx.x & 7) * per + (blockIdx.x >> 3), t_end = min(((int)(blockIdx.x & 7) + 1) * per, total);
+  if (t_first >= t_end) return;
+  const int nt = (t_end - t_first + nbx - 1) / nbx;
   const int nk = (g.K + BK - 1) / BK;
+  const int nsteps = nt * nk;
 
-  if constexpr (DEEP) {
-    if (mover) {
-      // Instruction c of wavefront w fills the 64 pieces from position 64 (2 w + c) on of every
-      // tensor's chunk; the lane at position P fetches the piece that the LDS order puts there.
-      const int lw = __builtin_amdgcn_readfirstlane(w);
-      int goff[2];
+  if (mover) {
+    // Instruction c of wavefront w fills the 64 pieces from position 64 (2 w + c) on of a slot;
+    // the lane at position P fetches the piece that the LDS order puts there.
+    const int lw = __builtin_amdgcn_readfirstlane(w);
+    int goff[2];
 #pragma unroll
-      for (int c = 0; c < 2; ++c) goff[c] = lds_piece((2 * lw + c) * 64 + lane) * 8;      // (the order is its own inverse)
-      auto fill = [&](int step, int stage) __attribute__((always_inline)) {
-        const int64_t k = (int64_t)min(step, nk - 1) << 12;         // steps past the end re-read the last chunk into a stage nobody reads
-        bf16_t *dst = lds + ((size_t)stage * NS << 12) + (2 * lw << 9);
+    for (int c = 0; c < 2; ++c) goff[c] = lds_piece((2 * lw + c) * 64 + lane) * 8;      // (the order is its own inverse)
+    // issue cursor: tile ordinal, step in the tile, first chunk of the tile's rows in every tensor, ring slot
+    int ord = 0, h = 0, slot = 0;
+    const bf16_t *pa[NA], *pb[NB];
+    auto set_tile = [&](int o) __attribute__((always_inline)) {
+      const int tix = t_first + o * nbx;
+      const int bx = tix % gx, by = (tix / gx) % gy, bz = tix / (gx * gy);
 #pragma unroll
-        for (int sl = 0; sl < NS; ++sl)
+      for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)bz * g.A.bstride[sl] + (((int64_t)by * g.A.kt[sl]) << 12);
 #pragma unroll
-          for (int c = 0; c < 2; ++c) {
-            const bf16_t *src = (sl < NA ? basea[sl < NA ? sl : 0] : baseb[sl < NA ? 0 : sl - NA]) + k + goff[c];
-            __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)(dst + (sl << 12) + (c << 9)), 16, 0, 0);
-          }
-      };
+      for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)bz * g.B.bstride[sl] + (((int64_t)bx * g.B.kt[sl]) << 12);
+    };
+    // next tile step; past the last one the cursor stays (those loads re-read the last chunk into slots nobody reads)
+    auto next_step = [&]() __attribute__((always_inline)) {
+      if (h + 1 < nk) ++h;
+      else if (ord + 1 < nt) { ++ord; h = 0; set_tile(ord); }
+    };
+    auto load = [&](int sl) __attribute__((always_inline)) {
+      const bf16_t *src = (sl < NA ? pa[sl < NA ? sl : 0] : pb[sl < NA ? 0 : sl - NA]) + ((int64_t)h << 12);
+      bf16_t *dst = lds + ((size_t)slot << 12) + (2 * lw << 9);
 #pragma unroll
-      for (int h = 0; h < NST - 1; ++h) fill(h, h);
-      for (int h = 0; h < nk; ++h) {
-        // own loads of step h have landed when at most the later steps' (NST - 2 of them) are outstanding
-        if constexpr (NST == 3) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(2 * NS) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-        const int hn = h + NST - 1;
-        fill(hn, hn % NST);                           // into the stage of step h - 1, which the barrier has freed
-      }
-      asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");     // nothing may land after the epilogue has taken over the LDS
-      return;        // the barriers of the epilogue count the remaining wavefronts only
+      for (int c = 0; c < 2; ++c)
+        __builtin_amdgcn_global_load_lds(src + goff[c], (__attribute__((address_space(3))) void *)(dst + (c << 9)), 16, 0, 0);
+      slot = slot + 1 == NSLOT ? 0 : slot + 1;
+    };
+    set_tile(0);
+#pragma unroll
+    for (int q = 0; q < NSLOT; ++q) {          // fill the ring
+      if (q % NS == 0 && q > 0) next_step();
+      load(q % NS);
     }
+    // Barrier m: step m has landed when at most the NSLOT - 2 NS tensors issued after it are
+    // outstanding (two instructions each); then the NS slots of step m - 1 are free.
+    for (int m = 0; m < nsteps; ++m) {
+      asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(2 * (NSLOT - 2 * NS)) : "memory");
+      if (m > 0) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+          constexpr int r0 = NSLOT % NS;
+          if ((r0 + i) % NS == 0) next_step();
+          load((r0 + i) % NS);
+        }
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");     // nothing may land after the workgroup has gone
+    return;
   }
+
+  // fragment of this lane inside a 32-row band: row lane % 32, piece lane / 32 (+ 2 in the second half step)
+  const int fro = lds_piece((lane & 31) * 4 + (lane >> 5)) * 8;
+  int sb = 0;                                  // ring slot of the current step's first tensor
+  for (int ord = 0; ord < nt; ++ord) {
+  const int tix = t_first + ord * nbx;
+  const int bx = tix % gx, by = (tix / gx) % gy, wk = tix / (gx * gy);     // wk: worker
+  const int m0 = by * BM, n0 = bx * BN;
 
   f32x16 acc1[2][2], acc2[2][2];
 #pragma unroll
@@ -227,34 +248,35 @@ __global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm
 #pragma unroll
       for (int r = 0; r < 16; ++r) { acc1[i][j][r] = 0.f; acc2[i][j][r] = 0.f; }
 
-  // fragment of this lane inside a 32-row band: row lane % 32, piece lane / 32 (+ 2 in the second half step)
-  const int fro = lds_piece((lane & 31) * 4 + (lane >> 5)) * 8;
-  auto multiply = [&](int stage) __attribute__((always_inline)) {
-    const bf16_t *ldsA = lds + ((size_t)stage * NS << 12), *ldsB = ldsA + NA * TILE;
+  for (int h = 0; h < nk; ++h) {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    auto slot_of = [&](int idx) __attribute__((always_inline)) { const int p = sb + idx; return lds + ((size_t)(p >= NSLOT ? p - NSLOT : p) << 12); };
+    const bf16_t *tah = slot_of(g.a_h), *tal = slot_of(g.a_l), *tad = slot_of(HAS_D ? g.a_d : 0), *tar = slot_of(NA == 4 ? g.a_r : 0);
+    const bf16_t *tbh = slot_of(NA + g.b_h), *tbl = slot_of(NA + g.b_l), *tbx = slot_of(NA + (HAS_D && NB == 4 ? g.b_x : 0)), *tbd = slot_of(NA + g.b_d);
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
-      bf16x8 ah[2], al[2], ad[2], ar[2], bh[2], bl[2], bx[2], bd[2];
+      bf16x8 ah[2], al[2], ad[2], ar[2], bh[2], bl[2], bx_[2], bd[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int o = (wy * 64 + i * 32) * BK + (fro ^ ks);
-        ah[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_h * TILE + o);
-        al[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_l * TILE + o);
-        if constexpr (HAS_D) ad[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_d * TILE + o);
+        ah[i] = *reinterpret_cast<const bf16x8 *>(tah + o);
+        al[i] = *reinterpret_cast<const bf16x8 *>(tal + o);
+        if constexpr (HAS_D) ad[i] = *reinterpret_cast<const bf16x8 *>(tad + o);
         // with fewer than four A tensors the reference operand is the hi part itself
-        if constexpr (NA == 4) ar[i] = *reinterpret_cast<const bf16x8 *>(ldsA + g.a_r * TILE + o);
+        if constexpr (NA == 4) ar[i] = *reinterpret_cast<const bf16x8 *>(tar + o);
         else ar[i] = ah[i];
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int o = (wx * 64 + j * 32) * BK + (fro ^ ks);
-        bh[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_h * TILE + o);
-        bl[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_l * TILE + o);
+        bh[j] = *reinterpret_cast<const bf16x8 *>(tbh + o);
+        bl[j] = *reinterpret_cast<const bf16x8 *>(tbl + o);
         // with fewer than four B tensors the single-bf16 operand is the hi part itself
         if constexpr (HAS_D) {
-          if constexpr (NB == 4) bx[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_x * TILE + o);
-          else bx[j] = bh[j];
+          if constexpr (NB == 4) bx_[j] = *reinterpret_cast<const bf16x8 *>(tbx + o);
+          else bx_[j] = bh[j];
         }
-        bd[j] = *reinterpret_cast<const bf16x8 *>(ldsB + g.b_d * TILE + o);
+        bd[j] = *reinterpret_cast<const bf16x8 *>(tbd + o);
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
@@ -263,54 +285,12 @@ __global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm
           acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc1[i][j], 0, 0, 0);
           acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc1[i][j], 0, 0, 0);
           acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc1[i][j], 0, 0, 0);
-          if constexpr (HAS_D) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad[i], bx[j], acc2[i][j], 0, 0, 0);
+          if constexpr (HAS_D) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad[i], bx_[j], acc2[i][j], 0, 0, 0);
           acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ar[i], bd[j], acc2[i][j], 0, 0, 0);
         }
     }
-  };
-
-  if constexpr (DEEP) {
-    // the same number of barriers as the movers' loop
-    for (int h = 0; h < nk; ++h) {
-      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-      multiply(h % NST);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  } else {
-    // this thread's two 16-byte pieces of a chunk: t and t + 256, stored at their LDS positions
-    u32x4 R[NS][2];
-    auto issue = [&](int step) __attribute__((always_inline)) {
-      const int64_t k = ((int64_t)min(step, nk - 1) << 12) + t * 8;       // the load past the end re-reads the last chunk and is dropped
-#pragma unroll
-      for (int sl = 0; sl < NA; ++sl)
-#pragma unroll
-        for (int c = 0; c < 2; ++c) R[sl][c] = *reinterpret_cast<const u32x4 *>(basea[sl] + k + c * 2048);
-#pragma unroll
-      for (int sl = 0; sl < NB; ++sl)
-#pragma unroll
-        for (int c = 0; c < 2; ++c) R[NA + sl][c] = *reinterpret_cast<const u32x4 *>(baseb[sl] + k + c * 2048);
-    };
-    const int pos = lds_piece(t) * 8;          // (piece t + 256 lands 2048 elements on: the order only touches the low bits)
-    auto stash = [&]() __attribute__((always_inline)) {
-#pragma unroll
-      for (int sl = 0; sl < NS; ++sl)
-#pragma unroll
-        for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4 *>(lds + sl * TILE + pos + c * 2048) = R[sl][c];
-    };
-    // The instruction scheduler is fenced at the phase boundaries: left alone it sinks the loads to
-    // the end of a step.
-    issue(0);
-    for (int h = 0; h < nk; ++h) {
-      __builtin_amdgcn_sched_barrier(0);
-      stash();
-      __syncthreads();
-      issue(h + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      multiply(0);
-      __syncthreads();
-    }
+    sb = sb + NS >= NSLOT ? sb + NS - NSLOT : sb + NS;
   }
-  __syncthreads();   // LDS is free for the epilogue
 
   // accumulator element (i, j, r) is output (row, col):
   //   row = m0 + wy*64 + i*32 + 8*(r>>2) + 4*(lane>>5) + (r&3),  col = n0 + wx*64 + j*32 + (lane&31)
@@ -385,7 +365,6 @@ __global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm
     }
   } else if constexpr (EPI == EPI_DA) {
     // ReLU masks of the layer below, hi/lo split of the signal, bias-gradient partial sums
-    float *red = reinterpret_cast<float *>(smem_raw);          // [2 (wy)][128 cols][2]
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = cbase + j * 32;
@@ -449,104 +428,98 @@ __global__ __launch_bounds__(DEEP ? 2 * kBlock : kBlock, DEEP ? 1 : 2) void k_mm
           }
         }
       }
-      // the other half-wave holds the rows offset by 4: add it, then one value per column and wave
+      // the other half-wave holds the rows offset by 4: add it, then one value per column and
+      // 64-row band (partial sum 2 by + wy of the column)
       sg += __shfl_xor(sg, 32, 64);
       sd += __shfl_xor(sd, 32, 64);
-      if (lane < 32) {
-        const int cl = wx * 64 + j * 32 + lane;
-        red[(wy * 128 + cl) * 2] = sg;
-        red[(wy * 128 + cl) * 2 + 1] = sd;
+      if (lane < 32 && cok) {
+        const int64_t o = ((int64_t)wk * (2 * gy) + 2 * by + wy) * g.N + col;
+        g.dbpart[o] = sg;
+        g.ddbpart[o] = sd;
       }
-    }
-    __syncthreads();
-    if (t < 128 && n0 + t < g.N) {
-      const int64_t o = ((int64_t)wk * ((g.M + BM - 1) / BM) + by) * g.N + n0 + t;
-      g.dbpart[o] = red[t * 2] + red[(128 + t) * 2];
-      g.ddbpart[o] = red[t * 2 + 1] + red[(128 + t) * 2 + 1];
     }
   } else {   // EPI_DW
     // A lane's accumulators are one column and 16 rows of the tile: stored from there, an
     // instruction moves 4 bytes per lane, and the 192 such instructions of a wavefront kept the
-    // CU's address unit busy for longer than the contraction took.  The tile goes through LDS
-    // instead and leaves row by row, 16 bytes per lane, 512 bytes per row.
-    constexpr int CP = kDwPitch;
-    float *ct = reinterpret_cast<float *>(smem_raw);           // [128][CP]
+    // CU's address unit busy for longer than the contraction took.  Each wavefront instead passes
+    // its 64 x 64 part through an LDS buffer of its own, one 32-row band at a time, and writes it
+    // out row by row, 16 bytes per lane, 256 bytes per row.  (LDS operations of one wavefront are
+    // carried out in order, so the buffer needs no barrier.)
+    constexpr int SP = kDwPitch;
+    float *st = reinterpret_cast<float *>(smem_raw + (size_t)NSLOT * TILE * sizeof(bf16_t)) + w * (32 * SP);
     float *gf = fresh_grad(s, wk) + g.offW;
     const bool cada1 = s.rule == CADA_RULE_CADA1;
     const int cur = s.sel[wk];
     float *ivf = cada1 ? s.dtl + ((int64_t)(1 - cur) * s.M + wk) * s.p + g.offW : nullptr;
     const float *ivs = cada1 ? s.dtl + ((int64_t)cur * s.M + wk) * s.p + g.offW : nullptr;
-    // row-wise pass: this thread has columns c4 .. c4+3 of the rows r0 + 8 it, it = 0..15
-    const int c4 = (t & 31) * 4, r0 = t >> 5;
-    const bool wide = n0 + BN <= g.N;       // every column of the tile exists: 16-byte accesses (4-byte aligned)
-    auto put_tile = [&](const f32x16 (&acc)[2][2]) __attribute__((always_inline)) {
+    // row-wise pass: this lane has columns c4 .. c4+3 of the band's rows rr + 4 it, it = 0..7
+    const int c4 = (lane & 15) * 4, rr = lane >> 4;
+    const int colg = n0 + wx * 64 + c4;
+    const bool wide = n0 + wx * 64 + 64 <= g.N;       // every column of this wavefront's part exists: 16-byte accesses (4-byte aligned)
+    auto put_band = [&](const f32x16 (&acc)[2]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * SP + j * 32 + (lane & 31)] = acc[j][r];
+      asm volatile("" ::: "memory");
+    };
+    // CADA1: the stored innovations of the part, all loads issued before anything waits for one
+    // (rows clamped into the matrix so that no load sits under a branch)
+    f32x4u old[2][8];
+    if (cada1 && wide) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            ct[(wy * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * CP + wx * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
-    };
-    // CADA1: the stored innovations of the tile, all loads issued before anything waits for one
-    // (rows clamped into the matrix so that no load sits under a branch)
-    f32x4u old[16];
-    if (cada1 && wide) {
-#pragma unroll
-      for (int it = 0; it < 16; ++it) {
-        const int row = min(m0 + r0 + 8 * it, g.M - 1);
-        old[it] = *reinterpret_cast<const f32x4u *>(ivs + (int64_t)row * g.N + n0 + c4);
-      }
+        for (int it = 0; it < 8; ++it) {
+          const int row = min(m0 + wy * 64 + i * 32 + rr + 4 * it, g.M - 1);
+          old[i][it] = *reinterpret_cast<const f32x4u *>(ivs + (int64_t)row * g.N + colg);
+        }
     }
     float sq = 0.f;
-    put_tile(acc1);
-    __syncthreads();
-    if (wide) {
 #pragma unroll
-      for (int it = 0; it < 16; ++it) {
-        const int rl = r0 + 8 * it;
-        const f32x4u v = *reinterpret_cast<const f32x4u *>(ct + rl * CP + c4);
-        if (m0 + rl < g.M) *reinterpret_cast<f32x4u *>(gf + (int64_t)(m0 + rl) * g.N + n0 + c4) = v;
-      }
-    } else if (n0 + c4 < g.N) {              // a tile that overhangs the matrix: element by element
-      for (int it = 0; it < 16; ++it) {
-        const int rl = r0 + 8 * it;
-        if (m0 + rl >= g.M) break;
-        for (int e = 0; e < 4 && n0 + c4 + e < g.N; ++e) gf[(int64_t)(m0 + rl) * g.N + n0 + c4 + e] = ct[rl * CP + c4 + e];
-      }
-    }
-    __syncthreads();
-    put_tile(acc2);
-    __syncthreads();
-    if (wide) {
+    for (int i = 0; i < 2; ++i) {
+      const int rowb = m0 + wy * 64 + i * 32 + rr;
+      put_band(acc1[i]);
+      if (wide) {
 #pragma unroll
-      for (int it = 0; it < 16; ++it) {
-        const int rl = r0 + 8 * it;
-        f32x4u v = *reinterpret_cast<const f32x4u *>(ct + rl * CP + c4);
-        if (m0 + rl < g.M) {
-          if (cada1) {
-            *reinterpret_cast<f32x4u *>(ivf + (int64_t)(m0 + rl) * g.N + n0 + c4) = v;
-            v -= old[it];
+        for (int it = 0; it < 8; ++it) {
+          const f32x4u v = *reinterpret_cast<const f32x4u *>(st + (rr + 4 * it) * SP + c4);
+          if (rowb + 4 * it < g.M) *reinterpret_cast<f32x4u *>(gf + (int64_t)(rowb + 4 * it) * g.N + colg) = v;
+        }
+      } else if (colg < g.N) {                 // a part that overhangs the matrix: element by element
+        for (int it = 0; it < 8 && rowb + 4 * it < g.M; ++it)
+          for (int e = 0; e < 4 && colg + e < g.N; ++e) gf[(int64_t)(rowb + 4 * it) * g.N + colg + e] = st[(rr + 4 * it) * SP + c4 + e];
+      }
+      asm volatile("" ::: "memory");
+      put_band(acc2[i]);
+      if (wide) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          f32x4u v = *reinterpret_cast<const f32x4u *>(st + (rr + 4 * it) * SP + c4);
+          if (rowb + 4 * it < g.M) {
+            if (cada1) {
+              *reinterpret_cast<f32x4u *>(ivf + (int64_t)(rowb + 4 * it) * g.N + colg) = v;
+              v -= old[i][it];
+            }
+            sq = fmaf(v.x, v.x, sq); sq = fmaf(v.y, v.y, sq); sq = fmaf(v.z, v.z, sq); sq = fmaf(v.w, v.w, sq);
           }
-          sq = fmaf(v.x, v.x, sq); sq = fmaf(v.y, v.y, sq); sq = fmaf(v.z, v.z, sq); sq = fmaf(v.w, v.w, sq);
         }
+      } else if (colg < g.N) {
+        for (int it = 0; it < 8 && rowb + 4 * it < g.M; ++it)
+          for (int e = 0; e < 4 && colg + e < g.N; ++e) {
+            const int64_t o = (int64_t)(rowb + 4 * it) * g.N + colg + e;
+            float iv = st[(rr + 4 * it) * SP + c4 + e];
+            if (cada1) { ivf[o] = iv; iv -= ivs[o]; }
+            sq = fmaf(iv, iv, sq);
+          }
       }
-    } else if (n0 + c4 < g.N) {
-      for (int it = 0; it < 16; ++it) {
-        const int rl = r0 + 8 * it;
-        if (m0 + rl >= g.M) break;
-        for (int e = 0; e < 4 && n0 + c4 + e < g.N; ++e) {
-          const int64_t o = (int64_t)(m0 + rl) * g.N + n0 + c4 + e;
-          float iv = ct[rl * CP + c4 + e];
-          if (cada1) { ivf[o] = iv; iv -= ivs[o]; }
-          sq = fmaf(iv, iv, sq);
-        }
-      }
+      asm volatile("" ::: "memory");
     }
-    __syncthreads();
-    const float tot = block_sum(sq, ct);
-    if (t == 0) s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + by * ((g.N + BN - 1) / BN) + bx] = tot;
+    const float tot = wave_sum(sq);           // one partial sum of the left-hand side per wavefront and tile
+    if (lane == 0) s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + (by * gx + bx) * 4 + w] = tot;
   }
+  }   // tiles
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // the movers' last barrier
 }
 
 // ------------------------------------------------------------------------------------------
@@ -575,7 +548,7 @@ struct MlpPlan {
   bf16_t *Gh[CADA_MAX_LAYERS + 1], *Gl[CADA_MAX_LAYERS + 1], *dG[CADA_MAX_LAYERS + 1], *Gref[CADA_MAX_LAYERS + 1];       // layer l >= 2, (row, unit)
   bf16_t *GhT[CADA_MAX_LAYERS + 1], *GlT[CADA_MAX_LAYERS + 1], *dGT[CADA_MAX_LAYERS + 1], *GrefT[CADA_MAX_LAYERS + 1];   // layer l, (unit, row)
   float *ZL, *dZL;                                        // logits [Rp][C]
-  float *dbpart, *ddbpart;                                // [M][RT][max hidden width]
+  float *dbpart, *ddbpart;                                // [M][2 RT][max hidden width]
 };
 
 namespace {
@@ -610,7 +583,7 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
     P.offb[l - 1] = o; o += P.d[l];
     P.wt_off[l - 1] = wt; wt += (int64_t)tm_elems(P.d[l], P.d[l - 1]);
     P.wn_off[l - 1] = wn; if (l >= 2) wn += (int64_t)tm_elems(P.d[l - 1], P.d[l]);
-    P.lhs_w_slot[l - 1] = slot; slot += tiles128(P.d[l - 1]) * tiles128(P.d[l]);
+    P.lhs_w_slot[l - 1] = slot; slot += 4 * tiles128(P.d[l - 1]) * tiles128(P.d[l]);
     P.lhs_b_slot[l - 1] = slot; slot += (P.d[l] + 255) / 256;
     if (l < P.L && P.d[l] > maxh) maxh = P.d[l];
   }
@@ -643,8 +616,8 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   }
   P.ZL = w.take<float>(Rp * P.d[P.L]);
   P.dZL = w.take<float>(Rp * P.d[P.L]);
-  P.dbpart = w.take<float>((size_t)cfg->M * P.RT * maxh);
-  P.ddbpart = w.take<float>((size_t)cfg->M * P.RT * maxh);
+  P.dbpart = w.take<float>((size_t)cfg->M * 2 * P.RT * maxh);
+  P.ddbpart = w.take<float>((size_t)cfg->M * 2 * P.RT * maxh);
 }
 }  // namespace
 
@@ -653,7 +626,7 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
 int mlp_lhs_slots(const cada_config *cfg) {
   int slot = 0;
   for (int l = 1; l <= cfg->n_layers; ++l)
-    slot += tiles128(cfg->layer_dims[l - 1]) * tiles128(cfg->layer_dims[l]) + (cfg->layer_dims[l] + 255) / 256;
+    slot += 4 * tiles128(cfg->layer_dims[l - 1]) * tiles128(cfg->layer_dims[l]) + (cfg->layer_dims[l] + 255) / 256;
   return slot;
 }
 
@@ -913,19 +886,19 @@ void side_add(Side &sd, const bf16_t *p, int64_t kt, int64_t bstride) {
 }
 
 // The (tensor count, product set) combinations the layers use.
-template <int EPI> constexpr bool mm5_deep() { return EPI != EPI_DW; }
 template <int EPI, int NA, int NB, bool HAS_D> hipError_t mm5_allow_lds() {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI, NA, NB, HAS_D, mm5_deep<EPI>()>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)mm5_lds_bytes(NA + NB, mm5_deep<EPI>()));
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)mm5_lds_bytes(EPI));
 }
-template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const Mm5Args &g, int workers) {
-  const unsigned gx = (g.N + BN - 1) / BN, gy = (g.M + BM - 1) / BM;
-  const dim3 grid(gx * gy * workers);
-  hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D, mm5_deep<EPI>()>), grid, dim3(mm5_deep<EPI>() ? 2 * kBlock : kBlock),
-                     mm5_lds_bytes(NA + NB, mm5_deep<EPI>()), c->stream, g);
+template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const Mm5Args &g) {
+  // one workgroup per CU at most (8 XCDs x 32 CUs), each XCD's tiles dealt over its workgroups
+  const int total = ((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM) * g.workers, per = (total + 7) / 8;
+  const dim3 grid(8 * (per < 32 ? per : 32));
+  hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D>), grid, dim3(2 * kBlock), mm5_lds_bytes(EPI), c->stream, g);
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
-template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
+template <int EPI> void launch_mm5(Ctx *c, Mm5Args &g, int workers) {
+  g.workers = workers;
   const bool has_d = g.a_d >= 0;
   // every tensor must hold the chunks the tile steps walk through
   for (int i = 0; i < g.A.n; ++i)
@@ -933,13 +906,13 @@ template <int EPI> void launch_mm5(Ctx *c, const Mm5Args &g, int workers) {
   for (int i = 0; i < g.B.n; ++i)
     if (g.B.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: B tensor with fewer chunks than tile steps"); return; }
   if constexpr (EPI == EPI_DW) {
-    if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g, workers);
-    if (has_d && g.A.n == 3 && g.B.n == 4) return launch_mm5_as<EPI, 3, 4, true>(c, g, workers);
+    if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g);
+    if (has_d && g.A.n == 3 && g.B.n == 4) return launch_mm5_as<EPI, 3, 4, true>(c, g);
   } else if constexpr (EPI == EPI_DA) {
-    if (has_d && g.A.n == 4 && g.B.n == 3) return launch_mm5_as<EPI, 4, 3, true>(c, g, workers);
+    if (has_d && g.A.n == 4 && g.B.n == 3) return launch_mm5_as<EPI, 4, 3, true>(c, g);
   } else {
-    if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g, workers);
-    if (has_d && g.A.n == 4 && g.B.n == 3) return launch_mm5_as<EPI, 4, 3, true>(c, g, workers);
+    if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g);
+    if (has_d && g.A.n == 4 && g.B.n == 3) return launch_mm5_as<EPI, 4, 3, true>(c, g);
   }
   set_error("internal: no MFMA kernel variant for %d + %d tensors", g.A.n, g.B.n);
 }
@@ -1088,7 +1061,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
       g.m_on = P.Ah[q]; g.m_onref = P.Aref[q];
       g.dbpart = P.dbpart; g.ddbpart = P.ddbpart;
       launch_mm5<EPI_DA>(c, g, M);
-      hipLaunchKernelGGL(k_bias_finish, dim3((din + 255) / 256, M), dim3(kBlock), 0, st, s, P.dbpart, P.ddbpart, P.RT, din,
+      hipLaunchKernelGGL(k_bias_finish, dim3((din + 255) / 256, M), dim3(kBlock), 0, st, s, P.dbpart, P.ddbpart, 2 * P.RT, din,
                          P.offb[q - 1], P.lhs_b_slot[q - 1]);
     }
   }
