@@ -141,6 +141,12 @@ __device__ __forceinline__ float *fresh_grad(const DevState &s, int m) {
 __device__ __forceinline__ uint2 pack4(const bf16_t (&v)[4]) {
   return make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
 }
+__device__ __forceinline__ u32x4 pack8(const bf16_t (&v)[8]) {
+  u32x4 o;
+  o.x = (uint32_t)v[0] | ((uint32_t)v[1] << 16); o.y = (uint32_t)v[2] | ((uint32_t)v[3] << 16);
+  o.z = (uint32_t)v[4] | ((uint32_t)v[5] << 16); o.w = (uint32_t)v[6] | ((uint32_t)v[7] << 16);
+  return o;
+}
 
 // NA, NB: tensors on the A and the B side (compile-time, so that the loads of a tile step are a
 // fixed number of instructions and the waits can count them).  HAS_D: the product Ad Bx^T is present.
@@ -685,31 +691,46 @@ __global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow, int 
 }
 
 // Chunked copies of the gathered minibatch in both orientations:
-// XG(m*Bp + b, c) = X[grow[m*Bp + b]][c] and XT(c, m*Bp + b) = the same.  grid (ceil(d0/64), ceil(B/64), M), block 256;
-// 64 x 64 tile through LDS.
+// XG(m*Bp + b, c) = X[grow[m*Bp + b]][c] and XT(c, m*Bp + b) = the same.  grid (ceil(ldx/64), ceil(B/64), M), block 256;
+// a 64 x 64 tile per block, moved 16 bytes (8 values) per lane: rows of X are read and written
+// to XG as they are, and turned through LDS for XT.
 __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, const bf16_t *Xl, int64_t ldx, const int64_t *grow,
                                                              bf16_t *XTh, bf16_t *XTl, bf16_t *XGh, bf16_t *XGl, int d0, int B, int Bp,
                                                              int64_t ktx, int64_t ktT) {
-  __shared__ bf16_t th[64][66], tl[64][66];
+  __shared__ __align__(16) bf16_t th[64][72], tl[64][72];      // pitch 72: 16-byte rows, 8 rows span all banks
   const int m = blockIdx.z, c0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4) {
-    const int b = b0 + r, c = c0 + tx;
-    bf16_t vh = 0, vl = 0;
-    if (b < B && c < d0) {
+  const int t = threadIdx.x;
+  const int cg = (t & 7) * 8;                   // this thread's 8 columns
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = (t >> 3) + 32 * pass, b = b0 + r, c = c0 + cg;
+    u32x4 vh = {0u, 0u, 0u, 0u}, vl = {0u, 0u, 0u, 0u};
+    if (b < B && c < ldx) {                     // (columns from d0 to ldx hold zeros in X's copies)
       const int64_t src = grow[(int64_t)m * Bp + b] * ldx + c;
-      vh = Xh[src]; vl = Xl[src];
+      vh = *reinterpret_cast<const u32x4 *>(Xh + src);
+      vl = *reinterpret_cast<const u32x4 *>(Xl + src);
       const int64_t dst = tm((int64_t)m * Bp + b, c, ktx);
-      XGh[dst] = vh; XGl[dst] = vl;
+      *reinterpret_cast<u32x4 *>(XGh + dst) = vh;
+      *reinterpret_cast<u32x4 *>(XGl + dst) = vl;
     }
-    th[r][tx] = vh; tl[r][tx] = vl;
+    *reinterpret_cast<u32x4 *>(&th[r][cg]) = vh;
+    *reinterpret_cast<u32x4 *>(&tl[r][cg]) = vl;
   }
   __syncthreads();
-  for (int r = ty; r < 64; r += 4) {
-    const int c = c0 + r, b = b0 + tx;
-    if (c < d0 && b < B) {
-      const int64_t o = tm(c, (int64_t)m * Bp + b, ktT);
-      XTh[o] = th[tx][r]; XTl[o] = tl[tx][r];
+  // 8 consecutive rows of one column are 16 consecutive bytes of XT (rows past B are written as zeros)
+  const int f = t & 63;
+  if (c0 + f < d0) {
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int rg = ((t >> 6) + 4 * pass) * 8;
+      if (b0 + rg < B) {
+        bf16_t h8[8], l8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { h8[e] = th[rg + e][f]; l8[e] = tl[rg + e][f]; }
+        const int64_t o = tm(c0 + f, (int64_t)m * Bp + b0 + rg, ktT);
+        *reinterpret_cast<u32x4 *>(XTh + o) = pack8(h8);
+        *reinterpret_cast<u32x4 *>(XTl + o) = pack8(l8);
+      }
     }
   }
 }
@@ -725,37 +746,65 @@ struct PrepArgs {
 
 // bf16 copies of one layer's weights (hi, lo) and of its difference to each reference point,
 // in the orientation(s) the contractions read.  grid (ceil(dout/64), ceil(din/64), nW + 1):
-// z = 0 -> W, z = 1 + m -> theta - theta_ref(m).  64 x 64 tile through LDS.
+// z = 0 -> W, z = 1 + m -> theta - theta_ref(m).  A 64 x 64 tile per block, 8 values per lane:
+// rows of W are read (4-byte aligned 16-byte loads) and written as they are, and turned
+// through LDS for the other orientation.
 __global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
   const DevState &s = a.s;
   __shared__ float tile[64][65];
   const int o0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int t = threadIdx.x;
   const bool is_w = blockIdx.z == 0;
   const int m = is_w ? 0 : blockIdx.z - 1;
   const RefPtr ref = theta_ref(s, m, s.k);
-  for (int r = ty; r < 64; r += 4) {
-    const int i = i0 + r, o = o0 + tx;
-    float v = 0.f;
+  const int og = (t & 7) * 8;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = (t >> 3) + 32 * pass, i = i0 + r, o = o0 + og;
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (i < a.din && o < a.dout) {
       const int64_t src = a.offW + (int64_t)i * a.dout + o;
-      v = is_w ? s.theta[src] : delta_theta(s, ref, src);
-      if (a.want_n) {
+      if (o + 8 <= a.dout) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          f32x4u x = *reinterpret_cast<const f32x4u *>(s.theta + src + 4 * q);
+          if (!is_w) {
+            const f32x4u xl = *reinterpret_cast<const f32x4u *>(s.theta_lo + src + 4 * q);
+            const f32x4u rh = *reinterpret_cast<const f32x4u *>(ref.hi + src + 4 * q);
+            const f32x4u rl = *reinterpret_cast<const f32x4u *>(ref.lo + src + 4 * q);
+            x = (x - rh) + (xl - rl);             // the same expression as delta_theta
+          }
+          v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+        }
+      } else {
+        for (int e = 0; e < 8 && o + e < a.dout; ++e) v[e] = is_w ? s.theta[src + e] : delta_theta(s, ref, src + e);
+      }
+      if (a.want_n) {                             // (values past dout are zeros, like the padding they land in)
         const int64_t dn = tm(i, o, a.ktn);
-        if (is_w) { const bf16_t hi = f2bf(v); a.WNh[dn] = hi; a.WNl[dn] = f2bf(v - bf2f(hi)); }
-        else a.dWN[(int64_t)m * a.wn_total + dn] = f2bf(v);
+        bf16_t h8[8], l8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { h8[e] = f2bf(v[e]); l8[e] = f2bf(v[e] - bf2f(h8[e])); }
+        if (is_w) { *reinterpret_cast<u32x4 *>(a.WNh + dn) = pack8(h8); *reinterpret_cast<u32x4 *>(a.WNl + dn) = pack8(l8); }
+        else *reinterpret_cast<u32x4 *>(a.dWN + (int64_t)m * a.wn_total + dn) = pack8(h8);
       }
     }
-    tile[r][tx] = v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[r][og + e] = v[e];
   }
   __syncthreads();
-  for (int r = ty; r < 64; r += 4) {
-    const int o = o0 + r, i = i0 + tx;
-    if (o < a.dout && i < a.din) {
-      const float v = tile[tx][r];
-      const int64_t dt = tm(o, i, a.ktt);
-      if (is_w) { const bf16_t hi = f2bf(v); a.WTh[dt] = hi; a.WTl[dt] = f2bf(v - bf2f(hi)); }
-      else a.dWT[(int64_t)m * a.wt_total + dt] = f2bf(v);
+  const int oo = t & 63;
+  if (o0 + oo < a.dout) {
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int ig = ((t >> 6) + 4 * pass) * 8;
+      if (i0 + ig < a.din) {                      // (rows past din are zeros in the tile)
+        bf16_t h8[8], l8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float x = tile[ig + e][oo]; h8[e] = f2bf(x); l8[e] = f2bf(x - bf2f(h8[e])); }
+        const int64_t dt = tm(o0 + oo, i0 + ig, a.ktt);
+        if (is_w) { *reinterpret_cast<u32x4 *>(a.WTh + dt) = pack8(h8); *reinterpret_cast<u32x4 *>(a.WTl + dt) = pack8(l8); }
+        else *reinterpret_cast<u32x4 *>(a.dWT + (int64_t)m * a.wt_total + dt) = pack8(h8);
+      }
     }
   }
 }
@@ -778,9 +827,9 @@ struct LossArgs {
 __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
   const DevState &s = a.s;
   constexpr int MAXC = 32;
-  __shared__ float red[kBlock];
-  __shared__ float sqs;
+  __shared__ float part[4][2 * MAXC];
   const int m = blockIdx.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const RefPtr ref = theta_ref(s, m, s.k);
   const int32_t *yv = static_cast<const int32_t *>(s.y);
   const float invB = 1.0f / (float)s.B;
@@ -807,47 +856,62 @@ __global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) if (c < a.C) { z[c] = z[c] / den; dz[c] = expm1f(-dz[c]); S = fmaf(z[c], dz[c], S); }
     const int label = yv[a.grow[r]];
+    // (row, class) tensors: a row's classes are consecutive, written two at a time (an absent odd
+    // class is a zero in the padding); (class, row) tensors: consecutive lanes, consecutive rows
+    const int64_t orow = tm(r, 0, a.ktg);
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) {
-      if (c < a.C) {
-        const float gl = (z[c] - (c == label ? 1.f : 0.f)) * invB;
-        const float dg = z[c] * (S - dz[c]) / (1.0f + S) * invB;
-        const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
-        const int64_t o = tm(r, c, a.ktg), ot = tm(c, r, a.ktT);
-        if (a.Gh) { a.Gh[o] = hi; a.Gl[o] = lo; a.dG[o] = bd; a.Gref[o] = br; }   // (a single-layer network has no layer below to pass them to)
-        a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
-        sumG[c] += gl;
-        sumD[c] += dg;
+    for (int c2 = 0; c2 < MAXC; c2 += 2) {
+      if (c2 < a.C) {
+        uint32_t ph = 0, pl = 0, pd = 0, pr = 0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int c = c2 + e;
+          if (c < a.C) {
+            const float gl = (z[c] - (c == label ? 1.f : 0.f)) * invB;
+            const float dg = z[c] * (S - dz[c]) / (1.0f + S) * invB;
+            const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
+            ph |= (uint32_t)hi << (16 * e); pl |= (uint32_t)lo << (16 * e); pd |= (uint32_t)bd << (16 * e); pr |= (uint32_t)br << (16 * e);
+            const int64_t ot = tm(c, r, a.ktT);
+            a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
+            sumG[c] += gl;
+            sumD[c] += dg;
+          }
+        }
+        if (a.Gh) {     // (a single-layer network has no layer below to pass them to)
+          const int64_t o = orow + c2;          // classes 0..31 lie in the row's first chunk
+          *reinterpret_cast<uint32_t *>(a.Gh + o) = ph; *reinterpret_cast<uint32_t *>(a.Gl + o) = pl;
+          *reinterpret_cast<uint32_t *>(a.dG + o) = pd; *reinterpret_cast<uint32_t *>(a.Gref + o) = pr;
+        }
       }
     }
   }
-  float *gf = fresh_grad(s, m) + a.offb;
-  const bool cada1 = s.rule == CADA_RULE_CADA1;
-  const int cur = s.sel[m];
-  float *ivf = cada1 ? s.dtl + ((int64_t)(1 - cur) * s.M + m) * s.p + a.offb : nullptr;
-  const float *ivs = cada1 ? s.dtl + ((int64_t)cur * s.M + m) * s.p + a.offb : nullptr;
-  if (threadIdx.x == 0) sqs = 0.f;
-  for (int c = 0; c < a.C; ++c) {
-    float vg = 0.f, vd = 0.f;
+  // bias gradient of the last layer, its innovation and that innovation's part of the left-hand
+  // side: sums over the rows in a fixed order (wavefront tree, then the four wavefronts)
 #pragma unroll
-    for (int cc = 0; cc < MAXC; ++cc) if (cc == c) { vg = sumG[cc]; vd = sumD[cc]; }
-    __syncthreads();
-    red[threadIdx.x] = vg;
-    __syncthreads();
-    for (int o = kBlock / 2; o > 0; o >>= 1) { if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o]; __syncthreads(); }
-    if (threadIdx.x == 0) gf[c] = red[0];
-    __syncthreads();
-    red[threadIdx.x] = vd;
-    __syncthreads();
-    for (int o = kBlock / 2; o > 0; o >>= 1) { if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o]; __syncthreads(); }
-    if (threadIdx.x == 0) {
-      float iv = red[0];
-      if (cada1) { ivf[c] = iv; iv -= ivs[c]; }
-      sqs = fmaf(iv, iv, sqs);
+  for (int c = 0; c < MAXC; ++c) {
+    if (c < a.C) {
+      const float g1 = wave_sum(sumG[c]), d1 = wave_sum(sumD[c]);
+      if (lane == 0) { part[w][2 * c] = g1; part[w][2 * c + 1] = d1; }
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + a.lhs_slot] = sqs;
+  if (w == 0) {
+    float sq = 0.f;
+    if (lane < a.C) {
+      const int c = lane;
+      const float gsum = (part[0][2 * c] + part[1][2 * c]) + (part[2][2 * c] + part[3][2 * c]);
+      float iv = (part[0][2 * c + 1] + part[1][2 * c + 1]) + (part[2][2 * c + 1] + part[3][2 * c + 1]);
+      fresh_grad(s, m)[a.offb + c] = gsum;
+      if (s.rule == CADA_RULE_CADA1) {
+        const int cur = s.sel[m];
+        s.dtl[((int64_t)(1 - cur) * s.M + m) * s.p + a.offb + c] = iv;
+        iv -= s.dtl[((int64_t)cur * s.M + m) * s.p + a.offb + c];
+      }
+      sq = iv * iv;
+    }
+    const float tot = wave_sum(sq);
+    if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + a.lhs_slot] = tot;
+  }
 }
 
 // Hidden-layer bias gradient and its innovation from the per-tile partial sums of k_mm5<EPI_DA>.
@@ -954,7 +1018,7 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
   const int64_t dwt_stride = per_worker ? P.wt_total : 0;
   hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp);
-  hipLaunchKernelGGL(k_gather_transpose, dim3((P.d[0] + 63) / 64, (B + 63) / 64, M), dim3(kBlock), 0, st,
+  hipLaunchKernelGGL(k_gather_transpose, dim3((unsigned)((P.ldx + 63) / 64), (B + 63) / 64, M), dim3(kBlock), 0, st,
                      P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, P.kta[0], P.ktT);
   for (int l = 1; l <= L; ++l) {
     PrepArgs pa;
