@@ -90,14 +90,16 @@ __device__ __forceinline__ int lds_piece(int piece) {   // piece = 4 row + q  ->
 
 enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
 
-// LDS: a ring of 8 KB slots (one chunk each); the weight-gradient variant keeps, behind a shorter
-// ring, a buffer of 32 rows x 64 floats per multiplying wavefront for the way out.  The pitch of
+// LDS: a ring of 8 KB slots (one chunk each); behind it a buffer per multiplying wavefront for the
+// way out: 32 rows x 64 floats for the weight gradients, 8 KB for the bf16 tensors of the forward
+// and activation-gradient variants (the logits of the last layer are stored directly).  The pitch of
 // 72 floats puts the two half-wavefronts of an accumulator store (rows 4 apart) into different
 // halves of the banks.
 constexpr int kDwPitch = 72;
-constexpr int mm5_slots(int epi) { return epi == EPI_DW ? 15 : 19; }
+constexpr int mm5_slots(int epi) { return epi == EPI_STORE2 ? 19 : 15; }
 constexpr size_t mm5_lds_bytes(int epi) {
-  return (size_t)mm5_slots(epi) * TILE * sizeof(bf16_t) + (epi == EPI_DW ? 4 * 32 * kDwPitch * sizeof(float) : 0);
+  return (size_t)mm5_slots(epi) * TILE * sizeof(bf16_t) +
+         (epi == EPI_DW ? 4 * 32 * kDwPitch * sizeof(float) : epi == EPI_STORE2 ? 0 : 4 * 8192);
 }
 
 // Up to four tensors that share the row index of one side of the product.
@@ -122,7 +124,7 @@ struct Mm5Args {
   bf16_t *o_h, *o_l, *o_d, *o_r;        // (padded row, column), kto chunks per tile
   bf16_t *t_h, *t_l, *t_d, *t_r;        // transposed: (column, padded row), ktT chunks per tile
   int64_t kto;
-  const bf16_t *m_on, *m_onref;         // EPI_DA: activations whose sign is the ReLU mask, laid out like o_h
+  uint64_t *maskbits;                   // ReLU mask bits [workers][row tiles][column tiles][256 lanes][2]: written by EPI_FWD_HIDDEN, read by EPI_DA
   float *dbpart, *ddbpart;              // EPI_DA: [M_workers][2 x row tiles][N], one partial sum per 64-row band
   // EPI_STORE2
   float *c1, *c2;                       // [Rp][N]
@@ -326,123 +328,124 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
           }
         }
       }
-  } else if constexpr (EPI == EPI_FWD_HIDDEN) {
+  } else if constexpr (EPI == EPI_FWD_HIDDEN || EPI == EPI_DA) {
+    // Forward: bias, ReLU of both evaluations.  Activation gradient: ReLU masks of the layer
+    // below, bias-gradient partial sums.  Both: the result split into hi/lo, its difference and
+    // its reference value, each written as a (row, column) and as a (column, row) tensor.
+    // A lane's accumulators are one column and 16 rows of a 32 x 32 quarter: written from there
+    // every store instruction would move 2 bytes per lane (some 300 instructions per wavefront and
+    // tile; the CU's address unit then needs longer for them than the whole contraction took for
+    // small K).  In both layouts a quarter is 2 KB of consecutive memory, so each wavefront puts
+    // the quarter's values into an LDS buffer of its own in the layout of the destination and
+    // copies it out 16 bytes per lane.  (LDS operations of one wavefront are carried out in
+    // order, so the buffer needs no barrier.)
+    bf16_t *sg = reinterpret_cast<bf16_t *>(smem_raw + (size_t)NSLOT * TILE * sizeof(bf16_t)) + w * 4096;   // 4 x 2 KB
+    const int wr0 = m0 + wy * 64, wc0 = n0 + wx * 64;       // first row and column of this wavefront's 64 x 64 part
+    bf16_t *const orow_t[4] = {g.o_h, g.o_l, g.o_d, g.o_r};
+    bf16_t *const ocol_t[4] = {g.t_h, g.t_l, g.t_d, g.t_r};
+    auto copy_out = [&](bf16_t *const (&dst)[4], int64_t goff) __attribute__((always_inline)) {
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        if (dst[b] != nullptr) {
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const int e8 = (hh * 64 + lane) * 8;
+            *reinterpret_cast<u32x4 *>(dst[b] + goff + e8) = *reinterpret_cast<const u32x4 *>(sg + b * 1024 + e8);
+          }
+        }
+      asm volatile("" ::: "memory");
+    };
+
+    // ReLU masks: one bit per accumulator element, set where the activation is positive (at theta,
+    // at the reference point).  The forward contraction of a layer and the activation-gradient
+    // contraction into it have the same tiles and the same element-to-lane map, so the forward
+    // epilogue leaves each lane's 2 x 64 bits where the backward one finds them: 16 bytes per lane.
+    uint64_t bit_on = 0, bit_ref = 0;
+    uint64_t *mbits = g.maskbits + ((((int64_t)wk * gy + by) * gx + bx) * kBlock + t) * 2;
+    if constexpr (EPI == EPI_DA) {
+      const u32x4 mb = *reinterpret_cast<const u32x4 *>(mbits);
+      bit_on = (uint64_t)mb.x | ((uint64_t)mb.y << 32);
+      bit_ref = (uint64_t)mb.z | ((uint64_t)mb.w << 32);
+    }
+
     const RefPtr ref = theta_ref(s, wk, s.k);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = cbase + j * 32;
       const bool cok = col < g.N;
-      const float b = cok ? s.theta[g.offb + col] : 0.f;
-      const float db = cok ? delta_theta(s, ref, g.offb + col) : 0.f;
+      float b = 0.f, db = 0.f;
+      if constexpr (EPI == EPI_FWD_HIDDEN) {
+        b = cok ? s.theta[g.offb + col] : 0.f;
+        db = cok ? delta_theta(s, ref, g.offb + col) : 0.f;
+      }
+      float sg_sum = 0.f, sd_sum = 0.f;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int64_t o0 = orow(i, j), ot0 = ocol(i, j);
+        // the quarter's four values per element, packed two rows to a register
+        uint32_t ph[8], pl[8], pd[8], pr[8];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {        // four groups of four consecutive rows
-          const int row0 = rbase + i * 32 + 8 * q;
-          bf16_t vh[4], vl[4], vd[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int row = row0 + e;
-            const float z = acc1[i][j][4 * q + e] + b;
-            const float dz = acc2[i][j][4 * q + e] + db;
-            const float act = fmaxf(z, 0.f), aref = fmaxf(z - dz, 0.f);
-            const bf16_t hi = f2bf(act);
-            vh[e] = hi; vl[e] = f2bf(act - bf2f(hi)); vd[e] = f2bf(act - aref);
-            if (cok && row < g.M) {
-              const int64_t o = o0 + 32 * (8 * q + e);
-              g.o_h[o] = hi; g.o_l[o] = vl[e]; g.o_d[o] = vd[e]; g.o_r[o] = f2bf(aref);
-            }
-          }
-          if (cok) {
-            const int64_t ot = ot0 + 8 * q;
-            if (row0 + 3 < g.M) {
-              *reinterpret_cast<uint2 *>(g.t_h + ot) = pack4(vh);
-              *reinterpret_cast<uint2 *>(g.t_l + ot) = pack4(vl);
-              *reinterpret_cast<uint2 *>(g.t_d + ot) = pack4(vd);
+        for (int r = 0; r < 16; ++r) {
+          const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+          float x = 0.f, xref = 0.f;                // value at theta, at the reference point
+          if (cok && row < g.M) {
+            if constexpr (EPI == EPI_FWD_HIDDEN) {
+              const float z = acc1[i][j][r] + b, dz = acc2[i][j][r] + db;
+              x = fmaxf(z, 0.f); xref = fmaxf(z - dz, 0.f);
             } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                if (row0 + e < g.M) { g.t_h[ot + e] = vh[e]; g.t_l[ot + e] = vl[e]; g.t_d[ot + e] = vd[e]; }
+              const float ga = acc1[i][j][r], dga = acc2[i][j][r];
+              x = (bit_on >> ((i * 2 + j) * 16 + r)) & 1 ? ga : 0.f;
+              xref = (bit_ref >> ((i * 2 + j) * 16 + r)) & 1 ? (ga - dga) : 0.f;
             }
           }
+          const float dx = x - xref;
+          const bf16_t hi = f2bf(x);
+          const uint32_t vh = hi, vl = f2bf(x - bf2f(hi)), vd = f2bf(dx), vr = f2bf(xref);
+          if constexpr (EPI == EPI_FWD_HIDDEN) {      // (the sign of the stored, rounded value)
+            bit_on |= (uint64_t)(bf2f(hi) > 0.f ? 1 : 0) << ((i * 2 + j) * 16 + r);
+            bit_ref |= (uint64_t)(bf2f((bf16_t)vr) > 0.f ? 1 : 0) << ((i * 2 + j) * 16 + r);
+          }
+          if (r & 1) { ph[r >> 1] |= vh << 16; pl[r >> 1] |= vl << 16; pd[r >> 1] |= vd << 16; pr[r >> 1] |= vr << 16; }
+          else { ph[r >> 1] = vh; pl[r >> 1] = vl; pd[r >> 1] = vd; pr[r >> 1] = vr; }
+          sg_sum += x; sd_sum += dx;
+        }
+        // (row, column) layout: element (rl, cl) of the quarter at 32 rl + cl
+        if (g.o_h != nullptr && wc0 + j * 32 < (int)g.kto * 32) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int e = (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 32 + (lane & 31), sh = 16 * (r & 1);
+            sg[e] = (bf16_t)(ph[r >> 1] >> sh); sg[1024 + e] = (bf16_t)(pl[r >> 1] >> sh);
+            sg[2048 + e] = (bf16_t)(pd[r >> 1] >> sh); sg[3072 + e] = (bf16_t)(pr[r >> 1] >> sh);
+          }
+          copy_out(orow_t, tm(rp0 + wr0 + i * 32, wc0 + j * 32, g.kto));
+        }
+        // (column, row) layout: element (rl, cl) at 32 cl + rl; four consecutive rows are one 8-byte write
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int e = (lane & 31) * 32 + 8 * q + 4 * (lane >> 5);
+          *reinterpret_cast<uint2 *>(sg + e) = make_uint2(ph[2 * q], ph[2 * q + 1]);
+          *reinterpret_cast<uint2 *>(sg + 1024 + e) = make_uint2(pl[2 * q], pl[2 * q + 1]);
+          *reinterpret_cast<uint2 *>(sg + 2048 + e) = make_uint2(pd[2 * q], pd[2 * q + 1]);
+          *reinterpret_cast<uint2 *>(sg + 3072 + e) = make_uint2(pr[2 * q], pr[2 * q + 1]);
+        }
+        copy_out(ocol_t, tm(wc0 + j * 32, rp0 + wr0 + i * 32, g.ktT));
+      }
+      if constexpr (EPI == EPI_DA) {
+        // the other half-wave holds the rows offset by 4: add it, then one value per column and
+        // 64-row band (partial sum 2 by + wy of the column)
+        sg_sum += __shfl_xor(sg_sum, 32, 64);
+        sd_sum += __shfl_xor(sd_sum, 32, 64);
+        if (lane < 32 && cok) {
+          const int64_t o = ((int64_t)wk * (2 * gy) + 2 * by + wy) * g.N + col;
+          g.dbpart[o] = sg_sum;
+          g.ddbpart[o] = sd_sum;
         }
       }
     }
-  } else if constexpr (EPI == EPI_DA) {
-    // ReLU masks of the layer below, hi/lo split of the signal, bias-gradient partial sums
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = cbase + j * 32;
-      const bool cok = col < g.N;
-      float sg = 0.f, sd = 0.f;
-      // the activations whose sign is the ReLU mask: all loads of this half of the columns are
-      // issued before anything waits for one (one half at a time keeps the wavefront within 256
-      // registers)
-      bf16_t mon[2][16], mref[2][16];
-      {
-        // (rows beyond the extent exist in the chunked tensors and hold zeros; whole chunks of columns may not)
-        const int colc = min(col, g.N - 1);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int64_t om = tm(rp0 + rbase + i * 32, colc, g.kto);
-          const bf16_t *pon = g.m_on + om, *pref = g.m_onref + om;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            mon[i][r] = pon[32 * (8 * (r >> 2) + (r & 3))];
-            mref[i][r] = pref[32 * (8 * (r >> 2) + (r & 3))];
-          }
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int64_t o0 = orow(i, j), ot0 = ocol(i, j);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int row0 = rbase + i * 32 + 8 * q;
-          bf16_t vh[4], vl[4], vd[4], vr[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int row = row0 + e;
-            float gl = 0.f, gref = 0.f;
-            if (cok && row < g.M) {
-              const float ga = acc1[i][j][4 * q + e], dga = acc2[i][j][4 * q + e];
-              gl = bf2f(mon[i][4 * q + e]) > 0.f ? ga : 0.f;
-              gref = bf2f(mref[i][4 * q + e]) > 0.f ? (ga - dga) : 0.f;
-            }
-            const float dg = gl - gref;
-            const bf16_t hi = f2bf(gl);
-            vh[e] = hi; vl[e] = f2bf(gl - bf2f(hi)); vd[e] = f2bf(dg); vr[e] = f2bf(gref);
-            sg += gl; sd += dg;
-            if (g.o_h && cok && row < g.M) {
-              const int64_t o = o0 + 32 * (8 * q + e);
-              g.o_h[o] = hi; g.o_l[o] = vl[e]; g.o_d[o] = vd[e]; g.o_r[o] = vr[e];
-            }
-          }
-          if (cok) {
-            const int64_t ot = ot0 + 8 * q;
-            if (row0 + 3 < g.M) {
-              *reinterpret_cast<uint2 *>(g.t_h + ot) = pack4(vh);
-              *reinterpret_cast<uint2 *>(g.t_l + ot) = pack4(vl);
-              *reinterpret_cast<uint2 *>(g.t_d + ot) = pack4(vd);
-              *reinterpret_cast<uint2 *>(g.t_r + ot) = pack4(vr);
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                if (row0 + e < g.M) { g.t_h[ot + e] = vh[e]; g.t_l[ot + e] = vl[e]; g.t_d[ot + e] = vd[e]; g.t_r[ot + e] = vr[e]; }
-            }
-          }
-        }
-      }
-      // the other half-wave holds the rows offset by 4: add it, then one value per column and
-      // 64-row band (partial sum 2 by + wy of the column)
-      sg += __shfl_xor(sg, 32, 64);
-      sd += __shfl_xor(sd, 32, 64);
-      if (lane < 32 && cok) {
-        const int64_t o = ((int64_t)wk * (2 * gy) + 2 * by + wy) * g.N + col;
-        g.dbpart[o] = sg;
-        g.ddbpart[o] = sd;
-      }
+    if constexpr (EPI == EPI_FWD_HIDDEN) {
+      u32x4 mb;
+      mb.x = (uint32_t)bit_on; mb.y = (uint32_t)(bit_on >> 32); mb.z = (uint32_t)bit_ref; mb.w = (uint32_t)(bit_ref >> 32);
+      *reinterpret_cast<u32x4 *>(mbits) = mb;
     }
   } else {   // EPI_DW
     // A lane's accumulators are one column and 16 rows of the tile: stored from there, an
@@ -554,6 +557,7 @@ struct MlpPlan {
   bf16_t *Gh[CADA_MAX_LAYERS + 1], *Gl[CADA_MAX_LAYERS + 1], *dG[CADA_MAX_LAYERS + 1], *Gref[CADA_MAX_LAYERS + 1];       // layer l >= 2, (row, unit)
   bf16_t *GhT[CADA_MAX_LAYERS + 1], *GlT[CADA_MAX_LAYERS + 1], *dGT[CADA_MAX_LAYERS + 1], *GrefT[CADA_MAX_LAYERS + 1];   // layer l, (unit, row)
   float *ZL, *dZL;                                        // logits [Rp][C]
+  uint64_t *maskbits[CADA_MAX_LAYERS];                    // hidden l: ReLU mask bits per tile and lane
   float *dbpart, *ddbpart;                                // [M][2 RT][max hidden width]
 };
 
@@ -610,6 +614,7 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
     const size_t n = tm_elems(Rp, P.d[l]), nt = tm_elems(P.d[l], Rp);
     P.Ah[l] = w.take<bf16_t>(n); P.Al[l] = w.take<bf16_t>(n); P.dA[l] = w.take<bf16_t>(n); P.Aref[l] = w.take<bf16_t>(n);
     P.AhT[l] = w.take<bf16_t>(nt); P.AlT[l] = w.take<bf16_t>(nt); P.dAT[l] = w.take<bf16_t>(nt);
+    P.maskbits[l] = w.take<uint64_t>((size_t)cfg->M * P.RT * tiles128(P.d[l]) * kBlock * 2);
   }
   for (int l = 1; l <= P.L; ++l) {
     const size_t n = tm_elems(Rp, P.d[l]), nt = tm_elems(P.d[l], Rp);
@@ -1053,6 +1058,7 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
       g.offb = P.offb[l - 1]; g.kto = P.kta[l];
       g.o_h = P.Ah[l]; g.o_l = P.Al[l]; g.o_d = P.dA[l]; g.o_r = P.Aref[l];
       g.t_h = P.AhT[l]; g.t_l = P.AlT[l]; g.t_d = P.dAT[l]; g.t_r = nullptr;
+      g.maskbits = P.maskbits[l];
       launch_mm5<EPI_FWD_HIDDEN>(c, g, M);
     } else {
       g.c1 = P.ZL; g.c2 = P.dZL;
@@ -1122,7 +1128,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
       g.offb = P.offb[q - 1]; g.kto = P.kta[q];
       g.o_h = P.Gh[q]; g.o_l = P.Gl[q]; g.o_d = P.dG[q]; g.o_r = P.Gref[q];     // null for q = 1
       g.t_h = P.GhT[q]; g.t_l = P.GlT[q]; g.t_d = P.dGT[q]; g.t_r = P.GrefT[q];
-      g.m_on = P.Ah[q]; g.m_onref = P.Aref[q];
+      g.maskbits = P.maskbits[q];
       g.dbpart = P.dbpart; g.ddbpart = P.ddbpart;
       launch_mm5<EPI_DA>(c, g, M);
       hipLaunchKernelGGL(k_bias_finish, dim3((din + 255) / 256, M), dim3(kBlock), 0, st, s, P.dbpart, P.ddbpart, 2 * P.RT, din,
