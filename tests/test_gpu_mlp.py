@@ -24,6 +24,9 @@ def _case(cfg):
     configs.CFG5.scaled(name="mlp3_tiny", layer_dims=(24, 16, 16, 10), M=3, N_m=60, B=6, K=40, D=6, alpha=0.002),
     configs.CFG4.scaled(name="mlp2_ragged", layer_dims=(150, 133, 10), M=5, N_m=300, B=70, K=30, D=8),
     configs.CFG5.scaled(name="mlp3_ragged", layer_dims=(200, 136, 72, 7), M=4, N_m=300, B=130, K=30, D=8),
+    # more tiles than CUs in every contraction shape: workgroups work through several tiles, the
+    # last of them overhanging (1100 = 8 x 128 + 76 columns, 200 = 6 x 32 + 8 contraction indices)
+    configs.CFG5.scaled(name="mlp3_many_tiles", layer_dims=(200, 1100, 136, 10), M=40, N_m=200, B=128, K=4, D=8),
 ], ids=lambda c: c.name)
 def test_first_step_gradients_match_oracle(cfg):
     """Step 0: every worker uploads, so the stored gradients are the fresh gradients at
@@ -76,4 +79,21 @@ def test_reduced_protocol(cfg):
     assert 0.02 < tr["mask"][free].mean() < 0.98, "the case must mix rule-driven uploads and skips"
     # the delta-form left-hand side keeps bf16-level relative accuracy
     assert stats["lhs_rel_median"] < 1e-2 and stats["lhs_rel_p99"] < 0.2
+    assert stats["own_disagreements"] <= max(2, 0.03 * tr["mask"].size)
+
+
+@pytest.mark.parametrize("cfg", [
+    configs.CFG5.scaled(name="mlp3_many_tiles_cada1", layer_dims=(200, 1100, 136, 10), M=40, N_m=200, B=128, K=6, D=4, c=50.0),
+    configs.CFG5.scaled(name="mlp3_many_tiles_cada2", layer_dims=(200, 1100, 136, 10), M=40, N_m=200, B=128, K=6, D=4, c=50.0,
+                        rule=configs.RULE_CADA2),
+], ids=lambda c: c.name)
+def test_many_tiles_per_workgroup(cfg):
+    """Several tiles per workgroup in every contraction shape, over steps with stored innovations
+    (CADA1) and per-worker reference points (CADA2), a snapshot refresh and forced uploads."""
+    prob, dev, sched = _case(cfg)
+    stats, o, tr, rep = check_protocol(cfg, prob, dev, sched, BF16_TOL, lhs_rtol=None, own_mask_exact=False, free_margin=None)
+    big = tr["lhs"] > 1e-9 * tr["lhs"].max()
+    rel = np.abs(rep["trace_lhs"] - tr["lhs"])[big] / tr["lhs"][big]
+    print(cfg.name, stats, "lhs rel median %.2e max %.2e" % (float(np.median(rel)), float(rel.max())))
+    assert float(np.median(rel)) < 1e-2 and float(np.quantile(rel, 0.99)) < 0.2
     assert stats["own_disagreements"] <= max(2, 0.03 * tr["mask"].size)
