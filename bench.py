@@ -63,6 +63,47 @@ def stored_traffic(workload: str):
         return None
 
 
+def bench_replicas(args, cfg, dev) -> int:
+    """R independent runs of a small logistic workload in one launch per call."""
+    import json as _json
+    import numpy as np
+    import torch
+    from cada_synth import generators
+    from paper_2012_15469_amd.binding import Cada
+    if cfg.model != "logreg" or cfg.p >= 8192:
+        print("--replicas serves the small logistic workloads (1 and 2)", file=sys.stderr)
+        return 2
+    R, K, W = args.replicas, args.steps, args.warmup
+    engines, scheds = [], []
+    for r in range(R):
+        c = cfg.scaled(seed=cfg.seed + 17 * r)
+        prob = generators.make_problem(c)
+        X, y = torch.from_numpy(prob.X).to(dev), torch.from_numpy(prob.y).to(dev)
+        engines.append(Cada.from_config(c, X, y, torch.from_numpy(prob.theta0).to(dev), whole_steps=True))
+        scheds.append(torch.from_numpy(generators.make_schedule(c, W + K)).to(dev))
+    Cada.run_replicas(engines, [s[:W].contiguous() for s in scheds])
+    timed = [s[W:].contiguous() for s in scheds]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    Cada.run_replicas(engines, timed)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    uploads = 0
+    for e in engines:
+        st = e.state()
+        torch.cuda.synchronize()
+        assert int(st["error_flags"].item()) == 0 and bool(torch.isfinite(st["theta"]).all())
+        uploads += int(st["uploads_total"].item())
+    out = {"metric": "worker-iterations/sec (grads+CADA rule+AMSGrad)", "value": R * cfg.M * K / dt, "unit": "worker-iterations/s",
+           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": 1e3 * dt / K, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "%s x %d independent runs in one launch" % (cfg.name, R), "replicas": R, "M": cfg.M, "p": cfg.p,
+                      "B": cfg.B, "N_m": cfg.N_m, "rule": "CADA%d" % cfg.rule, "D": cfg.D, "d_max": cfg.d_max, "c": cfg.c,
+                      "uploads_per_worker_step": uploads / float(R * cfg.M * (W + K))}}
+    print(_json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +111,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the HBM-bound logistic workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replicas", type=int, default=1,
+                    help="workloads 1-2 only: R independent runs (seeds seed, seed+17, ...) advanced side by side in one "
+                         "launch per call (cada_run_replicas); value counts the worker-iterations of all of them")
     ap.add_argument("--plain-launch", action="store_true",
                     help="launch the single-pass kernel without the cooperative-launch API (rocprofv3 on this "
                          "image crashes at exit after tracing a cooperative dispatch); same grid, same kernel")
@@ -92,6 +136,8 @@ def main() -> int:
         os.environ["CADA_FUSED_PLAIN_LAUNCH"] = "1"
     cfg = configs.ALL[args.config]
     dev = torch.device("cuda:0")
+    if args.replicas > 1:
+        return bench_replicas(args, cfg, dev)
     K, W = args.steps, args.warmup
     t0 = time.time()
     prob = generators.make_problem(cfg)

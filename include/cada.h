@@ -97,6 +97,9 @@ typedef struct cada_config {
   int64_t alpha_K0;          /* 0: constant stepsize alpha; K0 > 0: alpha_k = alpha K0/(k + K0), the
                                 decaying stepsize 2/(mu (k + K0)) of Theorem 2 with alpha = 2/(mu K0) */
   int64_t trace_steps;       /* steps of per-step trace to keep (0 = none) */
+  int32_t whole_steps;       /* LOGREG: 0 = the library picks the kernels; 1 = run whole iterations in one
+                                launch (one workgroup per worker) whenever the shape allows it, also where
+                                separate kernels would be faster for one run: cada_run_replicas needs it */
   void *workspace;           /* DEVICE, 256-byte aligned, caller-owned */
   size_t workspace_bytes;
   void *stream;              /* hipStream_t; NULL = the default stream */
@@ -145,6 +148,18 @@ int cada_step(cada_ctx *ctx, const int32_t *idx, const uint8_t *replay);
 /* n_steps iterations back to back: idx_sched DEVICE int32 [n_steps, M, B],
  * replay_sched DEVICE uint8 [n_steps, M] or NULL. */
 int cada_run(cada_ctx *ctx, const int32_t *idx_sched, const uint8_t *replay_sched, int64_t n_steps);
+
+/* Independent runs side by side (the experiments of Section 5 average several Monte-Carlo runs):
+ * the n_replicas contexts, all with the same M, p, B and rule, initialised with whole_steps = 1 on
+ * the same stream, advance n_steps iterations each in ONE launch (one workgroup per worker and
+ * replica), with their own data, iterates, schedules and decisions.  ctxs, idx_scheds,
+ * replay_scheds: HOST arrays of n_replicas entries; idx_scheds[r] DEVICE int32 [n_steps, M, B],
+ * replay_scheds NULL or replay_scheds[r] DEVICE uint8 [n_steps, M] or NULL.  At most
+ * CADA_MAX_REPLICAS contexts and n_replicas * M workgroups no more than the device's CUs; each
+ * context ends exactly where n_steps calls of cada_step would have left it. */
+#define CADA_MAX_REPLICAS 16
+int cada_run_replicas(cada_ctx *const *ctxs, int32_t n_replicas, const int32_t *const *idx_scheds,
+                      const uint8_t *const *replay_scheds, int64_t n_steps);
 
 /* Fills *out with device pointers and host counters.  Does not synchronise:
  * read the device memory after synchronising the stream. */

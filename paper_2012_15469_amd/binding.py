@@ -34,6 +34,7 @@ class cada_config(C.Structure):
                 ("alpha", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
                 ("lambda_l2", C.c_double), ("c", C.c_double), ("d_max", C.c_int32), ("D", C.c_int32),
                 ("rule", C.c_int32), ("gemm_dtype", C.c_int32), ("server", C.c_int32), ("alpha_K0", C.c_int64), ("trace_steps", C.c_int64),
+                ("whole_steps", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
@@ -52,6 +53,8 @@ _lib.cada_step.restype = C.c_int
 _lib.cada_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.cada_run.restype = C.c_int
 _lib.cada_run.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
+_lib.cada_run_replicas.restype = C.c_int
+_lib.cada_run_replicas.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int64]
 _lib.cada_get_state.restype = C.c_int
 _lib.cada_get_state.argtypes = [C.c_void_p, C.POINTER(cada_state)]
 _lib.cada_copy_stored_gradients.restype = C.c_int
@@ -157,6 +160,15 @@ def cada_profile_end(ctx: int) -> dict:
     return out
 
 
+def cada_run_replicas(ctxs: Sequence[int], idx_sched_ptrs: Sequence[int], replay_sched_ptrs: Optional[Sequence[Optional[int]]],
+                      n_steps: int):
+    n = len(ctxs)
+    a_ctx = (C.c_void_p * n)(*ctxs)
+    a_idx = (C.c_void_p * n)(*idx_sched_ptrs)
+    a_rep = None if replay_sched_ptrs is None else (C.c_void_p * n)(*replay_sched_ptrs)
+    _check(_lib.cada_run_replicas(a_ctx, n, a_idx, a_rep, n_steps))
+
+
 def cada_destroy(ctx: int):
     _lib.cada_destroy(ctx)
 
@@ -168,7 +180,7 @@ class Cada:
                  X: torch.Tensor, y: torch.Tensor, theta0: torch.Tensor, rule: int, D: int, d_max: int,
                  c: float, alpha: float, beta1: float, beta2: float, eps: float, lam: float = 0.0,
                  gemm_dtype: str = "fp32", trace_steps: int = 0, stream: Optional[torch.cuda.Stream] = None,
-                 server: int = 0, alpha_K0: int = 0):
+                 server: int = 0, alpha_K0: int = 0, whole_steps: bool = False):
         assert X.is_cuda and y.is_cuda and theta0.is_cuda
         assert X.dtype == torch.float32 and X.is_contiguous() and theta0.dtype == torch.float32
         assert y.dtype == (torch.float32 if model == "logreg" else torch.int32) and y.is_contiguous()
@@ -190,6 +202,7 @@ class Cada:
         cfg.server = server
         cfg.alpha_K0 = alpha_K0
         cfg.trace_steps = trace_steps
+        cfg.whole_steps = 1 if whole_steps else 0
         cfg.stream = self.stream.cuda_stream
         nbytes = cada_workspace_bytes(cfg)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=X.device)
@@ -224,6 +237,22 @@ class Cada:
             assert replay_sched.dtype == torch.uint8 and replay_sched.is_contiguous() and replay_sched.numel() == n * self.M
         cada_run(self.ctx, idx_sched.data_ptr(), None if replay_sched is None else replay_sched.data_ptr(), n)
         self.k += n
+
+    @staticmethod
+    def run_replicas(engines: Sequence["Cada"], idx_scheds: Sequence[torch.Tensor],
+                     replay_scheds: Optional[Sequence[Optional[torch.Tensor]]] = None):
+        """Independent runs (same shapes, created with whole_steps=True) advanced together in one launch."""
+        n = idx_scheds[0].shape[0]
+        for e, s in zip(engines, idx_scheds):
+            assert s.dtype == torch.int32 and s.is_cuda and s.is_contiguous() and s.numel() == n * e.M * e.B
+        reps = None
+        if replay_scheds is not None:
+            for e, r in zip(engines, replay_scheds):
+                assert r is None or (r.dtype == torch.uint8 and r.is_contiguous() and r.numel() == n * e.M)
+            reps = [None if r is None else r.data_ptr() for r in replay_scheds]
+        cada_run_replicas([e.ctx for e in engines], [s.data_ptr() for s in idx_scheds], reps, n)
+        for e in engines:
+            e.k += n
 
     def _view(self, ptr: int, n: int, dtype: torch.dtype) -> torch.Tensor:
         off = ptr - self.workspace.data_ptr()

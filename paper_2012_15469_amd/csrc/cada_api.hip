@@ -145,15 +145,18 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   float *zpart = nullptr;
   unsigned long long *post = nullptr;
   uint32_t *small_bar = nullptr;
+  unsigned char *small_args = nullptr;
   if (cfg->model == CADA_MODEL_LOGREG) {
     zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
     post = w.take<unsigned long long>(kFusedPostWords);
     small_bar = w.take<uint32_t>(64);
+    small_args = w.take<unsigned char>(kSmallArgsBytes);
   }
   if (!s) return;
   c->fused_post = post;
   c->eval_part = eval_part; c->eval_acc = eval_acc; c->eval_idx = eval_idx;
   c->small_bar = small_bar;
+  c->small_args = small_args;
   s->theta = theta; s->theta_lo = theta_lo; s->hist_lo = hist_lo; s->snap_lo = snap_lo; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
   s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl;
   s->tau = tau; s->sel = sel; s->lhs = lhs; s->lhs_part = lhs_part; s->mask = mask;
@@ -265,7 +268,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   s.eps = (float)cfg->eps; s.lam = (float)cfg->lambda_l2; s.c = cfg->c;
   if (cfg->model == CADA_MODEL_LOGREG) {
     if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = 4 * c->fused_Q;
-    else if (small_plan(c, cfg->p, cfg->B, cfg->M)) s.n_ring_part = cfg->M;
+    else if (small_plan(c, cfg->p, cfg->B, cfg->M, cfg->whole_steps != 0)) s.n_ring_part = cfg->M;
     if (c->small) {
       c->n_phases = 1; c->phase_names[0] = "logreg_whole_steps";
     } else if (c->fused) {
@@ -347,6 +350,31 @@ int cada_run(cada_ctx *ctx, const int32_t *idx_sched, const uint8_t *replay_sche
     if (rc != CADA_OK) return rc;
   }
   return CADA_OK;
+}
+
+int cada_run_replicas(cada_ctx *const *ctxs, int32_t n_replicas, const int32_t *const *idx_scheds,
+                      const uint8_t *const *replay_scheds, int64_t n_steps) {
+  if (!ctxs || !idx_scheds) { set_error("ctxs/idx_scheds is NULL"); return CADA_EINVAL; }
+  if (n_replicas < 1 || n_replicas > CADA_MAX_REPLICAS) { set_error("n_replicas must be 1..%d", CADA_MAX_REPLICAS); return CADA_EINVAL; }
+  if (n_steps < 0) { set_error("n_steps must be >= 0"); return CADA_EINVAL; }
+  if (n_steps == 0) return CADA_OK;
+  Ctx *cs[CADA_MAX_REPLICAS];
+  for (int r = 0; r < n_replicas; ++r) {
+    if (!ctxs[r] || !idx_scheds[r]) { set_error("replica %d: ctx or idx_sched is NULL", r); return CADA_EINVAL; }
+    cs[r] = &ctxs[r]->c;
+    for (int q = 0; q < r; ++q)
+      if (cs[q] == cs[r]) { set_error("replica %d: the same context twice", r); return CADA_EINVAL; }
+    if (!cs[r]->small) { set_error("replica %d does not run whole iterations in one launch (initialise a logistic workload with whole_steps = 1)", r); return CADA_EUNSUPPORTED; }
+    const DevState &a = cs[0]->s, &b = cs[r]->s;
+    if (a.M != b.M || a.p != b.p || a.B != b.B || a.rule != b.rule || cs[0]->stream != cs[r]->stream) {
+      set_error("replica %d differs from replica 0 in M, p, B, rule or stream", r);
+      return CADA_EINVAL;
+    }
+  }
+  const int rc = small_steps_replicas(cs, n_replicas, idx_scheds, replay_scheds, n_steps);
+  if (rc == CADA_OK)
+    for (int r = 0; r < n_replicas; ++r) cs[r]->k += n_steps;
+  return rc;
 }
 
 int cada_get_state(cada_ctx *ctx, cada_state *out) {

@@ -117,6 +117,7 @@ struct Ctx {
   size_t small_lds;
   uint32_t *small_bar;       // grid barrier counter in the workspace
   uint32_t small_seq;        // its value after everything enqueued so far
+  void *small_args;          // room in the workspace for this context's arguments of a replica launch
   // full-data evaluation scratch (cada_eval)
   double *eval_part;         // [M][kEvalBlocks][2] per-block sums of (loss, correct)
   double *eval_acc;          // [M][2]
@@ -136,8 +137,10 @@ void prof_mark(Ctx *c);
 int logreg_gradients(Ctx *c, const int32_t *idx);
 bool fused_plan(Ctx *c, int64_t p, int B, int M);
 int logreg_gradients_fused(Ctx *c, const int32_t *idx);
-bool small_plan(Ctx *c, int64_t p, int B, int M);
 int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps);
+int small_steps_replicas(Ctx *const *cs, int n, const int32_t *const *idx, const uint8_t *const *replay, int64_t n_steps);
+constexpr size_t kSmallArgsBytes = 1024;    // >= sizeof(SmallArgs), checked where it is defined
+bool small_plan(Ctx *c, int64_t p, int B, int M, bool prefer);
 constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgroups x 4 buffers x 16 values
 // S1+S2 for the MLP.
 int mlp_gradients(Ctx *c, const int32_t *idx);

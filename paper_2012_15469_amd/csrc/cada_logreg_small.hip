@@ -28,6 +28,15 @@ struct SmallArgs {
   uint32_t bar_base;         // its value when this launch starts
   uint32_t spin_limit;
 };
+static_assert(sizeof(SmallArgs) <= kSmallArgsBytes, "room kept in the workspace for a replica launch");
+
+// One launch serves one run (its arguments by value) or several independent runs (blockIdx.y
+// picks the run; each run's arguments lie in its own workspace).
+struct SmallLaunch {
+  SmallArgs one;
+  const SmallArgs *rep[CADA_MAX_REPLICAS];
+  int n_rep;                 // 0: `one`
+};
 
 __device__ __forceinline__ float sigmoid_s(float a) { return 1.0f / (1.0f + expf(-a)); }
 
@@ -51,8 +60,9 @@ __device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target
 // grid = M workgroups of kBlock threads; dynamic LDS: theta, d (2 p floats), r, dr, row offsets
 // (B each) and the worker's whole minibatch (B p floats): the rows are fetched once, with every
 // load independent of the others, and both passes over them run from LDS
-__global__ __launch_bounds__(kBlock) void k_small(const SmallArgs a) {
+__global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   extern __shared__ __align__(16) unsigned char small_smem[];
+  const SmallArgs a = launch.n_rep ? *launch.rep[blockIdx.y] : launch.one;
   DevState s = a.s;
   const int p = (int)s.p, B = s.B, M = s.M;
   float *th_s = reinterpret_cast<float *>(small_smem);     // [p] theta (hi part + lo part rounded once)
@@ -227,7 +237,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallArgs a) {
 }
 
 // Whether the multi-step kernel serves this configuration; sets the ring-partial count it uses.
-bool small_plan(Ctx *c, int64_t p, int B, int M) {
+bool small_plan(Ctx *c, int64_t p, int B, int M, bool prefer) {
   c->small = 0;
   const char *on = getenv("CADA_SMALL");
   if (on && atoi(on) == 0) return false;
@@ -236,7 +246,7 @@ bool small_plan(Ctx *c, int64_t p, int B, int M) {
   // M = 20, B = 32, p = 784 (20 workgroups cannot hide the latency of their dependent loads, and
   // each barrier invalidates the XCD's L2): only the tiny problems take this path unless asked to.
   const char *force = getenv("CADA_SMALL");
-  if (!(force && atoi(force) == 1) && (int64_t)M * B * p > 32768) return false;
+  if (!prefer && !(force && atoi(force) == 1) && (int64_t)M * B * p > 32768) return false;
   int dev = 0, coop = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
@@ -252,7 +262,7 @@ bool small_plan(Ctx *c, int64_t p, int B, int M) {
   return true;
 }
 
-int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps) {
+static SmallArgs small_args_of(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps) {
   SmallArgs a;
   a.s = c->s;
   a.s.k = c->k;
@@ -263,7 +273,42 @@ int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_ste
   a.bar_base = c->small_seq;
   a.spin_limit = 4000000u;
   c->small_seq += (uint32_t)(2 * n_steps * c->s.M);
-  void *args[] = {&a};
+  return a;
+}
+
+int small_steps_replicas(Ctx *const *cs, int n, const int32_t *const *idx, const uint8_t *const *replay, int64_t n_steps) {
+  Ctx *c0 = cs[0];
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    set_error("cannot query the device");
+    return CADA_EHIP;
+  }
+  if ((int64_t)n * c0->s.M > cus) { set_error("n_replicas x M = %lld workgroups exceed the %d CUs that must hold them at once", (long long)n * c0->s.M, cus); return CADA_EINVAL; }
+  SmallLaunch l{};
+  l.n_rep = n;
+  for (int r = 0; r < n; ++r) {
+    // (a pageable source: the copy is staged before the call returns)
+    const SmallArgs a = small_args_of(cs[r], idx[r], replay ? replay[r] : nullptr, n_steps);
+    const hipError_t e = hipMemcpyAsync(cs[r]->small_args, &a, sizeof(a), hipMemcpyHostToDevice, c0->stream);
+    if (e != hipSuccess) { set_error("copy of replica arguments failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
+    l.rep[r] = static_cast<const SmallArgs *>(cs[r]->small_args);
+  }
+  void *args[] = {&l};
+  prof_mark(c0);
+  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_small), dim3((unsigned)c0->s.M, (unsigned)n), dim3(kBlock), args,
+                                                  (unsigned)c0->small_lds, c0->stream);
+  prof_mark(c0);
+  if (e != hipSuccess) {
+    set_error("replica launch failed: %s", hipGetErrorString(e));
+    return CADA_EHIP;
+  }
+  return CADA_OK;
+}
+
+int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps) {
+  SmallLaunch l{};
+  l.one = small_args_of(c, idx, replay, n_steps);
+  void *args[] = {&l};
   prof_mark(c);
   const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_small), dim3((unsigned)c->s.M), dim3(kBlock), args,
                                                   (unsigned)c->small_lds, c->stream);
