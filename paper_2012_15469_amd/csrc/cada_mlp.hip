@@ -531,6 +531,115 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // the movers' last barrier
 }
 
+// The same products for an output of at most 32 columns (the last layer: C <= 32 classes).  A
+// 128 x 128 tile would leave nine tenths of its MFMAs and of its workgroups idle and the launch
+// would run on a few CUs (32 tiles for the logits of 16 workers).  Here a workgroup computes
+// 32 rows x 32 columns; its eight wavefronts split the tile steps (wavefront w takes steps w,
+// w + 8, ...), read their fragments straight from the chunks in global memory (a fragment is
+// 16 consecutive bytes of a chunk row) and add their partial accumulators up through LDS in a
+// fixed order.  grid (ceil(M / 32), workers), 512 threads, 64 KB of dynamic LDS.
+// EPI_STORE2: logits; EPI_DW: weight gradient, innovation, its squared norm (slot lhs_slot0 + row band).
+template <int EPI, int NA, int NB, bool HAS_D>
+__global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  float *red = reinterpret_cast<float *>(smem_raw);                  // [8 wavefronts][2 accumulators][16][64]
+  const DevState &s = g.s;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int m0 = blockIdx.x * 32, wk = blockIdx.y;
+  const int nk = (g.K + BK - 1) / BK;
+  // this lane's fragment in a chunk: row lane % 32 of the band (A) or of the first 32 rows (B), piece lane / 32 (+ 2)
+  const int64_t offa = (((int64_t)(m0 >> 7) * g.A.kt[0]) << 12) + (((m0 & 127) + (lane & 31)) << 5) + ((lane >> 5) << 3);
+  const int64_t offb = ((lane & 31) << 5) + ((lane >> 5) << 3);
+  const bf16_t *pa[NA], *pb[NB];
+#pragma unroll
+  for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + offa;
+#pragma unroll
+  for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl] + offb;
+  f32x16 acc1, acc2;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { acc1[r] = 0.f; acc2[r] = 0.f; }
+  for (int kc = w; kc < nk; kc += 8) {
+    u32x4 fa[2][NA], fb[2][NB];          // (kept as integer vectors: arrays of them stay in registers)
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int64_t o = ((int64_t)kc << 12) + half * 16;
+#pragma unroll
+      for (int sl = 0; sl < NA; ++sl) fa[half][sl] = *reinterpret_cast<const u32x4 *>(pa[sl] + o);
+#pragma unroll
+      for (int sl = 0; sl < NB; ++sl) fb[half][sl] = *reinterpret_cast<const u32x4 *>(pb[sl] + o);
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      // (the roles of the tensors follow from their number: hi, lo, [difference, [reference]] on the A
+      // side, hi, lo, [reference,] difference on the B side; the host checks it)
+      auto fr = [&](const u32x4 &v) __attribute__((always_inline)) { return __builtin_bit_cast(bf16x8, v); };
+      const bf16x8 ah = fr(fa[half][0]), al = fr(fa[half][1]), bh = fr(fb[half][0]), bl = fr(fb[half][1]), bd = fr(fb[half][NB - 1]);
+      const bf16x8 ar = NA == 4 ? fr(fa[half][NA - 1]) : ah;
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc1, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc1, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc1, 0, 0, 0);
+      if constexpr (HAS_D) {
+        const bf16x8 ad = fr(fa[half][2]), bx = NB == 4 ? fr(fb[half][2]) : bh;
+        acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, bx, acc2, 0, 0, 0);
+      }
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ar, bd, acc2, 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    red[((w * 2 + 0) * 16 + r) * 64 + lane] = acc1[r];
+    red[((w * 2 + 1) * 16 + r) * 64 + lane] = acc2[r];
+  }
+  __syncthreads();
+  // 2 x 16 x 64 values, four per thread, each the sum of the eight partial results in wavefront order
+  float *gf = nullptr, *ivf = nullptr;
+  const float *ivs = nullptr;
+  const bool cada1 = s.rule == CADA_RULE_CADA1;
+  if constexpr (EPI == EPI_DW) {
+    gf = fresh_grad(s, wk) + g.offW;
+    if (cada1) {
+      const int cur = s.sel[wk];
+      ivf = s.dtl + ((int64_t)(1 - cur) * s.M + wk) * s.p + g.offW;
+      ivs = s.dtl + ((int64_t)cur * s.M + wk) * s.p + g.offW;
+    }
+  }
+  float sq = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int e = t + q * 2 * kBlock;                 // (accumulator, r, lane)
+    const int a = e >> 10, r = (e >> 6) & 15, ln = e & 63;
+    float v = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 8; ++ww) v += red[((ww * 2 + a) * 16 + r) * 64 + ln];
+    const int row = m0 + 8 * (r >> 2) + 4 * (ln >> 5) + (r & 3), col = ln & 31;
+    if (row < g.M && col < g.N) {
+      if constexpr (EPI == EPI_STORE2) {
+        const int64_t o = ((int64_t)wk * g.Bp + row) * g.N + col;
+        if (a == 0) g.c1[o] = v; else g.c2[o] = v;
+      } else {
+        const int64_t o = (int64_t)row * g.N + col;
+        if (a == 0) gf[o] = v;
+        else {
+          if (cada1) { ivf[o] = v; v -= ivs[o]; }
+          sq = fmaf(v, v, sq);
+        }
+      }
+    }
+  }
+  if constexpr (EPI == EPI_DW) {
+    const float ws = wave_sum(sq);
+    __syncthreads();
+    if (lane == 0) red[w] = ws;
+    __syncthreads();
+    if (t == 0) {
+      float tot = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < 8; ++ww) tot += red[ww];
+      s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + blockIdx.x] = tot;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // plan
 // ------------------------------------------------------------------------------------------
@@ -966,9 +1075,32 @@ template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const 
   hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D>), grid, dim3(2 * kBlock), mm5_lds_bytes(EPI), c->stream, g);
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
+template <int EPI, int NA, int NB, bool HAS_D> void launch_skinny_as(Ctx *c, const Mm5Args &g) {
+  static bool allowed = false;      // (the default limit of dynamic LDS is exactly what the kernel needs; raised anyway)
+  if (!allowed) { (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize, 65536); allowed = true; }
+  hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(2 * kBlock), 65536, c->stream, g);
+}
 template <int EPI> void launch_mm5(Ctx *c, Mm5Args &g, int workers) {
   g.workers = workers;
   const bool has_d = g.a_d >= 0;
+  if constexpr (EPI == EPI_STORE2 || EPI == EPI_DW) {
+    if (g.N <= 32) {            // at most 32 output columns (the last layer)
+      for (int i = 1; i < g.A.n; ++i)
+        if (g.A.kt[i] != g.A.kt[0]) { set_error("internal: A tensors with different chunk counts"); return; }
+      if (g.a_h != 0 || g.a_l != 1 || (has_d && g.a_d != 2) || g.a_r != (g.A.n == 4 ? 3 : 0) || g.b_h != 0 || g.b_l != 1 ||
+          (has_d && g.b_x != (g.B.n == 4 ? 2 : 0)) || g.b_d != g.B.n - 1) {
+        set_error("internal: unexpected tensor roles");
+        return;
+      }
+      if (EPI == EPI_DW) {
+        if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_skinny_as<EPI, 2, 3, false>(c, g);
+        if (has_d && g.A.n == 3 && g.B.n == 4) return launch_skinny_as<EPI, 3, 4, true>(c, g);
+      } else {
+        if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_skinny_as<EPI, 2, 3, false>(c, g);
+        if (has_d && g.A.n == 4 && g.B.n == 3) return launch_skinny_as<EPI, 4, 3, true>(c, g);
+      }
+    }
+  }
   // every tensor must hold the chunks the tile steps walk through
   for (int i = 0; i < g.A.n; ++i)
     if (g.A.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: A tensor with fewer chunks than tile steps"); return; }
