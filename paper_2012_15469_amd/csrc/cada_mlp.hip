@@ -82,10 +82,11 @@ static inline int tiles128(int64_t x) { return (int)((x + 127) / 128); }
 static inline int chunks32(int64_t x) { return (int)((x + 31) / 32); }
 
 // In LDS a chunk keeps its 8 KB (row r at byte 64 r, no padding); the four 16-byte pieces of a row
-// are stored in the order q ^ ((r >> 1) & 3), so that the 16-byte fragment reads of eight
-// consecutive rows fall into eight different groups of four banks.
+// are stored in the order q ^ ((r >> 2) & 3).  A fragment read takes one piece of each of 32
+// consecutive rows; rows 4 apart lie 256 bytes = one pass over the 64 banks apart, and with this
+// order the same piece of 16 consecutive rows covers every bank once.
 __device__ __forceinline__ int lds_piece(int piece) {   // piece = 4 row + q  ->  position (16-byte units)
-  return piece ^ ((piece >> 3) & 3);
+  return piece ^ ((piece >> 4) & 3);
 }
 
 enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
