@@ -118,6 +118,7 @@ struct Mm5Args {
   int b_h, b_l, b_x, b_d;       // role -> slot of B
   int M, N, K;                  // extents of the tile index spaces and of the contraction
   int workers;
+  const int32_t *rep;           // optional: the B side of worker m is read at worker rep[m]'s offset (shared reference points)
   int Bp;                       // padded rows per worker (multiple of 128)
   int64_t ktT;                  // chunks per tile of the transposed tensors = M_workers * Bp / 32
   // EPI_FWD_HIDDEN / EPI_DA: bias offset, row-major and transposed outputs
@@ -202,8 +203,9 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
       const int bx = tix % gx, by = (tix / gx) % gy, bz = tix / (gx * gy);
 #pragma unroll
       for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)bz * g.A.bstride[sl] + (((int64_t)by * g.A.kt[sl]) << 12);
+      const int bzb = g.rep ? g.rep[bz] : bz;
 #pragma unroll
-      for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)bz * g.B.bstride[sl] + (((int64_t)bx * g.B.kt[sl]) << 12);
+      for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)bzb * g.B.bstride[sl] + (((int64_t)bx * g.B.kt[sl]) << 12);
     };
     // next tile step; past the last one the cursor stays (those loads re-read the last chunk into slots nobody reads)
     auto next_step = [&]() __attribute__((always_inline)) {
@@ -555,7 +557,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
 #pragma unroll
   for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + offa;
 #pragma unroll
-  for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl] + offb;
+  for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)(g.rep ? g.rep[wk] : wk) * g.B.bstride[sl] + offb;
   f32x16 acc1, acc2;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { acc1[r] = 0.f; acc2[r] = 0.f; }
@@ -668,6 +670,7 @@ struct MlpPlan {
   bf16_t *GhT[CADA_MAX_LAYERS + 1], *GlT[CADA_MAX_LAYERS + 1], *dGT[CADA_MAX_LAYERS + 1], *GrefT[CADA_MAX_LAYERS + 1];   // layer l, (unit, row)
   float *ZL, *dZL;                                        // logits [Rp][C]
   uint64_t *maskbits[CADA_MAX_LAYERS];                    // hidden l: ReLU mask bits per tile and lane
+  int32_t *rep;                                           // CADA2: first worker with the same reference point [M]
   float *dbpart, *ddbpart;                                // [M][2 RT][max hidden width]
 };
 
@@ -718,6 +721,7 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.XGh = w.take<bf16_t>(tm_elems(Rp, P.d[0]));
   P.XGl = w.take<bf16_t>(tm_elems(Rp, P.d[0]));
   P.grow = w.take<int64_t>(Rp);
+  P.rep = w.take<int32_t>((size_t)cfg->M);
   P.WTh = w.take<bf16_t>((size_t)wt); P.WTl = w.take<bf16_t>((size_t)wt); P.dWT = w.take<bf16_t>((size_t)wt * P.nW);
   P.WNh = w.take<bf16_t>((size_t)wn + 8); P.WNl = w.take<bf16_t>((size_t)wn + 8); P.dWN = w.take<bf16_t>((size_t)wn * P.nW + 8);
   for (int l = 1; l < P.L; ++l) {
@@ -850,6 +854,19 @@ __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, c
   }
 }
 
+// CADA2: workers whose last upload happened at the same iteration share their reference point
+// theta^{k - tau}, hence the difference theta - theta_ref and its bf16 copies.  rep[m] = the first
+// worker with worker m's (clamped) tau.  One block.
+__global__ __launch_bounds__(kBlock) void k_same_reference(const DevState s, int32_t *rep) {
+  for (int m = threadIdx.x; m < s.M; m += kBlock) {
+    const int tm_ = min(s.tau[m], s.D);
+    int r = m;
+    for (int j = 0; j < m; ++j)
+      if (min(s.tau[j], s.D) == tm_) { r = j; break; }
+    rep[m] = r;
+  }
+}
+
 struct PrepArgs {
   DevState s;
   bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;   // already offset to this layer
@@ -857,6 +874,7 @@ struct PrepArgs {
   int din, dout;
   int64_t ktt, ktn;      // chunks32(din), chunks32(dout)
   int want_n;            // also write the [in][out] orientation (layers >= 2)
+  const int32_t *rep;    // worker m's difference is computed only if rep[m] == m
 };
 
 // bf16 copies of one layer's weights (hi, lo) and of its difference to each reference point,
@@ -871,6 +889,7 @@ __global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
   const int t = threadIdx.x;
   const bool is_w = blockIdx.z == 0;
   const int m = is_w ? 0 : blockIdx.z - 1;
+  if (!is_w && a.rep && a.rep[m] != m) return;      // another worker with the same reference point stands for this one
   const RefPtr ref = theta_ref(s, m, s.k);
   const int og = (t & 7) * 8;
 #pragma unroll
@@ -1158,9 +1177,11 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
   hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp);
   hipLaunchKernelGGL(k_gather_transpose, dim3((unsigned)((P.ldx + 63) / 64), (B + 63) / 64, M), dim3(kBlock), 0, st,
                      P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, P.kta[0], P.ktT);
+  const int32_t *rep = per_worker ? P.rep : nullptr;
+  if (per_worker) hipLaunchKernelGGL(k_same_reference, dim3(1), dim3(kBlock), 0, st, s, P.rep);
   for (int l = 1; l <= L; ++l) {
     PrepArgs pa;
-    pa.s = s;
+    pa.s = s; pa.rep = rep;
     pa.WTh = P.WTh + P.wt_off[l - 1]; pa.WTl = P.WTl + P.wt_off[l - 1]; pa.dWT = P.dWT + P.wt_off[l - 1];
     pa.WNh = P.WNh + P.wn_off[l - 1]; pa.WNl = P.WNl + P.wn_off[l - 1]; pa.dWN = P.dWN + P.wn_off[l - 1];
     pa.offW = P.offW[l - 1]; pa.wt_total = P.wt_total; pa.wn_total = P.wn_total;
@@ -1187,6 +1208,7 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
     side_add(g.B, P.WTh + P.wt_off[l - 1], ktt, 0); side_add(g.B, P.WTl + P.wt_off[l - 1], ktt, 0);
     side_add(g.B, P.dWT + P.wt_off[l - 1], ktt, dwt_stride);
     g.b_h = 0; g.b_l = 1; g.b_x = 0; g.b_d = 2;
+    g.rep = rep;
     if (l < L) {
       g.offb = P.offb[l - 1]; g.kto = P.kta[l];
       g.o_h = P.Ah[l]; g.o_l = P.Al[l]; g.o_d = P.dA[l]; g.o_r = P.Aref[l];
@@ -1257,6 +1279,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
       side_add(g.B, P.WNh + P.wn_off[l - 1], ktn, 0); side_add(g.B, P.WNl + P.wn_off[l - 1], ktn, 0);
       side_add(g.B, P.dWN + P.wn_off[l - 1], ktn, dwn_stride);
       g.b_h = 0; g.b_l = 1; g.b_x = 0; g.b_d = 2;
+      g.rep = per_worker ? P.rep : nullptr;
       const int q = l - 1;
       g.offb = P.offb[q - 1]; g.kto = P.kta[q];
       g.o_h = P.Gh[q]; g.o_l = P.Gl[q]; g.o_d = P.dG[q]; g.o_r = P.Gref[q];     // null for q = 1
