@@ -32,12 +32,13 @@
 // activation gradient).  For a 128 x 128 output tile of worker m it accumulates
 //     C1 = Ah Bh^T + Ah Bl^T + Al Bh^T          (evaluation at theta, split operands)
 //     C2 = Ad Bx^T + Ar Bd^T                    (difference to the reference evaluation)
-// from up to four A-side and four B-side bf16 tensors, all stored with the contraction index
-// contiguous, staged through LDS in 128 x 32 tiles, with v_mfma_f32_32x32x16_bf16 on four
+// from up to four A-side and four B-side bf16 tensors, all stored in chunks of 128 rows x 32
+// contraction indices, moved into LDS chunk by chunk, with v_mfma_f32_32x32x16_bf16 on four
 // wavefronts of 64 x 64.  The epilogues apply bias/ReLU/masks, split results into hi/lo,
 // write the tensors the later contractions need in both orientations, reduce bias gradients
 // and the squared norm of the innovation, so no float32 intermediate except the logits
-// round-trips through HBM.
+// round-trips through HBM.  k_skinny computes the same products for outputs of at most 32
+// columns (the last layer).
 #include <cstdlib>
 #include <new>
 
