@@ -70,7 +70,10 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   float *r_s = d_s + p;                                    // [B]
   float *dr_s = r_s + B;                                   // [B]
   long long *row_s = reinterpret_cast<long long *>(dr_s + B + ((2 * p + 2 * B) & 1));   // [B], 8-byte aligned
-  float *x_s = reinterpret_cast<float *>(row_s + B);       // [B][p] the minibatch
+  const size_t x_off = ((size_t)(reinterpret_cast<unsigned char *>(row_s + B) - small_smem) + 15) & ~(size_t)15;
+  float *x_s = reinterpret_cast<float *>(small_smem + x_off);        // [B][p] the minibatch, 16-byte aligned
+  // rows and columns are moved four floats at a time when every row starts on a 16-byte boundary
+  const bool v4 = (p & 3) == 0 && (reinterpret_cast<uintptr_t>(s.X) & 15) == 0;
   __shared__ float red[4];
   __shared__ double redd[kBlock];
   __shared__ float bcast[2];
@@ -98,30 +101,80 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
       row_s[b] = (base + r) * s.p;
     }
     __syncthreads();
-    for (int e = tid; e < B * p; e += kBlock) {
-      const int b = e / p, j = e - b * p;
-      x_s[e] = s.X[row_s[b] + j];
+    // the rows: wavefront w fetches rows w, w+4, ..., eight rows at a time so that eight loads per
+    // lane are in flight (no division per element; every load independent of the others)
+    constexpr int NW = kBlock / kWave, RB = 8;
+    for (int b0 = w; b0 < B; b0 += NW * RB) {
+      const float *src[RB];
+#pragma unroll
+      for (int q = 0; q < RB; ++q) src[q] = s.X + row_s[min(b0 + NW * q, B - 1)];      // (a row past the end repeats the last one and is dropped)
+      if (v4) {
+#pragma unroll 2
+        for (int j = lane * 4; j < p; j += 4 * kWave) {
+          float4 v[RB];
+#pragma unroll
+          for (int q = 0; q < RB; ++q) v[q] = *reinterpret_cast<const float4 *>(src[q] + j);
+#pragma unroll
+          for (int q = 0; q < RB; ++q)
+            if (b0 + NW * q < B) *reinterpret_cast<float4 *>(x_s + (b0 + NW * q) * p + j) = v[q];
+        }
+      } else {
+#pragma unroll 2
+        for (int j = lane; j < p; j += kWave) {
+          float v[RB];
+#pragma unroll
+          for (int q = 0; q < RB; ++q) v[q] = src[q][j];
+#pragma unroll
+          for (int q = 0; q < RB; ++q)
+            if (b0 + NW * q < B) x_s[(b0 + NW * q) * p + j] = v[q];
+        }
+      }
     }
     if (tid < B) r_s[tid] = static_cast<const float *>(s.y)[row_s[tid] / s.p];     // the labels, for now
     for (int b = kBlock + tid; b < B; b += kBlock) r_s[b] = static_cast<const float *>(s.y)[row_s[b] / s.p];
     __syncthreads();
-    // rows over the wavefronts: z = x.theta, dz = x.d, then the residual and its difference
-    for (int b = w; b < B; b += kBlock / kWave) {
-      const float *x = x_s + b * p;
-      float z = 0.f, dz = 0.f;
-      for (int j = lane; j < p; j += kWave) {
-        const float xv = x[j];
-        z = fmaf(xv, th_s[j], z);
-        dz = fmaf(xv, d_s[j], dz);
+    // rows over the wavefronts, four at a time (their eight reductions overlap): z = x.theta,
+    // dz = x.d, then the residual and its difference
+    for (int b0 = w; b0 < B; b0 += 4 * NW) {
+      const float *x[4];
+      float z[4] = {0.f, 0.f, 0.f, 0.f}, dz[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) x[q] = x_s + min(b0 + q * NW, B - 1) * p;      // (a row past the end repeats the last one and is dropped)
+      if (v4) {
+        for (int j = lane * 4; j < p; j += 4 * kWave) {
+          const float4 th = *reinterpret_cast<const float4 *>(th_s + j), dd = *reinterpret_cast<const float4 *>(d_s + j);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float4 xv = *reinterpret_cast<const float4 *>(x[q] + j);
+            z[q] = fmaf(xv.x, th.x, z[q]); z[q] = fmaf(xv.y, th.y, z[q]); z[q] = fmaf(xv.z, th.z, z[q]); z[q] = fmaf(xv.w, th.w, z[q]);
+            dz[q] = fmaf(xv.x, dd.x, dz[q]); dz[q] = fmaf(xv.y, dd.y, dz[q]); dz[q] = fmaf(xv.z, dd.z, dz[q]); dz[q] = fmaf(xv.w, dd.w, dz[q]);
+          }
+        }
+      } else {
+        for (int j = lane; j < p; j += kWave) {
+          const float th = th_s[j], dd = d_s[j];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float xv = x[q][j];
+            z[q] = fmaf(xv, th, z[q]);
+            dz[q] = fmaf(xv, dd, dz[q]);
+          }
+        }
       }
-      z = wave_sum(z);
-      dz = wave_sum(dz);
-      if (lane == 0) {
-        const float y = r_s[b];
-        const float aa = -y * z, bb = aa + y * dz;
-        const float sa = sigmoid_s(aa);
-        r_s[b] = -y * sa * invB;
-        dr_s[b] = y * sa * sigmoid_s(-bb) * expm1f(y * dz) * invB;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { z[q] += __shfl_xor(z[q], o, 64); dz[q] += __shfl_xor(dz[q], o, 64); }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int b = b0 + q * NW;
+        if (lane == 0 && b < B) {
+          const float y = r_s[b];
+          const float aa = -y * z[q], bb = aa + y * dz[q];
+          const float sa = sigmoid_s(aa);
+          r_s[b] = -y * sa * invB;
+          dr_s[b] = y * sa * sigmoid_s(-bb) * expm1f(y * dz[q]) * invB;
+        }
       }
     }
     __syncthreads();
@@ -130,6 +183,37 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     float *gf = s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p;
     const float *gs = s.gbuf + (int64_t)cur * mp + (int64_t)m * s.p;
     float sq = 0.f;
+    if (v4) {
+      for (int j = tid * 4; j < p; j += 4 * kBlock) {
+        float g[4] = {0.f, 0.f, 0.f, 0.f}, iv[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int b = 0; b < B; ++b) {
+          const float4 xv = *reinterpret_cast<const float4 *>(x_s + b * p + j);
+          const float rb = r_s[b], db = dr_s[b];
+          g[0] = fmaf(rb, xv.x, g[0]); g[1] = fmaf(rb, xv.y, g[1]); g[2] = fmaf(rb, xv.z, g[2]); g[3] = fmaf(rb, xv.w, g[3]);
+          iv[0] = fmaf(db, xv.x, iv[0]); iv[1] = fmaf(db, xv.y, iv[1]); iv[2] = fmaf(db, xv.z, iv[2]); iv[3] = fmaf(db, xv.w, iv[3]);
+        }
+        float st[4] = {0.f, 0.f, 0.f, 0.f};
+        const int64_t o = (int64_t)m * s.p + j;
+        if (s.rule == CADA_RULE_CADA1) {
+          const float4 t = *reinterpret_cast<const float4 *>(s.dtl + (int64_t)cur * mp + o);
+          st[0] = t.x; st[1] = t.y; st[2] = t.z; st[3] = t.w;
+        } else if (s.rule != CADA_RULE_CADA2) {
+          const float4 t = *reinterpret_cast<const float4 *>(gs + j);
+          st[0] = t.x; st[1] = t.y; st[2] = t.z; st[3] = t.w;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          g[q] = fmaf(s.lam, th_s[j + q], g[q]);
+          iv[q] = fmaf(s.lam, d_s[j + q], iv[q]);
+          float lhs_term = iv[q];
+          if (s.rule == CADA_RULE_CADA1) lhs_term = iv[q] - st[q];
+          else if (s.rule != CADA_RULE_CADA2) lhs_term = g[q] - st[q];          // condition (LAGrule): against the stored gradient
+          sq = fmaf(lhs_term, lhs_term, sq);
+        }
+        if (s.rule == CADA_RULE_CADA1) *reinterpret_cast<float4 *>(s.dtl + (int64_t)(1 - cur) * mp + o) = make_float4(iv[0], iv[1], iv[2], iv[3]);
+        *reinterpret_cast<float4 *>(gf + j) = make_float4(g[0], g[1], g[2], g[3]);
+      }
+    } else
     for (int j = tid; j < p; j += kBlock) {
       float g = 0.f, iv = 0.f;
       for (int b = 0; b < B; ++b) {
@@ -252,7 +336,7 @@ bool small_plan(Ctx *c, int64_t p, int B, int M, bool prefer) {
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return false;
   if (M > cus) return false;
-  c->small_lds = (size_t)(2 * p + 2 * B + 1) * sizeof(float) + (size_t)B * sizeof(long long) + (size_t)B * p * sizeof(float);
+  c->small_lds = (size_t)(2 * p + 2 * B + 1) * sizeof(float) + (size_t)B * sizeof(long long) + 16 + (size_t)B * p * sizeof(float);
   if (c->small_lds > 150 * 1024) return false;      // the minibatch of a worker must fit in LDS
   if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_small), hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->small_lds) != hipSuccess) {
     (void)hipGetLastError();
