@@ -504,6 +504,17 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
           for (int e = 0; e < 4 && colg + e < g.N; ++e) gf[(int64_t)(rowb + 4 * it) * g.N + colg + e] = st[(rr + 4 * it) * SP + c4 + e];
       }
       asm volatile("" ::: "memory");
+      if (!cada1) {       // nothing to store or to subtract: the squared norm needs no particular order of the elements
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wy * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), col = n0 + wx * 64 + j * 32 + (lane & 31);
+            const float v = (row < g.M && col < g.N) ? acc2[i][j][r] : 0.f;
+            sq = fmaf(v, v, sq);
+          }
+        continue;
+      }
       put_band(acc2[i]);
       if (wide) {
 #pragma unroll
@@ -800,7 +811,19 @@ __global__ void k_x_to_bf16(const float *X, bf16_t *Xh, bf16_t *Xl, int64_t rows
 }
 
 // grow[m*Bp + b] = global row of worker m's b-th minibatch sample (b < B)
-__global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow, int Bp) {
+// rep (CADA2 only, else null): workers whose last upload happened at the same iteration share their
+// reference point theta^{k - tau}, hence the difference theta - theta_ref and its bf16 copies;
+// rep[m] = the first worker with worker m's (clamped) tau (written by the first block).
+__global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow, int Bp, int32_t *rep) {
+  if (rep != nullptr && blockIdx.x == 0) {
+    for (int m = threadIdx.x; m < s.M; m += blockDim.x) {
+      const int tm_ = min(s.tau[m], s.D);
+      int r = m;
+      for (int j = 0; j < m; ++j)
+        if (min(s.tau[j], s.D) == tm_) { r = j; break; }
+      rep[m] = r;
+    }
+  }
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)s.M * s.B) return;
   const int m = (int)(i / s.B), b = (int)(i % s.B);
@@ -852,19 +875,6 @@ __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, c
         *reinterpret_cast<u32x4 *>(XTl + o) = pack8(l8);
       }
     }
-  }
-}
-
-// CADA2: workers whose last upload happened at the same iteration share their reference point
-// theta^{k - tau}, hence the difference theta - theta_ref and its bf16 copies.  rep[m] = the first
-// worker with worker m's (clamped) tau.  One block.
-__global__ __launch_bounds__(kBlock) void k_same_reference(const DevState s, int32_t *rep) {
-  for (int m = threadIdx.x; m < s.M; m += kBlock) {
-    const int tm_ = min(s.tau[m], s.D);
-    int r = m;
-    for (int j = 0; j < m; ++j)
-      if (min(s.tau[j], s.D) == tm_) { r = j; break; }
-    rep[m] = r;
   }
 }
 
@@ -1175,11 +1185,11 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
   const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
   const int64_t dwt_stride = per_worker ? P.wt_total : 0;
-  hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp);
+  hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp,
+                     P.rule == CADA_RULE_CADA2 ? P.rep : nullptr);
   hipLaunchKernelGGL(k_gather_transpose, dim3((unsigned)((P.ldx + 63) / 64), (B + 63) / 64, M), dim3(kBlock), 0, st,
                      P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, P.kta[0], P.ktT);
   const int32_t *rep = per_worker ? P.rep : nullptr;
-  if (per_worker) hipLaunchKernelGGL(k_same_reference, dim3(1), dim3(kBlock), 0, st, s, P.rep);
   for (int l = 1; l <= L; ++l) {
     PrepArgs pa;
     pa.s = s; pa.rep = rep;
