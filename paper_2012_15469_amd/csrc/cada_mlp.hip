@@ -143,9 +143,6 @@ __device__ __forceinline__ float *fresh_grad(const DevState &s, int m) {
   return s.gbuf + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.p;
 }
 
-__device__ __forceinline__ uint2 pack4(const bf16_t (&v)[4]) {
-  return make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
-}
 __device__ __forceinline__ u32x4 pack8(const bf16_t (&v)[8]) {
   u32x4 o;
   o.x = (uint32_t)v[0] | ((uint32_t)v[1] << 16); o.y = (uint32_t)v[2] | ((uint32_t)v[3] << 16);
@@ -309,14 +306,6 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
   const int rbase = m0 + wy * 64 + 4 * (lane >> 5);
   const int cbase = n0 + wx * 64 + (lane & 31);
   const int64_t rp0 = (int64_t)wk * g.Bp;            // first padded row of this worker
-  // Places of the accumulator elements in chunked outputs.  The 32 rows of band i lie in one
-  // 128-row tile and in one 32-row chunk, the 32 columns of band j in one chunk and one tile, so
-  // element (i, j, r) is 32 (8 (r>>2) + (r&3)) elements past orow(i, j) in a (row, column) tensor
-  // and 8 (r>>2) + (r&3) elements past ocol(i, j) in a (column, row) tensor: one address per
-  // band pair, the rest are constants of the instruction.
-  auto orow = [&](int i, int j) __attribute__((always_inline)) { return tm(rp0 + rbase + i * 32, cbase + j * 32, g.kto); };
-  auto ocol = [&](int i, int j) __attribute__((always_inline)) { return tm(cbase + j * 32, rp0 + rbase + i * 32, g.ktT); };
-
   if constexpr (EPI == EPI_STORE2) {
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -1106,9 +1095,10 @@ template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const 
   hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D>), grid, dim3(2 * kBlock), mm5_lds_bytes(EPI), c->stream, g);
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
+template <int EPI, int NA, int NB, bool HAS_D> hipError_t skinny_allow_lds() {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+}
 template <int EPI, int NA, int NB, bool HAS_D> void launch_skinny_as(Ctx *c, const Mm5Args &g) {
-  static bool allowed = false;      // (the default limit of dynamic LDS is exactly what the kernel needs; raised anyway)
-  if (!allowed) { (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize, 65536); allowed = true; }
   hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(2 * kBlock), 65536, c->stream, g);
 }
 template <int EPI> void launch_mm5(Ctx *c, Mm5Args &g, int workers) {
@@ -1170,6 +1160,10 @@ int mlp_init_state(Ctx *c, const float *) {
   if (e == hipSuccess) e = mm5_allow_lds<EPI_DW, 2, 3, false>();
   if (e == hipSuccess) e = mm5_allow_lds<EPI_DW, 3, 4, true>();
   if (e == hipSuccess) e = mm5_allow_lds<EPI_DA, 4, 3, true>();
+  if (e == hipSuccess) e = skinny_allow_lds<EPI_STORE2, 2, 3, false>();
+  if (e == hipSuccess) e = skinny_allow_lds<EPI_STORE2, 4, 3, true>();
+  if (e == hipSuccess) e = skinny_allow_lds<EPI_DW, 2, 3, false>();
+  if (e == hipSuccess) e = skinny_allow_lds<EPI_DW, 3, 4, true>();
   if (e != hipSuccess) { set_error("hipFuncSetAttribute(LDS size) failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
   const int64_t n = P.total_rows * P.ldx;
   hipLaunchKernelGGL(k_x_to_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->s.X, P.Xh, P.Xl, P.total_rows, P.d[0], P.ldx);
