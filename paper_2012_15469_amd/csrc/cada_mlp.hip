@@ -466,7 +466,8 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
       asm volatile("" ::: "memory");
     };
     // CADA1: the stored innovations of the part, all loads issued before anything waits for one
-    // (rows clamped into the matrix so that no load sits under a branch)
+    // (rows clamped into the matrix so that no load sits under a branch).  Gradients and innovations
+    // are written once and read once per step, megabytes apart in time: non-temporal accesses.
     f32x4u old[2][8];
     if (cada1 && wide) {
 #pragma unroll
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
           const f32x4u v = *reinterpret_cast<const f32x4u *>(st + (rr + 4 * it) * SP + c4);
-          if (rowb + 4 * it < g.M) *reinterpret_cast<f32x4u *>(gf + (int64_t)(rowb + 4 * it) * g.N + colg) = v;
+          if (rowb + 4 * it < g.M) __builtin_nontemporal_store(v, reinterpret_cast<f32x4u *>(gf + (int64_t)(rowb + 4 * it) * g.N + colg));
         }
       } else if (colg < g.N) {                 // a part that overhangs the matrix: element by element
         for (int it = 0; it < 8 && rowb + 4 * it < g.M; ++it)
@@ -839,8 +840,8 @@ __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, c
     u32x4 vh = {0u, 0u, 0u, 0u}, vl = {0u, 0u, 0u, 0u};
     if (b < B && c < ldx) {                     // (columns from d0 to ldx hold zeros in X's copies)
       const int64_t src = grow[(int64_t)m * Bp + b] * ldx + c;
-      vh = *reinterpret_cast<const u32x4 *>(Xh + src);
-      vl = *reinterpret_cast<const u32x4 *>(Xl + src);
+      vh = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Xh + src));      // (a sampled row is not read again soon)
+      vl = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Xl + src));
       const int64_t dst = tm((int64_t)m * Bp + b, c, ktx);
       *reinterpret_cast<u32x4 *>(XGh + dst) = vh;
       *reinterpret_cast<u32x4 *>(XGl + dst) = vl;

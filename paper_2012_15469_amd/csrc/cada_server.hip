@@ -162,7 +162,9 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
     if (coord(0) < s.p) {
 #pragma unroll 5
       for (int m = w; m < s.M; m += 4) {
-        const float4 t = *reinterpret_cast<const float4 *>(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p + coord(0));
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        // (the stored gradients are read once per step: non-temporal loads, which stream from HBM faster)
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p + coord(0)));
         nab[0] += t.x; nab[1] += t.y; nab[2] += t.z; nab[3] += t.w;
       }
     }
@@ -170,7 +172,10 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
 #pragma unroll 4
     for (int m = w; m < s.M; m += 4) {
       float t[4] = {0.f, 0.f, 0.f, 0.f};
-      get(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p, t);
+      const float *gm = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (coord(v) < s.p) t[v] = __builtin_nontemporal_load(gm + coord(v));
 #pragma unroll
       for (int v = 0; v < 4; ++v) nab[v] += t[v];
     }
