@@ -762,6 +762,13 @@ size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows) {
   if (cfg->layer_dims[cfg->n_layers] > 32) { set_error("at most 32 classes"); return 0; }
   for (int l = 0; l <= cfg->n_layers; ++l)    // the kernels index one worker's activations with 32 bits
     if (((int64_t)cfg->B + 128) * (cfg->layer_dims[l] + 32) >= (1ll << 31)) { set_error("B x layer width must stay below 2^31"); return 0; }
+  {   // the staging launch numbers its 64 x 64 tiles of the minibatch and of every weight copy in one grid dimension
+    const int64_t nz = (cfg->rule == CADA_RULE_CADA2) ? cfg->M + 1 : 2;
+    int64_t nblk = ((int64_t)cfg->layer_dims[0] + 71) / 64 * ((cfg->B + 63) / 64) * cfg->M;
+    for (int l = 1; l <= cfg->n_layers; ++l)
+      nblk += ((int64_t)cfg->layer_dims[l] + 63) / 64 * ((cfg->layer_dims[l - 1] + 63) / 64) * nz;
+    if (nblk >= (1ll << 31)) { set_error("too many operand tiles for one launch (M x layer sizes / 4096 must stay below 2^31)"); return 0; }
+  }
   MlpPlan P;
   Carve w{nullptr, 0};
   layout(P, cfg, total_rows, w);
@@ -800,51 +807,67 @@ __global__ void k_x_to_bf16(const float *X, bf16_t *Xh, bf16_t *Xl, int64_t rows
   Xl[i] = f2bf(x - bf2f(hi));
 }
 
-// grow[m*Bp + b] = global row of worker m's b-th minibatch sample (b < B)
-// rep (CADA2 only, else null): workers whose last upload happened at the same iteration share their
-// reference point theta^{k - tau}, hence the difference theta - theta_ref and its bf16 copies;
-// rep[m] = the first worker with worker m's (clamped) tau (written by the first block).
-__global__ void k_rows(const DevState s, const int32_t *idx, int64_t *grow, int Bp, int32_t *rep) {
-  if (rep != nullptr && blockIdx.x == 0) {
-    for (int m = threadIdx.x; m < s.M; m += blockDim.x) {
-      const int tm_ = min(s.tau[m], s.D);
-      int r = m;
-      for (int j = 0; j < m; ++j)
-        if (min(s.tau[j], s.D) == tm_) { r = j; break; }
-      rep[m] = r;
-    }
-  }
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)s.M * s.B) return;
-  const int m = (int)(i / s.B), b = (int)(i % s.B);
-  const int64_t n = s.row_off[m + 1] - s.row_off[m];
-  int64_t r = idx[i];
-  if (r < 0 || r >= n) { atomicOr(s.err, 1u); r = r < 0 ? 0 : n - 1; }
-  grow[(int64_t)m * Bp + b] = s.row_off[m] + r;
-}
+// Per-step staging of the contractions' operands, one launch: chunked copies of the gathered
+// minibatch in both orientations, and bf16 copies of every layer's weights and of their
+// differences to the reference points.  The blocks of the launch are numbered through the parts
+// (minibatch tiles first, then the layers in order); the parts are independent of each other.
+struct PrepLayer {
+  bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;   // already offset to this layer
+  int64_t offW;
+  int din, dout;
+  int64_t ktt, ktn;      // chunks32(din), chunks32(dout)
+  int want_n;            // also write the [in][out] orientation (layers >= 2)
+  int gx, gy;            // 64 x 64 tiles over (dout, din)
+};
 
-// Chunked copies of the gathered minibatch in both orientations:
-// XG(m*Bp + b, c) = X[grow[m*Bp + b]][c] and XT(c, m*Bp + b) = the same.  grid (ceil(ldx/64), ceil(B/64), M), block 256;
-// a 64 x 64 tile per block, moved 16 bytes (8 values) per lane: rows of X are read and written
-// to XG as they are, and turned through LDS for XT.
-__global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, const bf16_t *Xl, int64_t ldx, const int64_t *grow,
-                                                             bf16_t *XTh, bf16_t *XTl, bf16_t *XGh, bf16_t *XGl, int d0, int B, int Bp,
-                                                             int64_t ktx, int64_t ktT) {
-  __shared__ __align__(16) bf16_t th[64][72], tl[64][72];      // pitch 72: 16-byte rows, 8 rows span all banks
-  const int m = blockIdx.z, c0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
+struct StageArgs {
+  DevState s;
+  // minibatch: XG(m*Bp + b, c) = X[grow[m*Bp + b]][c] and XT(c, m*Bp + b) = the same
+  const bf16_t *Xh, *Xl; int64_t ldx;
+  const int32_t *idx;    // [M][B] sampled rows, local to each worker's shard
+  int64_t *grow;         // out: grow[m*Bp + b] = global row of worker m's b-th sample (b < B)
+  bf16_t *XTh, *XTl, *XGh, *XGl;
+  int d0, B, Bp; int64_t ktx, ktT;
+  int gx, gy;            // 64 x 64 tiles over (ldx, B)
+  // weights
+  PrepLayer layer[CADA_MAX_LAYERS];
+  int n_layers, nz;      // nz = 1 + number of workers with a difference of their own
+  int64_t wt_total, wn_total;
+  // CADA2 only, else null: workers whose last upload happened at the same iteration share their
+  // reference point theta^{k - tau}, hence the difference theta - theta_ref and its bf16 copies;
+  // out: rep[m] = the first worker with worker m's (clamped) tau.  Only that worker's difference is computed.
+  int32_t *rep;
+  uint32_t first[CADA_MAX_LAYERS + 2];   // first block of the minibatch part (0), of each layer, and the total
+};
+
+// A 64 x 64 tile of the minibatch, moved 16 bytes (8 values) per lane: rows of X are read and
+// written to XG as they are, and turned through LDS for XT.
+__device__ __forceinline__ void stage_minibatch(const StageArgs &a, unsigned char *sm, int bx, int by, int m) {
+  typedef bf16_t tile_t[64][72];               // pitch 72: 16-byte rows, 8 rows span all banks
+  tile_t &th = *reinterpret_cast<tile_t *>(sm);
+  tile_t &tl = *reinterpret_cast<tile_t *>(sm + sizeof(tile_t));
+  const int c0 = bx * 64, b0 = by * 64;
   const int t = threadIdx.x;
   const int cg = (t & 7) * 8;                   // this thread's 8 columns
+  const int64_t row0 = a.s.row_off[m], n_m = a.s.row_off[m + 1] - row0;
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     const int r = (t >> 3) + 32 * pass, b = b0 + r, c = c0 + cg;
     u32x4 vh = {0u, 0u, 0u, 0u}, vl = {0u, 0u, 0u, 0u};
-    if (b < B && c < ldx) {                     // (columns from d0 to ldx hold zeros in X's copies)
-      const int64_t src = grow[(int64_t)m * Bp + b] * ldx + c;
-      vh = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Xh + src));      // (a sampled row is not read again soon)
-      vl = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Xl + src));
-      const int64_t dst = tm((int64_t)m * Bp + b, c, ktx);
-      *reinterpret_cast<u32x4 *>(XGh + dst) = vh;
-      *reinterpret_cast<u32x4 *>(XGl + dst) = vl;
+    if (b < a.B && c < a.ldx) {                 // (columns from d0 to ldx hold zeros in X's copies)
+      int64_t row = a.idx[(int64_t)m * a.B + b];
+      if (row < 0 || row >= n_m) {              // reported once per sample, by the tile that also records the row
+        if (bx == 0 && cg == 0) atomicOr(a.s.err, 1u);
+        row = row < 0 ? 0 : n_m - 1;
+      }
+      row += row0;
+      if (bx == 0 && cg == 0) a.grow[(int64_t)m * a.Bp + b] = row;
+      const int64_t src = row * a.ldx + c;
+      vh = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.Xh + src));      // (a sampled row is not read again soon)
+      vl = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.Xl + src));
+      const int64_t dst = tm((int64_t)m * a.Bp + b, c, a.ktx);
+      *reinterpret_cast<u32x4 *>(a.XGh + dst) = vh;
+      *reinterpret_cast<u32x4 *>(a.XGl + dst) = vl;
     }
     *reinterpret_cast<u32x4 *>(&th[r][cg]) = vh;
     *reinterpret_cast<u32x4 *>(&tl[r][cg]) = vl;
@@ -852,54 +875,53 @@ __global__ __launch_bounds__(kBlock) void k_gather_transpose(const bf16_t *Xh, c
   __syncthreads();
   // 8 consecutive rows of one column are 16 consecutive bytes of XT (rows past B are written as zeros)
   const int f = t & 63;
-  if (c0 + f < d0) {
+  if (c0 + f < a.d0) {
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
       const int rg = ((t >> 6) + 4 * pass) * 8;
-      if (b0 + rg < B) {
+      if (b0 + rg < a.B) {
         bf16_t h8[8], l8[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { h8[e] = th[rg + e][f]; l8[e] = tl[rg + e][f]; }
-        const int64_t o = tm(c0 + f, (int64_t)m * Bp + b0 + rg, ktT);
-        *reinterpret_cast<u32x4 *>(XTh + o) = pack8(h8);
-        *reinterpret_cast<u32x4 *>(XTl + o) = pack8(l8);
+        const int64_t o = tm(c0 + f, (int64_t)m * a.Bp + b0 + rg, a.ktT);
+        *reinterpret_cast<u32x4 *>(a.XTh + o) = pack8(h8);
+        *reinterpret_cast<u32x4 *>(a.XTl + o) = pack8(l8);
       }
     }
   }
 }
 
-struct PrepArgs {
-  DevState s;
-  bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;   // already offset to this layer
-  int64_t offW, wt_total, wn_total;
-  int din, dout;
-  int64_t ktt, ktn;      // chunks32(din), chunks32(dout)
-  int want_n;            // also write the [in][out] orientation (layers >= 2)
-  const int32_t *rep;    // worker m's difference is computed only if rep[m] == m
-};
-
-// bf16 copies of one layer's weights (hi, lo) and of its difference to each reference point,
-// in the orientation(s) the contractions read.  grid (ceil(dout/64), ceil(din/64), nW + 1):
-// z = 0 -> W, z = 1 + m -> theta - theta_ref(m).  A 64 x 64 tile per block, 8 values per lane:
-// rows of W are read (4-byte aligned 16-byte loads) and written as they are, and turned
-// through LDS for the other orientation.
-__global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
+// A 64 x 64 tile of one layer's weights (z = 0: hi and lo parts of W) or of their difference to
+// worker z - 1's reference point, 8 values per lane: rows of W are read (4-byte aligned 16-byte
+// loads) and written as they are, and turned through LDS for the other orientation.
+__device__ __forceinline__ void stage_weights(const StageArgs &a, const PrepLayer &p, unsigned char *sm, int bx, int by, int z, bool first_tile) {
   const DevState &s = a.s;
-  __shared__ float tile[64][65];
-  const int o0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
+  typedef float tile_t[64][65];
+  tile_t &tile = *reinterpret_cast<tile_t *>(sm);
+  const int o0 = bx * 64, i0 = by * 64;
   const int t = threadIdx.x;
-  const bool is_w = blockIdx.z == 0;
-  const int m = is_w ? 0 : blockIdx.z - 1;
-  if (!is_w && a.rep && a.rep[m] != m) return;      // another worker with the same reference point stands for this one
+  const bool is_w = z == 0;
+  const int m = is_w ? 0 : z - 1;
+  if (!is_w && a.rep) {
+    const int tau_m = min(s.tau[m], s.D);
+    int r = m;                                        // (every wavefront finds it for itself)
+    for (int j0 = 0; j0 < m && r == m; j0 += kWave) {
+      const int j = j0 + (t & 63);
+      const unsigned long long same = __ballot(j < m && min(s.tau[j], s.D) == tau_m);
+      if (same) r = j0 + __ffsll(same) - 1;
+    }
+    if (first_tile && t == 0) a.rep[m] = r;
+    if (r != m) return;                               // another worker with the same reference point stands for this one
+  }
   const RefPtr ref = theta_ref(s, m, s.k);
   const int og = (t & 7) * 8;
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     const int r = (t >> 3) + 32 * pass, i = i0 + r, o = o0 + og;
     float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (i < a.din && o < a.dout) {
-      const int64_t src = a.offW + (int64_t)i * a.dout + o;
-      if (o + 8 <= a.dout) {
+    if (i < p.din && o < p.dout) {
+      const int64_t src = p.offW + (int64_t)i * p.dout + o;
+      if (o + 8 <= p.dout) {
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
           f32x4u x = *reinterpret_cast<const f32x4u *>(s.theta + src + 4 * q);
@@ -912,15 +934,15 @@ __global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
           v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
         }
       } else {
-        for (int e = 0; e < 8 && o + e < a.dout; ++e) v[e] = is_w ? s.theta[src + e] : delta_theta(s, ref, src + e);
+        for (int e = 0; e < 8 && o + e < p.dout; ++e) v[e] = is_w ? s.theta[src + e] : delta_theta(s, ref, src + e);
       }
-      if (a.want_n) {                             // (values past dout are zeros, like the padding they land in)
-        const int64_t dn = tm(i, o, a.ktn);
+      if (p.want_n) {                             // (values past dout are zeros, like the padding they land in)
+        const int64_t dn = tm(i, o, p.ktn);
         bf16_t h8[8], l8[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { h8[e] = f2bf(v[e]); l8[e] = f2bf(v[e] - bf2f(h8[e])); }
-        if (is_w) { *reinterpret_cast<u32x4 *>(a.WNh + dn) = pack8(h8); *reinterpret_cast<u32x4 *>(a.WNl + dn) = pack8(l8); }
-        else *reinterpret_cast<u32x4 *>(a.dWN + (int64_t)m * a.wn_total + dn) = pack8(h8);
+        if (is_w) { *reinterpret_cast<u32x4 *>(p.WNh + dn) = pack8(h8); *reinterpret_cast<u32x4 *>(p.WNl + dn) = pack8(l8); }
+        else *reinterpret_cast<u32x4 *>(p.dWN + (int64_t)m * a.wn_total + dn) = pack8(h8);
       }
     }
 #pragma unroll
@@ -928,20 +950,39 @@ __global__ __launch_bounds__(kBlock) void k_prep_weights(const PrepArgs a) {
   }
   __syncthreads();
   const int oo = t & 63;
-  if (o0 + oo < a.dout) {
+  if (o0 + oo < p.dout) {
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
       const int ig = ((t >> 6) + 4 * pass) * 8;
-      if (i0 + ig < a.din) {                      // (rows past din are zeros in the tile)
+      if (i0 + ig < p.din) {                      // (rows past din are zeros in the tile)
         bf16_t h8[8], l8[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { const float x = tile[ig + e][oo]; h8[e] = f2bf(x); l8[e] = f2bf(x - bf2f(h8[e])); }
-        const int64_t dt = tm(o0 + oo, i0 + ig, a.ktt);
-        if (is_w) { *reinterpret_cast<u32x4 *>(a.WTh + dt) = pack8(h8); *reinterpret_cast<u32x4 *>(a.WTl + dt) = pack8(l8); }
-        else *reinterpret_cast<u32x4 *>(a.dWT + (int64_t)m * a.wt_total + dt) = pack8(h8);
+        const int64_t dt = tm(o0 + oo, i0 + ig, p.ktt);
+        if (is_w) { *reinterpret_cast<u32x4 *>(p.WTh + dt) = pack8(h8); *reinterpret_cast<u32x4 *>(p.WTl + dt) = pack8(l8); }
+        else *reinterpret_cast<u32x4 *>(p.dWT + (int64_t)m * a.wt_total + dt) = pack8(h8);
       }
     }
   }
+}
+
+__global__ __launch_bounds__(kBlock) void k_stage(const StageArgs a) {
+  __shared__ __align__(16) unsigned char sm[2 * 64 * 72 * sizeof(bf16_t)];
+  static_assert(sizeof(sm) >= 64 * 65 * sizeof(float), "the weight tile fits too");
+  const uint32_t blk = blockIdx.x;
+  if (blk < a.first[1]) {
+    const uint32_t per = (uint32_t)a.gx * a.gy;
+    const uint32_t m = blk / per, r = blk - m * per;
+    stage_minibatch(a, sm, (int)(r % a.gx), (int)(r / a.gx), (int)m);
+    return;
+  }
+  int l = 0;
+  while (blk >= a.first[l + 2]) ++l;             // (blk < first[n_layers + 1], the grid's size)
+  const PrepLayer &p = a.layer[l];
+  const uint32_t rel = blk - a.first[l + 1];
+  const uint32_t per = (uint32_t)p.gx * p.gy;
+  const uint32_t z = rel / per, r = rel - z * per;
+  stage_weights(a, p, sm, (int)(r % p.gx), (int)(r / p.gx), (int)z, l == 0 && r == 0);
 }
 
 struct LossArgs {
@@ -957,85 +998,92 @@ struct LossArgs {
 
 // softmax cross-entropy: G = (P - onehot)/B, dG = (P - Pref)/B with
 // P_i - Pref_i = P_i (S - expm1(-dz_i)) / (1 + S),  S = sum_j P_j expm1(-dz_j).
-// One block per worker; also the last layer's bias gradient, its innovation and the
-// innovation's contribution to the rule's left-hand side.
-__global__ __launch_bounds__(kBlock) void k_loss(const LossArgs a) {
+// One block of 1024 threads per worker; sixteen lanes share a row, each with two of the (at most
+// 32) classes, so a wavefront holds four rows and the block 64.  Also the last layer's bias
+// gradient, its innovation and the innovation's contribution to the rule's left-hand side.
+constexpr int kLossBlock = 1024;
+
+__device__ __forceinline__ float group16_sum(float x) {
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+__global__ __launch_bounds__(kLossBlock) void k_loss(const LossArgs a) {
   const DevState &s = a.s;
-  constexpr int MAXC = 32;
-  __shared__ float part[4][2 * MAXC];
+  __shared__ float part[kLossBlock / 64][16][4];
   const int m = blockIdx.x;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int cp = threadIdx.x & 15;               // class pair
+  const int c0 = 2 * cp;
+  const bool on[2] = {c0 < a.C, c0 + 1 < a.C};
   const RefPtr ref = theta_ref(s, m, s.k);
   const int32_t *yv = static_cast<const int32_t *>(s.y);
   const float invB = 1.0f / (float)s.B;
-  float sumG[MAXC], sumD[MAXC];
+  float bz[2], dbz[2];
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) { sumG[c] = 0.f; sumD[c] = 0.f; }
-  for (int b = threadIdx.x; b < s.B; b += kBlock) {
+  for (int e = 0; e < 2; ++e) {
+    bz[e] = on[e] ? s.theta[a.offb + c0 + e] : 0.f;
+    dbz[e] = on[e] ? delta_theta(s, ref, a.offb + c0 + e) : 0.f;
+  }
+  float sumG[2] = {0.f, 0.f}, sumD[2] = {0.f, 0.f};
+  for (int b = threadIdx.x >> 4; b < s.B; b += kLossBlock / 16) {
     const int64_t r = (int64_t)m * a.Bp + b;
-    float z[MAXC], dz[MAXC];
-    float zmax = -INFINITY;
+    float z[2], x[2];
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) {
-      if (c < a.C) {
-        const int64_t bi = a.offb + c;
-        z[c] = a.Z[r * a.C + c] + s.theta[bi];
-        dz[c] = a.dZ[r * a.C + c] + delta_theta(s, ref, bi);
-        zmax = fmaxf(zmax, z[c]);
+    for (int e = 0; e < 2; ++e) {
+      z[e] = on[e] ? a.Z[r * a.C + c0 + e] + bz[e] : -INFINITY;
+      x[e] = on[e] ? expm1f(-(a.dZ[r * a.C + c0 + e] + dbz[e])) : 0.f;
+    }
+    const int label = yv[a.grow[r]];
+    float zmax = fmaxf(z[0], z[1]);
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 64));
+#pragma unroll
+    for (int e = 0; e < 2; ++e) z[e] = on[e] ? expf(z[e] - zmax) : 0.f;
+    const float den = group16_sum(z[0] + z[1]);
+    z[0] = z[0] / den; z[1] = z[1] / den;
+    const float S = group16_sum(fmaf(z[0], x[0], z[1] * x[1]));
+    // (row, class) tensors: a row's classes are consecutive, written two at a time (an absent odd
+    // class is a zero in the padding); (class, row) tensors: one value per class and row
+    uint32_t ph = 0, pl = 0, pd = 0, pr = 0;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      if (on[e]) {
+        const int c = c0 + e;
+        const float gl = (z[e] - (c == label ? 1.f : 0.f)) * invB;
+        const float dg = z[e] * (S - x[e]) / (1.0f + S) * invB;
+        const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
+        ph |= (uint32_t)hi << (16 * e); pl |= (uint32_t)lo << (16 * e); pd |= (uint32_t)bd << (16 * e); pr |= (uint32_t)br << (16 * e);
+        const int64_t ot = tm(c, r, a.ktT);
+        a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
+        sumG[e] += gl;
+        sumD[e] += dg;
       }
     }
-    float den = 0.f;
-#pragma unroll
-    for (int c = 0; c < MAXC; ++c) if (c < a.C) { z[c] = expf(z[c] - zmax); den += z[c]; }
-    float S = 0.f;
-#pragma unroll
-    for (int c = 0; c < MAXC; ++c) if (c < a.C) { z[c] = z[c] / den; dz[c] = expm1f(-dz[c]); S = fmaf(z[c], dz[c], S); }
-    const int label = yv[a.grow[r]];
-    // (row, class) tensors: a row's classes are consecutive, written two at a time (an absent odd
-    // class is a zero in the padding); (class, row) tensors: consecutive lanes, consecutive rows
-    const int64_t orow = tm(r, 0, a.ktg);
-#pragma unroll
-    for (int c2 = 0; c2 < MAXC; c2 += 2) {
-      if (c2 < a.C) {
-        uint32_t ph = 0, pl = 0, pd = 0, pr = 0;
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const int c = c2 + e;
-          if (c < a.C) {
-            const float gl = (z[c] - (c == label ? 1.f : 0.f)) * invB;
-            const float dg = z[c] * (S - dz[c]) / (1.0f + S) * invB;
-            const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
-            ph |= (uint32_t)hi << (16 * e); pl |= (uint32_t)lo << (16 * e); pd |= (uint32_t)bd << (16 * e); pr |= (uint32_t)br << (16 * e);
-            const int64_t ot = tm(c, r, a.ktT);
-            a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
-            sumG[c] += gl;
-            sumD[c] += dg;
-          }
-        }
-        if (a.Gh) {     // (a single-layer network has no layer below to pass them to)
-          const int64_t o = orow + c2;          // classes 0..31 lie in the row's first chunk
-          *reinterpret_cast<uint32_t *>(a.Gh + o) = ph; *reinterpret_cast<uint32_t *>(a.Gl + o) = pl;
-          *reinterpret_cast<uint32_t *>(a.dG + o) = pd; *reinterpret_cast<uint32_t *>(a.Gref + o) = pr;
-        }
-      }
+    if (a.Gh && on[0]) {     // (a single-layer network has no layer below to pass them to)
+      const int64_t o = tm(r, 0, a.ktg) + c0;          // classes 0..31 lie in the row's first chunk
+      *reinterpret_cast<uint32_t *>(a.Gh + o) = ph; *reinterpret_cast<uint32_t *>(a.Gl + o) = pl;
+      *reinterpret_cast<uint32_t *>(a.dG + o) = pd; *reinterpret_cast<uint32_t *>(a.Gref + o) = pr;
     }
   }
   // bias gradient of the last layer, its innovation and that innovation's part of the left-hand
-  // side: sums over the rows in a fixed order (wavefront tree, then the four wavefronts)
+  // side: sums over the rows in a fixed order (a thread's rows, the wavefront's four row groups,
+  // then the wavefronts)
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) {
-    if (c < a.C) {
-      const float g1 = wave_sum(sumG[c]), d1 = wave_sum(sumD[c]);
-      if (lane == 0) { part[w][2 * c] = g1; part[w][2 * c + 1] = d1; }
-    }
+  for (int e = 0; e < 2; ++e) {
+    sumG[e] += __shfl_xor(sumG[e], 16, 64); sumG[e] += __shfl_xor(sumG[e], 32, 64);
+    sumD[e] += __shfl_xor(sumD[e], 16, 64); sumD[e] += __shfl_xor(sumD[e], 32, 64);
   }
+  if (lane < 16) { part[w][cp][0] = sumG[0]; part[w][cp][1] = sumG[1]; part[w][cp][2] = sumD[0]; part[w][cp][3] = sumD[1]; }
   __syncthreads();
   if (w == 0) {
     float sq = 0.f;
     if (lane < a.C) {
       const int c = lane;
-      const float gsum = (part[0][2 * c] + part[1][2 * c]) + (part[2][2 * c] + part[3][2 * c]);
-      float iv = (part[0][2 * c + 1] + part[1][2 * c + 1]) + (part[2][2 * c + 1] + part[3][2 * c + 1]);
+      float gsum = 0.f, iv = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < kLossBlock / 64; ++ww) { gsum += part[ww][c >> 1][c & 1]; iv += part[ww][c >> 1][2 + (c & 1)]; }
       fresh_grad(s, m)[a.offb + c] = gsum;
       if (s.rule == CADA_RULE_CADA1) {
         const int cur = s.sel[m];
@@ -1180,19 +1228,30 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
   const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
   const int64_t dwt_stride = per_worker ? P.wt_total : 0;
-  hipLaunchKernelGGL(k_rows, dim3((unsigned)(((int64_t)M * B + 255) / 256)), dim3(256), 0, st, s, idx, P.grow, Bp,
-                     P.rule == CADA_RULE_CADA2 ? P.rep : nullptr);
-  hipLaunchKernelGGL(k_gather_transpose, dim3((unsigned)((P.ldx + 63) / 64), (B + 63) / 64, M), dim3(kBlock), 0, st,
-                     P.Xh, P.Xl, P.ldx, P.grow, P.XTh, P.XTl, P.XGh, P.XGl, P.d[0], B, Bp, P.kta[0], P.ktT);
-  const int32_t *rep = per_worker ? P.rep : nullptr;
-  for (int l = 1; l <= L; ++l) {
-    PrepArgs pa;
-    pa.s = s; pa.rep = rep;
-    pa.WTh = P.WTh + P.wt_off[l - 1]; pa.WTl = P.WTl + P.wt_off[l - 1]; pa.dWT = P.dWT + P.wt_off[l - 1];
-    pa.WNh = P.WNh + P.wn_off[l - 1]; pa.WNl = P.WNl + P.wn_off[l - 1]; pa.dWN = P.dWN + P.wn_off[l - 1];
-    pa.offW = P.offW[l - 1]; pa.wt_total = P.wt_total; pa.wn_total = P.wn_total;
-    pa.din = P.d[l - 1]; pa.dout = P.d[l]; pa.ktt = P.kta[l - 1]; pa.ktn = P.kta[l]; pa.want_n = l >= 2;
-    hipLaunchKernelGGL(k_prep_weights, dim3((pa.dout + 63) / 64, (pa.din + 63) / 64, P.nW + 1), dim3(kBlock), 0, st, pa);
+  int32_t *rep = per_worker ? P.rep : nullptr;
+  {
+    StageArgs sa;
+    sa.s = s;
+    sa.Xh = P.Xh; sa.Xl = P.Xl; sa.ldx = P.ldx; sa.idx = idx; sa.grow = P.grow;
+    sa.XTh = P.XTh; sa.XTl = P.XTl; sa.XGh = P.XGh; sa.XGl = P.XGl;
+    sa.d0 = P.d[0]; sa.B = B; sa.Bp = Bp; sa.ktx = P.kta[0]; sa.ktT = P.ktT;
+    sa.gx = (int)((P.ldx + 63) / 64); sa.gy = (B + 63) / 64;
+    sa.n_layers = L; sa.nz = P.nW + 1; sa.wt_total = P.wt_total; sa.wn_total = P.wn_total; sa.rep = rep;
+    uint64_t nblk = (uint64_t)sa.gx * sa.gy * M;
+    sa.first[0] = 0;
+    for (int l = 1; l <= L; ++l) {
+      PrepLayer &pl = sa.layer[l - 1];
+      pl.WTh = P.WTh + P.wt_off[l - 1]; pl.WTl = P.WTl + P.wt_off[l - 1]; pl.dWT = P.dWT + P.wt_off[l - 1];
+      pl.WNh = P.WNh + P.wn_off[l - 1]; pl.WNl = P.WNl + P.wn_off[l - 1]; pl.dWN = P.dWN + P.wn_off[l - 1];
+      pl.offW = P.offW[l - 1];
+      pl.din = P.d[l - 1]; pl.dout = P.d[l]; pl.ktt = P.kta[l - 1]; pl.ktn = P.kta[l]; pl.want_n = l >= 2;
+      pl.gx = (pl.dout + 63) / 64; pl.gy = (pl.din + 63) / 64;
+      sa.first[l] = (uint32_t)nblk;
+      nblk += (uint64_t)pl.gx * pl.gy * sa.nz;
+    }
+    sa.first[L + 1] = (uint32_t)nblk;
+    for (int l = L + 2; l < CADA_MAX_LAYERS + 2; ++l) sa.first[l] = (uint32_t)nblk;
+    hipLaunchKernelGGL(k_stage, dim3((unsigned)nblk), dim3(kBlock), 0, st, sa);
   }
 
   // ---- forward: worker m owns padded rows [m*Bp, m*Bp + B)
@@ -1246,7 +1305,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
     la.GhT = P.GhT[L]; la.GlT = P.GlT[L]; la.dGT = P.dGT[L]; la.GrefT = P.GrefT[L];
     la.grow = P.grow; la.offb = P.offb[L - 1]; la.ktT = P.ktT; la.C = P.d[L]; la.Bp = Bp; la.ktg = P.kta[L];
     la.lhs_slot = P.lhs_b_slot[L - 1];
-    hipLaunchKernelGGL(k_loss, dim3(M), dim3(kBlock), 0, st, la);
+    hipLaunchKernelGGL(k_loss, dim3(M), dim3(kLossBlock), 0, st, la);
   }
 
   // ---- backward

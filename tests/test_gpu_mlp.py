@@ -97,3 +97,18 @@ def test_many_tiles_per_workgroup(cfg):
     print(cfg.name, stats, "lhs rel median %.2e max %.2e" % (float(np.median(rel)), float(rel.max())))
     assert float(np.median(rel)) < 1e-2 and float(np.quantile(rel, 0.99)) < 0.2
     assert stats["own_disagreements"] <= max(2, 0.03 * tr["mask"].size)
+
+
+@pytest.mark.parametrize("rule", [configs.RULE_CADA1, configs.RULE_CADA2], ids=["cada1", "cada2"])
+def test_out_of_range_sample_is_clamped_and_flagged(rule):
+    """A sample id past the worker's shard is clamped to its last row and reported; runs repeat bit for bit."""
+    cfg = configs.CFG4.scaled(name="mlp2_ragged", layer_dims=(150, 133, 10), M=5, N_m=300, B=70, K=6, D=3, c=20.0, rule=rule)
+    prob, dev, sched = _case(cfg)
+    bad = sched.copy(); bad[2, 3, 69] = cfg.N_m + 7; bad[4, 0, 0] = -3
+    out = run_library(cfg, dev, bad)
+    assert out["error_flags"][0] & 1
+    fixed = bad.copy(); fixed[2, 3, 69] = cfg.N_m - 1; fixed[4, 0, 0] = 0
+    ref = run_library(cfg, dev, fixed)
+    assert not ref["error_flags"][0] & 1
+    for key in ("theta", "h", "vhat", "trace_mask", "trace_lhs", "trace_rhs"):
+        assert np.array_equal(out[key], ref[key]), key
