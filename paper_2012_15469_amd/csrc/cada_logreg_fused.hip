@@ -19,10 +19,10 @@
 // path: the 128 KB ring holds 5.5 us of stream per CU.
 //
 // Loads return in order within a wavefront, so waiting for a young load (a poll, an index,
-// a label) means waiting for every older one: a wavefront that keeps 8 slabs of bulk loads
+// a label) means waiting for every older one: a wavefront that keeps 16 slabs of bulk loads
 // in flight must issue no other load in its steady state.  The workgroup is therefore split
 // into roles, six wavefronts that meet at one LDS-only barrier per slab:
-//   wavefronts 0-3  stream: bulk loads (PD = 8 slabs in flight), partial dot products,
+//   wavefronts 0-3  stream: bulk loads (PD = 16 slabs in flight), partial dot products,
 //                   parking, accumulation; row addresses come from LDS;
 //   wavefront 4     exchange: publishes the workgroup's partials, polls the cluster's
 //                   (P polls in flight, first issued LAG-2-P slabs after publication),
