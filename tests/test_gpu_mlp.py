@@ -112,3 +112,16 @@ def test_out_of_range_sample_is_clamped_and_flagged(rule):
     assert not ref["error_flags"][0] & 1
     for key in ("theta", "h", "vhat", "trace_mask", "trace_lhs", "trace_rhs"):
         assert np.array_equal(out[key], ref[key]), key
+
+
+def test_more_workers_than_a_wavefront_share_reference_points():
+    """CADA2 with 70 workers: the search for the first worker with the same delay runs over more
+    than one wavefront's worth of workers, and most reference points are shared."""
+    cfg = configs.CFG4.scaled(name="mlp2_70_workers", layer_dims=(20, 16, 10), M=70, N_m=40, B=6, K=14, D=4, c=20.0,
+                              alpha=0.002, rule=configs.RULE_CADA2)
+    prob, dev, sched = _case(cfg)
+    stats, o, tr, rep = check_protocol(cfg, prob, dev, sched, BF16_TOL, lhs_rtol=None, own_mask_exact=False, free_margin=None)
+    print(cfg.name, stats)
+    free = tr["tau"] < cfg.D
+    assert 0.02 < tr["mask"][free].mean() < 0.98, "the case must mix rule-driven uploads and skips"
+    assert stats["own_disagreements"] <= max(2, 0.03 * tr["mask"].size)
