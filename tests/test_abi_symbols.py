@@ -46,3 +46,40 @@ def test_argument_errors_without_gpu():
     cfg.p = 54
     assert b._lib.cada_init(ctypes.byref(cfg), None, ctypes.byref(out)) == -1     # theta0 NULL
     assert b._lib.cada_step(None, None, None) == -1
+
+
+def _mlp_cfg(b, dims, M, B, N_m, rule):
+    cfg = b.cada_config()
+    d = (ctypes.c_int32 * len(dims))(*dims)
+    ns = (ctypes.c_int64 * M)(*([N_m] * M))
+    p = sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(len(dims) - 1))
+    cfg.M, cfg.p, cfg.model, cfg.n_layers, cfg.layer_dims, cfg.B, cfg.n_samples = M, p, b.MODEL_MLP, len(dims) - 1, d, B, ns
+    cfg.d_max, cfg.D, cfg.rule, cfg.gemm_dtype = 10, 20, rule, b.GEMM_BF16
+    cfg._keep = (d, ns)
+    return cfg, p
+
+
+def test_mlp_workspace_sizing_without_gpu():
+    """Workspace of the MLP path: at least the state the method keeps (two gradient rows per worker,
+    the server vectors, CADA1's stored innovations or CADA2's iterate history), growing with the
+    number of workers; shapes the kernels do not cover are refused on the host."""
+    from paper_2012_15469_amd import binding as b
+    sizes = {}
+    for rule in (1, 2):
+        for M in (4, 8):
+            cfg, p = _mlp_cfg(b, (784, 512, 10), M, 128, 600, rule)
+            n = b._lib.cada_workspace_bytes(ctypes.byref(cfg))
+            assert n > 0, b.cada_last_error()
+            state = 4 * p * (2 * M + 6) + (4 * p * 2 * M if rule == 1 else 4 * p * 2 * (cfg.D + 1))
+            assert n > state
+            assert n < 4 * state + (1 << 28)           # and not absurdly more
+            sizes[rule, M] = n
+        assert sizes[rule, 8] > sizes[rule, 4]
+    cfg, p = _mlp_cfg(b, (784, 512, 40), 4, 128, 600, 2)
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "32 classes" in b.cada_last_error()
+    cfg, p = _mlp_cfg(b, (784, 512, 10), 4, 128, 600, 2)
+    cfg.gemm_dtype = b.GEMM_FP32
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "bf16" in b.cada_last_error()
+    cfg, p = _mlp_cfg(b, (784, 512, 10), 4, 128, 600, 2)
+    cfg.p = p + 1
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "does not match" in b.cada_last_error()
