@@ -11,14 +11,14 @@ namespace cada {
 // Sum of the per-block partial sums of the squared step of iteration k-1 (the value of
 // ring[(k-1) mod d_max]), in a fixed order; called by the whole block, valid in every thread.
 __device__ float last_step_sq(const DevState &s, double *red /* [kBlock] LDS */) {
-  // (eight loads in flight per thread; the additions keep their order, a missing term adds 0)
+  // (sixteen loads in flight per thread; the additions keep their order, a missing term adds 0)
   double acc = 0.0;
-  for (int i0 = threadIdx.x; i0 < s.n_ring_part; i0 += 8 * kBlock) {
-    float v[8];
+  for (int i0 = threadIdx.x; i0 < s.n_ring_part; i0 += 16 * kBlock) {
+    float v[16];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) { const int i = i0 + u * kBlock; v[u] = s.ring_part[min(i, s.n_ring_part - 1)]; if (i >= s.n_ring_part) v[u] = 0.f; }
+    for (int u = 0; u < 16; ++u) { const int i = i0 + u * kBlock; v[u] = s.ring_part[min(i, s.n_ring_part - 1)]; if (i >= s.n_ring_part) v[u] = 0.f; }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc += (double)v[u];
+    for (int u = 0; u < 16; ++u) acc += (double)v[u];
   }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -72,12 +72,12 @@ __global__ __launch_bounds__(kBlock) void k_rule(const DevState s, const uint8_t
   if (m < s.M) {
     double lhs = 0.0;
     const float *lp = s.lhs_part + (int64_t)m * s.n_lhs_part;
-    for (int t0 = lane; t0 < s.n_lhs_part; t0 += 8 * kWave) {        // eight loads in flight, additions in order
-      float v[8];
+    for (int t0 = lane; t0 < s.n_lhs_part; t0 += 16 * kWave) {       // sixteen loads in flight, additions in order
+      float v[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) { const int t = t0 + u * kWave; v[u] = lp[min(t, s.n_lhs_part - 1)]; if (t >= s.n_lhs_part) v[u] = 0.f; }
+      for (int u = 0; u < 16; ++u) { const int t = t0 + u * kWave; v[u] = lp[min(t, s.n_lhs_part - 1)]; if (t >= s.n_lhs_part) v[u] = 0.f; }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) lhs += (double)v[u];
+      for (int u = 0; u < 16; ++u) lhs += (double)v[u];
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) lhs += __shfl_xor(lhs, o, 64);   // fixed tree order
