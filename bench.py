@@ -132,8 +132,6 @@ def main() -> int:
     from paper_2012_15469_amd import binding
     from paper_2012_15469_amd.binding import Cada
 
-    if args.plain_launch:
-        os.environ["CADA_FUSED_PLAIN_LAUNCH"] = "1"
     cfg = configs.ALL[args.config]
     dev = torch.device("cuda:0")
     if args.replicas > 1:
@@ -153,7 +151,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
-    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0)
+    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0, plain_launch=args.plain_launch)
     # small logistic workloads run whole iterations inside one kernel: the K timed steps are one
     # cada_run call (one launch); everything else is one cada_step call per step
     whole = binding.cada_profile_phase_names(eng.ctx) == ["logreg_whole_steps"]

@@ -56,7 +56,19 @@ enum {
                               h, v, vhat stay at their initial zeros */
 };
 enum { CADA_MODEL_LOGREG = 0, CADA_MODEL_MLP = 1 };
-enum { CADA_GEMM_FP32 = 0, CADA_GEMM_BF16 = 1 };
+enum {
+  CADA_PATH_AUTO = 0,        /* single pass where it applies (p >= 8192, a multiple of 4), whole steps for tiny
+                                workloads (M B p <= 32768), two passes otherwise */
+  CADA_PATH_TWO_PASS = 1,    /* two streaming passes over the minibatch rows (any shape) */
+  CADA_PATH_SINGLE_PASS = 2, /* one pass: the rows stay in registers/LDS between the two products */
+  CADA_PATH_WHOLE_STEPS = 3  /* whole iterations in one launch, one workgroup per worker, whenever the shape allows it,
+                                also where separate kernels would be faster for one run: cada_run_replicas needs it */
+};
+enum {
+  CADA_GEMM_FP32 = 0, /* not implemented for the MLP model: cada_workspace_bytes/cada_init refuse it (CADA_EUNSUPPORTED) */
+  CADA_GEMM_BF16 = 1  /* bf16 MFMA products of split (hi + lo) operands, float32 accumulation; the MLP model
+                         supports at most 32 classes (width of the last layer) */
+};
 
 enum {
   CADA_OK = 0,
@@ -97,9 +109,17 @@ typedef struct cada_config {
   int64_t alpha_K0;          /* 0: constant stepsize alpha; K0 > 0: alpha_k = alpha K0/(k + K0), the
                                 decaying stepsize 2/(mu (k + K0)) of Theorem 2 with alpha = 2/(mu K0) */
   int64_t trace_steps;       /* steps of per-step trace to keep (0 = none) */
-  int32_t whole_steps;       /* LOGREG: 0 = the library picks the kernels; 1 = run whole iterations in one
-                                launch (one workgroup per worker) whenever the shape allows it, also where
-                                separate kernels would be faster for one run: cada_run_replicas needs it */
+  int32_t path;              /* LOGREG: which kernels compute the gradients and the rule's left-hand side, CADA_PATH_*.
+                                A request the shape does not allow falls back to the library's own choice;
+                                cada_profile_phase_name() tells which kernels a context runs.  MLP ignores it */
+  int32_t single_pass_rows;  /* CADA_PATH_SINGLE_PASS tuning: 0 = the library picks (two minibatch rows per iteration
+                                when B is even), 1 = one row per iteration */
+  int32_t single_pass_clusters; /* 0 = as many workgroup clusters as the device holds; n > 0: at most n (fewer,
+                                longer-lived clusters: every cluster then changes worker in mid-stream) */
+  int32_t plain_launch;      /* 1 = launch the single-pass kernel as an ordinary grid instead of cooperatively (for
+                                profilers that cannot trace cooperative dispatches; the device must be otherwise idle;
+                                every wait in the kernel is bounded and reports through error_flags bit 1) */
+  int32_t two_pass_group;    /* CADA_PATH_TWO_PASS tuning: workers per pair of launches, 0 = all */
   void *workspace;           /* DEVICE, 256-byte aligned, caller-owned */
   size_t workspace_bytes;
   void *stream;              /* hipStream_t; NULL = the default stream */
@@ -116,7 +136,13 @@ typedef struct cada_state {
   const uint8_t *mask;                       /* DEVICE [M], uploads of the last step */
   const float *lhs;                          /* DEVICE [M], rule left-hand sides of the last step */
   const uint64_t *uploads_total;             /* DEVICE [1], sum of all masks so far */
-  const uint32_t *error_flags;               /* DEVICE [1], bit 0: a minibatch index was out of range (clamped) */
+  const uint32_t *error_flags;               /* DEVICE [1]; bit 0: a minibatch index was out of range (clamped);
+                                                bit 1: a bounded wait among workgroups gave up (the single-pass and the
+                                                whole-iteration logistic kernels; results of that step are invalid);
+                                                bit 2: cada_set_state was given a delay outside [1, D] (clamped);
+                                                bit 3: a replay mask kept a CADA2 worker silent for more than D
+                                                iterations, so its reference point theta^{k - tau_m} was no longer
+                                                retained and theta^{k - D} was used instead */
   int64_t k;                                 /* steps enqueued so far */
   int64_t trace_steps;                       /* capacity of the trace */
   const uint8_t *trace_mask;                 /* DEVICE [trace_steps, M] applied masks */
@@ -149,8 +175,8 @@ int cada_step(cada_ctx *ctx, const int32_t *idx, const uint8_t *replay);
  * replay_sched DEVICE uint8 [n_steps, M] or NULL. */
 int cada_run(cada_ctx *ctx, const int32_t *idx_sched, const uint8_t *replay_sched, int64_t n_steps);
 
-/* Independent runs side by side (the experiments of Section 5 average several Monte-Carlo runs):
- * the n_replicas contexts, all with the same M, p, B and rule, initialised with whole_steps = 1 on
+/* Independent runs side by side (the simulations of Section 4 average several Monte-Carlo runs):
+ * the n_replicas contexts, all with the same M, p, B and rule, initialised with path = CADA_PATH_WHOLE_STEPS on
  * the same stream, advance n_steps iterations each in ONE launch (one workgroup per worker and
  * replica), with their own data, iterates, schedules and decisions.  ctxs, idx_scheds,
  * replay_scheds: HOST arrays of n_replicas entries; idx_scheds[r] DEVICE int32 [n_steps, M, B],
@@ -161,13 +187,46 @@ int cada_run(cada_ctx *ctx, const int32_t *idx_sched, const uint8_t *replay_sche
 int cada_run_replicas(cada_ctx *const *ctxs, int32_t n_replicas, const int32_t *const *idx_scheds,
                       const uint8_t *const *replay_scheds, int64_t n_steps);
 
-/* Fills *out with device pointers and host counters.  Does not synchronise:
- * read the device memory after synchronising the stream. */
+/* Fills *out with device pointers and host counters.  Enqueues one small kernel on the context's
+ * stream (it adds the last step's partial sums of |theta^{k+1} - theta^k|^2 into its ring slot, which
+ * the next step would otherwise do) and does not synchronise: read the device memory after
+ * synchronising the stream. */
 int cada_get_state(cada_ctx *ctx, cada_state *out);
 
 /* Enqueues a copy of the M stored (possibly stale) gradients, one row per
  * worker, into out (DEVICE float32 [M, p]). */
 int cada_copy_stored_gradients(cada_ctx *ctx, float *out);
+
+/* The state of Algorithm 1 before iteration k as explicit arrays: the iterate and the moments of
+ * equations (CADA-1)-(CADA-3), the stored stale gradients nabla l(theta-hat_m; xi-hat_m) that
+ * nabla^k sums (Section 1.2), each worker's reference point (CADA2: theta-hat_m = theta^{k - tau_m},
+ * the iterate of its last upload; CADA1: the snapshot theta-tilde and the stored innovations
+ * delta-tilde_m^{k - tau_m} of condition (workerrule1)), the delays tau_m^k and the last d_max
+ * squared steps of the rules' right-hand side.  Every pointer is DEVICE memory owned by the caller,
+ * float32 unless stated, read by kernels that cada_set_state enqueues on the context's stream (no
+ * host synchronisation; the arrays may be released once the stream has passed the call). */
+typedef struct cada_state_in {
+  int64_t k;                       /* the iteration the next cada_step performs, >= 0 */
+  const float *theta;              /* [p] */
+  const float *theta_lo;           /* [p] or NULL (zeros): the iterate is theta + theta_lo */
+  const float *h, *vhat;           /* [p]; v is an output of a step, not state */
+  const float *stored_gradients;   /* [M, p] */
+  const float *reference;          /* CADA2: [M, p], row m = theta^{k - tau_m}; workers with equal tau_m must
+                                      hold equal rows (they uploaded at the same iteration).  CADA1: [p], the
+                                      snapshot.  Other rules: ignored, may be NULL */
+  const float *reference_lo;       /* same shape, or NULL (zeros): low parts as for theta_lo */
+  const float *stored_innovations; /* CADA1: [M, p]; other rules: ignored, may be NULL */
+  const int32_t *tau;              /* int32 [M], each in [1, D]; a value outside sets bit 2 of error_flags and is clamped */
+  const float *ring;               /* [d_max], slot j mod d_max = |theta^{j+1} - theta^j|^2 for the last d_max j < k */
+  uint64_t uploads_total;          /* uploads counted so far */
+} cada_state_in;
+
+/* Replaces the context's state by *in and sets its step counter to in->k, so that the following
+ * steps continue Algorithm 1 from that state (resume from arrays that another implementation, or
+ * cada_get_state / cada_copy_stored_gradients of another context, produced).  The per-step trace
+ * keeps what it holds; steps k >= trace_steps are not traced.  Returns CADA_EINVAL (and changes
+ * nothing) if a required pointer is NULL or k < 0. */
+int cada_set_state(cada_ctx *ctx, const cada_state_in *in);
 
 /* Evaluation on all the data at the current iterate (the y-axes of the figures of Section 4):
  * out[0] = L(theta) = (1/M) sum_m L_m(theta), L_m the mean loss over worker m's N_m samples

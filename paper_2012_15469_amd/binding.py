@@ -25,6 +25,7 @@ RULE_CADA1, RULE_CADA2 = 1, 2
 MODEL_LOGREG, MODEL_MLP = 0, 1
 GEMM_FP32, GEMM_BF16 = 0, 1
 REPLAY_FREE = 255
+PATH_AUTO, PATH_TWO_PASS, PATH_SINGLE_PASS, PATH_WHOLE_STEPS = 0, 1, 2, 3
 
 
 class cada_config(C.Structure):
@@ -34,7 +35,8 @@ class cada_config(C.Structure):
                 ("alpha", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
                 ("lambda_l2", C.c_double), ("c", C.c_double), ("d_max", C.c_int32), ("D", C.c_int32),
                 ("rule", C.c_int32), ("gemm_dtype", C.c_int32), ("server", C.c_int32), ("alpha_K0", C.c_int64), ("trace_steps", C.c_int64),
-                ("whole_steps", C.c_int32),
+                ("path", C.c_int32), ("single_pass_rows", C.c_int32), ("single_pass_clusters", C.c_int32),
+                ("plain_launch", C.c_int32), ("two_pass_group", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
@@ -59,6 +61,15 @@ _lib.cada_get_state.restype = C.c_int
 _lib.cada_get_state.argtypes = [C.c_void_p, C.POINTER(cada_state)]
 _lib.cada_copy_stored_gradients.restype = C.c_int
 _lib.cada_copy_stored_gradients.argtypes = [C.c_void_p, C.c_void_p]
+class cada_state_in(C.Structure):
+    _fields_ = [("k", C.c_int64)] + \
+               [(n, C.c_void_p) for n in ("theta", "theta_lo", "h", "vhat", "stored_gradients", "reference", "reference_lo",
+                                           "stored_innovations", "tau", "ring")] + \
+               [("uploads_total", C.c_uint64)]
+
+
+_lib.cada_set_state.restype = C.c_int
+_lib.cada_set_state.argtypes = [C.c_void_p, C.POINTER(cada_state_in)]
 _lib.cada_eval.restype = C.c_int
 _lib.cada_eval.argtypes = [C.c_void_p, C.c_void_p]
 _lib.cada_checkpoint_bytes.restype = C.c_size_t
@@ -125,6 +136,10 @@ def cada_copy_stored_gradients(ctx: int, out_ptr: int):
     _check(_lib.cada_copy_stored_gradients(ctx, out_ptr))
 
 
+def cada_set_state(ctx: int, st: cada_state_in):
+    _check(_lib.cada_set_state(ctx, C.byref(st)))
+
+
 def cada_profile_begin(ctx: int, max_steps: int):
     _check(_lib.cada_profile_begin(ctx, max_steps))
 
@@ -180,7 +195,8 @@ class Cada:
                  X: torch.Tensor, y: torch.Tensor, theta0: torch.Tensor, rule: int, D: int, d_max: int,
                  c: float, alpha: float, beta1: float, beta2: float, eps: float, lam: float = 0.0,
                  gemm_dtype: str = "fp32", trace_steps: int = 0, stream: Optional[torch.cuda.Stream] = None,
-                 server: int = 0, alpha_K0: int = 0, whole_steps: bool = False):
+                 server: int = 0, alpha_K0: int = 0, whole_steps: bool = False, path: int = PATH_AUTO,
+                 single_pass_rows: int = 0, single_pass_clusters: int = 0, plain_launch: bool = False, two_pass_group: int = 0):
         assert X.is_cuda and y.is_cuda and theta0.is_cuda
         assert X.dtype == torch.float32 and X.is_contiguous() and theta0.dtype == torch.float32
         assert y.dtype == (torch.float32 if model == "logreg" else torch.int32) and y.is_contiguous()
@@ -202,7 +218,9 @@ class Cada:
         cfg.server = server
         cfg.alpha_K0 = alpha_K0
         cfg.trace_steps = trace_steps
-        cfg.whole_steps = 1 if whole_steps else 0
+        cfg.path = PATH_WHOLE_STEPS if whole_steps else path
+        cfg.single_pass_rows, cfg.single_pass_clusters = single_pass_rows, single_pass_clusters
+        cfg.plain_launch, cfg.two_pass_group = (1 if plain_launch else 0), two_pass_group
         cfg.stream = self.stream.cuda_stream
         nbytes = cada_workspace_bytes(cfg)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=X.device)
@@ -284,6 +302,28 @@ class Cada:
         out = torch.empty(self.M, self.p, dtype=torch.float32, device=self.workspace.device)
         cada_copy_stored_gradients(self.ctx, out.data_ptr())
         return out
+
+    def set_state(self, *, k: int, theta, h, vhat, stored_gradients, tau, ring, uploads_total: int = 0, theta_lo=None,
+                  reference=None, reference_lo=None, stored_innovations=None):
+        """Replaces the state by explicit device arrays (see cada_set_state): float32 tensors of the
+        shapes documented in cada.h, tau int32."""
+        M, p = self.M, self.p
+        def ptr(t, n, dtype=torch.float32):
+            if t is None:
+                return None
+            assert t.is_cuda and t.dtype == dtype and t.is_contiguous() and t.numel() == n, (t.shape, t.dtype, n)
+            return t.data_ptr()
+        st = cada_state_in()
+        st.k = k
+        st.theta, st.theta_lo, st.h, st.vhat = ptr(theta, p), ptr(theta_lo, p), ptr(h, p), ptr(vhat, p)
+        st.stored_gradients = ptr(stored_gradients, M * p)
+        nref = M * p if self.cfg.rule == RULE_CADA2 else p
+        st.reference, st.reference_lo = ptr(reference, nref), ptr(reference_lo, nref)
+        st.stored_innovations = ptr(stored_innovations, M * p)
+        st.tau, st.ring = ptr(tau, M, torch.int32), ptr(ring, self.d_max)
+        st.uploads_total = uploads_total
+        cada_set_state(self.ctx, st)
+        self.k = k
 
     def evaluate(self) -> torch.Tensor:
         """DEVICE float64 [2]: objective L(theta) and accuracy on all the data (see cada_eval)."""

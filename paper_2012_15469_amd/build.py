@@ -26,7 +26,15 @@ def _run(cmd):
 
 
 def build_libcada() -> str:
-    _run([HIPCC, *HIP_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIBCADA, *LIBCADA_SRC])
+    """Compiles the translation units side by side (objects in a temporary folder), then links."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    compile_flags = [f for f in HIP_FLAGS if f != "-shared"] + ["-c", "-I", os.path.join(ROOT, "include")]
+    with tempfile.TemporaryDirectory(prefix="libcada_build_") as tmp:
+        objs = [os.path.join(tmp, os.path.basename(src) + ".o") for src in LIBCADA_SRC]
+        with ThreadPoolExecutor(max_workers=min(len(objs), os.cpu_count() or 1)) as pool:
+            list(pool.map(lambda so: _run([HIPCC, *compile_flags, "-o", so[1], so[0]]), zip(LIBCADA_SRC, objs)))
+        _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIBCADA, *objs])
     return LIBCADA
 
 

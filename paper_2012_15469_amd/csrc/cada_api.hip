@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -74,6 +75,8 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   if (cfg->rule < CADA_RULE_ALWAYS || cfg->rule > CADA_RULE_LAG) { set_error("rule must be one of CADA_RULE_* (got %d)", cfg->rule); return false; }
   if (cfg->server != CADA_SERVER_AMSGRAD && cfg->server != CADA_SERVER_SGD) { set_error("server must be one of CADA_SERVER_* (got %d)", cfg->server); return false; }
   if (cfg->model != CADA_MODEL_LOGREG && cfg->model != CADA_MODEL_MLP) { set_error("unknown model %d", cfg->model); return false; }
+  if (cfg->path < CADA_PATH_AUTO || cfg->path > CADA_PATH_WHOLE_STEPS) { set_error("path must be one of CADA_PATH_* (got %d)", cfg->path); return false; }
+  if (cfg->single_pass_rows < 0 || cfg->single_pass_rows > 1 || cfg->single_pass_clusters < 0 || cfg->two_pass_group < 0) { set_error("negative tuning field"); return false; }
   if (!cfg->layer_dims) { set_error("layer_dims is NULL"); return false; }
   if (!cfg->n_samples) { set_error("n_samples is NULL"); return false; }
   if (cfg->trace_steps < 0) { set_error("trace_steps must be >= 0"); return false; }
@@ -187,6 +190,77 @@ __global__ void k_gather_stored(const DevState s, float *out) {
   if (i < s.p) out[(int64_t)m * s.p + i] = s.gbuf[((int64_t)s.sel[m] * s.M + m) * s.p + i];
 }
 
+// cada_set_state, [p]-sized part: iterate, moments, and the reference point that is one vector
+// (CADA1: the snapshot; CADA2: slot k mod R of the retained iterates holds theta^k itself).
+struct SetStateArgs {
+  DevState s;
+  cada_state_in in;
+};
+
+__global__ __launch_bounds__(kBlock) void k_set_vectors(const SetStateArgs a) {
+  const DevState &s = a.s;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
+    const float th = a.in.theta[i], tl = a.in.theta_lo ? a.in.theta_lo[i] : 0.f;
+    s.theta[i] = th; s.theta_lo[i] = tl;
+    s.h[i] = a.in.h[i]; s.vhat[i] = a.in.vhat[i]; s.v[i] = a.in.vhat[i];
+    if (s.rule == CADA_RULE_CADA2) {
+      const int64_t slot = a.in.k % s.R;
+      s.hist[slot * s.p + i] = th; s.hist_lo[slot * s.p + i] = tl;
+    } else if (s.rule == CADA_RULE_CADA1) {
+      s.snap[i] = a.in.reference[i];
+      s.snap_lo[i] = a.in.reference_lo ? a.in.reference_lo[i] : 0.f;
+    }
+  }
+}
+
+// cada_set_state, [M, p]-sized part; grid (blocks, M).  Stored gradients (and CADA1's stored
+// innovations) go to buffer 0 of worker m, which the small kernel below makes the selected one.
+// CADA2: theta-hat_m goes to the slot of theta^{k - tau_m}; among workers with the same delay
+// the first one writes it.
+__global__ __launch_bounds__(kBlock) void k_set_rows(const SetStateArgs a) {
+  const DevState &s = a.s;
+  __shared__ int dup;
+  const int m = blockIdx.y;
+  const int64_t row = (int64_t)m * s.p;
+  int64_t slot = -1;
+  if (s.rule == CADA_RULE_CADA2) {
+    const int32_t tau_m = min(max(a.in.tau[m], 1), s.D);
+    if (threadIdx.x == 0) dup = 0;
+    __syncthreads();
+    for (int j = threadIdx.x; j < m; j += kBlock)
+      if (min(max(a.in.tau[j], 1), s.D) == tau_m) dup = 1;       // (every writer writes the same value)
+    __syncthreads();
+    if (!dup) {
+      slot = (a.in.k - tau_m) % s.R;
+      if (slot < 0) slot += s.R;
+    }
+  }
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
+    s.gbuf[row + i] = a.in.stored_gradients[row + i];
+    if (s.rule == CADA_RULE_CADA1) s.dtl[row + i] = a.in.stored_innovations[row + i];
+    if (slot >= 0) {
+      s.hist[slot * s.p + i] = a.in.reference[row + i];
+      s.hist_lo[slot * s.p + i] = a.in.reference_lo ? a.in.reference_lo[row + i] : 0.f;
+    }
+  }
+}
+
+// cada_set_state, the small pieces: delays, buffer selectors, the squared steps (the newest one
+// is kept as partial sums that the next rule evaluation adds up: all of it goes to the first), counters.
+__global__ __launch_bounds__(kBlock) void k_set_small(const SetStateArgs a, int n_ring_cap) {
+  const DevState &s = a.s;
+  for (int m = threadIdx.x; m < s.M; m += kBlock) {
+    const int32_t t = a.in.tau[m];
+    if (t < 1 || t > s.D) atomicOr(s.err, 4u);
+    s.tau[m] = min(max(t, 1), s.D);
+    s.sel[m] = 0;
+  }
+  for (int j = threadIdx.x; j < s.d_max; j += kBlock) s.ring[j] = a.in.ring[j];
+  const float newest = a.in.k > 0 ? a.in.ring[(a.in.k - 1) % s.d_max] : 0.f;
+  for (int i = threadIdx.x; i < n_ring_cap; i += kBlock) s.ring_part[i] = i == 0 ? newest : 0.f;
+  if (threadIdx.x == 0) *s.uploads = a.in.uploads_total;
+}
+
 #define HIP_TRY(expr)                                                        \
   do {                                                                       \
     hipError_t e_ = (expr);                                                  \
@@ -254,8 +328,9 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   c->n_col_chunks = g.n_col_chunks;
   c->chunk_cols = g.chunk_cols;
   c->ws_bytes = need;
+  c->ring_cap = g.ring_cap;
   c->ws_base = cfg->workspace;
-  if (const char *e = getenv("CADA_LOGREG_GROUP")) c->logreg_group = atoi(e);   // tuning knob
+  c->logreg_group = cfg->two_pass_group > 0 ? cfg->two_pass_group : 0;
   Carver w{static_cast<char *>(cfg->workspace)};
   carve_common(w, cfg, g, &s, c);
   s.X = cfg->X; s.y = cfg->y;
@@ -267,8 +342,10 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   s.omb1 = (float)(1.0 - cfg->beta1); s.omb2 = (float)(1.0 - cfg->beta2);
   s.eps = (float)cfg->eps; s.lam = (float)cfg->lambda_l2; s.c = cfg->c;
   if (cfg->model == CADA_MODEL_LOGREG) {
-    if (fused_plan(c, cfg->p, cfg->B, cfg->M)) s.n_lhs_part = 4 * c->fused_Q;
-    else if (small_plan(c, cfg->p, cfg->B, cfg->M, cfg->whole_steps != 0)) s.n_ring_part = cfg->M;
+    // the requested path first; a request that the shape does not allow falls back to the others
+    if (cfg->path == CADA_PATH_WHOLE_STEPS && small_plan(c, cfg)) s.n_ring_part = cfg->M;
+    else if (cfg->path != CADA_PATH_TWO_PASS && fused_plan(c, cfg)) s.n_lhs_part = 4 * c->fused_Q;
+    else if (cfg->path == CADA_PATH_AUTO && small_plan(c, cfg)) s.n_ring_part = cfg->M;
     if (c->small) {
       c->n_phases = 1; c->phase_names[0] = "logreg_whole_steps";
     } else if (c->fused) {
@@ -293,6 +370,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   auto fail = [&](hipError_t e, const char *what) {
     set_error("%s failed: %s", what, hipGetErrorString(e));
     mlp_free(c);
+    small_free(c);
     delete h;
     return CADA_EHIP;
   };
@@ -312,6 +390,10 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   if (cfg->model == CADA_MODEL_MLP) {
     const int rc = mlp_init_state(c, theta0);
     if (rc != CADA_OK) { mlp_free(c); delete h; return rc; }
+  } else {
+    int rc = logreg_init(c);
+    if (rc == CADA_OK) rc = small_publish_args(c);
+    if (rc != CADA_OK) { small_free(c); delete h; return rc; }
   }
   *out = h;
   return CADA_OK;
@@ -364,7 +446,7 @@ int cada_run_replicas(cada_ctx *const *ctxs, int32_t n_replicas, const int32_t *
     cs[r] = &ctxs[r]->c;
     for (int q = 0; q < r; ++q)
       if (cs[q] == cs[r]) { set_error("replica %d: the same context twice", r); return CADA_EINVAL; }
-    if (!cs[r]->small) { set_error("replica %d does not run whole iterations in one launch (initialise a logistic workload with whole_steps = 1)", r); return CADA_EUNSUPPORTED; }
+    if (!cs[r]->small) { set_error("replica %d does not run whole iterations in one launch (initialise a logistic workload with path = CADA_PATH_WHOLE_STEPS)", r); return CADA_EUNSUPPORTED; }
     const DevState &a = cs[0]->s, &b = cs[r]->s;
     if (a.M != b.M || a.p != b.p || a.B != b.B || a.rule != b.rule || cs[0]->stream != cs[r]->stream) {
       set_error("replica %d differs from replica 0 in M, p, B, rule or stream", r);
@@ -398,6 +480,35 @@ int cada_copy_stored_gradients(cada_ctx *ctx, float *out) {
   const int tb = 256;
   hipLaunchKernelGGL(k_gather_stored, dim3((unsigned)((c->s.p + tb - 1) / tb), c->s.M), dim3(tb), 0, c->stream, c->s, out);
   HIP_TRY(hipGetLastError());
+  return CADA_OK;
+}
+
+int cada_set_state(cada_ctx *ctx, const cada_state_in *in) {
+  if (!ctx || !in) { set_error("ctx/in is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  const DevState &s = c->s;
+  if (in->k < 0) { set_error("cada_set_state: k must be >= 0"); return CADA_EINVAL; }
+  if (!in->theta || !in->h || !in->vhat || !in->stored_gradients || !in->tau || !in->ring) {
+    set_error("cada_set_state: theta, h, vhat, stored_gradients, tau and ring are required");
+    return CADA_EINVAL;
+  }
+  if ((s.rule == CADA_RULE_CADA1 || s.rule == CADA_RULE_CADA2) && !in->reference) {
+    set_error("cada_set_state: reference is required for the CADA rules");
+    return CADA_EINVAL;
+  }
+  if (s.rule == CADA_RULE_CADA1 && !in->stored_innovations) {
+    set_error("cada_set_state: stored_innovations is required for CADA1");
+    return CADA_EINVAL;
+  }
+  SetStateArgs a;
+  a.s = s;
+  a.in = *in;
+  const unsigned pb = (unsigned)std::min<int64_t>((s.p + kBlock - 1) / kBlock, 4096);
+  hipLaunchKernelGGL(k_set_vectors, dim3(pb), dim3(kBlock), 0, c->stream, a);
+  hipLaunchKernelGGL(k_set_rows, dim3(std::min(pb, 1024u), (unsigned)s.M), dim3(kBlock), 0, c->stream, a);
+  hipLaunchKernelGGL(k_set_small, dim3(1), dim3(kBlock), 0, c->stream, a, c->ring_cap);
+  HIP_TRY(hipGetLastError());
+  c->k = in->k;
   return CADA_OK;
 }
 
@@ -457,6 +568,10 @@ int cada_checkpoint_load(cada_ctx *ctx, const void *src) {
   c->k = h.k;
   c->fused_seq = h.fused_seq;
   c->small_seq = h.small_seq;
+  // (the image holds the saving context's launch arguments, which point into its workspace)
+  const int rc = small_publish_args(c);
+  if (rc != CADA_OK) return rc;
+  HIP_TRY(hipStreamSynchronize(c->stream));
   return CADA_OK;
 }
 
@@ -526,6 +641,7 @@ void cada_destroy(cada_ctx *ctx) {
   if (!ctx) return;
   prof_drop(&ctx->c);
   mlp_free(&ctx->c);
+  small_free(&ctx->c);
   delete ctx;
 }
 

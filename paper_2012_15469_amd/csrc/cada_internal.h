@@ -107,6 +107,7 @@ struct Ctx {
   int64_t chunk_cols;
   float *zpart;              // [M][B][n_col_chunks][2]
   int n_server_blocks;
+  int ring_cap;               // entries of ring_part in the workspace
   // single-pass (register-resident) logistic path, cada_logreg_fused.hip
   int fused, fused_Q, fused_clusters, fused_rs, fused_plain_launch;
   int64_t fused_cols;
@@ -117,7 +118,8 @@ struct Ctx {
   size_t small_lds;
   uint32_t *small_bar;       // grid barrier counter in the workspace
   uint32_t small_seq;        // its value after everything enqueued so far
-  void *small_args;          // room in the workspace for this context's arguments of a replica launch
+  void *small_args;          // room in the workspace for this context's launch-invariant arguments (replica launches)
+  void *small_args_host;     // their host copy (owned by the context)
   // full-data evaluation scratch (cada_eval)
   double *eval_part;         // [M][kEvalBlocks][2] per-block sums of (loss, correct)
   double *eval_acc;          // [M][2]
@@ -135,12 +137,15 @@ void prof_mark(Ctx *c);
 
 // S1+S2 for the logistic model: fresh gradients into gbuf[1-sel], left-hand sides into lhs_part.
 int logreg_gradients(Ctx *c, const int32_t *idx);
-bool fused_plan(Ctx *c, int64_t p, int B, int M);
+bool fused_plan(Ctx *c, const cada_config *cfg);
 int logreg_gradients_fused(Ctx *c, const int32_t *idx);
 int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps);
 int small_steps_replicas(Ctx *const *cs, int n, const int32_t *const *idx, const uint8_t *const *replay, int64_t n_steps);
 constexpr size_t kSmallArgsBytes = 1024;    // >= sizeof(SmallArgs), checked where it is defined
-bool small_plan(Ctx *c, int64_t p, int B, int M, bool prefer);
+bool small_plan(Ctx *c, const cada_config *cfg);
+int small_publish_args(Ctx *c);             // after the state pointers are final, and after a checkpoint was loaded
+void small_free(Ctx *c);
+int logreg_init(Ctx *c);                    // LDS allowance of the two-pass kernels
 constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgroups x 4 buffers x 16 values
 // S1+S2 for the MLP.
 int mlp_gradients(Ctx *c, const int32_t *idx);

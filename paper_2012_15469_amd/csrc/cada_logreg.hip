@@ -219,6 +219,16 @@ __global__ __launch_bounds__(kBlock) void k_grad(const LogregArgs a) {
   if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + blockIdx.x] = tot;
 }
 
+// The second pass keeps row offsets and residuals of the B rows in dynamic LDS: 16 bytes per row,
+// 64 KB at the largest minibatch, which with the static part needs the allowance raised.
+int logreg_init(Ctx *) {
+  const int lds = CADA_MAX_B * (int)(sizeof(int64_t) + 2 * sizeof(float));
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_grad<4>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_grad<1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) { set_error("hipFuncSetAttribute(LDS size) failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
+  return CADA_OK;
+}
+
 int logreg_gradients(Ctx *c, const int32_t *idx) {
   LogregArgs a;
   a.s = c->s;

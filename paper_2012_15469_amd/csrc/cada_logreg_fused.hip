@@ -514,10 +514,10 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
 }
 
 // Chooses the cluster geometry; returns false if the single-pass path does not apply.
-bool fused_plan(Ctx *c, int64_t p, int B, int M) {
+bool fused_plan(Ctx *c, const cada_config *cfg) {
   c->fused = 0;
-  const char *on = getenv("CADA_FUSED");
-  if (on && atoi(on) == 0) return false;
+  const int64_t p = cfg->p;
+  const int B = cfg->B, M = cfg->M;
   if (c->vec != 4 || p < 8192) return false;
   int dev = 0, coop = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
@@ -527,9 +527,7 @@ bool fused_plan(Ctx *c, int64_t p, int B, int M) {
   int Q = (int)((p + per_block - 1) / per_block);
   if (Q > F_QMAX || Q > cus) return false;
   int R = (B % 2 == 0) ? 2 : 1;                            // rows per iteration
-  if (const char *e = getenv("CADA_FUSED_ROWS")) {         // tuning / test knob
-    if (atoi(e) == 1) R = 1;
-  }
+  if (cfg->single_pass_rows == 1) R = 1;
   const void *fn = R == 2 ? reinterpret_cast<const void *>(k_fused<2>) : reinterpret_cast<const void *>(k_fused<1>);
   const size_t lds = R == 2 ? FusedGeom<2>::lds : FusedGeom<1>::lds;
   if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -546,18 +544,14 @@ bool fused_plan(Ctx *c, int64_t p, int B, int M) {
   int ncl = cus / Q;                       // one workgroup per CU
   if (ncl < 1) return false;
   ncl = min(ncl, M);
-  if (const char *e = getenv("CADA_FUSED_CLUSTERS")) {     // tuning / test knob: fewer, longer-lived clusters
-    const int want = atoi(e);
-    if (want >= 1 && want < ncl) ncl = want;
-  }
+  if (cfg->single_pass_clusters >= 1 && cfg->single_pass_clusters < ncl) ncl = cfg->single_pass_clusters;
   if ((size_t)ncl * F_NP * F_V * Q > kFusedPostWords) return false;
   c->fused = 1;
   c->fused_Q = Q;
   c->fused_clusters = ncl;
   c->fused_cols = ((p + Q - 1) / Q + 3) / 4 * 4;
   c->fused_rs = R;
-  const char *plain = getenv("CADA_FUSED_PLAIN_LAUNCH");
-  c->fused_plain_launch = (plain && atoi(plain) != 0) ? 1 : 0;
+  c->fused_plain_launch = cfg->plain_launch != 0 ? 1 : 0;
   const int nslab = B;
   c->fused_seq_per_step = (uint32_t)(((M + ncl - 1) / ncl) * nslab);
   return true;
@@ -574,7 +568,6 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
   a.cols_per_block = c->fused_cols;
   a.seq_base = c->fused_seq;
   a.spin_limit = 2000000u;
-  c->fused_seq += c->fused_seq_per_step;
   void *args[] = {&a};
   prof_mark(c);
   hipError_t e;
@@ -597,6 +590,7 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
     set_error("fused logistic gradient launch failed: %s", hipGetErrorString(e));
     return CADA_EHIP;
   }
+  c->fused_seq += c->fused_seq_per_step;      // (the tags advance only with a launch that was accepted)
   return CADA_OK;
 }
 

@@ -13,7 +13,8 @@
 // A barrier is an agent-scope counter in the workspace; arrivals release (write back) and
 // departures acquire (invalidate) the XCD-local caches.  Every wait is bounded: a wait that
 // exceeds the bound sets bit 1 of the error flags and the workgroup stops waiting.
-#include <cstdlib>
+#include <cstring>
+#include <new>
 
 #include "cada_internal.h"
 
@@ -31,12 +32,23 @@ struct SmallArgs {
 static_assert(sizeof(SmallArgs) <= kSmallArgsBytes, "room kept in the workspace for a replica launch");
 
 // One launch serves one run (its arguments by value) or several independent runs (blockIdx.y
-// picks the run; each run's arguments lie in its own workspace).
+// picks the run).  A run's arguments that do not change from launch to launch (where its state
+// lies) are kept in its own workspace, written once when the context is set up; what changes
+// (schedules, iteration, barrier count) travels by value with the launch.
+struct SmallVar {
+  const int32_t *idx;
+  const uint8_t *replay;
+  int64_t k;
+  uint32_t bar_base;
+};
 struct SmallLaunch {
   SmallArgs one;
   const SmallArgs *rep[CADA_MAX_REPLICAS];
+  SmallVar var[CADA_MAX_REPLICAS];
+  int64_t n_steps;
   int n_rep;                 // 0: `one`
 };
+static_assert(sizeof(SmallLaunch) <= 4096, "kernel arguments");
 
 __device__ __forceinline__ float sigmoid_s(float a) { return 1.0f / (1.0f + expf(-a)); }
 
@@ -62,7 +74,11 @@ __device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target
 // load independent of the others, and both passes over them run from LDS
 __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   extern __shared__ __align__(16) unsigned char small_smem[];
-  const SmallArgs a = launch.n_rep ? *launch.rep[blockIdx.y] : launch.one;
+  SmallArgs a = launch.n_rep ? *launch.rep[blockIdx.y] : launch.one;
+  if (launch.n_rep) {
+    const SmallVar &v = launch.var[blockIdx.y];
+    a.idx = v.idx; a.replay = v.replay; a.s.k = v.k; a.bar_base = v.bar_base; a.n_steps = launch.n_steps;
+  }
   DevState s = a.s;
   const int p = (int)s.p, B = s.B, M = s.M;
   float *th_s = reinterpret_cast<float *>(small_smem);     // [p] theta (hi part + lo part rounded once)
@@ -272,6 +288,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
         atomicAdd(reinterpret_cast<unsigned long long *>(s.uploads), 1ull);
       } else {
         s.tau[m] = tau + 1;
+        if (s.rule == CADA_RULE_CADA2 && tau >= s.D) atomicOr(s.err, 8u);   // (a replay mask outlasting the retained iterates)
       }
       bcast[0] = newest;
     }
@@ -321,16 +338,15 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
 }
 
 // Whether the multi-step kernel serves this configuration; sets the ring-partial count it uses.
-bool small_plan(Ctx *c, int64_t p, int B, int M, bool prefer) {
+bool small_plan(Ctx *c, const cada_config *cfg) {
   c->small = 0;
-  const char *on = getenv("CADA_SMALL");
-  if (on && atoi(on) == 0) return false;
+  const int64_t p = cfg->p;
+  const int B = cfg->B, M = cfg->M;
   if (p >= 8192) return false;
   // Measured: 16 us per step against 36 us for M = 10, B = 10, p = 54, but 73 us against 39 us for
   // M = 20, B = 32, p = 784 (20 workgroups cannot hide the latency of their dependent loads, and
   // each barrier invalidates the XCD's L2): only the tiny problems take this path unless asked to.
-  const char *force = getenv("CADA_SMALL");
-  if (!prefer && !(force && atoi(force) == 1) && (int64_t)M * B * p > 32768) return false;
+  if (cfg->path != CADA_PATH_WHOLE_STEPS && (int64_t)M * B * p > 32768) return false;
   int dev = 0, coop = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
@@ -346,6 +362,8 @@ bool small_plan(Ctx *c, int64_t p, int B, int M, bool prefer) {
   return true;
 }
 
+constexpr uint32_t kSmallSpinLimit = 4000000u;
+
 static SmallArgs small_args_of(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_steps) {
   SmallArgs a;
   a.s = c->s;
@@ -355,9 +373,28 @@ static SmallArgs small_args_of(Ctx *c, const int32_t *idx, const uint8_t *replay
   a.n_steps = n_steps;
   a.bar = c->small_bar;
   a.bar_base = c->small_seq;
-  a.spin_limit = 4000000u;
-  c->small_seq += (uint32_t)(2 * n_steps * c->s.M);
+  a.spin_limit = kSmallSpinLimit;
   return a;
+}
+
+// Writes the launch-invariant arguments of this context into its workspace (for replica launches).
+// The source is host memory that lives as long as the context.
+int small_publish_args(Ctx *c) {
+  if (!c->small) return CADA_OK;
+  if (!c->small_args_host) {
+    c->small_args_host = new (std::nothrow) unsigned char[sizeof(SmallArgs)];
+    if (!c->small_args_host) { set_error("out of host memory"); return CADA_EINVAL; }
+  }
+  const SmallArgs a = small_args_of(c, nullptr, nullptr, 0);
+  memcpy(c->small_args_host, &a, sizeof(a));
+  const hipError_t e = hipMemcpyAsync(c->small_args, c->small_args_host, sizeof(SmallArgs), hipMemcpyHostToDevice, c->stream);
+  if (e != hipSuccess) { set_error("copy of launch arguments failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
+  return CADA_OK;
+}
+
+void small_free(Ctx *c) {
+  delete[] static_cast<unsigned char *>(c->small_args_host);
+  c->small_args_host = nullptr;
 }
 
 int small_steps_replicas(Ctx *const *cs, int n, const int32_t *const *idx, const uint8_t *const *replay, int64_t n_steps) {
@@ -370,12 +407,10 @@ int small_steps_replicas(Ctx *const *cs, int n, const int32_t *const *idx, const
   if ((int64_t)n * c0->s.M > cus) { set_error("n_replicas x M = %lld workgroups exceed the %d CUs that must hold them at once", (long long)n * c0->s.M, cus); return CADA_EINVAL; }
   SmallLaunch l{};
   l.n_rep = n;
+  l.n_steps = n_steps;
   for (int r = 0; r < n; ++r) {
-    // (a pageable source: the copy is staged before the call returns)
-    const SmallArgs a = small_args_of(cs[r], idx[r], replay ? replay[r] : nullptr, n_steps);
-    const hipError_t e = hipMemcpyAsync(cs[r]->small_args, &a, sizeof(a), hipMemcpyHostToDevice, c0->stream);
-    if (e != hipSuccess) { set_error("copy of replica arguments failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
     l.rep[r] = static_cast<const SmallArgs *>(cs[r]->small_args);
+    l.var[r] = SmallVar{idx[r], replay ? replay[r] : nullptr, cs[r]->k, cs[r]->small_seq};
   }
   void *args[] = {&l};
   prof_mark(c0);
@@ -386,6 +421,8 @@ int small_steps_replicas(Ctx *const *cs, int n, const int32_t *const *idx, const
     set_error("replica launch failed: %s", hipGetErrorString(e));
     return CADA_EHIP;
   }
+  // (the barrier counters advance only with a launch that was accepted)
+  for (int r = 0; r < n; ++r) cs[r]->small_seq += (uint32_t)(2 * n_steps * cs[r]->s.M);
   return CADA_OK;
 }
 
@@ -401,6 +438,7 @@ int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_ste
     set_error("multi-step logistic launch failed: %s", hipGetErrorString(e));
     return CADA_EHIP;
   }
+  c->small_seq += (uint32_t)(2 * n_steps * c->s.M);
   return CADA_OK;
 }
 

@@ -1137,30 +1137,34 @@ template <int EPI, int NA, int NB, bool HAS_D> hipError_t mm5_allow_lds() {
   return hipFuncSetAttribute(reinterpret_cast<const void *>(k_mm5<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)mm5_lds_bytes(EPI));
 }
-template <int EPI, int NA, int NB, bool HAS_D> void launch_mm5_as(Ctx *c, const Mm5Args &g) {
+template <int EPI, int NA, int NB, bool HAS_D> int launch_mm5_as(Ctx *c, const Mm5Args &g) {
   // one workgroup per CU at most (8 XCDs x 32 CUs), each XCD's tiles dealt over its workgroups
   const int total = ((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM) * g.workers, per = (total + 7) / 8;
   const dim3 grid(8 * (per < 32 ? per : 32));
   hipLaunchKernelGGL((k_mm5<EPI, NA, NB, HAS_D>), grid, dim3(2 * kBlock), mm5_lds_bytes(EPI), c->stream, g);
+  return CADA_OK;
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
 template <int EPI, int NA, int NB, bool HAS_D> hipError_t skinny_allow_lds() {
   return hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
 }
-template <int EPI, int NA, int NB, bool HAS_D> void launch_skinny_as(Ctx *c, const Mm5Args &g) {
+template <int EPI, int NA, int NB, bool HAS_D> int launch_skinny_as(Ctx *c, const Mm5Args &g) {
   hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(2 * kBlock), 65536, c->stream, g);
+  return CADA_OK;
 }
-template <int EPI> void launch_mm5(Ctx *c, Mm5Args &g, int workers) {
+// Returns CADA_OK after enqueueing the launch, CADA_EUNSUPPORTED (and launches nothing) when the
+// operands do not fit a compiled variant.
+template <int EPI> int launch_mm5(Ctx *c, Mm5Args &g, int workers) {
   g.workers = workers;
   const bool has_d = g.a_d >= 0;
   if constexpr (EPI == EPI_STORE2 || EPI == EPI_DW) {
     if (g.N <= 32) {            // at most 32 output columns (the last layer)
       for (int i = 1; i < g.A.n; ++i)
-        if (g.A.kt[i] != g.A.kt[0]) { set_error("internal: A tensors with different chunk counts"); return; }
+        if (g.A.kt[i] != g.A.kt[0]) { set_error("internal: A tensors with different chunk counts"); return CADA_EUNSUPPORTED; }
       if (g.a_h != 0 || g.a_l != 1 || (has_d && g.a_d != 2) || g.a_r != (g.A.n == 4 ? 3 : 0) || g.b_h != 0 || g.b_l != 1 ||
           (has_d && g.b_x != (g.B.n == 4 ? 2 : 0)) || g.b_d != g.B.n - 1) {
         set_error("internal: unexpected tensor roles");
-        return;
+        return CADA_EUNSUPPORTED;
       }
       if (EPI == EPI_DW) {
         if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_skinny_as<EPI, 2, 3, false>(c, g);
@@ -1173,9 +1177,9 @@ template <int EPI> void launch_mm5(Ctx *c, Mm5Args &g, int workers) {
   }
   // every tensor must hold the chunks the tile steps walk through
   for (int i = 0; i < g.A.n; ++i)
-    if (g.A.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: A tensor with fewer chunks than tile steps"); return; }
+    if (g.A.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: A tensor with fewer chunks than tile steps"); return CADA_EUNSUPPORTED; }
   for (int i = 0; i < g.B.n; ++i)
-    if (g.B.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: B tensor with fewer chunks than tile steps"); return; }
+    if (g.B.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: B tensor with fewer chunks than tile steps"); return CADA_EUNSUPPORTED; }
   if constexpr (EPI == EPI_DW) {
     if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g);
     if (has_d && g.A.n == 3 && g.B.n == 4) return launch_mm5_as<EPI, 3, 4, true>(c, g);
@@ -1186,6 +1190,7 @@ template <int EPI> void launch_mm5(Ctx *c, Mm5Args &g, int workers) {
     if (has_d && g.A.n == 4 && g.B.n == 3) return launch_mm5_as<EPI, 4, 3, true>(c, g);
   }
   set_error("internal: no MFMA kernel variant for %d + %d tensors", g.A.n, g.B.n);
+  return CADA_EUNSUPPORTED;
 }
 
 Mm5Args blank(const DevState &s, const MlpPlan &P) {
@@ -1223,7 +1228,7 @@ int mlp_init_state(Ctx *c, const float *) {
 
 // Gathers the minibatch rows, prepares the bf16 weights and runs the forward contractions:
 // leaves the activations of every layer and the logits (without bias) of the last one.
-static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx) {
+static int mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx) {
   hipStream_t st = c->stream;
   const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
@@ -1279,12 +1284,13 @@ static void mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *id
       g.o_h = P.Ah[l]; g.o_l = P.Al[l]; g.o_d = P.dA[l]; g.o_r = P.Aref[l];
       g.t_h = P.AhT[l]; g.t_l = P.AlT[l]; g.t_d = P.dAT[l]; g.t_r = nullptr;
       g.maskbits = P.maskbits[l];
-      launch_mm5<EPI_FWD_HIDDEN>(c, g, M);
+      if (const int rc = launch_mm5<EPI_FWD_HIDDEN>(c, g, M)) return rc;
     } else {
       g.c1 = P.ZL; g.c2 = P.dZL;
-      launch_mm5<EPI_STORE2>(c, g, M);
+      if (const int rc = launch_mm5<EPI_STORE2>(c, g, M)) return rc;
     }
   }
+  return CADA_OK;
 }
 
 int mlp_gradients(Ctx *c, const int32_t *idx) {
@@ -1297,7 +1303,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
   const int64_t dwn_stride = per_worker ? P.wn_total : 0;
 
   prof_mark(c);
-  mlp_forward(c, P, s, idx);
+  if (const int rc = mlp_forward(c, P, s, idx)) return rc;
   {
     LossArgs la;
     la.s = s; la.Z = P.ZL; la.dZ = P.dZL;
@@ -1331,7 +1337,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
         g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
       }
       g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1];
-      launch_mm5<EPI_DW>(c, g, M);
+      if (const int rc = launch_mm5<EPI_DW>(c, g, M)) return rc;
     }
     if (l >= 2) {   // gradient w.r.t. the activations of layer l-1, masks, bias partials
       Mm5Args g = blank(s, P);
@@ -1351,7 +1357,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
       g.t_h = P.GhT[q]; g.t_l = P.GlT[q]; g.t_d = P.dGT[q]; g.t_r = P.GrefT[q];
       g.maskbits = P.maskbits[q];
       g.dbpart = P.dbpart; g.ddbpart = P.ddbpart;
-      launch_mm5<EPI_DA>(c, g, M);
+      if (const int rc = launch_mm5<EPI_DA>(c, g, M)) return rc;
       hipLaunchKernelGGL(k_bias_finish, dim3((din + 255) / 256, M), dim3(kBlock), 0, st, s, P.dbpart, P.ddbpart, 2 * P.RT, din,
                          P.offb[q - 1], P.lhs_b_slot[q - 1]);
     }
@@ -1440,7 +1446,7 @@ int mlp_eval(Ctx *c, double *out) {
   const unsigned nb = (unsigned)(((int64_t)P.M * P.B + 255) / 256);
   for (int ch = 0; ch < chunks; ++ch) {
     hipLaunchKernelGGL(k_eval_idx, dim3(nb), dim3(256), 0, st, s, c->eval_idx, ch);
-    mlp_forward(c, P, s, c->eval_idx);
+    if (const int rc = mlp_forward(c, P, s, c->eval_idx)) return rc;
     hipLaunchKernelGGL(k_eval_chunk, dim3((unsigned)P.M), dim3(kBlock), 0, st, s, P.ZL, P.grow, P.offb[P.L - 1], P.d[P.L], P.Bp, ch, c->eval_acc);
   }
   hipLaunchKernelGGL(k_eval_means, dim3((unsigned)((P.M + 63) / 64)), dim3(64), 0, st, s, c->eval_acc);

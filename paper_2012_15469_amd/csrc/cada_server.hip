@@ -101,6 +101,8 @@ __global__ __launch_bounds__(kBlock) void k_rule(const DevState s, const uint8_t
         atomicAdd(&cnt, 1u);
       } else {
         s.tau[m] = tau + 1;
+        // (only a replay mask can do this: the reference point theta^{k+1-(tau+1)} leaves the D+1 retained iterates)
+        if (s.rule == CADA_RULE_CADA2 && tau >= s.D) atomicOr(s.err, 8u);
       }
     }
   }

@@ -32,12 +32,15 @@ def upload(prob):
     return X, y, to_dev(prob.theta0)
 
 
-def run_library(cfg, dev, sched, replay=None, **kw):
-    """K = len(sched) steps through cada_run; returns the state as numpy arrays."""
-    from paper_2012_15469_amd.binding import Cada
+def run_library(cfg, dev, sched, replay=None, expect_phase=None, **kw):
+    """K = len(sched) steps through cada_run; returns the state as numpy arrays.
+    expect_phase: name of a kernel phase the context must run (the path a test asked for was taken)."""
+    from paper_2012_15469_amd.binding import Cada, cada_profile_phase_names
     X, y, th0 = dev
     K = sched.shape[0]
     eng = Cada.from_config(cfg, X, y, th0, trace_steps=K, **kw)
+    if expect_phase is not None:
+        assert expect_phase in cada_profile_phase_names(eng.ctx), cada_profile_phase_names(eng.ctx)
     idx = to_dev(sched.astype(np.int32))
     rp = None if replay is None else to_dev(np.ascontiguousarray(replay, dtype=np.uint8))
     eng.run(idx, rp)
@@ -80,6 +83,7 @@ def check_protocol(cfg, prob, dev, sched, theta_tol, lhs_rtol=None, own_mask_exa
                 "free run: first mask disagreement at step %d worker %d has oracle margin %.3e" % (kk, m, mg[kk, m]))
     # (ii) replay of the oracle's masks
     rep = run_library(cfg, dev, sched, replay=tr["mask"], **kw)
+    assert rep["error_flags"][0] == 0
     assert np.array_equal(rep["trace_mask"], tr["mask"])
     assert np.array_equal(rep["trace_tau"], tr["tau"])
     own_diff = rep["trace_own_mask"] != tr["own_mask"]
@@ -108,3 +112,35 @@ def check_protocol(cfg, prob, dev, sched, theta_tol, lhs_rtol=None, own_mask_exa
     if report is not None:
         report.update(stats)
     return stats, o, tr, rep
+
+
+def split64(a):
+    """float64 array -> (hi, lo) float32 device tensors with hi + lo = a to ~2^-48 relative."""
+    a = np.asarray(a, dtype=np.float64)
+    hi = a.astype(np.float32)
+    lo = (a - hi.astype(np.float64)).astype(np.float32)
+    return to_dev(hi), to_dev(lo)
+
+
+def inject_oracle_state(eng, o):
+    """Hands the oracle's whole state (before its iteration o.k) to the library through
+    cada_set_state: the library then continues Algorithm 1 from the oracle's own trajectory."""
+    th, tl = split64(o.theta)
+    kw = dict(k=int(o.k), theta=th, theta_lo=tl, h=to_dev(o.h, torch.float32), vhat=to_dev(o.vhat, torch.float32),
+              stored_gradients=to_dev(o.G, torch.float32), tau=to_dev(o.tau, torch.int32),
+              ring=to_dev(o.ring, torch.float32), uploads_total=int(o.uploads_total))
+    if o.rule == 2:
+        kw["reference"], kw["reference_lo"] = split64(o.theta_hat)
+    elif o.rule == 1:
+        kw["reference"], kw["reference_lo"] = split64(o.theta_snap)
+        kw["stored_innovations"] = to_dev(o.delta_stored, torch.float32)
+    eng.set_state(**kw)
+
+
+def library_state(eng):
+    torch.cuda.synchronize()
+    st = eng.state()
+    torch.cuda.synchronize()
+    out = {k: (v.cpu().numpy().copy() if isinstance(v, torch.Tensor) else v) for k, v in st.items()}
+    out["theta64"] = out["theta"].astype(np.float64) + out["theta_lo"].astype(np.float64)
+    return out

@@ -5,6 +5,8 @@ import torch
 
 from cada_synth import configs, generators
 
+from paper_2012_15469_amd.binding import PATH_TWO_PASS, PATH_SINGLE_PASS, PATH_WHOLE_STEPS
+
 from common import check_protocol, upload, run_library, oracle_run, rel_l2
 
 pytestmark = pytest.mark.gpu
@@ -19,36 +21,33 @@ def _case(cfg):
 
 # small: 1 = whole iterations in one launch (cada_logreg_small.hip), 0 = one launch per kernel
 @pytest.mark.parametrize("small", [1, 0])
-def test_cfg1_full(small, monkeypatch):
-    monkeypatch.setenv("CADA_SMALL", str(small))
+def test_cfg1_full(small):
     cfg = configs.CFG1
     prob, dev, sched = _case(cfg)
-    stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
+    stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_WHOLE_STEPS if small else PATH_TWO_PASS)
     print("cfg1", stats)
     assert stats["h_rel_l2"] < 1e-4 and stats["vhat_rel_l2"] < 1e-4 and stats["ring_rel"] < 1e-4
     assert stats["stored_rel_l2"] < 1e-5
 
 
 @pytest.mark.parametrize("small", [1, 0])
-def test_cfg2_full(small, monkeypatch):
-    monkeypatch.setenv("CADA_SMALL", str(small))
+def test_cfg2_full(small):
     cfg = configs.CFG2
     prob, dev, sched = _case(cfg)
-    stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
+    stats, *_ = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_WHOLE_STEPS if small else PATH_TWO_PASS)
     print("cfg2", stats)
     assert stats["stored_rel_l2"] < 1e-5
 
 
 @pytest.mark.parametrize("p,rule,fused", [(8200, 2, 0), (8200, 1, 0), (4099, 2, 0), (4099, 1, 0), (8200, 2, 1), (8200, 1, 1),
-                                          (4099, 2, -1), (4099, 1, -1)])
-def test_cfg3_reduced_ragged(p, rule, fused, monkeypatch):
+                                          (1027, 2, -1), (1027, 1, -1)])
+def test_cfg3_reduced_ragged(p, rule, fused):
     """The high-dimensional recipe at reduced size: several column chunks with a ragged
     tail (p = 8200 = 8192 + 8), a row count that is no multiple of the row group (B = 20)
     and the scalar-load path (p = 4099 is not a multiple of 4)."""
     # fused 1: the single-pass register-resident kernel; 0: the two streaming passes;
-    # -1: the multi-step kernel for small problems (p < 8192)
-    monkeypatch.setenv("CADA_FUSED", str(max(fused, 0)))
-    monkeypatch.setenv("CADA_SMALL", "1" if fused < 0 else "0")
+    # -1: the multi-step kernel for small problems (a worker's minibatch must fit in LDS: p = 1027)
+    path = {1: PATH_SINGLE_PASS, 0: PATH_TWO_PASS, -1: PATH_WHOLE_STEPS}[fused]
     # c is lowered from the workload's 0.3: a minibatch spans only B of the p directions, so
     # with c = 0.3 the rule never fires at this size and only forced uploads would be tested
     cfg = configs.CFG3.scaled(layer_dims=(p,), M=5, N_m=64, B=20, K=60, D=10, rule=rule, alpha=0.02, c=1e-4)
@@ -61,7 +60,8 @@ def test_cfg3_reduced_ragged(p, rule, fused, monkeypatch):
         Xs, ys = zip(*(prob.rows(m, np.arange(cfg.N_m)) for m in range(cfg.M)))
         prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
     sched = generators.make_schedule(cfg)
-    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4)
+    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4, path=path,
+                                       expect_phase={1: "logreg_single_pass", 0: "logreg_dots", -1: "logreg_whole_steps"}[fused])
     print(p, rule, stats)
     free = tr["tau"] < cfg.D
     assert 0.1 < tr["mask"][free].mean() < 0.9, "the case must mix rule-driven uploads and skips"
@@ -69,13 +69,10 @@ def test_cfg3_reduced_ragged(p, rule, fused, monkeypatch):
 
 # even B: two rows per iteration; odd B: one row per iteration
 @pytest.mark.parametrize("rule,B,clusters", [(2, 48, 0), (1, 48, 0), (2, 100, 2), (1, 72, 2), (2, 200, 1), (2, 51, 0), (1, 75, 2)])
-def test_single_pass_kernel_steady_state(rule, B, clusters, monkeypatch):
+def test_single_pass_kernel_steady_state(rule, B, clusters):
     """The single-pass kernel's unrolled steady-state loop only runs once a cluster of
     workgroups streams more than 40 rows: longer minibatches, and fewer clusters than workers
     so that a cluster changes worker (reference point, gradient store) in mid-stream."""
-    monkeypatch.setenv("CADA_FUSED", "1")
-    if clusters:
-        monkeypatch.setenv("CADA_FUSED_CLUSTERS", str(clusters))
     # K = 30: later the left-hand sides are differences of nearly converged iterates, and both
     # logistic paths lose digits there alike (the cancellation, not the kernel, sets the error)
     cfg = configs.CFG3.scaled(layer_dims=(8200,), M=5, N_m=256, B=B, K=30, D=10, rule=rule, alpha=0.02, c=1e-4)
@@ -83,7 +80,8 @@ def test_single_pass_kernel_steady_state(rule, B, clusters, monkeypatch):
     Xs, ys = zip(*(prob.rows(m, np.arange(cfg.N_m)) for m in range(cfg.M)))
     prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
     sched = generators.make_schedule(cfg)
-    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4)
+    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_SINGLE_PASS,
+                                       single_pass_clusters=clusters, expect_phase="logreg_single_pass")
     print(rule, B, clusters, stats)
 
 

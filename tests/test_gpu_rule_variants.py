@@ -7,6 +7,8 @@ import pytest
 
 from cada_synth import configs, generators
 
+from paper_2012_15469_amd.binding import PATH_TWO_PASS, PATH_SINGLE_PASS, PATH_WHOLE_STEPS
+
 from common import check_protocol, upload
 
 pytestmark = pytest.mark.gpu
@@ -36,15 +38,14 @@ def test_logistic_small(rule, server, c, alpha):
 
 
 @pytest.mark.parametrize("rule,server,c", [(configs.RULE_LAG, configs.SERVER_SGD, 3e4), (configs.RULE_ALWAYS, configs.SERVER_AMSGRAD, 0.3)])
-def test_logistic_single_pass_kernel(rule, server, c, monkeypatch):
-    monkeypatch.setenv("CADA_FUSED", "1")
-    monkeypatch.setenv("CADA_FUSED_CLUSTERS", "2")
+def test_logistic_single_pass_kernel(rule, server, c):
     cfg = configs.CFG3.scaled(layer_dims=(8200,), M=5, N_m=256, B=72, K=30, D=10, rule=rule, server=server, alpha=0.02, c=c)
     prob = generators.make_problem(cfg)
     Xs, ys = zip(*(prob.rows(m, np.arange(cfg.N_m)) for m in range(cfg.M)))
     prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
     sched = generators.make_schedule(cfg)
-    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4)
+    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_SINGLE_PASS,
+                                       single_pass_clusters=2, expect_phase="logreg_single_pass")
     print(rule, server, stats, tr["mask"].mean())
 
 
@@ -65,12 +66,11 @@ def test_mlp_reduced(rule, server, c, alpha):
 
 
 @pytest.mark.parametrize("small", [1, 0])
-def test_decaying_stepsize(small, monkeypatch):
+def test_decaying_stepsize(small):
     """alpha_k = alpha K0/(k+K0), Theorem 2."""
-    monkeypatch.setenv("CADA_SMALL", str(small))
     cfg = configs.CFG1.scaled(alpha=0.05, alpha_K0=15, K=120, D=20, c=0.5)
     prob, dev, sched = _case(cfg)
-    stats, o, tr, rep = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4)
+    stats, o, tr, rep = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_WHOLE_STEPS if small else PATH_TWO_PASS)
     print(small, stats)
     free = tr["tau"] < cfg.D
     assert 0.05 < tr["mask"][free].mean() < 0.95
@@ -108,15 +108,10 @@ def test_uneven_samples_per_worker():
                    alpha=cfg.alpha, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, lam=cfg.lam, theta0=prob.theta0, rows=rows)
     o.run(sched)
     tr = o.trace_arrays()
-    for small in ("1", "0"):
-        import os
-        os.environ["CADA_SMALL"] = small
-        try:
-            eng = Cada(model=cfg.model, layer_dims=cfg.layer_dims, M=cfg.M, B=cfg.B, n_samples=list(n), X=to_dev(X), y=to_dev(y),
-                       theta0=to_dev(prob.theta0), rule=cfg.rule, D=cfg.D, d_max=cfg.d_max, c=cfg.c, alpha=cfg.alpha,
-                       beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, lam=cfg.lam, trace_steps=cfg.K)
-        finally:
-            del os.environ["CADA_SMALL"]
+    for path in (PATH_WHOLE_STEPS, PATH_TWO_PASS):
+        eng = Cada(model=cfg.model, layer_dims=cfg.layer_dims, M=cfg.M, B=cfg.B, n_samples=list(n), X=to_dev(X), y=to_dev(y),
+                   theta0=to_dev(prob.theta0), rule=cfg.rule, D=cfg.D, d_max=cfg.d_max, c=cfg.c, alpha=cfg.alpha,
+                   beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, lam=cfg.lam, trace_steps=cfg.K, path=path)
         eng.run(to_dev(sched))
         ev = eng.evaluate().cpu().numpy()
         st = eng.state()
