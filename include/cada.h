@@ -238,6 +238,18 @@ int cada_set_state(cada_ctx *ctx, const cada_state_in *in);
  * activation buffers of the last step. */
 int cada_eval(cada_ctx *ctx, double *out);
 
+/* cada_eval for callers that cannot allocate device memory or hand over a workspace sized for it:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels, same result as cada_eval (bit for bit), but the per-block partial sums and the
+ * per-worker means live in a fixed array inside the library (2.1 MB per GPU, held until the
+ * process ends) instead of in the context's workspace.  Logistic model only, at most
+ * CADA_EVAL_NOALLOC_MAX_M workers: more workers return CADA_EINVAL, the MLP model
+ * CADA_EUNSUPPORTED, and nothing is launched.  The call allocates and frees nothing, records no
+ * memset, and does not synchronise.  All calls on one GPU share the array: calls that may overlap
+ * on that GPU (different streams) race; calls on one stream are safe.  out: DEVICE double[2]. */
+#define CADA_EVAL_NOALLOC_MAX_M 256
+int cada_eval_noalloc(cada_ctx *ctx, double *out);
+
 /* Checkpoint / resume.  A checkpoint is the whole workspace (iterate, moments, stored
  * gradients, reference points, delays, ring, trace, ...) plus the host-side counters, as one
  * opaque block of cada_checkpoint_bytes(ctx) bytes of DEVICE memory owned by the caller.

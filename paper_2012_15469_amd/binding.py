@@ -25,6 +25,7 @@ RULE_CADA1, RULE_CADA2 = 1, 2
 MODEL_LOGREG, MODEL_MLP = 0, 1
 GEMM_FP32, GEMM_BF16 = 0, 1
 REPLAY_FREE = 255
+EVAL_NOALLOC_MAX_M = 256
 PATH_AUTO, PATH_TWO_PASS, PATH_SINGLE_PASS, PATH_WHOLE_STEPS = 0, 1, 2, 3
 
 
@@ -72,6 +73,8 @@ _lib.cada_set_state.restype = C.c_int
 _lib.cada_set_state.argtypes = [C.c_void_p, C.POINTER(cada_state_in)]
 _lib.cada_eval.restype = C.c_int
 _lib.cada_eval.argtypes = [C.c_void_p, C.c_void_p]
+_lib.cada_eval_noalloc.restype = C.c_int
+_lib.cada_eval_noalloc.argtypes = [C.c_void_p, C.c_void_p]
 _lib.cada_checkpoint_bytes.restype = C.c_size_t
 _lib.cada_checkpoint_bytes.argtypes = [C.c_void_p]
 _lib.cada_checkpoint_save.restype = C.c_int
@@ -146,6 +149,10 @@ def cada_profile_begin(ctx: int, max_steps: int):
 
 def cada_eval(ctx: int, out_ptr: int):
     _check(_lib.cada_eval(ctx, out_ptr))
+
+
+def cada_eval_noalloc(ctx: int, out_ptr: int):
+    _check(_lib.cada_eval_noalloc(ctx, out_ptr))
 
 
 def cada_checkpoint_bytes(ctx: int) -> int:

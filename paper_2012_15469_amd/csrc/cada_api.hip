@@ -392,6 +392,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
     if (rc != CADA_OK) { mlp_free(c); delete h; return rc; }
   } else {
     int rc = logreg_init(c);
+    if (rc == CADA_OK) rc = eval_scratch_init();
     if (rc == CADA_OK) rc = small_publish_args(c);
     if (rc != CADA_OK) { small_free(c); delete h; return rc; }
   }
@@ -516,6 +517,16 @@ int cada_eval(cada_ctx *ctx, double *out) {
   if (!ctx || !out) { set_error("ctx/out is NULL"); return CADA_EINVAL; }
   Ctx *c = &ctx->c;
   return c->model == CADA_MODEL_LOGREG ? logreg_eval(c, out) : mlp_eval(c, out);
+}
+
+int cada_eval_noalloc(cada_ctx *ctx, double *out) {
+  if (!ctx || !out) { set_error("ctx/out is NULL"); return CADA_EINVAL; }
+  Ctx *c = &ctx->c;
+  if (c->model != CADA_MODEL_LOGREG) {
+    set_error("cada_eval_noalloc serves the logistic model: the MLP evaluation stages a chunk's activations, far more than its fixed scratch array");
+    return CADA_EUNSUPPORTED;
+  }
+  return logreg_eval_noalloc(c, out);
 }
 
 namespace {

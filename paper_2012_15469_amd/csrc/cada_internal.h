@@ -152,6 +152,8 @@ int mlp_gradients(Ctx *c, const int32_t *idx);
 int mlp_lhs_slots(const cada_config *cfg);
 int mlp_eval(Ctx *c, double *out);
 int logreg_eval(Ctx *c, double *out);
+int logreg_eval_noalloc(Ctx *c, double *out);   // the same kernels with their scratch in a file-scope device array
+int eval_scratch_init();                        // looks that array's address up on the current device
 void eval_finish(Ctx *c, double *out, int with_reg);   // out = mean over the workers of eval_acc (+ regulariser)
 constexpr int kEvalBlocks = 512;      // blocks per worker of the logistic evaluation kernel
 size_t mlp_workspace_bytes(const cada_config *cfg, const int64_t total_rows);

@@ -343,6 +343,51 @@ void eval_finish(Ctx *c, double *out, int with_reg) {
   hipLaunchKernelGGL(k_eval_finish, dim3(1), dim3(kBlock), 0, c->stream, c->s, c->eval_acc, out, with_reg);
 }
 
+// Evaluation for callers that cannot allocate: the per-block sums and the per-worker means live
+// in this array instead of in a workspace.  One copy per GPU, held until the process ends and
+// shared by every call on that GPU.  In host code the name is only a handle: the address on the
+// current device comes from hipGetSymbolAddress, once per device.
+constexpr size_t kEvalStaticDoubles = (size_t)CADA_EVAL_NOALLOC_MAX_M * (kEvalBlocks + 1) * 2;   // 2.1 MB
+static __device__ __align__(256) double scratch[kEvalStaticDoubles];
+
+constexpr int kMaxDevices = 64;
+static double *g_scratch_ptr[kMaxDevices];      // address of `scratch` on each device, null until asked for
+
+// Address of the array on the current device (asked for once per device), or null with the error text set.
+static double *eval_scratch() {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) { set_error("hipGetDevice failed or device index beyond %d", kMaxDevices); return nullptr; }
+  double *ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (ptr) return ptr;
+  e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !ptr) { set_error("hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e)); return nullptr; }
+  __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);
+  return ptr;
+}
+
+int eval_scratch_init() { return eval_scratch() ? CADA_OK : CADA_EHIP; }
+
+int logreg_eval_noalloc(Ctx *c, double *out) {
+  const DevState &s = c->s;
+  if (s.M > CADA_EVAL_NOALLOC_MAX_M) {
+    set_error("cada_eval_noalloc serves at most %d workers (got %d): its fixed scratch array holds no more", CADA_EVAL_NOALLOC_MAX_M, s.M);
+    return CADA_EINVAL;
+  }
+  double *ptr = eval_scratch();
+  if (!ptr) return CADA_EHIP;
+  // every element the later kernels read is written first by this call: nothing has to start at zero
+  double *part = ptr, *acc = ptr + (size_t)s.M * kEvalBlocks * 2;
+  const dim3 grid(kEvalBlocks, (unsigned)s.M);
+  if (c->vec == 4) hipLaunchKernelGGL(k_eval_rows<4>, grid, dim3(kBlock), 0, c->stream, s, part);
+  else hipLaunchKernelGGL(k_eval_rows<1>, grid, dim3(kBlock), 0, c->stream, s, part);
+  hipLaunchKernelGGL(k_eval_worker, dim3((unsigned)s.M), dim3(kWave), 0, c->stream, s, part, kEvalBlocks, acc);
+  hipLaunchKernelGGL(k_eval_finish, dim3(1), dim3(kBlock), 0, c->stream, s, acc, out, 1);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_error("evaluation launch failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
+  return CADA_OK;
+}
+
 int logreg_eval(Ctx *c, double *out) {
   const DevState &s = c->s;
   const dim3 grid(kEvalBlocks, (unsigned)s.M);
