@@ -104,12 +104,109 @@ def bench_replicas(args, cfg, dev) -> int:
     return 0
 
 
+def kernel_bytes_per_launch(cfg) -> float:
+    """Algorithmic bytes of ONE launch of the logistic gradient kernel(s): the B gathered rows of every
+    worker once, the reference iterate (CADA1: the stored innovation) read and the fresh gradient
+    written (CADA1: plus the fresh innovation written): M (4 B p + 8 p), CADA1 M (4 B p + 12 p)."""
+    per_worker = 4.0 * cfg.B * cfg.p + 8.0 * cfg.p + (4.0 * cfg.p if cfg.rule == 1 else 0.0)
+    return cfg.M * per_worker
+
+
+def measure(cfg, K: int, W: int, plain_launch: bool = False):
+    """W warm-up steps, K timed steps (no events inside the loop), then K more steps with an event
+    around every kernel phase.  Returns (record for the JSON line, problem, seconds of set-up)."""
+    import torch
+    from cada_synth import generators, native
+    from paper_2012_15469_amd import binding
+    from paper_2012_15469_amd.binding import Cada
+    dev = torch.device("cuda:0")
+    t0 = time.time()
+    prob = generators.make_problem(cfg)
+    if prob.X is None:                  # counter-based recipe: generated in HBM
+        shift = torch.from_numpy(prob.shift).to(dev)
+        X = torch.empty((cfg.M * cfg.N_m, cfg.p), dtype=torch.float32, device=dev)
+        y = torch.empty(cfg.M * cfg.N_m, dtype=torch.float32, device=dev)
+        native.fill_device(cfg, shift, X, y)
+    else:
+        X, y = torch.from_numpy(prob.X).to(dev), torch.from_numpy(prob.y).to(dev)
+    theta0 = torch.from_numpy(prob.theta0).to(dev)
+    sched = torch.from_numpy(generators.make_schedule(cfg, W + 2 * K)).to(dev)
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+
+    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0, plain_launch=plain_launch)
+    # small logistic workloads run whole iterations inside one kernel: the K timed steps are one
+    # cada_run call (one launch); everything else is one cada_step call per step
+    whole = binding.cada_profile_phase_names(eng.ctx) == ["logreg_whole_steps"]
+
+    def advance(k0, k1):
+        if whole:
+            eng.run(sched[k0:k1])
+        else:
+            for k in range(k0, k1):
+                eng.step(sched[k])
+
+    advance(0, W)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    advance(W, W + K)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    uploads_timed = int(eng.state()["uploads_total"].item())
+    binding.cada_profile_begin(eng.ctx, K)
+    advance(W + K, W + 2 * K)
+    torch.cuda.synchronize()
+    prof = binding.cada_profile_end(eng.ctx)
+    if whole:       # one profiled launch covered K steps
+        prof = {k: (v / K if k != "steps" else K) for k, v in prof.items()}
+    st = eng.state()
+    torch.cuda.synchronize()
+    assert int(st["error_flags"].item()) == 0
+    assert bool(torch.isfinite(st["theta"]).all())
+
+    rec = {"value": cfg.M * K / dt, "unit": "worker-iterations/s", "steps": K, "warmup": W, "ms_per_step": 1e3 * dt / K,
+           "dtype": "f32" if cfg.gemm_dtype == "fp32" else "bf16",
+           "config": {"workload": cfg.name, "M": cfg.M, "p": cfg.p, "B": cfg.B, "N_m": cfg.N_m,
+                      "rule": "CADA%d" % cfg.rule, "D": cfg.D, "d_max": cfg.d_max, "c": cfg.c,
+                      "uploads_per_worker_step": uploads_timed / float(cfg.M * (W + K)), "setup_s": round(t_setup, 1)},
+           "kernel_ms": {k: v for k, v in prof.items() if k != "steps"}}
+    if cfg.model == "logreg":
+        # the gradient phase is one launch of the single-pass kernel (p >= 8192), the two streaming
+        # passes over the gathered rows, or (tiny workloads) whole iterations in one kernel
+        single = "logreg_single_pass" in prof
+        grad_ms = sum(v for k, v in prof.items() if k.startswith("logreg_"))
+        alg = kernel_bytes_per_launch(cfg) if not whole else algorithmic_bytes_per_step(cfg)
+        achieved = alg / (grad_ms * 1e-3) / 1e9
+        name = "k_fused" if single else ("k_small (whole iterations; latency-bound)" if whole else "k_dots+k_grad")
+        rec["roofline"] = {"bound": "hbm", "kernel": name, "achieved": achieved,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": stored_traffic(cfg.name) if single else None,
+                           "algorithmic_bytes_per_launch": alg, "avg_launch_ms": grad_ms,
+                           "whole_step_bytes": algorithmic_bytes_per_step(cfg)}
+    else:
+        fl = algorithmic_flops_per_step(cfg)
+        ms = prof["mlp_gradients"]
+        achieved = fl / (ms * 1e-3) / 1e12
+        rec["roofline"] = {"bound": "mfma", "kernel": "mlp_gradients (all contraction and elementwise kernels of S1+S2)",
+                           "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                           "algorithmic_flops_per_launch": fl, "avg_launch_ms": ms}
+    eng.close()
+    del X, y, eng, sched
+    torch.cuda.empty_cache()
+    return rec, prob, t_setup
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=120,
+                    help="timed steps of the headline workload (the default passes the forced upload at k = D = 100)")
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the HBM-bound logistic workload)")
+    ap.add_argument("--config", type=int, default=3, help="headline workload 1..5 (default 3: the HBM-bound logistic workload)")
+    ap.add_argument("--others", type=str, default="1,2,4,5",
+                    help="workloads also measured in this process and reported under \"other_workloads\" ('' = none)")
+    ap.add_argument("--other-steps", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=int, default=1,
                     help="workloads 1-2 only: R independent runs (seeds seed, seed+17, ...) advanced side by side in one "
@@ -128,86 +225,18 @@ def main() -> int:
 
     import numpy as np
     import torch
-    from cada_synth import configs, generators, native
-    from paper_2012_15469_amd import binding
-    from paper_2012_15469_amd.binding import Cada
+    from cada_synth import configs, generators
 
     cfg = configs.ALL[args.config]
     dev = torch.device("cuda:0")
     if args.replicas > 1:
         return bench_replicas(args, cfg, dev)
     K, W = args.steps, args.warmup
-    t0 = time.time()
-    prob = generators.make_problem(cfg)
-    if prob.X is None:                  # counter-based recipe: generated in HBM
-        shift = torch.from_numpy(prob.shift).to(dev)
-        X = torch.empty((cfg.M * cfg.N_m, cfg.p), dtype=torch.float32, device=dev)
-        y = torch.empty(cfg.M * cfg.N_m, dtype=torch.float32, device=dev)
-        native.fill_device(cfg, shift, X, y)
-    else:
-        X, y = torch.from_numpy(prob.X).to(dev), torch.from_numpy(prob.y).to(dev)
-    theta0 = torch.from_numpy(prob.theta0).to(dev)
-    sched = torch.from_numpy(generators.make_schedule(cfg, W + K)).to(dev)
-    torch.cuda.synchronize()
-    t_setup = time.time() - t0
-
-    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0, plain_launch=args.plain_launch)
-    # small logistic workloads run whole iterations inside one kernel: the K timed steps are one
-    # cada_run call (one launch); everything else is one cada_step call per step
-    whole = binding.cada_profile_phase_names(eng.ctx) == ["logreg_whole_steps"]
-    for k in range(W):
-        eng.step(sched[k])
-    torch.cuda.synchronize()
-    binding.cada_profile_begin(eng.ctx, K)
-    t1 = time.perf_counter()
-    if whole:
-        eng.run(sched[W:W + K])
-    else:
-        for k in range(W, W + K):
-            eng.step(sched[k])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t1
-    prof = binding.cada_profile_end(eng.ctx)
-    if whole:       # one profiled launch covered K steps
-        prof = {k: (v / K if k != "steps" else K) for k, v in prof.items()}
-    st = eng.state()
-    torch.cuda.synchronize()
-    uploads = int(st["uploads_total"].item())
-    assert int(st["error_flags"].item()) == 0
-    assert bool(torch.isfinite(st["theta"]).all())
-
-    value = cfg.M * K / dt
-    out = {"metric": "worker-iterations/sec (grads+CADA rule+AMSGrad)", "value": value, "unit": "worker-iterations/s",
-           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": 1e3 * dt / K, "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f32" if cfg.gemm_dtype == "fp32" else "bf16",
-           "data": "synthetic",
-           "config": {"workload": cfg.name, "M": cfg.M, "p": cfg.p, "B": cfg.B, "N_m": cfg.N_m,
-                      "rule": "CADA%d" % cfg.rule, "D": cfg.D, "d_max": cfg.d_max, "c": cfg.c,
-                      "uploads_per_worker_step": uploads / float(cfg.M * (W + K)), "setup_s": round(t_setup, 1)},
-           "kernel_ms": {k: v for k, v in prof.items() if k != "steps"}}
-
-    if cfg.model == "logreg":
-        # the gradient phase is one launch of the single-pass kernel (p >= 8192) or the two
-        # streaming passes over the gathered rows; its algorithmic bytes are those of the whole
-        # step (rows counted once)
-        single = "logreg_single_pass" in prof
-        grad_ms = sum(v for k, v in prof.items() if k.startswith("logreg_"))
-        alg = algorithmic_bytes_per_step(cfg)
-        achieved = alg / (grad_ms * 1e-3) / 1e9
-        name = "k_fused" if single else ("k_small (whole iterations; latency-bound)" if whole else "k_dots+k_grad")
-        out["roofline"] = {"bound": "hbm", "kernel": name, "achieved": achieved,
-                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                           "traffic": stored_traffic(cfg.name) if single else None,
-                           "algorithmic_bytes_per_launch": alg, "avg_launch_ms": grad_ms}
-
-    if cfg.model == "mlp":
-        fl = algorithmic_flops_per_step(cfg)
-        ms = prof["mlp_gradients"]
-        achieved = fl / (ms * 1e-3) / 1e12
-        out["roofline"] = {"bound": "mfma", "kernel": "mlp_gradients (all GEMM and elementwise kernels of S1+S2)",
-                           "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                           "algorithmic_flops_per_launch": fl, "avg_launch_ms": ms}
+    rec, prob, _ = measure(cfg, K, W, args.plain_launch)
+    out = {"metric": "worker-iterations/sec (grads+CADA rule+AMSGrad)", "value": rec["value"], "unit": rec["unit"],
+           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": rec["ms_per_step"], "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": rec["dtype"], "data": "synthetic",
+           "config": rec["config"], "kernel_ms": rec["kernel_ms"], "roofline": rec["roofline"]}
 
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -215,6 +244,13 @@ def main() -> int:
         torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+
+    others = [int(x) for x in args.others.split(",") if x.strip() and int(x) != args.config]
+    if others:
+        out["other_workloads"] = {}
+        for n in others:
+            r, _, _ = measure(configs.ALL[n], args.other_steps, W)
+            out["other_workloads"][configs.ALL[n].name] = r
 
     if not args.no_cpu_baseline:
         from oracle.driver import oracle_for

@@ -120,15 +120,20 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   const size_t p = (size_t)cfg->p, M = (size_t)cfg->M;
   float *theta = w.take<float>(p), *theta_lo = w.take<float>(p), *h = w.take<float>(p), *v = w.take<float>(p);
   float *vhat = w.take<float>(p), *nabla = w.take<float>(p);
-  float *gbuf = w.take<float>(2 * M * p);
+  // rows of the per-worker stores: the MLP path pads them to 16 bytes (its p is rarely a multiple of 4)
+  const bool mlp = cfg->model == CADA_MODEL_MLP;
+  const size_t ps = mlp ? (p + 3) / 4 * 4 : p, ps16 = (p + 7) / 8 * 8;
+  float *gbuf = w.take<float>(2 * M * ps);
   float *hist = nullptr, *hist_lo = nullptr, *snap = nullptr, *snap_lo = nullptr, *dtl = nullptr;
+  uint16_t *dtl16 = nullptr;
   if (cfg->rule == CADA_RULE_CADA2) {
-    hist = w.take<float>((size_t)(cfg->D + 1) * p);
-    hist_lo = w.take<float>((size_t)(cfg->D + 1) * p);
+    hist = w.take<float>((size_t)(cfg->D + 1) * ps);
+    hist_lo = w.take<float>((size_t)(cfg->D + 1) * ps);
   } else if (cfg->rule == CADA_RULE_CADA1) {
     snap = w.take<float>(p);
     snap_lo = w.take<float>(p);
-    dtl = w.take<float>(2 * M * p);
+    if (mlp) dtl16 = w.take<uint16_t>(2 * M * ps16);
+    else dtl = w.take<float>(2 * M * ps);
   }
   int32_t *tau = w.take<int32_t>(M), *sel = w.take<int32_t>(M);
   float *lhs = w.take<float>(M);
@@ -137,6 +142,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   float *ring = w.take<float>((size_t)cfg->d_max);
   float *ring_part = w.take<float>((size_t)g.ring_cap);
   uint64_t *uploads = w.take<uint64_t>(1);
+  uint32_t *n_up = w.take<uint32_t>(2);
   uint32_t *err = w.take<uint32_t>(1);
   int64_t *row_off = w.take<int64_t>(M + 1);
   const size_t T = (size_t)cfg->trace_steps;
@@ -161,9 +167,10 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   c->small_bar = small_bar;
   c->small_args = small_args;
   s->theta = theta; s->theta_lo = theta_lo; s->hist_lo = hist_lo; s->snap_lo = snap_lo; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
-  s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl;
+  s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl; s->dtl16 = dtl16;
+  s->ps = (int64_t)ps; s->ps16 = (int64_t)ps16;
   s->tau = tau; s->sel = sel; s->lhs = lhs; s->lhs_part = lhs_part; s->mask = mask;
-  s->ring = ring; s->ring_part = ring_part; s->uploads = uploads; s->err = err;
+  s->ring = ring; s->ring_part = ring_part; s->uploads = uploads; s->n_up = n_up; s->err = err;
   s->row_off = row_off;
   s->t_mask = t_mask; s->t_own = t_own; s->t_lhs = t_lhs; s->t_rhs = t_rhs; s->t_tau = t_tau;
   s->trace_steps = cfg->trace_steps;
@@ -175,19 +182,19 @@ __global__ void k_fill_i32(int32_t *p, int32_t v, int64_t n) {
   if (i < n) p[i] = v;
 }
 
-// dst[r][i] = src[i] for r < reps
-__global__ void k_broadcast_rows(float *dst, const float *src, int64_t p, int64_t reps) {
+// dst[r][i] = src[i] for r < reps, rows `stride` floats apart
+__global__ void k_broadcast_rows(float *dst, const float *src, int64_t p, int64_t reps, int64_t stride) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= p) return;
   const float v = src[i];
-  for (int64_t r = 0; r < reps; ++r) dst[r * p + i] = v;
+  for (int64_t r = 0; r < reps; ++r) dst[r * stride + i] = v;
 }
 
 // out[m][i] = gbuf[sel[m]][m][i]
 __global__ void k_gather_stored(const DevState s, float *out) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int m = blockIdx.y;
-  if (i < s.p) out[(int64_t)m * s.p + i] = s.gbuf[((int64_t)s.sel[m] * s.M + m) * s.p + i];
+  if (i < s.p) out[(int64_t)m * s.p + i] = s.gbuf[((int64_t)s.sel[m] * s.M + m) * s.ps + i];
 }
 
 // cada_set_state, [p]-sized part: iterate, moments, and the reference point that is one vector
@@ -205,7 +212,7 @@ __global__ __launch_bounds__(kBlock) void k_set_vectors(const SetStateArgs a) {
     s.h[i] = a.in.h[i]; s.vhat[i] = a.in.vhat[i]; s.v[i] = a.in.vhat[i];
     if (s.rule == CADA_RULE_CADA2) {
       const int64_t slot = a.in.k % s.R;
-      s.hist[slot * s.p + i] = th; s.hist_lo[slot * s.p + i] = tl;
+      s.hist[slot * s.ps + i] = th; s.hist_lo[slot * s.ps + i] = tl;
     } else if (s.rule == CADA_RULE_CADA1) {
       s.snap[i] = a.in.reference[i];
       s.snap_lo[i] = a.in.reference_lo ? a.in.reference_lo[i] : 0.f;
@@ -236,11 +243,14 @@ __global__ __launch_bounds__(kBlock) void k_set_rows(const SetStateArgs a) {
     }
   }
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
-    s.gbuf[row + i] = a.in.stored_gradients[row + i];
-    if (s.rule == CADA_RULE_CADA1) s.dtl[row + i] = a.in.stored_innovations[row + i];
+    s.gbuf[(int64_t)m * s.ps + i] = a.in.stored_gradients[row + i];
+    if (s.rule == CADA_RULE_CADA1) {
+      if (s.dtl16) s.dtl16[(int64_t)m * s.ps16 + i] = f2bf(a.in.stored_innovations[row + i]);
+      else s.dtl[(int64_t)m * s.ps + i] = a.in.stored_innovations[row + i];
+    }
     if (slot >= 0) {
-      s.hist[slot * s.p + i] = a.in.reference[row + i];
-      s.hist_lo[slot * s.p + i] = a.in.reference_lo ? a.in.reference_lo[row + i] : 0.f;
+      s.hist[slot * s.ps + i] = a.in.reference[row + i];
+      s.hist_lo[slot * s.ps + i] = a.in.reference_lo ? a.in.reference_lo[row + i] : 0.f;
     }
   }
 }
@@ -258,7 +268,7 @@ __global__ __launch_bounds__(kBlock) void k_set_small(const SetStateArgs a, int 
   for (int j = threadIdx.x; j < s.d_max; j += kBlock) s.ring[j] = a.in.ring[j];
   const float newest = a.in.k > 0 ? a.in.ring[(a.in.k - 1) % s.d_max] : 0.f;
   for (int i = threadIdx.x; i < n_ring_cap; i += kBlock) s.ring_part[i] = i == 0 ? newest : 0.f;
-  if (threadIdx.x == 0) *s.uploads = a.in.uploads_total;
+  if (threadIdx.x == 0) { *s.uploads = a.in.uploads_total; s.n_up[0] = 0u; s.n_up[1] = 0u; }
 }
 
 #define HIP_TRY(expr)                                                        \
@@ -308,6 +318,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   if (!cfg->workspace) { set_error("workspace is NULL"); return CADA_EWORKSPACE; }
   if (reinterpret_cast<uintptr_t>(cfg->workspace) % kAlign != 0) { set_error("workspace must be %zu-byte aligned", kAlign); return CADA_EWORKSPACE; }
   if (g.vec == 4 && reinterpret_cast<uintptr_t>(cfg->X) % 16 != 0) g.vec = 1;
+  if (cfg->model == CADA_MODEL_MLP) g.vec = 4;      // (its rows are padded to 16 bytes; X is read through copies of its own)
   const size_t need = cada_workspace_bytes(cfg);
   if (need == 0) return CADA_EINVAL;
   if (cfg->workspace_bytes < need) {
@@ -329,6 +340,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   c->chunk_cols = g.chunk_cols;
   c->ws_bytes = need;
   c->ring_cap = g.ring_cap;
+  c->force_resum = 1;
   c->ws_base = cfg->workspace;
   c->logreg_group = cfg->two_pass_group > 0 ? cfg->two_pass_group : 0;
   Carver w{static_cast<char *>(cfg->workspace)};
@@ -383,9 +395,9 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((M + tb - 1) / tb)), dim3(tb), 0, st, s.tau, (int32_t)s.D, (int64_t)M);
   const unsigned pb = (unsigned)((p + tb - 1) / tb);
   if (s.rule == CADA_RULE_CADA2)
-    hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.hist, theta0, (int64_t)p, (int64_t)s.R);
+    hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.hist, theta0, (int64_t)p, (int64_t)s.R, s.ps);
   else if (s.rule == CADA_RULE_CADA1)
-    hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.snap, theta0, (int64_t)p, (int64_t)1);
+    hipLaunchKernelGGL(k_broadcast_rows, dim3(pb), dim3(tb), 0, st, s.snap, theta0, (int64_t)p, (int64_t)1, (int64_t)p);
   if ((e = hipGetLastError()) != hipSuccess) return fail(e, "init kernels");
   if (cfg->model == CADA_MODEL_MLP) {
     const int rc = mlp_init_state(c, theta0);
@@ -510,6 +522,7 @@ int cada_set_state(cada_ctx *ctx, const cada_state_in *in) {
   hipLaunchKernelGGL(k_set_small, dim3(1), dim3(kBlock), 0, c->stream, a, c->ring_cap);
   HIP_TRY(hipGetLastError());
   c->k = in->k;
+  c->force_resum = 1;       // (the aggregate of the step before is not part of the state handed over)
   return CADA_OK;
 }
 
@@ -535,6 +548,7 @@ struct CheckpointHeader {          // in front of the workspace image
   int64_t k, p;
   int32_t M, B, rule, model, D, d_max, server_sgd;
   uint32_t fused_seq, small_seq;
+  int32_t force_resum;
 };
 static_assert(sizeof(CheckpointHeader) <= 128, "checkpoint header");
 constexpr uint64_t kCheckpointMagic = 0x43414441434b5031ull;   // "CADACKP1"
@@ -545,6 +559,7 @@ CheckpointHeader header_of(const Ctx *c) {
   h.magic = kCheckpointMagic; h.ws_bytes = c->ws_bytes; h.k = c->k; h.p = c->s.p;
   h.M = c->s.M; h.B = c->s.B; h.rule = c->s.rule; h.model = c->model; h.D = c->s.D; h.d_max = c->s.d_max;
   h.server_sgd = c->s.server_sgd; h.fused_seq = c->fused_seq; h.small_seq = c->small_seq;
+  h.force_resum = c->force_resum;
   return h;
 }
 }  // namespace
@@ -579,6 +594,7 @@ int cada_checkpoint_load(cada_ctx *ctx, const void *src) {
   c->k = h.k;
   c->fused_seq = h.fused_seq;
   c->small_seq = h.small_seq;
+  c->force_resum = h.force_resum;
   // (the image holds the saving context's launch arguments, which point into its workspace)
   const int rc = small_publish_args(c);
   if (rc != CADA_OK) return rc;

@@ -28,6 +28,13 @@ struct DevState {
   float *hist, *hist_lo;
   // CADA1: snapshot theta-tilde [p] and innovations dtl[s][m][p] indexed by sel like gbuf.
   float *snap, *snap_lo, *dtl;
+  // MLP with CADA1: the stored innovations are kept as bf16, dtl16[s][m][ps16] (dtl is null).  They
+  // enter only the rule's left-hand side |fresh - stored|^2, whose other operand comes from bf16
+  // contractions anyway; the stored GRADIENTS, which the server sums, stay float32.
+  uint16_t *dtl16;
+  int64_t ps;               // floats from one row of gbuf / dtl / hist to the next: p, or p rounded up to a
+                            // multiple of 4 (MLP) so that every row starts on a 16-byte boundary
+  int64_t ps16;             // elements from one row of dtl16 to the next (a multiple of 8)
   int32_t *tau, *sel;     // [M]
   float *lhs;             // [M]
   float *lhs_part;        // [M][n_lhs_part] partial sums of the left-hand side
@@ -36,6 +43,9 @@ struct DevState {
   float *ring_part;       // [n_ring_part] per-block partial sums of the last squared step,
                           // folded into ring[(k-1) mod d_max] by the next rule kernel
   uint64_t *uploads;
+  uint32_t *n_up;          // [2]: uploads of iteration k in slot k mod 2 (the server kernel clears the other slot)
+  int32_t resum;           // this launch: form the aggregate as the plain sum over all workers (0: the kernel may
+                           // take the incremental form of Section 1.2 when few workers uploaded)
   uint32_t *err;
   // trace
   uint8_t *t_mask, *t_own;
@@ -66,13 +76,24 @@ __device__ __forceinline__ RefPtr theta_ref(const DevState &s, int m, int64_t k)
   int64_t j = k - (int64_t)min(s.tau[m], s.D);   // tau <= D unless a replay kept m silent longer
   int64_t slot = j % s.R;
   if (slot < 0) slot += s.R;
-  return RefPtr{s.hist + slot * s.p, s.hist_lo + slot * s.p};
+  return RefPtr{s.hist + slot * s.ps, s.hist_lo + slot * s.ps};
 }
 
 // Stepsize of iteration k (constant, or the decaying 2/(mu(k+K0)) of Theorem 2).
 __host__ __device__ __forceinline__ float stepsize(const DevState &s, int64_t k) {
   return s.alpha_K0 <= 0 ? (float)s.alpha0 : (float)(s.alpha0 * (double)s.alpha_K0 / (double)(k + s.alpha_K0));
 }
+
+// bf16 storage: the hardware conversion (v_cvt_pk_bf16_f32: round to nearest even, NaN stays NaN),
+// one value, or two packed into a register (first argument in the low half).
+__device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ uint32_t f2bf_pk(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
@@ -125,6 +146,7 @@ struct Ctx {
   double *eval_acc;          // [M][2]
   int32_t *eval_idx;         // [M][B] row ids of one evaluation chunk (MLP)
   int logreg_group;          // workers per launch pair of the logistic gradient kernels (0 = all)
+  int force_resum;           // the stored aggregate does not belong to the state (first step, after cada_set_state)
   void *mlp;                 // MLP plan (cada_mlp.hip), or nullptr
   void *prof;                // profiling events (cada_api.hip), or nullptr
   int n_phases;              // phases per step = marks per step - 1

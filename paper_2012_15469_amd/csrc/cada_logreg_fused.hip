@@ -55,7 +55,7 @@ constexpr int F_NP = 32;             // publication buffers, in slabs
 constexpr int F_V = 2;               // exchanged values per slab and workgroup: z and dz
 constexpr int F_STREAM = 256;        // streaming threads (4 wavefronts)
 constexpr int F_THREADS = F_STREAM + 128;   // + exchange wavefront + residual/feeder wavefront
-constexpr int F_QMAX = 32;
+constexpr int F_QMAX = 64;            // workgroups per cluster: 32 per poll word of an exchange lane, NJ = 1 or 2 words
 constexpr int F_NE = 256;            // slabs whose row address and label are held in LDS (4 chunks of 64)
 template <int R> struct FusedGeom {
   static constexpr int NL = 16 + 2 * (R - 1);     // one-row slabs parked in LDS (128 KB, 144 KB)
@@ -130,7 +130,9 @@ __device__ __forceinline__ void wait_rows(v4f (&x)[R][2]) {
   else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[1][0]), "+v"(x[1][1]) : "n"(N));
 }
 
-template <int R>
+// NJ: poll words per lane of the exchange wavefront (a lane sums the partials of workgroups j, j + 32, ...):
+// 1 for clusters of up to 32 workgroups (p <= 65536), 2 for up to 64 (p <= 131072).
+template <int R, int NJ = 1>
 __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   using G = FusedGeom<R>;
   constexpr int NL = G::NL, LAGI = G::LAGI, PDI = G::PDI, P = G::P, IPC = G::IPC;
@@ -233,14 +235,18 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   if (w == 4) {
     // ================= exchange wavefront =================
     const int j = lane & 31, half = lane >> 5, par = lane & 1, pr = (lane >> 1) & (R - 1);
-    const bool jok = j < Q;
-    const int jc = jok ? j : Q - 1;
+    bool jok[NJ];
+    int jc[NJ];
+#pragma unroll
+    for (int q = 0; q < NJ; ++q) { jok[q] = j + 32 * q < Q; jc[q] = jok[q] ? j + 32 * q : Q - 1; }
     bool dead = false;
-    unsigned long long pw[P][R];
+    unsigned long long pw[P][R][NJ];
 #pragma unroll
     for (int i = 0; i < P; ++i)
 #pragma unroll
-      for (int r = 0; r < R; ++r) pw[i][r] = 0ull;
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int q = 0; q < NJ; ++q) pw[i][r][q] = 0ull;
     lds_barrier();
 
     auto comm_iter = [&](auto PI, auto ST, const int it) __attribute__((always_inline)) {
@@ -265,16 +271,20 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
         for (int r = 0; r < R; ++r) {
           const int t = c1 * R + r;
           const uint32_t tag = a.seq_base + 1u + (uint32_t)t;
-          if ((uint32_t)(pw[pi][r] >> 32) != tag) {      // not there yet: rare
-            const unsigned long long *pp = post_base + ((int64_t)(t % F_NP) * F_V + half) * Q + jc;
-            uint32_t spins = 0;
-            while (!dead && (uint32_t)(pw[pi][r] >> 32) != tag) {
-              if (++spins > a.spin_limit) { dead = true; atomicOr(s.err, 2u); break; }
-              __builtin_amdgcn_s_sleep(1);
-              pw[pi][r] = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          float v = 0.f;
+#pragma unroll
+          for (int q = 0; q < NJ; ++q) {
+            if ((uint32_t)(pw[pi][r][q] >> 32) != tag) {      // not there yet: rare
+              const unsigned long long *pp = post_base + ((int64_t)(t % F_NP) * F_V + half) * Q + jc[q];
+              uint32_t spins = 0;
+              while (!dead && (uint32_t)(pw[pi][r][q] >> 32) != tag) {
+                if (++spins > a.spin_limit) { dead = true; atomicOr(s.err, 2u); break; }
+                __builtin_amdgcn_s_sleep(1);
+                pw[pi][r][q] = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              }
             }
+            v += jok[q] ? __uint_as_float((uint32_t)pw[pi][r][q]) : 0.f;       // (NJ = 1: the value itself)
           }
-          float v = jok ? __uint_as_float((uint32_t)pw[pi][r]) : 0.f;
           v += dpp_get<0xB1>(v);
           v = row16_parity_sum(v);                     // every lane: sum of its row of 16
           const float z0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
@@ -289,8 +299,10 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       if (st || (c2 >= 0 && c2 < IS)) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
-          pw[pi][r] = __hip_atomic_load(post_base + ((int64_t)((c2 * R + r) % F_NP) * F_V + half) * Q + jc, __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+          for (int q = 0; q < NJ; ++q)
+            pw[pi][r][q] = __hip_atomic_load(post_base + ((int64_t)((c2 * R + r) % F_NP) * F_V + half) * Q + jc[q], __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
       }
     };
 
@@ -513,6 +525,11 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   if (pending) accumulate();
 }
 
+static const void *fused_kernel(int R, int NJ) {
+  if (R == 2) return NJ == 2 ? reinterpret_cast<const void *>(k_fused<2, 2>) : reinterpret_cast<const void *>(k_fused<2, 1>);
+  return NJ == 2 ? reinterpret_cast<const void *>(k_fused<1, 2>) : reinterpret_cast<const void *>(k_fused<1, 1>);
+}
+
 // Chooses the cluster geometry; returns false if the single-pass path does not apply.
 bool fused_plan(Ctx *c, const cada_config *cfg) {
   c->fused = 0;
@@ -528,15 +545,15 @@ bool fused_plan(Ctx *c, const cada_config *cfg) {
   if (Q > F_QMAX || Q > cus) return false;
   int R = (B % 2 == 0) ? 2 : 1;                            // rows per iteration
   if (cfg->single_pass_rows == 1) R = 1;
-  const void *fn = R == 2 ? reinterpret_cast<const void *>(k_fused<2>) : reinterpret_cast<const void *>(k_fused<1>);
+  const int NJ = Q > 32 ? 2 : 1;
+  const void *fn = fused_kernel(R, NJ);
   const size_t lds = R == 2 ? FusedGeom<2>::lds : FusedGeom<1>::lds;
   if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return false;
   }
   int per_cu = 0;
-  const hipError_t oe = R == 2 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<2>, F_THREADS, lds)
-                               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<1>, F_THREADS, lds);
+  const hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, F_THREADS, lds);
   if (oe != hipSuccess || per_cu < 1) {
     (void)hipGetLastError();
     return false;
@@ -578,12 +595,9 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
     // Same grid without the cooperative-launch guarantee: one workgroup per CU is resident at once
     // on an otherwise idle device, and every wait in the kernel is bounded.  For profilers that
     // cannot trace cooperative dispatches.
-    if (two) hipLaunchKernelGGL(k_fused<2>, grid, block, lds, c->stream, a);
-    else hipLaunchKernelGGL(k_fused<1>, grid, block, lds, c->stream, a);
-    e = hipGetLastError();
+    e = hipLaunchKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1), grid, block, args, lds, c->stream);
   } else {
-    const void *fn = two ? reinterpret_cast<const void *>(k_fused<2>) : reinterpret_cast<const void *>(k_fused<1>);
-    e = hipLaunchCooperativeKernel(fn, grid, block, args, (unsigned)lds, c->stream);
+    e = hipLaunchCooperativeKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1), grid, block, args, (unsigned)lds, c->stream);
   }
   prof_mark(c);
   if (e != hipSuccess) {

@@ -28,6 +28,10 @@
 // bf16 products (0.2% gradient error) the iterate drifts from the fp64 trajectory by
 // percents within tens of steps.  The difference contractions are single bf16 products.
 //
+// Every activation-side tensor (sampled rows, activations, back-propagated signals) exists in ONE
+// orientation, (row, unit).  The weight-gradient contractions, which sum over the rows, read the
+// same chunks and transpose on the way from LDS into the registers (ds_read_b64_tr_b16).
+//
 // One kernel, k_mm5, serves all three contraction shapes (forward, weight gradient,
 // activation gradient).  For a 128 x 128 output tile of worker m it accumulates
 //     C1 = Ah Bh^T + Ah Bl^T + Al Bh^T          (evaluation at theta, split operands)
@@ -51,14 +55,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef uint16_t bf16_t;   // storage type
 typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));   // four floats at any 4-byte aligned address
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes in flight (a native vector: stays in registers)
-
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);   // NaN stays NaN
-  u += 0x7fffu + ((u >> 16) & 1u);                                          // round to nearest even
-  return (bf16_t)(u >> 16);
-}
-__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+typedef uint32_t u32x2u __attribute__((ext_vector_type(2), aligned(4)));   // four bf16 values at any 4-byte aligned address
 
 static inline int64_t P8(int64_t x) { return (x + 7) / 8 * 8; }
 
@@ -80,7 +77,10 @@ __host__ __device__ __forceinline__ int64_t tm(int64_t r, int64_t k, int64_t kt)
   return (((r >> 7) * kt + (k >> 5)) << 12) + ((r & 127) << 5) + (k & 31);
 }
 static inline int tiles128(int64_t x) { return (int)((x + 127) / 128); }
-static inline int chunks32(int64_t x) { return (int)((x + 31) / 32); }
+// chunks per 128-row tile of a tensor with x contraction indices: whole groups of four, so that a
+// 128-unit tile of the weight-gradient contractions (which take units as output rows) finds all its
+// four chunks; the padding stays zero
+static inline int chunks32(int64_t x) { return 4 * (int)((x + 127) / 128); }
 
 // In LDS a chunk keeps its 8 KB (row r at byte 64 r, no padding); the four 16-byte pieces of a row
 // are stored in the order q ^ ((r >> 2) & 3).  A fragment read takes one piece of each of 32
@@ -121,11 +121,9 @@ struct Mm5Args {
   int workers;
   const int32_t *rep;           // optional: the B side of worker m is read at worker rep[m]'s offset (shared reference points)
   int Bp;                       // padded rows per worker (multiple of 128)
-  int64_t ktT;                  // chunks per tile of the transposed tensors = M_workers * Bp / 32
-  // EPI_FWD_HIDDEN / EPI_DA: bias offset, row-major and transposed outputs
+  // EPI_FWD_HIDDEN / EPI_DA: bias offset, outputs
   int64_t offb;
   bf16_t *o_h, *o_l, *o_d, *o_r;        // (padded row, column), kto chunks per tile
-  bf16_t *t_h, *t_l, *t_d, *t_r;        // transposed: (column, padded row), ktT chunks per tile
   int64_t kto;
   uint64_t *maskbits;                   // ReLU mask bits [workers][row tiles][column tiles][256 lanes][2]: written by EPI_FWD_HIDDEN, read by EPI_DA
   float *dbpart, *ddbpart;              // EPI_DA: [M_workers][2 x row tiles][N], one partial sum per 64-row band
@@ -140,7 +138,15 @@ __device__ __forceinline__ float delta_theta(const DevState &s, const RefPtr &re
   return (s.theta[i] - ref.hi[i]) + (s.theta_lo[i] - ref.lo[i]);
 }
 __device__ __forceinline__ float *fresh_grad(const DevState &s, int m) {
-  return s.gbuf + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.p;
+  return s.gbuf + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.ps;
+}
+
+// CADA1's stored innovations (bf16): the row this step writes and the row of the last upload.
+__device__ __forceinline__ bf16_t *fresh_innov(const DevState &s, int m) {
+  return s.dtl16 + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.ps16;
+}
+__device__ __forceinline__ const bf16_t *stored_innov(const DevState &s, int m) {
+  return s.dtl16 + ((int64_t)s.sel[m] * s.M + m) * s.ps16;
 }
 
 __device__ __forceinline__ u32x4 pack8(const bf16_t (&v)[8]) {
@@ -163,11 +169,33 @@ __device__ __forceinline__ u32x4 pack8(const bf16_t (&v)[8]) {
 // are free (NS more loads may go out).  The epilogues use no workgroup barrier, so both roles
 // execute the same number of them.  (With four wavefronts doing load, LDS write and multiply in
 // turn, the three phases of a step, each near 1000 cycles, ran one after the other.)
+//
+// Weight gradient (EPI_DW): the product sums over a worker's rows, and both operands are (row, unit)
+// tensors whose 128-row tiles hold the rows.  A tile step covers 32 rows; the operand of a side is the
+// 32 rows x 128 units block of them, which lies in four chunks (one per 32 units) as 2 KB of
+// consecutive memory each.  It is stored in its ring slot as [unit chunk][row][unit], and a fragment
+// (8 consecutive rows of one unit per lane) is read with two transposing LDS loads.
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+
+// Fragment of a transposed operand: 8 consecutive rows (k) of unit (lane % 32) from a [32 rows][32 units]
+// block at `blk` (bf16), rows from `krow` on.  ds_read_b64_tr_b16 works on groups of 16 lanes: source lane s
+// of a group passes the address of four consecutive units of row s / 4, and lane l receives, for
+// e = 0..3, element l % 4 of source lane 4 e + l / 4: unit l of rows 0..3.  The four groups of a
+// wavefront are (units 0-15 | 16-31) x (rows 0-7 | 8-15 of the half step, as the MFMA operand wants).
+__device__ __forceinline__ bf16x8 tr_fragment(const bf16_t *blk, int lane_off) {
+  const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(blk + lane_off));
+  const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(blk + lane_off + 4 * 32));
+  typedef short i16x8 __attribute__((ext_vector_type(8)));
+  const i16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 template <int EPI, int NA, int NB, bool HAS_D>
 __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = reinterpret_cast<bf16_t *>(smem_raw);
   constexpr int NS = NA + NB, NSLOT = mm5_slots(EPI);
+  constexpr bool TR = EPI == EPI_DW;          // operands are (row, unit) tensors read across the rows
   static_assert(NSLOT >= 2 * NS, "the ring must hold two tile steps");
   const DevState &s = g.s;
   const bool mover = __builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kBlock;   // uniform per wavefront
@@ -192,18 +220,22 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
     const int lw = __builtin_amdgcn_readfirstlane(w);
     int goff[2];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) goff[c] = lds_piece((2 * lw + c) * 64 + lane) * 8;      // (the order is its own inverse)
+    for (int c = 0; c < 2; ++c) {
+      if constexpr (TR) goff[c] = (lw << 12) + (c << 9) + lane * 8;    // kilobyte 2 w + c of the step's operand: half c of unit chunk w
+      else goff[c] = lds_piece((2 * lw + c) * 64 + lane) * 8;          // (the order is its own inverse)
+    }
     // issue cursor: tile ordinal, step in the tile, first chunk of the tile's rows in every tensor, ring slot
     int ord = 0, h = 0, slot = 0;
     const bf16_t *pa[NA], *pb[NB];
     auto set_tile = [&](int o) __attribute__((always_inline)) {
       const int tix = t_first + o * nbx;
       const int bx = tix % gx, by = (tix / gx) % gy, bz = tix / (gx * gy);
+      // (TR: the worker's first row tile, chunk 4 by / 4 bx of its units; else row tile by / bx, first chunk)
 #pragma unroll
-      for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)bz * g.A.bstride[sl] + (((int64_t)by * g.A.kt[sl]) << 12);
+      for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)bz * g.A.bstride[sl] + (((int64_t)by * (TR ? 4 : g.A.kt[sl])) << 12);
       const int bzb = g.rep ? g.rep[bz] : bz;
 #pragma unroll
-      for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)bzb * g.B.bstride[sl] + (((int64_t)bx * g.B.kt[sl]) << 12);
+      for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)bzb * g.B.bstride[sl] + (((int64_t)bx * (TR ? 4 : g.B.kt[sl])) << 12);
     };
     // next tile step; past the last one the cursor stays (those loads re-read the last chunk into slots nobody reads)
     auto next_step = [&]() __attribute__((always_inline)) {
@@ -211,7 +243,13 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
       else if (ord + 1 < nt) { ++ord; h = 0; set_tile(ord); }
     };
     auto load = [&](int sl) __attribute__((always_inline)) {
-      const bf16_t *src = (sl < NA ? pa[sl < NA ? sl : 0] : pb[sl < NA ? 0 : sl - NA]) + ((int64_t)h << 12);
+      const bf16_t *src = sl < NA ? pa[sl < NA ? sl : 0] : pb[sl < NA ? 0 : sl - NA];
+      if constexpr (TR) {      // rows 32 h .. 32 h + 31 of the worker: row tile h / 4, 32 rows of 32 units from row 32 (h % 4) on
+        const int64_t kt = sl < NA ? g.A.kt[sl < NA ? sl : 0] : g.B.kt[sl < NA ? 0 : sl - NA];
+        src += (((int64_t)(h >> 2) * kt) << 12) + ((h & 3) << 10);
+      } else {
+        src += (int64_t)h << 12;
+      }
       bf16_t *dst = lds + ((size_t)slot << 12) + (2 * lw << 9);
 #pragma unroll
       for (int c = 0; c < 2; ++c)
@@ -243,6 +281,8 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
 
   // fragment of this lane inside a 32-row band: row lane % 32, piece lane / 32 (+ 2 in the second half step)
   const int fro = lds_piece((lane & 31) * 4 + (lane >> 5)) * 8;
+  // transposed operands: this lane's source address inside a [32 rows][32 units] block (see tr_fragment)
+  const int fro_tr = (8 * (lane >> 5) + ((lane & 15) >> 2)) * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   int sb = 0;                                  // ring slot of the current step's first tensor
   for (int ord = 0; ord < nt; ++ord) {
   const int tix = t_first + ord * nbx;
@@ -265,27 +305,30 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       bf16x8 ah[2], al[2], ad[2], ar[2], bh[2], bl[2], bx_[2], bd[2];
+      // (TR: unit block 2 wy + i of the step's [4][32 rows][32 units], rows ks .. ks + 15)
+      auto frag = [&](const bf16_t *slot, int half, int blk) __attribute__((always_inline)) -> bf16x8 {
+        if constexpr (TR) return tr_fragment(slot + (half * 2 + blk) * 1024 + ks * 32, fro_tr);
+        else return *reinterpret_cast<const bf16x8 *>(slot + (half * 64 + blk * 32) * BK + (fro ^ ks));
+      };
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int o = (wy * 64 + i * 32) * BK + (fro ^ ks);
-        ah[i] = *reinterpret_cast<const bf16x8 *>(tah + o);
-        al[i] = *reinterpret_cast<const bf16x8 *>(tal + o);
-        if constexpr (HAS_D) ad[i] = *reinterpret_cast<const bf16x8 *>(tad + o);
+        ah[i] = frag(tah, wy, i);
+        al[i] = frag(tal, wy, i);
+        if constexpr (HAS_D) ad[i] = frag(tad, wy, i);
         // with fewer than four A tensors the reference operand is the hi part itself
-        if constexpr (NA == 4) ar[i] = *reinterpret_cast<const bf16x8 *>(tar + o);
+        if constexpr (NA == 4) ar[i] = frag(tar, wy, i);
         else ar[i] = ah[i];
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const int o = (wx * 64 + j * 32) * BK + (fro ^ ks);
-        bh[j] = *reinterpret_cast<const bf16x8 *>(tbh + o);
-        bl[j] = *reinterpret_cast<const bf16x8 *>(tbl + o);
+        bh[j] = frag(tbh, wx, j);
+        bl[j] = frag(tbl, wx, j);
         // with fewer than four B tensors the single-bf16 operand is the hi part itself
         if constexpr (HAS_D) {
-          if constexpr (NB == 4) bx_[j] = *reinterpret_cast<const bf16x8 *>(tbx + o);
+          if constexpr (NB == 4) bx_[j] = frag(tbx, wx, j);
           else bx_[j] = bh[j];
         }
-        bd[j] = *reinterpret_cast<const bf16x8 *>(tbd + o);
+        bd[j] = frag(tbd, wx, j);
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
@@ -335,7 +378,6 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
     bf16_t *sg = reinterpret_cast<bf16_t *>(smem_raw + (size_t)NSLOT * TILE * sizeof(bf16_t)) + w * 4096;   // 4 x 2 KB
     const int wr0 = m0 + wy * 64, wc0 = n0 + wx * 64;       // first row and column of this wavefront's 64 x 64 part
     bf16_t *const orow_t[4] = {g.o_h, g.o_l, g.o_d, g.o_r};
-    bf16_t *const ocol_t[4] = {g.t_h, g.t_l, g.t_d, g.t_r};
     auto copy_out = [&](bf16_t *const (&dst)[4], int64_t goff) __attribute__((always_inline)) {
       asm volatile("" ::: "memory");
 #pragma unroll
@@ -362,45 +404,56 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
       bit_ref = (uint64_t)mb.z | ((uint64_t)mb.w << 32);
     }
 
-    const RefPtr ref = theta_ref(s, wk, s.k);
+    // (both columns' biases are asked for before either is used: one memory latency, not two)
+    float bias[2] = {0.f, 0.f}, dbias[2] = {0.f, 0.f};
+    if constexpr (EPI == EPI_FWD_HIDDEN) {
+      const RefPtr ref = theta_ref(s, wk, s.k);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = min(cbase + j * 32, g.N - 1);
+        bias[j] = s.theta[g.offb + col];
+        dbias[j] = delta_theta(s, ref, g.offb + col);
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = cbase + j * 32;
       const bool cok = col < g.N;
-      float b = 0.f, db = 0.f;
-      if constexpr (EPI == EPI_FWD_HIDDEN) {
-        b = cok ? s.theta[g.offb + col] : 0.f;
-        db = cok ? delta_theta(s, ref, g.offb + col) : 0.f;
-      }
+      const float b = bias[j], db = dbias[j];
       float sg_sum = 0.f, sd_sum = 0.f;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         // the quarter's four values per element, packed two rows to a register
         uint32_t ph[8], pl[8], pd[8], pr[8];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
-          float x = 0.f, xref = 0.f;                // value at theta, at the reference point
-          if (cok && row < g.M) {
-            if constexpr (EPI == EPI_FWD_HIDDEN) {
-              const float z = acc1[i][j][r] + b, dz = acc2[i][j][r] + db;
-              x = fmaxf(z, 0.f); xref = fmaxf(z - dz, 0.f);
-            } else {
-              const float ga = acc1[i][j][r], dga = acc2[i][j][r];
-              x = (bit_on >> ((i * 2 + j) * 16 + r)) & 1 ? ga : 0.f;
-              xref = (bit_ref >> ((i * 2 + j) * 16 + r)) & 1 ? (ga - dga) : 0.f;
+        for (int rp = 0; rp < 8; ++rp) {
+          float x[2], xref[2];                      // value at theta, at the reference point; rows r, r + 1
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int r = 2 * rp + e;
+            const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+            x[e] = 0.f; xref[e] = 0.f;
+            if (cok && row < g.M) {
+              if constexpr (EPI == EPI_FWD_HIDDEN) {
+                const float z = acc1[i][j][r] + b, dz = acc2[i][j][r] + db;
+                x[e] = fmaxf(z, 0.f); xref[e] = fmaxf(z - dz, 0.f);
+              } else {
+                const float ga = acc1[i][j][r], dga = acc2[i][j][r];
+                x[e] = (bit_on >> ((i * 2 + j) * 16 + r)) & 1 ? ga : 0.f;
+                xref[e] = (bit_ref >> ((i * 2 + j) * 16 + r)) & 1 ? (ga - dga) : 0.f;
+              }
             }
+            sg_sum += x[e]; sd_sum += x[e] - xref[e];
           }
-          const float dx = x - xref;
-          const bf16_t hi = f2bf(x);
-          const uint32_t vh = hi, vl = f2bf(x - bf2f(hi)), vd = f2bf(dx), vr = f2bf(xref);
+          const uint32_t vh = f2bf_pk(x[0], x[1]), vr = f2bf_pk(xref[0], xref[1]);
+          ph[rp] = vh; pr[rp] = vr;
+          pl[rp] = f2bf_pk(x[0] - __uint_as_float(vh << 16), x[1] - __uint_as_float(vh & 0xffff0000u));
+          pd[rp] = f2bf_pk(x[0] - xref[0], x[1] - xref[1]);
           if constexpr (EPI == EPI_FWD_HIDDEN) {      // (the sign of the stored, rounded value)
-            bit_on |= (uint64_t)(bf2f(hi) > 0.f ? 1 : 0) << ((i * 2 + j) * 16 + r);
-            bit_ref |= (uint64_t)(bf2f((bf16_t)vr) > 0.f ? 1 : 0) << ((i * 2 + j) * 16 + r);
+            const int sh = (i * 2 + j) * 16 + 2 * rp;
+            bit_on |= (uint64_t)((__uint_as_float(vh << 16) > 0.f ? 1u : 0u) | (__uint_as_float(vh & 0xffff0000u) > 0.f ? 2u : 0u)) << sh;
+            bit_ref |= (uint64_t)((__uint_as_float(vr << 16) > 0.f ? 1u : 0u) | (__uint_as_float(vr & 0xffff0000u) > 0.f ? 2u : 0u)) << sh;
           }
-          if (r & 1) { ph[r >> 1] |= vh << 16; pl[r >> 1] |= vl << 16; pd[r >> 1] |= vd << 16; pr[r >> 1] |= vr << 16; }
-          else { ph[r >> 1] = vh; pl[r >> 1] = vl; pd[r >> 1] = vd; pr[r >> 1] = vr; }
-          sg_sum += x; sd_sum += dx;
         }
         // (row, column) layout: element (rl, cl) of the quarter at 32 rl + cl
         if (g.o_h != nullptr && wc0 + j * 32 < (int)g.kto * 32) {
@@ -412,16 +465,6 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
           }
           copy_out(orow_t, tm(rp0 + wr0 + i * 32, wc0 + j * 32, g.kto));
         }
-        // (column, row) layout: element (rl, cl) at 32 cl + rl; four consecutive rows are one 8-byte write
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int e = (lane & 31) * 32 + 8 * q + 4 * (lane >> 5);
-          *reinterpret_cast<uint2 *>(sg + e) = make_uint2(ph[2 * q], ph[2 * q + 1]);
-          *reinterpret_cast<uint2 *>(sg + 1024 + e) = make_uint2(pl[2 * q], pl[2 * q + 1]);
-          *reinterpret_cast<uint2 *>(sg + 2048 + e) = make_uint2(pd[2 * q], pd[2 * q + 1]);
-          *reinterpret_cast<uint2 *>(sg + 3072 + e) = make_uint2(pr[2 * q], pr[2 * q + 1]);
-        }
-        copy_out(ocol_t, tm(wc0 + j * 32, rp0 + wr0 + i * 32, g.ktT));
       }
       if constexpr (EPI == EPI_DA) {
         // the other half-wave holds the rows offset by 4: add it, then one value per column and
@@ -451,13 +494,14 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
     float *st = reinterpret_cast<float *>(smem_raw + (size_t)NSLOT * TILE * sizeof(bf16_t)) + w * (32 * SP);
     float *gf = fresh_grad(s, wk) + g.offW;
     const bool cada1 = s.rule == CADA_RULE_CADA1;
-    const int cur = s.sel[wk];
-    float *ivf = cada1 ? s.dtl + ((int64_t)(1 - cur) * s.M + wk) * s.p + g.offW : nullptr;
-    const float *ivs = cada1 ? s.dtl + ((int64_t)cur * s.M + wk) * s.p + g.offW : nullptr;
+    bf16_t *ivf = cada1 ? fresh_innov(s, wk) + g.offW : nullptr;
+    const bf16_t *ivs = cada1 ? stored_innov(s, wk) + g.offW : nullptr;
     // row-wise pass: this lane has columns c4 .. c4+3 of the band's rows rr + 4 it, it = 0..7
     const int c4 = (lane & 15) * 4, rr = lane >> 4;
     const int colg = n0 + wx * 64 + c4;
-    const bool wide = n0 + wx * 64 + 64 <= g.N;       // every column of this wavefront's part exists: 16-byte accesses (4-byte aligned)
+    // every column of this wavefront's part exists: 16-byte accesses (4-byte aligned; with stored bf16
+    // innovations their 8-byte accesses need an even offset and row length for that)
+    const bool wide = n0 + wx * 64 + 64 <= g.N && (!cada1 || ((g.offW | (int64_t)g.N) & 1) == 0);
     auto put_band = [&](const f32x16 (&acc)[2]) __attribute__((always_inline)) {
 #pragma unroll
       for (int j = 0; j < 2; ++j)
@@ -468,32 +512,23 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
     // CADA1: the stored innovations of the part, all loads issued before anything waits for one
     // (rows clamped into the matrix so that no load sits under a branch).  Gradients and innovations
     // are written once and read once per step, megabytes apart in time: non-temporal accesses.
-    f32x4u old[2][8];
+    u32x2u old[2][8];        // four bf16 values each
     if (cada1 && wide) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
           const int row = min(m0 + wy * 64 + i * 32 + rr + 4 * it, g.M - 1);
-          old[i][it] = *reinterpret_cast<const f32x4u *>(ivs + (int64_t)row * g.N + colg);
+          old[i][it] = *reinterpret_cast<const u32x2u *>(ivs + (int64_t)row * g.N + colg);
         }
     }
+    // The innovation first, the gradient last: the innovation's part waits for the loads of the stored
+    // innovations (and a wait for a load also waits for every store issued before it), whereas nothing
+    // in this tile waits behind the gradient's stores: they drain while the next tile's products run.
     float sq = 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int rowb = m0 + wy * 64 + i * 32 + rr;
-      put_band(acc1[i]);
-      if (wide) {
-#pragma unroll
-        for (int it = 0; it < 8; ++it) {
-          const f32x4u v = *reinterpret_cast<const f32x4u *>(st + (rr + 4 * it) * SP + c4);
-          if (rowb + 4 * it < g.M) __builtin_nontemporal_store(v, reinterpret_cast<f32x4u *>(gf + (int64_t)(rowb + 4 * it) * g.N + colg));
-        }
-      } else if (colg < g.N) {                 // a part that overhangs the matrix: element by element
-        for (int it = 0; it < 8 && rowb + 4 * it < g.M; ++it)
-          for (int e = 0; e < 4 && colg + e < g.N; ++e) gf[(int64_t)(rowb + 4 * it) * g.N + colg + e] = st[(rr + 4 * it) * SP + c4 + e];
-      }
-      asm volatile("" ::: "memory");
       if (!cada1) {       // nothing to store or to subtract: the squared norm needs no particular order of the elements
 #pragma unroll
         for (int j = 0; j < 2; ++j)
@@ -511,21 +546,39 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
         for (int it = 0; it < 8; ++it) {
           f32x4u v = *reinterpret_cast<const f32x4u *>(st + (rr + 4 * it) * SP + c4);
           if (rowb + 4 * it < g.M) {
-            if (cada1) {
-              *reinterpret_cast<f32x4u *>(ivf + (int64_t)(rowb + 4 * it) * g.N + colg) = v;
-              v -= old[i][it];
-            }
+            u32x2u nw;
+            nw.x = f2bf_pk(v.x, v.y); nw.y = f2bf_pk(v.z, v.w);
+            *reinterpret_cast<u32x2u *>(ivf + (int64_t)(rowb + 4 * it) * g.N + colg) = nw;
+            const u32x2u o = old[i][it];
+            v.x -= bf2f((bf16_t)o.x); v.y -= bf2f((bf16_t)(o.x >> 16)); v.z -= bf2f((bf16_t)o.y); v.w -= bf2f((bf16_t)(o.y >> 16));
             sq = fmaf(v.x, v.x, sq); sq = fmaf(v.y, v.y, sq); sq = fmaf(v.z, v.z, sq); sq = fmaf(v.w, v.w, sq);
           }
         }
-      } else if (colg < g.N) {
+      } else if (colg < g.N) {                 // a part that overhangs the matrix: element by element
         for (int it = 0; it < 8 && rowb + 4 * it < g.M; ++it)
           for (int e = 0; e < 4 && colg + e < g.N; ++e) {
             const int64_t o = (int64_t)(rowb + 4 * it) * g.N + colg + e;
             float iv = st[(rr + 4 * it) * SP + c4 + e];
-            if (cada1) { ivf[o] = iv; iv -= ivs[o]; }
+            ivf[o] = f2bf(iv);
+            iv -= bf2f(ivs[o]);
             sq = fmaf(iv, iv, sq);
           }
+      }
+      asm volatile("" ::: "memory");
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int rowb = m0 + wy * 64 + i * 32 + rr;
+      put_band(acc1[i]);
+      if (wide) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          const f32x4u v = *reinterpret_cast<const f32x4u *>(st + (rr + 4 * it) * SP + c4);
+          if (rowb + 4 * it < g.M) __builtin_nontemporal_store(v, reinterpret_cast<f32x4u *>(gf + (int64_t)(rowb + 4 * it) * g.N + colg));
+        }
+      } else if (colg < g.N) {
+        for (int it = 0; it < 8 && rowb + 4 * it < g.M; ++it)
+          for (int e = 0; e < 4 && colg + e < g.N; ++e) gf[(int64_t)(rowb + 4 * it) * g.N + colg + e] = st[(rr + 4 * it) * SP + c4 + e];
       }
       asm volatile("" ::: "memory");
     }
@@ -542,8 +595,11 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
 // 32 rows x 32 columns; its eight wavefronts split the tile steps (wavefront w takes steps w,
 // w + 8, ...), read their fragments straight from the chunks in global memory (a fragment is
 // 16 consecutive bytes of a chunk row) and add their partial accumulators up through LDS in a
-// fixed order.  grid (ceil(M / 32), workers), 512 threads, 64 KB of dynamic LDS.
+// fixed order.  grid (ceil(M / 32), workers), 512 threads, 64 KB of dynamic LDS (EPI_DW: 112 KB).
 // EPI_STORE2: logits; EPI_DW: weight gradient, innovation, its squared norm (slot lhs_slot0 + row band).
+// The weight gradient sums over the worker's rows: its operands are (row, unit) tensors, a step's part of
+// one is a [32 rows][32 units] block (2 KB of consecutive memory), which the wavefront copies into an
+// LDS area of its own and reads back transposed (tr_fragment).
 template <int EPI, int NA, int NB, bool HAS_D>
 __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -556,13 +612,54 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
   const int64_t offa = (((int64_t)(m0 >> 7) * g.A.kt[0]) << 12) + (((m0 & 127) + (lane & 31)) << 5) + ((lane >> 5) << 3);
   const int64_t offb = ((lane & 31) << 5) + ((lane >> 5) << 3);
   const bf16_t *pa[NA], *pb[NB];
+  f32x16 acc1, acc2;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { acc1[r] = 0.f; acc2[r] = 0.f; }
+  if constexpr (EPI == EPI_DW) {
+    // units m0 .. m0 + 31 of the A tensors are chunk m0 / 32 of every row tile, the (at most 32) output
+    // columns chunk 0 of the B tensors; step kc covers the worker's rows 32 kc .. 32 kc + 31
+#pragma unroll
+    for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + ((int64_t)(m0 >> 5) << 12);
+#pragma unroll
+    for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl];
+    bf16_t *area = reinterpret_cast<bf16_t *>(smem_raw) + w * (7 * 1024);       // room for seven blocks per wavefront
+    const int fro_tr = (8 * (lane >> 5) + ((lane & 15) >> 2)) * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    for (int kc = w; kc < nk; kc += 8) {
+      u32x4 v[NA + NB][2];
+#pragma unroll
+      for (int sl = 0; sl < NA + NB; ++sl) {
+        const bf16_t *src = (sl < NA ? pa[sl < NA ? sl : 0] + (((int64_t)(kc >> 2) * g.A.kt[sl < NA ? sl : 0]) << 12)
+                                     : pb[sl < NA ? 0 : sl - NA] + (((int64_t)(kc >> 2) * g.B.kt[sl < NA ? 0 : sl - NA]) << 12)) + ((kc & 3) << 10);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) v[sl][hh] = *reinterpret_cast<const u32x4 *>(src + (hh * 64 + lane) * 8);
+      }
+#pragma unroll
+      for (int sl = 0; sl < NA + NB; ++sl)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) *reinterpret_cast<u32x4 *>(area + sl * 1024 + (hh * 64 + lane) * 8) = v[sl][hh];
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // (one wavefront's LDS operations are carried out in order)
+#pragma unroll
+      for (int ks = 0; ks < BK; ks += 16) {
+        auto fr = [&](int sl) __attribute__((always_inline)) { return tr_fragment(area + sl * 1024 + ks * 32, fro_tr); };
+        // (roles as below: hi, lo, [difference] on the A side; hi, lo, [reference,] difference on the B side)
+        const bf16x8 ah = fr(0), al = fr(1), bh = fr(NA), bl = fr(NA + 1), bd = fr(NA + NB - 1);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc1, 0, 0, 0);
+        if constexpr (HAS_D) {
+          const bf16x8 ad = fr(2), bx = NB == 4 ? fr(NA + 2) : bh;
+          acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, bx, acc2, 0, 0, 0);
+        }
+        acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bd, acc2, 0, 0, 0);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the fragments are in registers before the area is written again
+    }
+    __syncthreads();                                         // the areas are done with: `red` lies over them
+  } else {
 #pragma unroll
   for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + offa;
 #pragma unroll
   for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)(g.rep ? g.rep[wk] : wk) * g.B.bstride[sl] + offb;
-  f32x16 acc1, acc2;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { acc1[r] = 0.f; acc2[r] = 0.f; }
   for (int kc = w; kc < nk; kc += 8) {
     u32x4 fa[2][NA], fb[2][NB];          // (kept as integer vectors: arrays of them stay in registers)
 #pragma unroll
@@ -590,6 +687,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
       acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ar, bd, acc2, 0, 0, 0);
     }
   }
+  }
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     red[((w * 2 + 0) * 16 + r) * 64 + lane] = acc1[r];
@@ -597,15 +695,15 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
   }
   __syncthreads();
   // 2 x 16 x 64 values, four per thread, each the sum of the eight partial results in wavefront order
-  float *gf = nullptr, *ivf = nullptr;
-  const float *ivs = nullptr;
+  float *gf = nullptr;
+  bf16_t *ivf = nullptr;
+  const bf16_t *ivs = nullptr;
   const bool cada1 = s.rule == CADA_RULE_CADA1;
   if constexpr (EPI == EPI_DW) {
     gf = fresh_grad(s, wk) + g.offW;
     if (cada1) {
-      const int cur = s.sel[wk];
-      ivf = s.dtl + ((int64_t)(1 - cur) * s.M + wk) * s.p + g.offW;
-      ivs = s.dtl + ((int64_t)cur * s.M + wk) * s.p + g.offW;
+      ivf = fresh_innov(s, wk) + g.offW;
+      ivs = stored_innov(s, wk) + g.offW;
     }
   }
   float sq = 0.f;
@@ -625,7 +723,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
         const int64_t o = (int64_t)row * g.N + col;
         if (a == 0) gf[o] = v;
         else {
-          if (cada1) { ivf[o] = v; v -= ivs[o]; }
+          if (cada1) { ivf[o] = f2bf(v); v -= bf2f(ivs[o]); }
           sq = fmaf(v, v, sq);
         }
       }
@@ -651,7 +749,6 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
 struct MlpPlan {
   int L, M, B, Bp, rule, RT;
   int64_t Rp;                     // M * Bp padded rows per step (Bp a multiple of 128: a worker's rows start a tile)
-  int64_t ktT;                    // Rp / 32: chunks per tile of the transposed tensors
   int64_t total_rows;             // rows of X
   int64_t max_rows_per_worker;
   int d[CADA_MAX_LAYERS + 1];
@@ -662,14 +759,11 @@ struct MlpPlan {
   int lhs_w_slot[CADA_MAX_LAYERS], lhs_b_slot[CADA_MAX_LAYERS];
   int nW;                                                 // delta-weight copies: 1 (CADA1) or M (CADA2)
   bf16_t *Xh, *Xl; int64_t ldx;                           // all features, rows one after the other [total_rows][ldx]
-  bf16_t *XTh, *XTl;                                      // gathered minibatch, (feature, padded row)
   bf16_t *XGh, *XGl;                                      // gathered minibatch, (padded row, feature)
   int64_t *grow;
   bf16_t *WTh, *WTl, *dWT, *WNh, *WNl, *dWN;
   bf16_t *Ah[CADA_MAX_LAYERS], *Al[CADA_MAX_LAYERS], *dA[CADA_MAX_LAYERS], *Aref[CADA_MAX_LAYERS];   // hidden l, (row, unit)
-  bf16_t *AhT[CADA_MAX_LAYERS], *AlT[CADA_MAX_LAYERS], *dAT[CADA_MAX_LAYERS];                        // hidden l, (unit, row)
-  bf16_t *Gh[CADA_MAX_LAYERS + 1], *Gl[CADA_MAX_LAYERS + 1], *dG[CADA_MAX_LAYERS + 1], *Gref[CADA_MAX_LAYERS + 1];       // layer l >= 2, (row, unit)
-  bf16_t *GhT[CADA_MAX_LAYERS + 1], *GlT[CADA_MAX_LAYERS + 1], *dGT[CADA_MAX_LAYERS + 1], *GrefT[CADA_MAX_LAYERS + 1];   // layer l, (unit, row)
+  bf16_t *Gh[CADA_MAX_LAYERS + 1], *Gl[CADA_MAX_LAYERS + 1], *dG[CADA_MAX_LAYERS + 1], *Gref[CADA_MAX_LAYERS + 1];       // layer l >= 1, (row, unit)
   float *ZL, *dZL;                                        // logits [Rp][C]
   uint64_t *maskbits[CADA_MAX_LAYERS];                    // hidden l: ReLU mask bits per tile and lane
   int32_t *rep;                                           // CADA2: first worker with the same reference point [M]
@@ -695,7 +789,6 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.RT = tiles128(cfg->B);
   P.Bp = P.RT * 128;
   P.Rp = (int64_t)cfg->M * P.Bp;
-  P.ktT = P.Rp / 32;
   P.total_rows = total_rows;
   P.max_rows_per_worker = 0;
   for (int m = 0; m < cfg->M; ++m)
@@ -718,8 +811,6 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   const size_t Rp = (size_t)P.Rp;
   P.Xh = w.take<bf16_t>((size_t)total_rows * P.ldx);
   P.Xl = w.take<bf16_t>((size_t)total_rows * P.ldx);
-  P.XTh = w.take<bf16_t>(tm_elems(P.d[0], Rp));
-  P.XTl = w.take<bf16_t>(tm_elems(P.d[0], Rp));
   P.XGh = w.take<bf16_t>(tm_elems(Rp, P.d[0]));
   P.XGl = w.take<bf16_t>(tm_elems(Rp, P.d[0]));
   P.grow = w.take<int64_t>(Rp);
@@ -727,19 +818,14 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.WTh = w.take<bf16_t>((size_t)wt); P.WTl = w.take<bf16_t>((size_t)wt); P.dWT = w.take<bf16_t>((size_t)wt * P.nW);
   P.WNh = w.take<bf16_t>((size_t)wn + 8); P.WNl = w.take<bf16_t>((size_t)wn + 8); P.dWN = w.take<bf16_t>((size_t)wn * P.nW + 8);
   for (int l = 1; l < P.L; ++l) {
-    const size_t n = tm_elems(Rp, P.d[l]), nt = tm_elems(P.d[l], Rp);
+    const size_t n = tm_elems(Rp, P.d[l]);
     P.Ah[l] = w.take<bf16_t>(n); P.Al[l] = w.take<bf16_t>(n); P.dA[l] = w.take<bf16_t>(n); P.Aref[l] = w.take<bf16_t>(n);
-    P.AhT[l] = w.take<bf16_t>(nt); P.AlT[l] = w.take<bf16_t>(nt); P.dAT[l] = w.take<bf16_t>(nt);
     P.maskbits[l] = w.take<uint64_t>((size_t)cfg->M * P.RT * tiles128(P.d[l]) * kBlock * 2);
   }
   for (int l = 1; l <= P.L; ++l) {
-    const size_t n = tm_elems(Rp, P.d[l]), nt = tm_elems(P.d[l], Rp);
-    P.GhT[l] = w.take<bf16_t>(nt); P.GlT[l] = w.take<bf16_t>(nt); P.dGT[l] = w.take<bf16_t>(nt); P.GrefT[l] = w.take<bf16_t>(nt);
-    if (l >= 2) {
-      P.Gh[l] = w.take<bf16_t>(n); P.Gl[l] = w.take<bf16_t>(n); P.dG[l] = w.take<bf16_t>(n); P.Gref[l] = w.take<bf16_t>(n);
-    } else {
-      P.Gh[l] = P.Gl[l] = P.dG[l] = P.Gref[l] = nullptr;
-    }
+    const size_t n = tm_elems(Rp, P.d[l]);
+    P.Gh[l] = w.take<bf16_t>(n); P.Gl[l] = w.take<bf16_t>(n); P.dG[l] = w.take<bf16_t>(n);
+    P.Gref[l] = l >= 2 ? w.take<bf16_t>(n) : nullptr;       // (the first layer has no propagated difference to pair it with)
   }
   P.ZL = w.take<float>(Rp * P.d[P.L]);
   P.dZL = w.take<float>(Rp * P.d[P.L]);
@@ -822,12 +908,12 @@ struct PrepLayer {
 
 struct StageArgs {
   DevState s;
-  // minibatch: XG(m*Bp + b, c) = X[grow[m*Bp + b]][c] and XT(c, m*Bp + b) = the same
+  // minibatch: XG(m*Bp + b, c) = X[grow[m*Bp + b]][c]
   const bf16_t *Xh, *Xl; int64_t ldx;
   const int32_t *idx;    // [M][B] sampled rows, local to each worker's shard
   int64_t *grow;         // out: grow[m*Bp + b] = global row of worker m's b-th sample (b < B)
-  bf16_t *XTh, *XTl, *XGh, *XGl;
-  int d0, B, Bp; int64_t ktx, ktT;
+  bf16_t *XGh, *XGl;
+  int d0, B, Bp; int64_t ktx;
   int gx, gy;            // 64 x 64 tiles over (ldx, B)
   // weights
   PrepLayer layer[CADA_MAX_LAYERS];
@@ -840,12 +926,9 @@ struct StageArgs {
   uint32_t first[CADA_MAX_LAYERS + 2];   // first block of the minibatch part (0), of each layer, and the total
 };
 
-// A 64 x 64 tile of the minibatch, moved 16 bytes (8 values) per lane: rows of X are read and
-// written to XG as they are, and turned through LDS for XT.
-__device__ __forceinline__ void stage_minibatch(const StageArgs &a, unsigned char *sm, int bx, int by, int m) {
-  typedef bf16_t tile_t[64][72];               // pitch 72: 16-byte rows, 8 rows span all banks
-  tile_t &th = *reinterpret_cast<tile_t *>(sm);
-  tile_t &tl = *reinterpret_cast<tile_t *>(sm + sizeof(tile_t));
+// A 64 x 64 tile of the minibatch, moved 16 bytes (8 values) per lane: the sampled rows of X's bf16
+// copies go to XG as they are.
+__device__ __forceinline__ void stage_minibatch(const StageArgs &a, int bx, int by, int m) {
   const int c0 = bx * 64, b0 = by * 64;
   const int t = threadIdx.x;
   const int cg = (t & 7) * 8;                   // this thread's 8 columns
@@ -853,7 +936,6 @@ __device__ __forceinline__ void stage_minibatch(const StageArgs &a, unsigned cha
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     const int r = (t >> 3) + 32 * pass, b = b0 + r, c = c0 + cg;
-    u32x4 vh = {0u, 0u, 0u, 0u}, vl = {0u, 0u, 0u, 0u};
     if (b < a.B && c < a.ldx) {                 // (columns from d0 to ldx hold zeros in X's copies)
       int64_t row = a.idx[(int64_t)m * a.B + b];
       if (row < 0 || row >= n_m) {              // reported once per sample, by the tile that also records the row
@@ -863,30 +945,11 @@ __device__ __forceinline__ void stage_minibatch(const StageArgs &a, unsigned cha
       row += row0;
       if (bx == 0 && cg == 0) a.grow[(int64_t)m * a.Bp + b] = row;
       const int64_t src = row * a.ldx + c;
-      vh = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.Xh + src));      // (a sampled row is not read again soon)
-      vl = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.Xl + src));
+      const u32x4 vh = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.Xh + src));      // (a sampled row is not read again soon)
+      const u32x4 vl = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.Xl + src));
       const int64_t dst = tm((int64_t)m * a.Bp + b, c, a.ktx);
       *reinterpret_cast<u32x4 *>(a.XGh + dst) = vh;
       *reinterpret_cast<u32x4 *>(a.XGl + dst) = vl;
-    }
-    *reinterpret_cast<u32x4 *>(&th[r][cg]) = vh;
-    *reinterpret_cast<u32x4 *>(&tl[r][cg]) = vl;
-  }
-  __syncthreads();
-  // 8 consecutive rows of one column are 16 consecutive bytes of XT (rows past B are written as zeros)
-  const int f = t & 63;
-  if (c0 + f < a.d0) {
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-      const int rg = ((t >> 6) + 4 * pass) * 8;
-      if (b0 + rg < a.B) {
-        bf16_t h8[8], l8[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { h8[e] = th[rg + e][f]; l8[e] = tl[rg + e][f]; }
-        const int64_t o = tm(c0 + f, (int64_t)m * a.Bp + b0 + rg, a.ktT);
-        *reinterpret_cast<u32x4 *>(a.XTh + o) = pack8(h8);
-        *reinterpret_cast<u32x4 *>(a.XTl + o) = pack8(l8);
-      }
     }
   }
 }
@@ -967,13 +1030,12 @@ __device__ __forceinline__ void stage_weights(const StageArgs &a, const PrepLaye
 }
 
 __global__ __launch_bounds__(kBlock) void k_stage(const StageArgs a) {
-  __shared__ __align__(16) unsigned char sm[2 * 64 * 72 * sizeof(bf16_t)];
-  static_assert(sizeof(sm) >= 64 * 65 * sizeof(float), "the weight tile fits too");
+  __shared__ __align__(16) unsigned char sm[64 * 65 * sizeof(float)];     // a weight tile on its way to the other orientation
   const uint32_t blk = blockIdx.x;
   if (blk < a.first[1]) {
     const uint32_t per = (uint32_t)a.gx * a.gy;
     const uint32_t m = blk / per, r = blk - m * per;
-    stage_minibatch(a, sm, (int)(r % a.gx), (int)(r / a.gx), (int)m);
+    stage_minibatch(a, (int)(r % a.gx), (int)(r / a.gx), (int)m);
     return;
   }
   int l = 0;
@@ -988,16 +1050,21 @@ __global__ __launch_bounds__(kBlock) void k_stage(const StageArgs a) {
 struct LossArgs {
   DevState s;
   const float *Z, *dZ;            // logits without bias [Rp][C]
-  bf16_t *Gh, *Gl, *dG, *Gref;    // (padded row, class), ktg chunks per tile
-  bf16_t *GhT, *GlT, *dGT, *GrefT;   // (class, padded row), ktT chunks per tile
+  bf16_t *Gh, *Gl, *dG, *Gref;    // (padded row, class), ktg chunks per tile; Gref null for a single-layer network
   const int64_t *grow;
-  int64_t offb, ktT;
+  int64_t offb;
   int C, Bp; int64_t ktg;
   int lhs_slot;
 };
 
-// softmax cross-entropy: G = (P - onehot)/B, dG = (P - Pref)/B with
-// P_i - Pref_i = P_i (S - expm1(-dz_i)) / (1 + S),  S = sum_j P_j expm1(-dz_j).
+// softmax cross-entropy: G = (P - onehot)/B, dG = (P - Pref)/B.  With e_i = exp(-dz_i) and
+// T = sum_j P_j e_j the reference probabilities are Pref_i = P_i e_i / T, so
+//     P_i - Pref_i = P_i (S - expm1(-dz_i)) / (1 + S),  S = sum_j P_j expm1(-dz_j) = T - 1,
+// which keeps the digits of a small difference (no subtraction of nearly equal probabilities) and
+// is used while every |dz_j| of the row is below 1/2.  For larger differences (a reference point
+// many iterations old) 1 + S cancels instead (T can be far below float32's resolution of 1), so
+// there P_i - Pref_i is formed directly with Pref = softmax(z - dz), the exponents shifted by their
+// maximum; the difference is then no longer small against its operands.
 // One block of 1024 threads per worker; sixteen lanes share a row, each with two of the (at most
 // 32) classes, so a wavefront holds four rows and the block 64.  Also the last layer's bias
 // gradient, its innovation and the innovation's contribution to the rule's left-hand side.
@@ -1029,12 +1096,18 @@ __global__ __launch_bounds__(kLossBlock) void k_loss(const LossArgs a) {
   float sumG[2] = {0.f, 0.f}, sumD[2] = {0.f, 0.f};
   for (int b = threadIdx.x >> 4; b < s.B; b += kLossBlock / 16) {
     const int64_t r = (int64_t)m * a.Bp + b;
-    float z[2], x[2];
+    float z[2], x[2], ndz[2];
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       z[e] = on[e] ? a.Z[r * a.C + c0 + e] + bz[e] : -INFINITY;
-      x[e] = on[e] ? expm1f(-(a.dZ[r * a.C + c0 + e] + dbz[e])) : 0.f;
+      ndz[e] = on[e] ? -(a.dZ[r * a.C + c0 + e] + dbz[e]) : 0.f;
+      x[e] = expm1f(ndz[e]);
     }
+    const float zr[2] = {z[0] + ndz[0], z[1] + ndz[1]};       // logits at the reference point (-inf for an absent class)
+    float nabs = fmaxf(fabsf(ndz[0]), fabsf(ndz[1]));        // (an absent class contributes 0)
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) nabs = fmaxf(nabs, __shfl_xor(nabs, o, 64));
+    const bool far = !(nabs < 0.5f);             // (also taken by a NaN, which then shows in the result)
     const int label = yv[a.grow[r]];
     float zmax = fmaxf(z[0], z[1]);
 #pragma unroll
@@ -1044,27 +1117,32 @@ __global__ __launch_bounds__(kLossBlock) void k_loss(const LossArgs a) {
     const float den = group16_sum(z[0] + z[1]);
     z[0] = z[0] / den; z[1] = z[1] / den;
     const float S = group16_sum(fmaf(z[0], x[0], z[1] * x[1]));
+    // the direct form: Pref = softmax of the reference logits z - dz, shifted by their maximum
+    float rmax = fmaxf(zr[0], zr[1]);
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) rmax = fmaxf(rmax, __shfl_xor(rmax, o, 64));
+    const float er[2] = {on[0] ? expf(zr[0] - rmax) : 0.f, on[1] ? expf(zr[1] - rmax) : 0.f};
+    const float rden = group16_sum(er[0] + er[1]);
     // (row, class) tensors: a row's classes are consecutive, written two at a time (an absent odd
-    // class is a zero in the padding); (class, row) tensors: one value per class and row
+    // class is a zero in the padding)
     uint32_t ph = 0, pl = 0, pd = 0, pr = 0;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       if (on[e]) {
         const int c = c0 + e;
         const float gl = (z[e] - (c == label ? 1.f : 0.f)) * invB;
-        const float dg = z[e] * (S - x[e]) / (1.0f + S) * invB;
+        const float dg = (far ? z[e] - er[e] / rden : z[e] * (S - x[e]) / (1.0f + S)) * invB;
         const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
         ph |= (uint32_t)hi << (16 * e); pl |= (uint32_t)lo << (16 * e); pd |= (uint32_t)bd << (16 * e); pr |= (uint32_t)br << (16 * e);
-        const int64_t ot = tm(c, r, a.ktT);
-        a.GhT[ot] = hi; a.GlT[ot] = lo; a.dGT[ot] = bd; a.GrefT[ot] = br;
         sumG[e] += gl;
         sumD[e] += dg;
       }
     }
-    if (a.Gh && on[0]) {     // (a single-layer network has no layer below to pass them to)
+    if (on[0]) {
       const int64_t o = tm(r, 0, a.ktg) + c0;          // classes 0..31 lie in the row's first chunk
       *reinterpret_cast<uint32_t *>(a.Gh + o) = ph; *reinterpret_cast<uint32_t *>(a.Gl + o) = pl;
-      *reinterpret_cast<uint32_t *>(a.dG + o) = pd; *reinterpret_cast<uint32_t *>(a.Gref + o) = pr;
+      *reinterpret_cast<uint32_t *>(a.dG + o) = pd;
+      if (a.Gref) *reinterpret_cast<uint32_t *>(a.Gref + o) = pr;
     }
   }
   // bias gradient of the last layer, its innovation and that innovation's part of the left-hand
@@ -1086,9 +1164,8 @@ __global__ __launch_bounds__(kLossBlock) void k_loss(const LossArgs a) {
       for (int ww = 0; ww < kLossBlock / 64; ++ww) { gsum += part[ww][c >> 1][c & 1]; iv += part[ww][c >> 1][2 + (c & 1)]; }
       fresh_grad(s, m)[a.offb + c] = gsum;
       if (s.rule == CADA_RULE_CADA1) {
-        const int cur = s.sel[m];
-        s.dtl[((int64_t)(1 - cur) * s.M + m) * s.p + a.offb + c] = iv;
-        iv -= s.dtl[((int64_t)cur * s.M + m) * s.p + a.offb + c];
+        fresh_innov(s, m)[a.offb + c] = f2bf(iv);
+        iv -= bf2f(stored_innov(s, m)[a.offb + c]);
       }
       sq = iv * iv;
     }
@@ -1113,9 +1190,8 @@ __global__ __launch_bounds__(kBlock) void k_bias_finish(const DevState s, const 
     }
     fresh_grad(s, m)[offb + c] = gsum;
     if (s.rule == CADA_RULE_CADA1) {
-      const int cur = s.sel[m];
-      s.dtl[((int64_t)(1 - cur) * s.M + m) * s.p + offb + c] = dsum;
-      dsum -= s.dtl[((int64_t)cur * s.M + m) * s.p + offb + c];
+      fresh_innov(s, m)[offb + c] = f2bf(dsum);
+      dsum -= bf2f(stored_innov(s, m)[offb + c]);
     }
     sq = dsum * dsum;
   }
@@ -1145,11 +1221,13 @@ template <int EPI, int NA, int NB, bool HAS_D> int launch_mm5_as(Ctx *c, const M
   return CADA_OK;
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
+constexpr int skinny_lds_bytes(int epi) { return epi == EPI_DW ? 8 * 7 * 1024 * (int)sizeof(bf16_t) : 65536; }   // (>= the 64 KB of partial results)
 template <int EPI, int NA, int NB, bool HAS_D> hipError_t skinny_allow_lds() {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             skinny_lds_bytes(EPI));
 }
 template <int EPI, int NA, int NB, bool HAS_D> int launch_skinny_as(Ctx *c, const Mm5Args &g) {
-  hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(2 * kBlock), 65536, c->stream, g);
+  hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(2 * kBlock), skinny_lds_bytes(EPI), c->stream, g);
   return CADA_OK;
 }
 // Returns CADA_OK after enqueueing the launch, CADA_EUNSUPPORTED (and launches nothing) when the
@@ -1175,11 +1253,16 @@ template <int EPI> int launch_mm5(Ctx *c, Mm5Args &g, int workers) {
       }
     }
   }
-  // every tensor must hold the chunks the tile steps walk through
+  // every tensor must hold the chunks the tile steps walk through: the contraction indices along a row
+  // tile, or (weight gradient: units are output rows, the steps walk down the worker's rows) whole
+  // 128-unit tiles and the worker's padded rows
+  const int64_t needA = EPI == EPI_DW ? 4 * ((g.M + BM - 1) / BM) : (g.K + BK - 1) / BK;
+  const int64_t needB = EPI == EPI_DW ? 4 * ((g.N + BN - 1) / BN) : (g.K + BK - 1) / BK;
   for (int i = 0; i < g.A.n; ++i)
-    if (g.A.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: A tensor with fewer chunks than tile steps"); return CADA_EUNSUPPORTED; }
+    if (g.A.kt[i] < needA) { set_error("internal: A tensor with fewer chunks than the tiles walk through"); return CADA_EUNSUPPORTED; }
   for (int i = 0; i < g.B.n; ++i)
-    if (g.B.kt[i] < (g.K + BK - 1) / BK) { set_error("internal: B tensor with fewer chunks than tile steps"); return CADA_EUNSUPPORTED; }
+    if (g.B.kt[i] < needB) { set_error("internal: B tensor with fewer chunks than the tiles walk through"); return CADA_EUNSUPPORTED; }
+  if (EPI == EPI_DW && (int64_t)((g.K + BK - 1) / BK) * BK > g.Bp) { set_error("internal: more rows than a worker's padded tile"); return CADA_EUNSUPPORTED; }
   if constexpr (EPI == EPI_DW) {
     if (!has_d && g.A.n == 2 && g.B.n == 3) return launch_mm5_as<EPI, 2, 3, false>(c, g);
     if (has_d && g.A.n == 3 && g.B.n == 4) return launch_mm5_as<EPI, 3, 4, true>(c, g);
@@ -1195,7 +1278,7 @@ template <int EPI> int launch_mm5(Ctx *c, Mm5Args &g, int workers) {
 
 Mm5Args blank(const DevState &s, const MlpPlan &P) {
   Mm5Args g{};
-  g.s = s; g.Bp = P.Bp; g.ktT = P.ktT;
+  g.s = s; g.Bp = P.Bp;
   g.a_h = g.a_l = g.a_d = g.a_r = -1;
   g.b_h = g.b_l = g.b_x = g.b_d = -1;
   return g;
@@ -1238,8 +1321,8 @@ static int mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx
     StageArgs sa;
     sa.s = s;
     sa.Xh = P.Xh; sa.Xl = P.Xl; sa.ldx = P.ldx; sa.idx = idx; sa.grow = P.grow;
-    sa.XTh = P.XTh; sa.XTl = P.XTl; sa.XGh = P.XGh; sa.XGl = P.XGl;
-    sa.d0 = P.d[0]; sa.B = B; sa.Bp = Bp; sa.ktx = P.kta[0]; sa.ktT = P.ktT;
+    sa.XGh = P.XGh; sa.XGl = P.XGl;
+    sa.d0 = P.d[0]; sa.B = B; sa.Bp = Bp; sa.ktx = P.kta[0];
     sa.gx = (int)((P.ldx + 63) / 64); sa.gy = (B + 63) / 64;
     sa.n_layers = L; sa.nz = P.nW + 1; sa.wt_total = P.wt_total; sa.wn_total = P.wn_total; sa.rep = rep;
     uint64_t nblk = (uint64_t)sa.gx * sa.gy * M;
@@ -1282,7 +1365,6 @@ static int mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx
     if (l < L) {
       g.offb = P.offb[l - 1]; g.kto = P.kta[l];
       g.o_h = P.Ah[l]; g.o_l = P.Al[l]; g.o_d = P.dA[l]; g.o_r = P.Aref[l];
-      g.t_h = P.AhT[l]; g.t_l = P.AlT[l]; g.t_d = P.dAT[l]; g.t_r = nullptr;
       g.maskbits = P.maskbits[l];
       if (const int rc = launch_mm5<EPI_FWD_HIDDEN>(c, g, M)) return rc;
     } else {
@@ -1308,8 +1390,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
     LossArgs la;
     la.s = s; la.Z = P.ZL; la.dZ = P.dZL;
     la.Gh = P.Gh[L]; la.Gl = P.Gl[L]; la.dG = P.dG[L]; la.Gref = P.Gref[L];
-    la.GhT = P.GhT[L]; la.GlT = P.GlT[L]; la.dGT = P.dGT[L]; la.GrefT = P.GrefT[L];
-    la.grow = P.grow; la.offb = P.offb[L - 1]; la.ktT = P.ktT; la.C = P.d[L]; la.Bp = Bp; la.ktg = P.kta[L];
+    la.grow = P.grow; la.offb = P.offb[L - 1]; la.C = P.d[L]; la.Bp = Bp; la.ktg = P.kta[L];
     la.lhs_slot = P.lhs_b_slot[L - 1];
     hipLaunchKernelGGL(k_loss, dim3(M), dim3(kLossBlock), 0, st, la);
   }
@@ -1317,23 +1398,23 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
   // ---- backward
   for (int l = L; l >= 1; --l) {
     const int din = P.d[l - 1], dout = P.d[l];
-    {   // weight gradient and its innovation: contraction over the worker's rows
+    {   // weight gradient and its innovation: contraction over the worker's rows, both operands (row, unit) tensors
       Mm5Args g = blank(s, P);
       g.M = din; g.N = dout; g.K = B;
-      const int64_t bsT = (int64_t)Bp * 128;              // a worker's Bp / 32 chunks of every row tile
+      const int64_t bsA = (int64_t)Bp * P.kta[l - 1] * 32, bsB = (int64_t)Bp * P.kta[l] * 32;     // a worker's Bp / 128 row tiles
       if (l == 1) {
-        side_add(g.A, P.XTh, P.ktT, bsT); side_add(g.A, P.XTl, P.ktT, bsT);
+        side_add(g.A, P.XGh, P.kta[0], bsA); side_add(g.A, P.XGl, P.kta[0], bsA);
         g.a_h = 0; g.a_l = 1; g.a_r = 0;
       } else {
-        side_add(g.A, P.AhT[l - 1], P.ktT, bsT); side_add(g.A, P.AlT[l - 1], P.ktT, bsT); side_add(g.A, P.dAT[l - 1], P.ktT, bsT);
+        side_add(g.A, P.Ah[l - 1], P.kta[l - 1], bsA); side_add(g.A, P.Al[l - 1], P.kta[l - 1], bsA); side_add(g.A, P.dA[l - 1], P.kta[l - 1], bsA);
         g.a_h = 0; g.a_l = 1; g.a_d = 2; g.a_r = 0;       // innov = A^T dG + dA^T Gref
       }
-      side_add(g.B, P.GhT[l], P.ktT, bsT); side_add(g.B, P.GlT[l], P.ktT, bsT);
+      side_add(g.B, P.Gh[l], P.kta[l], bsB); side_add(g.B, P.Gl[l], P.kta[l], bsB);
       if (l == 1) {     // no dA^T Gref term in the first layer
-        side_add(g.B, P.dGT[l], P.ktT, bsT);
+        side_add(g.B, P.dG[l], P.kta[l], bsB);
         g.b_h = 0; g.b_l = 1; g.b_d = 2;
       } else {
-        side_add(g.B, P.GrefT[l], P.ktT, bsT); side_add(g.B, P.dGT[l], P.ktT, bsT);
+        side_add(g.B, P.Gref[l], P.kta[l], bsB); side_add(g.B, P.dG[l], P.kta[l], bsB);
         g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
       }
       g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1];
@@ -1353,8 +1434,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
       g.rep = per_worker ? P.rep : nullptr;
       const int q = l - 1;
       g.offb = P.offb[q - 1]; g.kto = P.kta[q];
-      g.o_h = P.Gh[q]; g.o_l = P.Gl[q]; g.o_d = P.dG[q]; g.o_r = P.Gref[q];     // null for q = 1
-      g.t_h = P.GhT[q]; g.t_l = P.GlT[q]; g.t_d = P.dGT[q]; g.t_r = P.GrefT[q];
+      g.o_h = P.Gh[q]; g.o_l = P.Gl[q]; g.o_d = P.dG[q]; g.o_r = P.Gref[q];     // (Gref: null for q = 1)
       g.maskbits = P.maskbits[q];
       g.dbpart = P.dbpart; g.ddbpart = P.ddbpart;
       if (const int rc = launch_mm5<EPI_DA>(c, g, M)) return rc;

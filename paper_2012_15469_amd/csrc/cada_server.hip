@@ -37,9 +37,9 @@ __device__ float last_step_sq(const DevState &s, double *red /* [kBlock] LDS */)
 __global__ __launch_bounds__(kBlock) void k_lag_lhs(const DevState s) {
   __shared__ float red[4];
   const int m = blockIdx.y;
-  const int64_t mp = (int64_t)s.M * s.p;
-  const float *gs = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p;
-  const float *gf = s.gbuf + (int64_t)(1 - s.sel[m]) * mp + (int64_t)m * s.p;
+  const int64_t mp = (int64_t)s.M * s.ps;
+  const float *gs = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.ps;
+  const float *gf = s.gbuf + (int64_t)(1 - s.sel[m]) * mp + (int64_t)m * s.ps;
   float sq = 0.f;
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
     const float d = gf[i] - gs[i];
@@ -108,7 +108,10 @@ __global__ __launch_bounds__(kBlock) void k_rule(const DevState s, const uint8_t
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    if (cnt) atomicAdd(reinterpret_cast<unsigned long long *>(s.uploads), (unsigned long long)cnt);
+    if (cnt) {
+      atomicAdd(reinterpret_cast<unsigned long long *>(s.uploads), (unsigned long long)cnt);
+      atomicAdd(s.n_up + (k & 1), cnt);
+    }
     if (blockIdx.x == 0) {
       if (last >= 0) s.ring[last] = newest;
       if (tr) s.t_rhs[k] = (float)rhs;
@@ -135,7 +138,7 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
   __shared__ float part[4][4][64];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int64_t base = (int64_t)blockIdx.x * 256;
-  const int64_t mp = (int64_t)s.M * s.p;
+  const int64_t mp = (int64_t)s.M * s.ps;
   // coordinate of this lane's v-th value, and whether it exists
   auto coord = [&](int v) -> int64_t { return VEC == 4 ? base + lane * 4 + v : base + lane + 64 * v; };
   auto get = [&](const float *x, float (&o)[4]) {
@@ -159,14 +162,33 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
         if (coord(v) < s.p) x[coord(v)] = o[v];
     }
   };
+  // Aggregate.  Plain form: the sum of all M stored gradients (eq. (CADA-1)).  Incremental form of
+  // Section 1.2, nabla^k = nabla^{k-1} + (1/M) sum over the uploading workers of (fresh gradient - the
+  // gradient it replaces): taken when it reads fewer rows (2 per upload + 1 against M); the plain
+  // sum is formed whenever the host asks for it (every D iterations, and when the stored nabla is not that
+  // of the step before), so rounding differences between the two forms cannot pile up.  The choice is
+  // the same in every block: it depends on the iteration's upload count alone.
+  const uint32_t n_up = s.n_up[s.k & 1];
+  const bool incremental = !s.resum && 2 * (int64_t)n_up + 1 < (int64_t)s.M;
+  if (blockIdx.x == 0 && threadIdx.x == 0) s.n_up[(s.k + 1) & 1] = 0u;      // (nobody reads that slot during this launch)
   float nab[4] = {0.f, 0.f, 0.f, 0.f};
-  if constexpr (VEC == 4) {
+  auto row_of = [&](int buf, int m) -> const float * { return s.gbuf + (int64_t)buf * mp + (int64_t)m * s.ps; };
+  if (incremental) {
+    for (int m = w; m < s.M; m += 4) {
+      if (!s.mask[m]) continue;                       // (uniform in the wavefront)
+      const int cur = s.sel[m];                       // after the swap: cur holds the fresh gradient, 1 - cur the replaced one
+      float a4[4] = {0.f, 0.f, 0.f, 0.f}, b4[4] = {0.f, 0.f, 0.f, 0.f};
+      get(row_of(cur, m), a4); get(row_of(1 - cur, m), b4);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) nab[v] += a4[v] - b4[v];
+    }
+  } else if constexpr (VEC == 4) {
     if (coord(0) < s.p) {
 #pragma unroll 5
       for (int m = w; m < s.M; m += 4) {
         typedef float f32x4 __attribute__((ext_vector_type(4)));
         // (the stored gradients are read once per step: non-temporal loads, which stream from HBM faster)
-        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p + coord(0)));
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.ps + coord(0)));
         nab[0] += t.x; nab[1] += t.y; nab[2] += t.z; nab[3] += t.w;
       }
     }
@@ -174,7 +196,7 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
 #pragma unroll 4
     for (int m = w; m < s.M; m += 4) {
       float t[4] = {0.f, 0.f, 0.f, 0.f};
-      const float *gm = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.p;
+      const float *gm = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.ps;
 #pragma unroll
       for (int v = 0; v < 4; ++v)
         if (coord(v) < s.p) t[v] = __builtin_nontemporal_load(gm + coord(v));
@@ -190,10 +212,12 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
   const float fM = (float)s.M;
   float th[4] = {0.f, 0.f, 0.f, 0.f}, tl[4] = {0.f, 0.f, 0.f, 0.f}, hh[4] = {0.f, 0.f, 0.f, 0.f};
   float vv[4], vh[4] = {0.f, 0.f, 0.f, 0.f};
+  float prev[4] = {0.f, 0.f, 0.f, 0.f};
   get(s.h, hh); get(s.vhat, vh); get(s.theta, th); get(s.theta_lo, tl);
+  if (incremental) get(s.nabla, prev);
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
-    nab[v] = ((part[0][v][lane] + part[1][v][lane]) + (part[2][v][lane] + part[3][v][lane])) / fM;
+    nab[v] = prev[v] + ((part[0][v][lane] + part[1][v][lane]) + (part[2][v][lane] + part[3][v][lane])) / fM;
     // beta*x + (1-beta)*y written as x + (1-beta)*(y - x): float32(0.999) is off by 1.3e-8
     // relative, which compounds to 1e-5 over the ~1000-step memory of vhat, whereas
     // float32(1-beta) enters only linearly
@@ -209,6 +233,7 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
       vh[v] = fmaxf(vv[v], vo);
       step = s.alpha * hh[v] / sqrtf(s.eps + vh[v]);
     }
+    if (VEC == 4 && coord(v) >= s.p) step = 0.f;   // (a coordinate of the 16-byte padding past p stays as it is, also with eps = 0)
     // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
     const float a = th[v], ms = -step;
     const float sum = a + ms;
@@ -221,8 +246,8 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
   }
   put(s.nabla, nab); put(s.h, hh); put(s.v, vv); put(s.vhat, vh); put(s.theta, th); put(s.theta_lo, tl);
   if (s.rule == CADA_RULE_CADA2) {
-    put(s.hist + ((s.k + 1) % s.R) * s.p, th);
-    put(s.hist_lo + ((s.k + 1) % s.R) * s.p, tl);
+    put(s.hist + ((s.k + 1) % s.R) * s.ps, th);
+    put(s.hist_lo + ((s.k + 1) % s.R) * s.ps, tl);
   } else if (s.rule == CADA_RULE_CADA1 && (s.k + 1) % s.D == 0) {
     put(s.snap, th);
     put(s.snap_lo, tl);
@@ -235,6 +260,7 @@ int rule_and_server(Ctx *c, const uint8_t *replay) {
   DevState s = c->s;
   s.k = c->k;
   s.alpha = stepsize(s, s.k);
+  s.resum = (c->force_resum || s.k % s.D == 0) ? 1 : 0;
   if (s.rule == CADA_RULE_LAG || s.rule == CADA_RULE_ALWAYS) {   // (the always-upload rule only records it)
     const int nb = (int)min((int64_t)s.n_lhs_part, (s.p + 4 * kBlock - 1) / (4 * kBlock));
     hipLaunchKernelGGL(k_lag_lhs, dim3((unsigned)max(nb, 1), (unsigned)s.M), dim3(kBlock), 0, c->stream, s);
@@ -251,6 +277,7 @@ int rule_and_server(Ctx *c, const uint8_t *replay) {
     set_error("rule/server launch failed: %s", hipGetErrorString(e));
     return CADA_EHIP;
   }
+  c->force_resum = 0;
   return CADA_OK;
 }
 

@@ -85,6 +85,22 @@ def test_single_pass_kernel_steady_state(rule, B, clusters):
     print(rule, B, clusters, stats)
 
 
+@pytest.mark.parametrize("rule,clusters", [(2, 0), (1, 2)])
+def test_single_pass_kernel_wide_clusters(rule, clusters):
+    """p = 131072: clusters of 64 workgroups, each exchange lane sums two partials per value.  With two
+    clusters for three workers a cluster changes worker in mid-stream."""
+    cfg = configs.CFG3.scaled(layer_dims=(131072,), M=3, N_m=96, B=48, K=14, D=5, rule=rule, alpha=0.02, c=1e-4)
+    prob = generators.make_problem(cfg)
+    Xs, ys = zip(*(prob.rows(m, np.arange(cfg.N_m)) for m in range(cfg.M)))
+    prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
+    sched = generators.make_schedule(cfg)
+    stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_SINGLE_PASS,
+                                       single_pass_clusters=clusters, expect_phase="logreg_single_pass")
+    print(rule, clusters, stats)
+    free = tr["tau"] < cfg.D
+    assert 0.02 < tr["mask"][free].mean() < 0.98, "the case must mix rule-driven uploads and skips"
+
+
 def test_special_cases_c0_and_huge_c():
     cfg = configs.CFG1.scaled(c=0.0, K=50)
     prob, dev, sched = _case(cfg)

@@ -125,3 +125,24 @@ def test_more_workers_than_a_wavefront_share_reference_points():
     free = tr["tau"] < cfg.D
     assert 0.02 < tr["mask"][free].mean() < 0.98, "the case must mix rule-driven uploads and skips"
     assert stats["own_disagreements"] <= max(2, 0.03 * tr["mask"].size)
+
+
+def test_reference_point_far_from_the_iterate():
+    """Large steps and a rule that never fires: each worker's reference point ages until the forced
+    upload, so the logits at the iterate and at the reference point differ by tens -- the softmax
+    difference must stay finite and accurate there (its small-difference form cancels)."""
+    cfg = configs.CFG4.scaled(name="mlp2_far", layer_dims=(150, 133, 10), M=5, N_m=300, B=70, K=26, D=12, c=1e9, alpha=0.02)
+    prob, dev, sched = _case(cfg)
+    o, tr = oracle_run(cfg, prob, sched)
+    from oracle.cada_oracle import mlp_logits
+    # the premise: some logits move by more than 10 between an iterate and a 12-step old one
+    out = run_library(cfg, dev, sched, replay=tr["mask"])
+    assert out["error_flags"][0] == 0
+    assert np.isfinite(out["trace_lhs"]).all()
+    assert tr["lhs"].max() > 1e2 * np.median(tr["lhs"][1]), "the case must reach large differences"
+    big = tr["lhs"] > 1e-9 * tr["lhs"].max()
+    rel = np.abs(out["trace_lhs"] - tr["lhs"])[big] / tr["lhs"][big]
+    print(cfg.name, "lhs rel median %.2e max %.2e" % (np.median(rel), rel.max()), "theta", rel_l2(out["theta64"], o.theta))
+    assert np.median(rel) < 1e-2 and rel.max() < 0.2
+    assert np.array_equal(out["trace_own_mask"], tr["own_mask"])
+    assert rel_l2(out["theta64"], o.theta) < BF16_TOL
