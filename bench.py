@@ -174,7 +174,8 @@ def measure(cfg, K: int, W: int, plain_launch: bool = False):
         # the gradient phase is one launch of the single-pass kernel (p >= 8192), the two streaming
         # passes over the gathered rows, or (tiny workloads) whole iterations in one kernel
         single = "logreg_single_pass" in prof
-        grad_ms = sum(v for k, v in prof.items() if k.startswith("logreg_"))
+        # (single pass: the kernel's own launches; the few microseconds of "logreg_split_round_sum" are listed beside it)
+        grad_ms = prof["logreg_single_pass"] if single else sum(v for k, v in prof.items() if k.startswith("logreg_"))
         alg = kernel_bytes_per_launch(cfg) if not whole else algorithmic_bytes_per_step(cfg)
         achieved = alg / (grad_ms * 1e-3) / 1e9
         name = "k_fused" if single else ("k_small (whole iterations; latency-bound)" if whole else "k_dots+k_grad")

@@ -153,16 +153,19 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   int32_t *eval_idx = w.take<int32_t>(M * (size_t)cfg->B);
   float *zpart = nullptr;
   unsigned long long *post = nullptr;
+  float *tail = nullptr;
   uint32_t *small_bar = nullptr;
   unsigned char *small_args = nullptr;
   if (cfg->model == CADA_MODEL_LOGREG) {
     zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
     post = w.take<unsigned long long>(kFusedPostWords);
+    if (cfg->p >= 8192 && cfg->p % 4 == 0) tail = w.take<float>(kFusedTailFloatsPerP * (size_t)cfg->p);   // (shapes the single-pass kernel serves)
     small_bar = w.take<uint32_t>(64);
     small_args = w.take<unsigned char>(kSmallArgsBytes);
   }
   if (!s) return;
   c->fused_post = post;
+  c->fused_tail = tail;
   c->eval_part = eval_part; c->eval_acc = eval_acc; c->eval_idx = eval_idx;
   c->small_bar = small_bar;
   c->small_args = small_args;
@@ -360,6 +363,9 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
     else if (cfg->path == CADA_PATH_AUTO && small_plan(c, cfg)) s.n_ring_part = cfg->M;
     if (c->small) {
       c->n_phases = 1; c->phase_names[0] = "logreg_whole_steps";
+    } else if (c->fused && c->fused_tail_f > 0) {
+      c->n_phases = 4; c->phase_names[0] = "logreg_single_pass"; c->phase_names[1] = "logreg_split_round_sum";
+      c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
     } else if (c->fused) {
       c->n_phases = 3; c->phase_names[0] = "logreg_single_pass"; c->phase_names[1] = "rule"; c->phase_names[2] = "server_update";
     } else {

@@ -134,6 +134,8 @@ struct Ctx {
   int64_t fused_cols;
   uint32_t fused_seq, fused_seq_per_step;
   unsigned long long *fused_post;
+  int fused_tail_f, fused_tail_rows, fused_tail_rem;   // split of the last round's workers over the clusters (0: none)
+  float *fused_tail;         // [clusters][2][p]: the clusters' parts of the split workers' sums
   // whole iterations in one launch for small logistic workloads, cada_logreg_small.hip
   int small;
   size_t small_lds;
@@ -168,6 +170,7 @@ bool small_plan(Ctx *c, const cada_config *cfg);
 int small_publish_args(Ctx *c);             // after the state pointers are final, and after a checkpoint was loaded
 void small_free(Ctx *c);
 int logreg_init(Ctx *c);                    // LDS allowance of the two-pass kernels
+constexpr size_t kFusedTailFloatsPerP = 2 * 32;     // room for the parts of 32 clusters (one per cluster, two sums)
 constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgroups x 4 buffers x 16 values
 // S1+S2 for the MLP.
 int mlp_gradients(Ctx *c, const int32_t *idx);

@@ -75,6 +75,14 @@ struct FusedArgs {
   int64_t cols_per_block;        // multiple of 4, <= 2048
   uint32_t seq_base;             // tag of slab t of this launch is seq_base + 1 + t
   uint32_t spin_limit;
+  // Last round.  With M = full * n_clusters + rem workers, 0 < rem < n_clusters, the last round would keep only
+  // rem clusters busy.  When tail_f = n_clusters / rem is a whole number >= 2 that divides the minibatch, the
+  // rows of each of the rem last workers are split over tail_f clusters instead (tail_rows = B / tail_f each):
+  // cluster c takes rows [(c % tail_f) tail_rows, +tail_rows) of worker full * n_clusters + c / tail_f and leaves
+  // its part of the two sums (no regulariser) in tail_part[c % tail_f][c / tail_f][0|1][p]; k_fused_tail adds
+  // the parts up in a fixed order.  tail_f = 0: no split.
+  int tail_f, tail_rows, tail_rem;
+  float *tail_part;
 };
 
 __device__ __forceinline__ float sigmoid_f(float a) { return 1.0f / (1.0f + expf(-a)); }
@@ -151,13 +159,28 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   const int Q = a.Q, ncl = a.n_clusters;
   const int cluster = blockIdx.x / Q, cb = blockIdx.x % Q;
   const int nslab = s.B;                                      // one row per slab; a multiple of R
-  const int rounds = (s.M - cluster + ncl - 1) / ncl;         // workers of this cluster
-  const int S = rounds * nslab;                               // slabs of this cluster
+  const bool split = a.tail_f > 0;
+  // whole workers of this cluster, then (split) its share of one of the last workers
+  const int rounds = split ? s.M / ncl : (s.M - cluster + ncl - 1) / ncl;
+  const int m_end = cluster + rounds * ncl;                   // one past the last whole worker of this cluster
+  const int mt = split ? (s.M / ncl) * ncl + cluster / a.tail_f : 0x40000000;     // the shared worker (none: never reached)
+  const int ot = split ? (cluster % a.tail_f) * a.tail_rows : 0;                   // this cluster's first row of it
+  const int S = rounds * nslab + (split ? a.tail_rows : 0);   // slabs of this cluster
   const int IS = S / R;                                       // iterations that produce
   const int total = IS + LAGI;                                // iterations (= barriers after the first) of every wavefront
   unsigned long long *post_base = a.zpost + (int64_t)cluster * F_NP * F_V * Q;
   // (worker, slab within worker) cursors advance one iteration (R slabs) at a time
-  auto advance = [&](int &m, int &loc) __attribute__((always_inline)) { loc += R; if (loc == nslab) { loc = 0; m += ncl; } };
+  // (a cursor is (worker, slab, one past the worker's last slab for this cluster); the comparison of every
+  // iteration is against a register, everything about the split worker sits in the rarely taken block)
+  auto first_of = [&](int m) __attribute__((always_inline)) { return m == mt ? ot : 0; };
+  auto end_of = [&](int m) __attribute__((always_inline)) { return m == mt ? ot + a.tail_rows : nslab; };
+  auto advance = [&](int &m, int &loc, int &end, int &first) __attribute__((always_inline)) {
+    loc += R;
+    if (loc == end) {
+      if (m + ncl < m_end) { m += ncl; loc = 0; }
+      else { m = mt; loc = ot; end = ot + a.tail_rows; first = ot; }
+    }
+  };
 
   if (w == 5) {
     // ================= residual / feeder wavefront =================
@@ -170,10 +193,12 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     auto feed_issue = [&](int chunk) __attribute__((always_inline)) {                 // stage 1: index and row range
       const int t = chunk * 64 + lane;
       const int tt = t < S ? t : S - 1;
-      const int m = cluster + (tt / nslab) * ncl;
+      const bool whole = tt < rounds * nslab;
+      const int m = whole ? cluster + (tt / nslab) * ncl : mt;
+      const int row = whole ? tt % nslab : ot + (tt - rounds * nslab);
       f_base = s.row_off[m];
       f_end = s.row_off[m + 1];
-      f_r = a.idx[(int64_t)m * s.B + tt % nslab];
+      f_r = a.idx[(int64_t)m * s.B + row];
     };
     auto feed_label = [&]() __attribute__((always_inline)) {                          // stage 2: range check, label
       const int64_t n_m = f_end - f_base;
@@ -361,8 +386,10 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
 #pragma unroll
   for (int q = 0; q < 2; ++q) th[q] = dd[q] = g[q] = iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-  int pm = cluster, ploc = 0;           // first slab produced (dot products, parked) this iteration
-  int cm = cluster, cloc = 0;           // first slab accumulated this iteration
+  const int m_first = rounds > 0 ? cluster : mt;
+  int pm = m_first, ploc = first_of(m_first), pend = end_of(m_first);   // first slab produced (dot products, parked) this iteration
+  int cm = m_first, cloc = first_of(m_first), cend = end_of(m_first);   // first slab accumulated this iteration
+  int pfirst = ploc, cfirst = cloc;                                     // first slab of the worker being produced / accumulated
   lds_barrier();                        // the feeder's first chunk is in LDS
   // prologue: loads of the first PDI iterations
 #pragma unroll
@@ -394,7 +421,20 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
         iv[q].x = fmaf(dr[r], x.x, iv[q].x); iv[q].y = fmaf(dr[r], x.y, iv[q].y);
         iv[q].z = fmaf(dr[r], x.z, iv[q].z); iv[q].w = fmaf(dr[r], x.w, iv[q].w);
       }
-    if (cloc + R == nslab) {
+    if (cloc + R == cend && cm == mt) {
+      // last rows of this cluster's share of a split worker: its part of the two sums, as they are
+      float *pg = a.tail_part + (((int64_t)(cluster % a.tail_f) * a.tail_rem + cluster / a.tail_f) * 2) * s.p;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        if (cv[q]) {
+          *reinterpret_cast<float4 *>(pg + col[q]) = g[q];
+          *reinterpret_cast<float4 *>(pg + s.p + col[q]) = iv[q];
+        }
+        g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), see load_theta
+    } else if (cloc + R == cend) {
       // last rows of worker cm: regulariser, stores, squared norm of the rule's left-hand side
       const int m = cm;
       float4 tm[2], dm[2];
@@ -424,7 +464,7 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + cb * 4 + w] = tot;
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), see load_theta
     }
-    advance(cm, cloc);
+    advance(cm, cloc, cend, cfirst);
   };
 
   // LDS words of the row addresses of iteration it + PDI, read one iteration before their use
@@ -461,7 +501,7 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       }
     }
     if (prod) {
-      if (ploc == 0) load_theta(pm, th, dd);
+      if (ploc == pfirst) load_theta(pm, th, dd);
       if constexpr (st) wait_rows<(PDI - 1) * 2 * R, R>(xb[bi]);
 #pragma unroll
       for (int r = 0; r < R; ++r) {
@@ -483,7 +523,7 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
         v = row16_parity_sum(v);
         if ((lane & 15) < F_V) red[it & 1][r][lane & 1][w * 4 + (lane >> 4)] = v;
       }
-      advance(pm, ploc);
+      advance(pm, ploc, pend, pfirst);
       // the registers are free for the rows PDI iterations ahead
       if constexpr (st) {
 #pragma unroll
@@ -523,6 +563,46 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       if (s0 + I.value < total) stream_iter(I, bc<false>{}, s0 + I.value);
     });
   if (pending) accumulate();
+}
+
+// Adds up the parts of the workers whose rows the last round split over several clusters (in the order
+// of the row ranges), adds the regulariser's terms, stores the fresh gradient (CADA1: and the fresh
+// innovation) and the partial sums of the rule's left-hand side.  grid (4 Q, rem), 128 threads, four columns
+// each: block b owns columns [512 b, 512 b + 512) and slot b of the worker's partial sums.
+__global__ __launch_bounds__(128) void k_fused_tail(const FusedArgs a) {
+  const DevState &s = a.s;
+  __shared__ float red[2];
+  const int j = blockIdx.y, m = (s.M / a.n_clusters) * a.n_clusters + j;
+  const int64_t c0 = ((int64_t)blockIdx.x * 128 + threadIdx.x) * 4;
+  float sq = 0.f;
+  if (c0 < s.p) {
+    const RefPtr ref = theta_ref(s, m, s.k);
+    const float4 tt = *reinterpret_cast<const float4 *>(s.theta + c0), tl = *reinterpret_cast<const float4 *>(s.theta_lo + c0);
+    const float4 rh = *reinterpret_cast<const float4 *>(ref.hi + c0), rl = *reinterpret_cast<const float4 *>(ref.lo + c0);
+    const float4 d = make_float4((tt.x - rh.x) + (tl.x - rl.x), (tt.y - rh.y) + (tl.y - rl.y), (tt.z - rh.z) + (tl.z - rl.z), (tt.w - rh.w) + (tl.w - rl.w));
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f), iv = g;
+    for (int h = 0; h < a.tail_f; ++h) {
+      const float *pg = a.tail_part + (((int64_t)h * a.tail_rem + j) * 2) * s.p;
+      const float4 x = *reinterpret_cast<const float4 *>(pg + c0), y = *reinterpret_cast<const float4 *>(pg + s.p + c0);
+      g.x += x.x; g.y += x.y; g.z += x.z; g.w += x.w;
+      iv.x += y.x; iv.y += y.y; iv.z += y.z; iv.w += y.w;
+    }
+    g.x = fmaf(s.lam, tt.x, g.x); g.y = fmaf(s.lam, tt.y, g.y); g.z = fmaf(s.lam, tt.z, g.z); g.w = fmaf(s.lam, tt.w, g.w);
+    iv.x = fmaf(s.lam, d.x, iv.x); iv.y = fmaf(s.lam, d.y, iv.y); iv.z = fmaf(s.lam, d.z, iv.z); iv.w = fmaf(s.lam, d.w, iv.w);
+    const int cur = s.sel[m];
+    const int64_t mp = (int64_t)s.M * s.p;
+    *reinterpret_cast<float4 *>(s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + c0) = g;
+    if (s.rule == CADA_RULE_CADA1) {
+      const float4 stv = *reinterpret_cast<const float4 *>(s.dtl + (int64_t)cur * mp + (int64_t)m * s.p + c0);
+      *reinterpret_cast<float4 *>(s.dtl + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + c0) = iv;
+      iv.x -= stv.x; iv.y -= stv.y; iv.z -= stv.z; iv.w -= stv.w;
+    }
+    sq = fmaf(iv.x, iv.x, sq); sq = fmaf(iv.y, iv.y, sq); sq = fmaf(iv.z, iv.z, sq); sq = fmaf(iv.w, iv.w, sq);
+  }
+  const float ws = wave_sum(sq);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ws;
+  __syncthreads();
+  if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + blockIdx.x] = red[0] + red[1];
 }
 
 static const void *fused_kernel(int R, int NJ) {
@@ -570,7 +650,14 @@ bool fused_plan(Ctx *c, const cada_config *cfg) {
   c->fused_rs = R;
   c->fused_plain_launch = cfg->plain_launch != 0 ? 1 : 0;
   const int nslab = B;
-  c->fused_seq_per_step = (uint32_t)(((M + ncl - 1) / ncl) * nslab);
+  // last round: split the rows of the rem last workers over all clusters when that divides evenly
+  const int rem = M % ncl;
+  c->fused_tail_f = 0; c->fused_tail_rows = 0; c->fused_tail_rem = 0;
+  if (rem > 0 && ncl % rem == 0 && nslab % (ncl / rem) == 0 && (nslab / (ncl / rem)) % R == 0 &&
+      (size_t)ncl * 2 * (size_t)p <= kFusedTailFloatsPerP * (size_t)p) {
+    c->fused_tail_f = ncl / rem; c->fused_tail_rows = nslab / (ncl / rem); c->fused_tail_rem = rem;
+  }
+  c->fused_seq_per_step = (uint32_t)(c->fused_tail_f ? (M / ncl) * nslab + c->fused_tail_rows : ((M + ncl - 1) / ncl) * nslab);
   return true;
 }
 
@@ -585,6 +672,7 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
   a.cols_per_block = c->fused_cols;
   a.seq_base = c->fused_seq;
   a.spin_limit = 2000000u;
+  a.tail_f = c->fused_tail_f; a.tail_rows = c->fused_tail_rows; a.tail_rem = c->fused_tail_rem; a.tail_part = c->fused_tail;
   void *args[] = {&a};
   prof_mark(c);
   hipError_t e;
@@ -598,6 +686,11 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
     e = hipLaunchKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1), grid, block, args, lds, c->stream);
   } else {
     e = hipLaunchCooperativeKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1), grid, block, args, (unsigned)lds, c->stream);
+  }
+  if (a.tail_f > 0) prof_mark(c);          // (a phase of its own)
+  if (e == hipSuccess && a.tail_f > 0) {
+    hipLaunchKernelGGL(k_fused_tail, dim3((unsigned)(4 * a.Q), (unsigned)a.tail_rem), dim3(128), 0, c->stream, a);
+    e = hipGetLastError();
   }
   prof_mark(c);
   if (e != hipSuccess) {

@@ -39,7 +39,7 @@
 // from up to four A-side and four B-side bf16 tensors, all stored in chunks of 128 rows x 32
 // contraction indices, moved into LDS chunk by chunk, with v_mfma_f32_32x32x16_bf16 on four
 // wavefronts of 64 x 64.  The epilogues apply bias/ReLU/masks, split results into hi/lo,
-// write the tensors the later contractions need in both orientations, reduce bias gradients
+// write the tensors the later contractions need, reduce bias gradients
 // and the squared norm of the innovation, so no float32 intermediate except the logits
 // round-trips through HBM.  k_skinny computes the same products for outputs of at most 32
 // columns (the last layer).
@@ -367,11 +367,11 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
   } else if constexpr (EPI == EPI_FWD_HIDDEN || EPI == EPI_DA) {
     // Forward: bias, ReLU of both evaluations.  Activation gradient: ReLU masks of the layer
     // below, bias-gradient partial sums.  Both: the result split into hi/lo, its difference and
-    // its reference value, each written as a (row, column) and as a (column, row) tensor.
+    // its reference value, each written as a (row, column) tensor.
     // A lane's accumulators are one column and 16 rows of a 32 x 32 quarter: written from there
     // every store instruction would move 2 bytes per lane (some 300 instructions per wavefront and
     // tile; the CU's address unit then needs longer for them than the whole contraction took for
-    // small K).  In both layouts a quarter is 2 KB of consecutive memory, so each wavefront puts
+    // small K).  In the chunked layout a quarter is 2 KB of consecutive memory, so each wavefront puts
     // the quarter's values into an LDS buffer of its own in the layout of the destination and
     // copies it out 16 bytes per lane.  (LDS operations of one wavefront are carried out in
     // order, so the buffer needs no barrier.)
@@ -893,8 +893,8 @@ __global__ void k_x_to_bf16(const float *X, bf16_t *Xh, bf16_t *Xl, int64_t rows
   Xl[i] = f2bf(x - bf2f(hi));
 }
 
-// Per-step staging of the contractions' operands, one launch: chunked copies of the gathered
-// minibatch in both orientations, and bf16 copies of every layer's weights and of their
+// Per-step staging of the contractions' operands, one launch: the chunked copy of the gathered
+// minibatch, and bf16 copies (in both orientations) of every layer's weights and of their
 // differences to the reference points.  The blocks of the launch are numbered through the parts
 // (minibatch tiles first, then the layers in order); the parts are independent of each other.
 struct PrepLayer {

@@ -1,9 +1,9 @@
 """Turns two rocprofv3 counter runs of bench.py into the HBM traffic of the single-pass kernel.
 
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d DIR_F -- python3 bench.py --steps 3 --warmup 1 \\
-        --no-cpu-baseline --pmc-calibration
+        --no-cpu-baseline --others '' --plain-launch --pmc-calibration
     rocprofv3 --pmc WRITE_SIZE --output-format csv -d DIR_W -- python3 bench.py --steps 3 --warmup 1 \\
-        --no-cpu-baseline --pmc-calibration
+        --no-cpu-baseline --others '' --plain-launch --pmc-calibration
     python -m paper_2012_15469_amd.pmc_summary DIR_F DIR_W cfg3_logreg_p65536_cada2 > profiles/..._traffic.json
 
 FETCH_SIZE / WRITE_SIZE count in KiB per dispatch.  Each is scaled by what the same counter reads
@@ -40,7 +40,7 @@ def _mean_counter(d, counter, match, largest_only=False):
 
 def main(argv):
     dir_f, dir_w, workload = argv[1:4]
-    is_fused = lambda n: "k_fused" in n
+    is_fused = lambda n: "k_fused<" in n          # (not k_fused_tail, the small kernel that adds up a split last round)
     is_cal = lambda n: "elementwise_kernel" in n
     out = {"workload": workload}
     total = 0.0

@@ -42,9 +42,17 @@ def test_argument_errors_without_gpu():
     assert n > 4 * 54 * (5 + 2 * 2 + 6)
     cfg.p = 55
     assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "does not match" in b.cada_last_error()
-    out = ctypes.c_void_p()
     cfg.p = 54
+    cfg.path = 7
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "path must be" in b.cada_last_error()
+    cfg.path = b.PATH_AUTO
+    cfg.single_pass_clusters = -1
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "tuning" in b.cada_last_error()
+    cfg.single_pass_clusters = 0
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) > 0
+    out = ctypes.c_void_p()
     assert b._lib.cada_init(ctypes.byref(cfg), None, ctypes.byref(out)) == -1     # theta0 NULL
+    assert b._lib.cada_set_state(None, None) == -1 and b._lib.cada_eval_noalloc(None, None) == -1
     assert b._lib.cada_step(None, None, None) == -1
 
 

@@ -171,3 +171,17 @@ def test_bad_arguments_are_errors():
         b.Cada.from_config(cfg.scaled(d_max=0), *dev)
     with pytest.raises(b.CadaError, match="does not match"):
         b.Cada.from_config(cfg, dev[0], dev[1], dev[2][:50].contiguous())
+
+
+def test_largest_minibatch_two_pass():
+    """B = 4096, the largest minibatch the interface takes: the second pass keeps 16 bytes per row in
+    LDS (64 KB), which needs the kernel's allowance raised."""
+    cfg = configs.CFG1.scaled(name="big_batch", layer_dims=(64,), M=2, N_m=4500, B=4096, K=4, D=3, c=1e-3)
+    prob, dev, sched = _case(cfg)
+    o, tr = oracle_run(cfg, prob, sched)
+    out = run_library(cfg, dev, sched, replay=tr["mask"], path=PATH_TWO_PASS, expect_phase="logreg_dots")
+    assert out["error_flags"][0] == 0
+    assert np.array_equal(out["trace_own_mask"], tr["own_mask"])
+    assert rel_l2(out["theta64"], o.theta) < FP32_TOL
+    big = tr["lhs"] > 0
+    assert (np.abs(out["trace_lhs"] - tr["lhs"])[big] / tr["lhs"][big]).max() < 1e-4
