@@ -112,9 +112,10 @@ def kernel_bytes_per_launch(cfg) -> float:
     return cfg.M * per_worker
 
 
-def measure(cfg, K: int, W: int, plain_launch: bool = False):
+def measure(cfg, K: int, W: int, plain_launch: bool = False, bf16_store: bool = False):
     """W warm-up steps, K timed steps (no events inside the loop), then K more steps with an event
-    around every kernel phase.  Returns (record for the JSON line, problem, seconds of set-up)."""
+    around every kernel phase.  Returns (record for the JSON line, problem, seconds of set-up).
+    bf16_store: the MLP workloads with the stored gradients kept as bf16 (CADA_STORE_BF16)."""
     import torch
     from cada_synth import generators, native
     from paper_2012_15469_amd import binding
@@ -134,7 +135,8 @@ def measure(cfg, K: int, W: int, plain_launch: bool = False):
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
-    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0, plain_launch=plain_launch)
+    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0, plain_launch=plain_launch,
+                           gradient_store=binding.STORE_BF16 if bf16_store else binding.STORE_F32)
     # small logistic workloads run whole iterations inside one kernel: the K timed steps are one
     # cada_run call (one launch); everything else is one cada_step call per step
     whole = binding.cada_profile_phase_names(eng.ctx) == ["logreg_whole_steps"]
@@ -168,6 +170,7 @@ def measure(cfg, K: int, W: int, plain_launch: bool = False):
            "dtype": "f32" if cfg.gemm_dtype == "fp32" else "bf16",
            "config": {"workload": cfg.name, "M": cfg.M, "p": cfg.p, "B": cfg.B, "N_m": cfg.N_m,
                       "rule": "CADA%d" % cfg.rule, "D": cfg.D, "d_max": cfg.d_max, "c": cfg.c,
+                      "gradient_store": "bf16" if bf16_store else "f32",
                       "uploads_per_worker_step": uploads_timed / float(cfg.M * (W + K)), "setup_s": round(t_setup, 1)},
            "kernel_ms": {k: v for k, v in prof.items() if k != "steps"}}
     if cfg.model == "logreg":
@@ -205,8 +208,9 @@ def main() -> int:
                     help="timed steps of the headline workload (the default passes the forced upload at k = D = 100)")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="headline workload 1..5 (default 3: the HBM-bound logistic workload)")
-    ap.add_argument("--others", type=str, default="1,2,4,5",
-                    help="workloads also measured in this process and reported under \"other_workloads\" ('' = none)")
+    ap.add_argument("--others", type=str, default="1,2,4,5,4b,5b",
+                    help="workloads also measured in this process and reported under \"other_workloads\" ('' = none); "
+                         "4b, 5b: the MLP workloads with the bf16 gradient store")
     ap.add_argument("--other-steps", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=int, default=1,
@@ -246,12 +250,13 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    others = [int(x) for x in args.others.split(",") if x.strip() and int(x) != args.config]
+    others = [x.strip() for x in args.others.split(",") if x.strip() and x.strip() != str(args.config)]
     if others:
         out["other_workloads"] = {}
-        for n in others:
-            r, _, _ = measure(configs.ALL[n], args.other_steps, W)
-            out["other_workloads"][configs.ALL[n].name] = r
+        for x in others:
+            n, b16 = int(x.rstrip("b")), x.endswith("b")
+            r, _, _ = measure(configs.ALL[n], args.other_steps, W, bf16_store=b16)
+            out["other_workloads"][configs.ALL[n].name + ("+bf16_gradient_store" if b16 else "")] = r
 
     if not args.no_cpu_baseline:
         from oracle.driver import oracle_for

@@ -70,6 +70,17 @@ enum {
                          supports at most 32 classes (width of the last layer) */
 };
 
+/* How the server keeps the workers' last uploaded (stale) stochastic gradients, the terms that the aggregate of
+ * (CADA-1) sums (Section 1.2). */
+enum {
+  CADA_STORE_F32 = 0, /* float32: the aggregate is the sum of the gradients as computed */
+  CADA_STORE_BF16 = 1 /* bf16 (MLP model with the CADA1, CADA2 or always-upload rule): every gradient is rounded to
+                         nearest-even when its worker writes it, so each term of the aggregate carries a relative
+                         error of at most 2^-9 (the rule's left-hand side is formed before the rounding and does not
+                         change); halves the bytes that the weight-gradient kernels write and the server reads.
+                         cada_copy_stored_gradients returns the rounded values, cada_set_state rounds what it is given */
+};
+
 enum {
   CADA_OK = 0,
   CADA_EINVAL = -1,     /* bad argument (message says which) */
@@ -120,6 +131,8 @@ typedef struct cada_config {
                                 profilers that cannot trace cooperative dispatches; the device must be otherwise idle;
                                 every wait in the kernel is bounded and reports through error_flags bit 1) */
   int32_t two_pass_group;    /* CADA_PATH_TWO_PASS tuning: workers per pair of launches, 0 = all */
+  int32_t gradient_store;    /* CADA_STORE_*; anything but CADA_STORE_F32 on a model or rule that does not support it is
+                                refused (CADA_EUNSUPPORTED) */
   void *workspace;           /* DEVICE, 256-byte aligned, caller-owned */
   size_t workspace_bytes;
   void *stream;              /* hipStream_t; NULL = the default stream */
@@ -153,7 +166,7 @@ typedef struct cada_state {
 } cada_state;
 
 /* Bytes of device workspace cada_init needs for this configuration (only the
- * shape fields, rule, model, gemm_dtype, D, d_max and trace_steps are read).
+ * shape fields, rule, model, gemm_dtype, gradient_store, D, d_max and trace_steps are read).
  * Returns 0 and sets the error text if the configuration is invalid. */
 size_t cada_workspace_bytes(const cada_config *cfg);
 

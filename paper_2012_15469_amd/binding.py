@@ -27,6 +27,7 @@ GEMM_FP32, GEMM_BF16 = 0, 1
 REPLAY_FREE = 255
 EVAL_NOALLOC_MAX_M = 256
 PATH_AUTO, PATH_TWO_PASS, PATH_SINGLE_PASS, PATH_WHOLE_STEPS = 0, 1, 2, 3
+STORE_F32, STORE_BF16 = 0, 1
 
 
 class cada_config(C.Structure):
@@ -37,7 +38,7 @@ class cada_config(C.Structure):
                 ("lambda_l2", C.c_double), ("c", C.c_double), ("d_max", C.c_int32), ("D", C.c_int32),
                 ("rule", C.c_int32), ("gemm_dtype", C.c_int32), ("server", C.c_int32), ("alpha_K0", C.c_int64), ("trace_steps", C.c_int64),
                 ("path", C.c_int32), ("single_pass_rows", C.c_int32), ("single_pass_clusters", C.c_int32),
-                ("plain_launch", C.c_int32), ("two_pass_group", C.c_int32),
+                ("plain_launch", C.c_int32), ("two_pass_group", C.c_int32), ("gradient_store", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
@@ -203,7 +204,8 @@ class Cada:
                  c: float, alpha: float, beta1: float, beta2: float, eps: float, lam: float = 0.0,
                  gemm_dtype: str = "fp32", trace_steps: int = 0, stream: Optional[torch.cuda.Stream] = None,
                  server: int = 0, alpha_K0: int = 0, whole_steps: bool = False, path: int = PATH_AUTO,
-                 single_pass_rows: int = 0, single_pass_clusters: int = 0, plain_launch: bool = False, two_pass_group: int = 0):
+                 single_pass_rows: int = 0, single_pass_clusters: int = 0, plain_launch: bool = False, two_pass_group: int = 0,
+                 gradient_store: int = STORE_F32):
         assert X.is_cuda and y.is_cuda and theta0.is_cuda
         assert X.dtype == torch.float32 and X.is_contiguous() and theta0.dtype == torch.float32
         assert y.dtype == (torch.float32 if model == "logreg" else torch.int32) and y.is_contiguous()
@@ -228,6 +230,7 @@ class Cada:
         cfg.path = PATH_WHOLE_STEPS if whole_steps else path
         cfg.single_pass_rows, cfg.single_pass_clusters = single_pass_rows, single_pass_clusters
         cfg.plain_launch, cfg.two_pass_group = (1 if plain_launch else 0), two_pass_group
+        cfg.gradient_store = gradient_store
         cfg.stream = self.stream.cuda_stream
         nbytes = cada_workspace_bytes(cfg)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=X.device)

@@ -76,6 +76,7 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   if (cfg->server != CADA_SERVER_AMSGRAD && cfg->server != CADA_SERVER_SGD) { set_error("server must be one of CADA_SERVER_* (got %d)", cfg->server); return false; }
   if (cfg->model != CADA_MODEL_LOGREG && cfg->model != CADA_MODEL_MLP) { set_error("unknown model %d", cfg->model); return false; }
   if (cfg->path < CADA_PATH_AUTO || cfg->path > CADA_PATH_WHOLE_STEPS) { set_error("path must be one of CADA_PATH_* (got %d)", cfg->path); return false; }
+  if (cfg->gradient_store != CADA_STORE_F32 && cfg->gradient_store != CADA_STORE_BF16) { set_error("gradient_store must be one of CADA_STORE_* (got %d)", cfg->gradient_store); return false; }
   if (cfg->single_pass_rows < 0 || cfg->single_pass_rows > 1 || cfg->single_pass_clusters < 0 || cfg->two_pass_group < 0) { set_error("negative tuning field"); return false; }
   if (!cfg->layer_dims) { set_error("layer_dims is NULL"); return false; }
   if (!cfg->n_samples) { set_error("n_samples is NULL"); return false; }
@@ -123,7 +124,10 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   // rows of the per-worker stores: the MLP path pads them to 16 bytes (its p is rarely a multiple of 4)
   const bool mlp = cfg->model == CADA_MODEL_MLP;
   const size_t ps = mlp ? (p + 3) / 4 * 4 : p, ps16 = (p + 7) / 8 * 8;
-  float *gbuf = w.take<float>(2 * M * ps);
+  float *gbuf = nullptr;
+  uint16_t *gbuf16 = nullptr;
+  if (cfg->gradient_store == CADA_STORE_BF16) gbuf16 = w.take<uint16_t>(2 * M * ps16);
+  else gbuf = w.take<float>(2 * M * ps);
   float *hist = nullptr, *hist_lo = nullptr, *snap = nullptr, *snap_lo = nullptr, *dtl = nullptr;
   uint16_t *dtl16 = nullptr;
   if (cfg->rule == CADA_RULE_CADA2) {
@@ -170,7 +174,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
   c->small_bar = small_bar;
   c->small_args = small_args;
   s->theta = theta; s->theta_lo = theta_lo; s->hist_lo = hist_lo; s->snap_lo = snap_lo; s->h = h; s->v = v; s->vhat = vhat; s->nabla = nabla;
-  s->gbuf = gbuf; s->hist = hist; s->snap = snap; s->dtl = dtl; s->dtl16 = dtl16;
+  s->gbuf = gbuf; s->gbuf16 = gbuf16; s->hist = hist; s->snap = snap; s->dtl = dtl; s->dtl16 = dtl16;
   s->ps = (int64_t)ps; s->ps16 = (int64_t)ps16;
   s->tau = tau; s->sel = sel; s->lhs = lhs; s->lhs_part = lhs_part; s->mask = mask;
   s->ring = ring; s->ring_part = ring_part; s->uploads = uploads; s->n_up = n_up; s->err = err;
@@ -193,11 +197,13 @@ __global__ void k_broadcast_rows(float *dst, const float *src, int64_t p, int64_
   for (int64_t r = 0; r < reps; ++r) dst[r * stride + i] = v;
 }
 
-// out[m][i] = gbuf[sel[m]][m][i]
+// out[m][i] = gbuf[sel[m]][m][i] (as float32, whatever the store holds)
 __global__ void k_gather_stored(const DevState s, float *out) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int m = blockIdx.y;
-  if (i < s.p) out[(int64_t)m * s.p + i] = s.gbuf[((int64_t)s.sel[m] * s.M + m) * s.ps + i];
+  if (i >= s.p) return;
+  if (s.gbuf16) out[(int64_t)m * s.p + i] = bf2f(s.gbuf16[((int64_t)s.sel[m] * s.M + m) * s.ps16 + i]);
+  else out[(int64_t)m * s.p + i] = s.gbuf[((int64_t)s.sel[m] * s.M + m) * s.ps + i];
 }
 
 // cada_set_state, [p]-sized part: iterate, moments, and the reference point that is one vector
@@ -246,7 +252,8 @@ __global__ __launch_bounds__(kBlock) void k_set_rows(const SetStateArgs a) {
     }
   }
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
-    s.gbuf[(int64_t)m * s.ps + i] = a.in.stored_gradients[row + i];
+    if (s.gbuf16) s.gbuf16[(int64_t)m * s.ps16 + i] = f2bf(a.in.stored_gradients[row + i]);
+    else s.gbuf[(int64_t)m * s.ps + i] = a.in.stored_gradients[row + i];
     if (s.rule == CADA_RULE_CADA1) {
       if (s.dtl16) s.dtl16[(int64_t)m * s.ps16 + i] = f2bf(a.in.stored_innovations[row + i]);
       else s.dtl[(int64_t)m * s.ps + i] = a.in.stored_innovations[row + i];
@@ -288,6 +295,14 @@ __global__ __launch_bounds__(kBlock) void k_set_small(const SetStateArgs a, int 
 
 using namespace cada;
 
+// The bf16 gradient store exists on the MLP path, for the rules whose left-hand side does not read the store.
+static bool store_supported(const cada_config *cfg) {
+  if (cfg->gradient_store == CADA_STORE_F32) return true;
+  if (cfg->model != CADA_MODEL_MLP) { set_error("gradient_store = CADA_STORE_BF16 is implemented for the MLP model only"); return false; }
+  if (cfg->rule == CADA_RULE_LAG) { set_error("gradient_store = CADA_STORE_BF16: the stochastic LAG rule compares stored gradients themselves and keeps them in float32"); return false; }
+  return true;
+}
+
 struct cada_ctx {
   Ctx c;
   std::vector<int64_t> row_off_host;
@@ -299,7 +314,7 @@ const char *cada_last_error(void) { return g_err; }
 
 size_t cada_workspace_bytes(const cada_config *cfg) {
   Geometry g;
-  if (!check_config(cfg, &g)) return 0;
+  if (!check_config(cfg, &g) || !store_supported(cfg)) return 0;
   Carver w{nullptr};
   carve_common(w, cfg, g, nullptr, nullptr);
   size_t total = w.off;
@@ -316,6 +331,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   *out = nullptr;
   Geometry g;
   if (!check_config(cfg, &g)) return CADA_EINVAL;
+  if (!store_supported(cfg)) return CADA_EUNSUPPORTED;
   if (!theta0) { set_error("theta0 is NULL"); return CADA_EINVAL; }
   if (!cfg->X || !cfg->y) { set_error("X and y must be device pointers"); return CADA_EINVAL; }
   if (!cfg->workspace) { set_error("workspace is NULL"); return CADA_EWORKSPACE; }

@@ -24,6 +24,9 @@ struct DevState {
   // gradient is gbuf[sel[m]][m]; the fresh one of the current step is written to
   // gbuf[1-sel[m]][m] and an upload is sel[m] ^= 1 (no copy).
   float *gbuf;
+  // CADA_STORE_BF16: the same two rows per worker as bf16, gbuf16[s][m][ps16] (gbuf is null).  Written rounded to
+  // nearest even by the gradient kernels, summed as they are by the server.
+  uint16_t *gbuf16;
   // CADA2: hist[R][p], slot j mod R holds theta^j, R = D+1.  theta^{k-tau_m} is read here.
   float *hist, *hist_lo;
   // CADA1: snapshot theta-tilde [p] and innovations dtl[s][m][p] indexed by sel like gbuf.
@@ -34,7 +37,7 @@ struct DevState {
   uint16_t *dtl16;
   int64_t ps;               // floats from one row of gbuf / dtl / hist to the next: p, or p rounded up to a
                             // multiple of 4 (MLP) so that every row starts on a 16-byte boundary
-  int64_t ps16;             // elements from one row of dtl16 to the next (a multiple of 8)
+  int64_t ps16;             // elements from one row of dtl16 / gbuf16 to the next (a multiple of 8)
   int32_t *tau, *sel;     // [M]
   float *lhs;             // [M]
   float *lhs_part;        // [M][n_lhs_part] partial sums of the left-hand side

@@ -140,6 +140,15 @@ __device__ __forceinline__ float delta_theta(const DevState &s, const RefPtr &re
 __device__ __forceinline__ float *fresh_grad(const DevState &s, int m) {
   return s.gbuf + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.ps;
 }
+// (bf16 gradient store: the same row of gbuf16; exactly one of the two stores exists)
+__device__ __forceinline__ uint16_t *fresh_grad16(const DevState &s, int m) {
+  return s.gbuf16 + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.ps16;
+}
+// coordinate i of worker m's fresh gradient, into whichever store the context keeps
+__device__ __forceinline__ void put_fresh_grad(const DevState &s, int m, int64_t i, float v) {
+  if (s.gbuf16) fresh_grad16(s, m)[i] = f2bf(v);
+  else fresh_grad(s, m)[i] = v;
+}
 
 // CADA1's stored innovations (bf16): the row this step writes and the row of the last upload.
 __device__ __forceinline__ bf16_t *fresh_innov(const DevState &s, int m) {
@@ -492,7 +501,9 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
     // carried out in order, so the buffer needs no barrier.)
     constexpr int SP = kDwPitch;
     float *st = reinterpret_cast<float *>(smem_raw + (size_t)NSLOT * TILE * sizeof(bf16_t)) + w * (32 * SP);
-    float *gf = fresh_grad(s, wk) + g.offW;
+    const bool g16 = s.gbuf16 != nullptr;
+    float *gf = g16 ? nullptr : fresh_grad(s, wk) + g.offW;
+    bf16_t *gf16 = g16 ? fresh_grad16(s, wk) + g.offW : nullptr;
     const bool cada1 = s.rule == CADA_RULE_CADA1;
     bf16_t *ivf = cada1 ? fresh_innov(s, wk) + g.offW : nullptr;
     const bf16_t *ivs = cada1 ? stored_innov(s, wk) + g.offW : nullptr;
@@ -500,8 +511,8 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
     const int c4 = (lane & 15) * 4, rr = lane >> 4;
     const int colg = n0 + wx * 64 + c4;
     // every column of this wavefront's part exists: 16-byte accesses (4-byte aligned; with stored bf16
-    // innovations their 8-byte accesses need an even offset and row length for that)
-    const bool wide = n0 + wx * 64 + 64 <= g.N && (!cada1 || ((g.offW | (int64_t)g.N) & 1) == 0);
+    // innovations or gradients their 8-byte accesses need an even offset and row length for that)
+    const bool wide = n0 + wx * 64 + 64 <= g.N && (!(cada1 || g16) || ((g.offW | (int64_t)g.N) & 1) == 0);
     auto put_band = [&](const f32x16 (&acc)[2]) __attribute__((always_inline)) {
 #pragma unroll
       for (int j = 0; j < 2; ++j)
@@ -574,11 +585,23 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
           const f32x4u v = *reinterpret_cast<const f32x4u *>(st + (rr + 4 * it) * SP + c4);
-          if (rowb + 4 * it < g.M) __builtin_nontemporal_store(v, reinterpret_cast<f32x4u *>(gf + (int64_t)(rowb + 4 * it) * g.N + colg));
+          if (rowb + 4 * it < g.M) {
+            if (g16) {
+              u32x2u nw;
+              nw.x = f2bf_pk(v.x, v.y); nw.y = f2bf_pk(v.z, v.w);
+              __builtin_nontemporal_store(nw, reinterpret_cast<u32x2u *>(gf16 + (int64_t)(rowb + 4 * it) * g.N + colg));
+            } else {
+              __builtin_nontemporal_store(v, reinterpret_cast<f32x4u *>(gf + (int64_t)(rowb + 4 * it) * g.N + colg));
+            }
+          }
         }
       } else if (colg < g.N) {
         for (int it = 0; it < 8 && rowb + 4 * it < g.M; ++it)
-          for (int e = 0; e < 4 && colg + e < g.N; ++e) gf[(int64_t)(rowb + 4 * it) * g.N + colg + e] = st[(rr + 4 * it) * SP + c4 + e];
+          for (int e = 0; e < 4 && colg + e < g.N; ++e) {
+            const int64_t o = (int64_t)(rowb + 4 * it) * g.N + colg + e;
+            const float v = st[(rr + 4 * it) * SP + c4 + e];
+            if (g16) gf16[o] = f2bf(v); else gf[o] = v;
+          }
       }
       asm volatile("" ::: "memory");
     }
@@ -696,11 +719,13 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
   __syncthreads();
   // 2 x 16 x 64 values, four per thread, each the sum of the eight partial results in wavefront order
   float *gf = nullptr;
+  bf16_t *gf16 = nullptr;
   bf16_t *ivf = nullptr;
   const bf16_t *ivs = nullptr;
   const bool cada1 = s.rule == CADA_RULE_CADA1;
   if constexpr (EPI == EPI_DW) {
-    gf = fresh_grad(s, wk) + g.offW;
+    if (s.gbuf16) gf16 = fresh_grad16(s, wk) + g.offW;
+    else gf = fresh_grad(s, wk) + g.offW;
     if (cada1) {
       ivf = fresh_innov(s, wk) + g.offW;
       ivs = stored_innov(s, wk) + g.offW;
@@ -721,8 +746,9 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
         if (a == 0) g.c1[o] = v; else g.c2[o] = v;
       } else {
         const int64_t o = (int64_t)row * g.N + col;
-        if (a == 0) gf[o] = v;
-        else {
+        if (a == 0) {
+          if (gf16) gf16[o] = f2bf(v); else gf[o] = v;
+        } else {
           if (cada1) { ivf[o] = f2bf(v); v -= bf2f(ivs[o]); }
           sq = fmaf(v, v, sq);
         }
@@ -1162,7 +1188,7 @@ __global__ __launch_bounds__(kLossBlock) void k_loss(const LossArgs a) {
       float gsum = 0.f, iv = 0.f;
 #pragma unroll
       for (int ww = 0; ww < kLossBlock / 64; ++ww) { gsum += part[ww][c >> 1][c & 1]; iv += part[ww][c >> 1][2 + (c & 1)]; }
-      fresh_grad(s, m)[a.offb + c] = gsum;
+      put_fresh_grad(s, m, a.offb + c, gsum);
       if (s.rule == CADA_RULE_CADA1) {
         fresh_innov(s, m)[a.offb + c] = f2bf(iv);
         iv -= bf2f(stored_innov(s, m)[a.offb + c]);
@@ -1188,7 +1214,7 @@ __global__ __launch_bounds__(kBlock) void k_bias_finish(const DevState s, const 
       gsum += dbpart[((int64_t)m * RT + rt) * d + c];
       dsum += ddbpart[((int64_t)m * RT + rt) * d + c];
     }
-    fresh_grad(s, m)[offb + c] = gsum;
+    put_fresh_grad(s, m, offb + c, gsum);
     if (s.rule == CADA_RULE_CADA1) {
       fresh_innov(s, m)[offb + c] = f2bf(dsum);
       dsum -= bf2f(stored_innov(s, m)[offb + c]);

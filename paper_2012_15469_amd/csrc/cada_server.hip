@@ -38,12 +38,21 @@ __global__ __launch_bounds__(kBlock) void k_lag_lhs(const DevState s) {
   __shared__ float red[4];
   const int m = blockIdx.y;
   const int64_t mp = (int64_t)s.M * s.ps;
-  const float *gs = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.ps;
-  const float *gf = s.gbuf + (int64_t)(1 - s.sel[m]) * mp + (int64_t)m * s.ps;
   float sq = 0.f;
-  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
-    const float d = gf[i] - gs[i];
-    sq = fmaf(d, d, sq);
+  if (s.gbuf16) {      // bf16 store (always-upload rule, which only records this value): the rows as they are kept
+    const uint16_t *gs = s.gbuf16 + ((int64_t)s.sel[m] * s.M + m) * s.ps16;
+    const uint16_t *gf = s.gbuf16 + ((int64_t)(1 - s.sel[m]) * s.M + m) * s.ps16;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
+      const float d = bf2f(gf[i]) - bf2f(gs[i]);
+      sq = fmaf(d, d, sq);
+    }
+  } else {
+    const float *gs = s.gbuf + (int64_t)s.sel[m] * mp + (int64_t)m * s.ps;
+    const float *gf = s.gbuf + (int64_t)(1 - s.sel[m]) * mp + (int64_t)m * s.ps;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.p; i += (int64_t)gridDim.x * kBlock) {
+      const float d = gf[i] - gs[i];
+      sq = fmaf(d, d, sq);
+    }
   }
   const float tot = block_sum(sq, red);
   float *lp = s.lhs_part + (int64_t)m * s.n_lhs_part;
@@ -173,14 +182,32 @@ __global__ __launch_bounds__(kBlock) void k_server(const DevState s) {
   if (blockIdx.x == 0 && threadIdx.x == 0) s.n_up[(s.k + 1) & 1] = 0u;      // (nobody reads that slot during this launch)
   float nab[4] = {0.f, 0.f, 0.f, 0.f};
   auto row_of = [&](int buf, int m) -> const float * { return s.gbuf + (int64_t)buf * mp + (int64_t)m * s.ps; };
+  // bf16 store (rows of ps16 elements, 16-byte aligned; VEC == 4 on that path): four coordinates are 8 bytes
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  auto get16 = [&](int buf, int m, float (&o)[4]) {
+    if (coord(0) < s.p) {
+      const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(s.gbuf16 + ((int64_t)buf * s.M + m) * s.ps16 + coord(0)));
+      o[0] = __uint_as_float(t.x << 16); o[1] = __uint_as_float(t.x & 0xffff0000u);
+      o[2] = __uint_as_float(t.y << 16); o[3] = __uint_as_float(t.y & 0xffff0000u);
+    }
+  };
   if (incremental) {
     for (int m = w; m < s.M; m += 4) {
       if (!s.mask[m]) continue;                       // (uniform in the wavefront)
       const int cur = s.sel[m];                       // after the swap: cur holds the fresh gradient, 1 - cur the replaced one
       float a4[4] = {0.f, 0.f, 0.f, 0.f}, b4[4] = {0.f, 0.f, 0.f, 0.f};
-      get(row_of(cur, m), a4); get(row_of(1 - cur, m), b4);
+      if (VEC == 4 && s.gbuf16) { get16(cur, m, a4); get16(1 - cur, m, b4); }
+      else { get(row_of(cur, m), a4); get(row_of(1 - cur, m), b4); }
 #pragma unroll
       for (int v = 0; v < 4; ++v) nab[v] += a4[v] - b4[v];
+    }
+  } else if (VEC == 4 && s.gbuf16) {
+#pragma unroll 4
+    for (int m = w; m < s.M; m += 4) {
+      float t[4] = {0.f, 0.f, 0.f, 0.f};
+      get16(s.sel[m], m, t);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) nab[v] += t[v];
     }
   } else if constexpr (VEC == 4) {
     if (coord(0) < s.p) {

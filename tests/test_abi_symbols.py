@@ -91,3 +91,31 @@ def test_mlp_workspace_sizing_without_gpu():
     cfg, p = _mlp_cfg(b, (784, 512, 10), 4, 128, 600, 2)
     cfg.p = p + 1
     assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "does not match" in b.cada_last_error()
+
+
+def test_gradient_store_choices_without_gpu():
+    """The bf16 gradient store: two bytes instead of four for each of the 2 M p stored values, refused where
+    no kernel writes it (logistic model) or where the rule reads the stored gradients (stochastic LAG)."""
+    from paper_2012_15469_amd import binding as b
+    for rule in (0, 1, 2):
+        cfg, p = _mlp_cfg(b, (784, 512, 10), 8, 128, 600, rule)
+        n32 = b._lib.cada_workspace_bytes(ctypes.byref(cfg))
+        cfg.gradient_store = b.STORE_BF16
+        n16 = b._lib.cada_workspace_bytes(ctypes.byref(cfg))
+        assert 0 < n16 < n32, b.cada_last_error()
+        assert abs((n32 - n16) - 2 * 8 * p * 2) < 2 * 8 * 64 + 4096          # (rows are padded to 16 bytes)
+    cfg, p = _mlp_cfg(b, (784, 512, 10), 8, 128, 600, 3)
+    cfg.gradient_store = b.STORE_BF16
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "LAG" in b.cada_last_error()
+    out = ctypes.c_void_p()
+    assert b._lib.cada_init(ctypes.byref(cfg), None, ctypes.byref(out)) == -4          # CADA_EUNSUPPORTED, before any pointer is looked at
+    cfg.gradient_store = 7
+    assert b._lib.cada_workspace_bytes(ctypes.byref(cfg)) == 0 and "gradient_store must be" in b.cada_last_error()
+    lr = b.cada_config()
+    dims = (ctypes.c_int32 * 2)(54, 1)
+    ns = (ctypes.c_int64 * 2)(10, 10)
+    lr.M, lr.p, lr.model, lr.n_layers, lr.layer_dims, lr.B, lr.n_samples = 2, 54, 0, 1, dims, 4, ns
+    lr.d_max, lr.D, lr.rule = 10, 5, 2
+    assert b._lib.cada_workspace_bytes(ctypes.byref(lr)) > 0
+    lr.gradient_store = b.STORE_BF16
+    assert b._lib.cada_workspace_bytes(ctypes.byref(lr)) == 0 and "MLP model only" in b.cada_last_error()

@@ -9,7 +9,10 @@ trajectory the library is re-synchronised to the oracle's state (cada_set_state)
 of every segment, replays the oracle's upload decisions inside it, and at the end of each
 segment its iterate, delays, upload count, left- and right-hand sides and its own rule
 decisions are compared with the oracle's.  The horizon is cut into one test per segment so
-that every test finishes in well under a minute."""
+that every test finishes in well under a minute.
+
+Where a run names two gradient stores, a second library context that keeps the stored gradients as bf16
+(CADA_STORE_BF16) goes through the same segments beside the float32 one, against the same oracle run."""
 import json
 import os
 
@@ -20,7 +23,7 @@ import torch
 from cada_synth import configs, generators
 from oracle.cada_oracle import margins
 from oracle.driver import oracle_for
-from paper_2012_15469_amd.binding import Cada
+from paper_2012_15469_amd.binding import Cada, STORE_F32, STORE_BF16
 
 from common import upload, to_dev, inject_oracle_state, library_state, rel_l2
 
@@ -31,16 +34,17 @@ BF16_TOL = 2e-2
 # makes every worker upload at every step of these horizons (the stored results checked in
 # test_gpu_mlp_full.py cover that regime); here c is raised until rule-driven uploads and skips mix,
 # and further until workers stay silent for D iterations and are forced to upload.
+STORES = {"f32": STORE_F32, "bf16": STORE_BF16}
 RUNS = {
-    "cfg4_c30": (configs.CFG4.scaled(c=30.0), 104, 26),
+    "cfg4_c30": (configs.CFG4.scaled(c=30.0), 104, 26, ("f32", "bf16")),
     # nobody uploads by the rule: every worker is forced at tau_m = D = 100, where the reference point
     # theta^{k - 100} is the oldest of the D + 1 retained iterates, and the ring of iterates wraps
-    "cfg4_forced": (configs.CFG4.scaled(c=1e9), 104, 26),
+    "cfg4_forced": (configs.CFG4.scaled(c=1e9), 104, 26, ("f32", "bf16")),
     # CADA1 with D = 200: the snapshot refresh at k = 200 is crossed, decisions mix
-    "cfg5_c20": (configs.CFG5.scaled(c=20.0), 204, 17),
+    "cfg5_c20": (configs.CFG5.scaled(c=20.0), 204, 17, ("f32", "bf16")),
     # nobody uploads by the rule: every worker is forced at tau_m = D, together with the snapshot refresh
     # (D shortened from the workload's 200 to 40 to keep the fp64 oracle's share of this test short)
-    "cfg5_D40_forced": (configs.CFG5.scaled(c=1e6, D=40), 46, 23),
+    "cfg5_D40_forced": (configs.CFG5.scaled(c=1e6, D=40), 46, 23, ("f32",)),
 }
 FORCED = ("cfg4_forced", "cfg5_D40_forced")       # runs in which workers reach tau_m = D
 SUMMARY = -1
@@ -53,22 +57,26 @@ def bounds(K, n):
 
 
 ITEMS = []
-for _name, (_, _K, _n) in RUNS.items():
+for _name, (_, _K, _n, _) in RUNS.items():
     ITEMS += [(_name, s) for s in range(len(bounds(_K, _n)) - 1)] + [(_name, SUMMARY)]
 
 
 class Session:
     def __init__(self, name):
-        self.cfg, self.K, self.n = RUNS[name]
+        self.cfg, self.K, self.n, stores = RUNS[name]
         self.prob = generators.make_problem(self.cfg)
         self.dev = upload(self.prob)
         self.sched = generators.make_schedule(self.cfg, self.K)
         self.o = oracle_for(self.cfg, self.prob)
-        self.eng = Cada.from_config(self.cfg, *self.dev, trace_steps=self.K)
+        self.engs = {t: Cada.from_config(self.cfg, *self.dev, trace_steps=self.K, gradient_store=STORES[t]) for t in stores}
         self.done = 0                       # segments finished
-        self.diff_margins = []              # oracle margins where the library's own decision differs
-        self.lhs_rel = []                   # relative LHS errors of all (step, worker) pairs
-        self.theta_err = []
+        self.diff_margins = {t: [] for t in stores}   # oracle margins where the library's own decision differs
+        self.lhs_rel = {t: [] for t in stores}        # relative LHS errors of all (step, worker) pairs
+        self.theta_err = {t: [] for t in stores}
+
+    def close(self):
+        for e in self.engs.values():
+            e.close()
 
 
 _sessions = {}
@@ -79,13 +87,13 @@ def session():
     def get(name):
         if name not in _sessions:
             for other in list(_sessions):           # one workload's buffers at a time
-                _sessions.pop(other).eng.close()
+                _sessions.pop(other).close()
             torch.cuda.empty_cache()
             _sessions[name] = Session(name)
         return _sessions[name]
     yield get
     for s in _sessions.values():
-        s.eng.close()
+        s.close()
     _sessions.clear()
 
 
@@ -95,13 +103,21 @@ def test_horizon(session, name, seg):
         return summary(name)
     S = session(name)
     assert S.done == seg, "segments run in order (an earlier one failed or was deselected)"
-    cfg, o, eng = S.cfg, S.o, S.eng
+    cfg, o = S.cfg, S.o
     k0, k1 = bounds(S.K, S.n)[seg], bounds(S.K, S.n)[seg + 1]
-    if seg > 0:
-        inject_oracle_state(eng, o)          # re-synchronise: the library continues from the oracle's state
-    assert eng.k == o.k == k0
+    for eng in S.engs.values():
+        if seg > 0:
+            inject_oracle_state(eng, o)      # re-synchronise: the library continues from the oracle's state
+        assert eng.k == o.k == k0
     o.run(S.sched[k0:k1])
     tr = {k: v[k0:k1] for k, v in o.trace_arrays().items()}
+    for tag, eng in S.engs.items():
+        _segment(S, name, tag, eng, tr, k0, k1)
+    S.done += 1
+
+
+def _segment(S, name, tag, eng, tr, k0, k1):
+    o = S.o
     eng.run(to_dev(S.sched[k0:k1].astype(np.int32)), to_dev(tr["mask"]))
     st = library_state(eng)
     assert st["k"] == k1 and st["error_flags"][0] == 0
@@ -114,13 +130,13 @@ def test_horizon(session, name, seg):
     rhs_rel = np.abs(st["trace_rhs"][k0:k1] - tr["rhs"]) / np.maximum(tr["rhs"], 1e-300)
     rhs_rel = rhs_rel[tr["rhs"] > 0]
     own_diff = st["trace_own_mask"][k0:k1] != tr["own_mask"]
-    S.diff_margins += mg[own_diff].tolist()
-    S.lhs_rel += rel[big].tolist()
-    S.theta_err.append(err)
+    S.diff_margins[tag] += mg[own_diff].tolist()
+    S.lhs_rel[tag] += rel[big].tolist()
+    S.theta_err[tag].append(err)
     G = eng.stored_gradients().cpu().numpy()
     g_err = rel_l2(G, o.G)
-    print("%s steps %d-%d: theta %.2e  stored gradients %.2e  lhs rel median %.2e p99 %.2e max %.2e  rhs rel max %.2e  uploads %.2f  "
-          "own-rule disagreements %d (margins %s)" % (name, k0, k1, err, g_err, np.median(rel[big]), np.quantile(rel[big], 0.99), rel[big].max(),
+    print("%s [%s store] steps %d-%d: theta %.2e  stored gradients %.2e  lhs rel median %.2e p99 %.2e max %.2e  rhs rel max %.2e  uploads %.2f  "
+          "own-rule disagreements %d (margins %s)" % (name, tag, k0, k1, err, g_err, np.median(rel[big]), np.quantile(rel[big], 0.99), rel[big].max(),
                                                      rhs_rel.max() if rhs_rel.size else 0.0, tr["mask"].mean(), own_diff.sum(),
                                                      ['%.1e' % x for x in mg[own_diff]]))
     # one segment after a hand-over: bf16 contractions, float32 master iterate
@@ -135,7 +151,6 @@ def test_horizon(session, name, seg):
     # left- and right-hand sides, so none may sit at a margin beyond the largest such error measured here
     bound = rel[big].max() + (rhs_rel.max() if rhs_rel.size else 0.0)
     assert not (own_diff & (mg > bound)).any(), (np.argwhere(own_diff & (mg > bound))[:4].tolist(), bound)
-    S.done += 1
 
 
 def summary(name):
@@ -155,14 +170,15 @@ def summary(name):
         assert 0.02 < tr["mask"][free].mean() < 0.98, "rule-driven uploads and skips must mix"
     assert S.K > cfg.D, "the horizon passes D (history wrap / snapshot refresh)"
     edges = [0, 1e-5, 1e-4, 1e-3, 1e-2, 3e-2, 1e-1, np.inf]
-    hist = np.histogram(np.asarray(S.diff_margins), bins=edges)[0].tolist()
-    rec = {"workload": cfg.name, "c": cfg.c, "K": S.K, "decisions": int(tr["mask"].size), "forced_uploads": int(forced.sum()),
-           "upload_fraction_of_free_decisions": float(tr["mask"][free].mean()),
-           "own_rule_disagreements": len(S.diff_margins), "margin_histogram_edges": [str(e) for e in edges],
-           "margin_histogram": hist, "lhs_rel_median": float(np.median(S.lhs_rel)), "lhs_rel_p99": float(np.quantile(S.lhs_rel, 0.99)),
-           "lhs_rel_max": float(np.max(S.lhs_rel)), "theta_rel_l2_per_segment": S.theta_err}
-    print(json.dumps(rec))
     out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out):
-        with open(os.path.join(out, "mlp_horizon_%s.json" % name), "w") as f:
-            json.dump(rec, f, indent=1)
+    for tag in S.engs:
+        hist = np.histogram(np.asarray(S.diff_margins[tag]), bins=edges)[0].tolist()
+        rec = {"workload": cfg.name, "gradient_store": tag, "c": cfg.c, "K": S.K, "decisions": int(tr["mask"].size), "forced_uploads": int(forced.sum()),
+               "upload_fraction_of_free_decisions": float(tr["mask"][free].mean()),
+               "own_rule_disagreements": len(S.diff_margins[tag]), "margin_histogram_edges": [str(e) for e in edges],
+               "margin_histogram": hist, "lhs_rel_median": float(np.median(S.lhs_rel[tag])), "lhs_rel_p99": float(np.quantile(S.lhs_rel[tag], 0.99)),
+               "lhs_rel_max": float(np.max(S.lhs_rel[tag])), "theta_rel_l2_per_segment": S.theta_err[tag]}
+        print(json.dumps(rec))
+        if os.path.isdir(out):
+            with open(os.path.join(out, "mlp_horizon_%s%s.json" % (name, "" if tag == "f32" else "_" + tag)), "w") as f:
+                json.dump(rec, f, indent=1)
