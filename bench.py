@@ -216,6 +216,8 @@ def main() -> int:
     ap.add_argument("--replicas", type=int, default=1,
                     help="workloads 1-2 only: R independent runs (seeds seed, seed+17, ...) advanced side by side in one "
                          "launch per call (cada_run_replicas); value counts the worker-iterations of all of them")
+    ap.add_argument("--bf16-gradient-store", action="store_true",
+                    help="workloads 4-5 as the headline workload with the stored gradients kept as bf16 (CADA_STORE_BF16)")
     ap.add_argument("--plain-launch", action="store_true",
                     help="launch the single-pass kernel without the cooperative-launch API (rocprofv3 on this "
                          "image crashes at exit after tracing a cooperative dispatch); same grid, same kernel")
@@ -237,7 +239,7 @@ def main() -> int:
     if args.replicas > 1:
         return bench_replicas(args, cfg, dev)
     K, W = args.steps, args.warmup
-    rec, prob, _ = measure(cfg, K, W, args.plain_launch)
+    rec, prob, _ = measure(cfg, K, W, args.plain_launch, bf16_store=args.bf16_gradient_store)
     out = {"metric": "worker-iterations/sec (grads+CADA rule+AMSGrad)", "value": rec["value"], "unit": rec["unit"],
            "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": rec["ms_per_step"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": rec["dtype"], "data": "synthetic",
