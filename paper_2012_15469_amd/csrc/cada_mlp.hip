@@ -615,10 +615,11 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
 // The same products for an output of at most 32 columns (the last layer: C <= 32 classes).  A
 // 128 x 128 tile would leave nine tenths of its MFMAs and of its workgroups idle and the launch
 // would run on a few CUs (32 tiles for the logits of 16 workers).  Here a workgroup computes
-// 32 rows x 32 columns; its eight wavefronts split the tile steps (wavefront w takes steps w,
-// w + 8, ...), read their fragments straight from the chunks in global memory (a fragment is
-// 16 consecutive bytes of a chunk row) and add their partial accumulators up through LDS in a
-// fixed order.  grid (ceil(M / 32), workers), 512 threads, 64 KB of dynamic LDS (EPI_DW: 112 KB).
+// 32 rows x 32 columns; its wavefronts (eight; fewer for the few steps of a weight gradient) split the
+// tile steps (wavefront w takes steps w, w + nw, ...), read their fragments straight from the chunks in
+// global memory (a fragment is 16 consecutive bytes of a chunk row) and add their partial accumulators up
+// through LDS in a fixed order.  grid (ceil(M / 32), workers), 64 nw threads, 8 KB of dynamic LDS per
+// wavefront (EPI_DW: 14 KB).
 // EPI_STORE2: logits; EPI_DW: weight gradient, innovation, its squared norm (slot lhs_slot0 + row band).
 // The weight gradient sums over the worker's rows: its operands are (row, unit) tensors, a step's part of
 // one is a [32 rows][32 units] block (2 KB of consecutive memory), which the wavefront copies into an
@@ -629,6 +630,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
   float *red = reinterpret_cast<float *>(smem_raw);                  // [8 wavefronts][2 accumulators][16][64]
   const DevState &s = g.s;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int nw = blockDim.x >> 6;          // wavefronts of this launch (1..8): fewer for short contractions, so that more workgroups fit a CU
   const int m0 = blockIdx.x * 32, wk = blockIdx.y;
   const int nk = (g.K + BK - 1) / BK;
   // this lane's fragment in a chunk: row lane % 32 of the band (A) or of the first 32 rows (B), piece lane / 32 (+ 2)
@@ -647,7 +649,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
     for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)wk * g.B.bstride[sl];
     bf16_t *area = reinterpret_cast<bf16_t *>(smem_raw) + w * (7 * 1024);       // room for seven blocks per wavefront
     const int fro_tr = (8 * (lane >> 5) + ((lane & 15) >> 2)) * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    for (int kc = w; kc < nk; kc += 8) {
+    for (int kc = w; kc < nk; kc += nw) {
       u32x4 v[NA + NB][2];
 #pragma unroll
       for (int sl = 0; sl < NA + NB; ++sl) {
@@ -683,7 +685,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
   for (int sl = 0; sl < NA; ++sl) pa[sl] = g.A.ptr[sl] + (int64_t)wk * g.A.bstride[sl] + offa;
 #pragma unroll
   for (int sl = 0; sl < NB; ++sl) pb[sl] = g.B.ptr[sl] + (int64_t)(g.rep ? g.rep[wk] : wk) * g.B.bstride[sl] + offb;
-  for (int kc = w; kc < nk; kc += 8) {
+  for (int kc = w; kc < nk; kc += nw) {
     u32x4 fa[2][NA], fb[2][NB];          // (kept as integer vectors: arrays of them stay in registers)
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
@@ -717,7 +719,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
     red[((w * 2 + 1) * 16 + r) * 64 + lane] = acc2[r];
   }
   __syncthreads();
-  // 2 x 16 x 64 values, four per thread, each the sum of the eight partial results in wavefront order
+  // 2 x 16 x 64 values over the threads, each the sum of the wavefronts' partial results in wavefront order
   float *gf = nullptr;
   bf16_t *gf16 = nullptr;
   bf16_t *ivf = nullptr;
@@ -732,13 +734,10 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
     }
   }
   float sq = 0.f;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int e = t + q * 2 * kBlock;                 // (accumulator, r, lane)
+  for (int e = t; e < 2 * 16 * 64; e += (int)blockDim.x) {       // (accumulator, r, lane)
     const int a = e >> 10, r = (e >> 6) & 15, ln = e & 63;
     float v = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < 8; ++ww) v += red[((ww * 2 + a) * 16 + r) * 64 + ln];
+    for (int ww = 0; ww < nw; ++ww) v += red[((ww * 2 + a) * 16 + r) * 64 + ln];
     const int row = m0 + 8 * (r >> 2) + 4 * (ln >> 5) + (r & 3), col = ln & 31;
     if (row < g.M && col < g.N) {
       if constexpr (EPI == EPI_STORE2) {
@@ -762,8 +761,7 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
     __syncthreads();
     if (t == 0) {
       float tot = 0.f;
-#pragma unroll
-      for (int ww = 0; ww < 8; ++ww) tot += red[ww];
+      for (int ww = 0; ww < nw; ++ww) tot += red[ww];
       s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot0 + blockIdx.x] = tot;
     }
   }
@@ -1247,13 +1245,22 @@ template <int EPI, int NA, int NB, bool HAS_D> int launch_mm5_as(Ctx *c, const M
   return CADA_OK;
 }
 // first layer: two A tensors (hi, lo) and no propagated difference on the A side; deeper layers: all of them
-constexpr int skinny_lds_bytes(int epi) { return epi == EPI_DW ? 8 * 7 * 1024 * (int)sizeof(bf16_t) : 65536; }   // (>= the 64 KB of partial results)
+// per wavefront: its partial results (8 KB); weight gradient: the seven blocks it stages (14 KB), over which the partial results are laid later
+constexpr int skinny_lds_bytes(int epi, int nw = 8) { return nw * (epi == EPI_DW ? 7 * 1024 * (int)sizeof(bf16_t) : 8192); }
+// Wavefronts of a launch: one per two tile steps, eight at most.  A weight gradient sums over a worker's few rows (4-8
+// steps); with eight wavefronts half of them would idle while their LDS kept other workgroups off the CU.
+static int skinny_waves(int epi, int K) {
+  const int nk = (K + BK - 1) / BK;
+  if (epi != EPI_DW) return 8;
+  return nk >= 16 ? 8 : nk >= 2 ? nk / 2 : 1;
+}
 template <int EPI, int NA, int NB, bool HAS_D> hipError_t skinny_allow_lds() {
   return hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny<EPI, NA, NB, HAS_D>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              skinny_lds_bytes(EPI));
 }
 template <int EPI, int NA, int NB, bool HAS_D> int launch_skinny_as(Ctx *c, const Mm5Args &g) {
-  hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(2 * kBlock), skinny_lds_bytes(EPI), c->stream, g);
+  const int nw = skinny_waves(EPI, g.K);
+  hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(64 * nw), skinny_lds_bytes(EPI, nw), c->stream, g);
   return CADA_OK;
 }
 // Returns CADA_OK after enqueueing the launch, CADA_EUNSUPPORTED (and launches nothing) when the
