@@ -90,7 +90,7 @@ __device__ __forceinline__ int lds_piece(int piece) {   // piece = 4 row + q  ->
   return piece ^ ((piece >> 4) & 3);
 }
 
-enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3 };
+enum { EPI_FWD_HIDDEN = 0, EPI_STORE2 = 1, EPI_DW = 2, EPI_DA = 3, EPI_LOSS = 4 };
 
 // LDS: a ring of 8 KB slots (one chunk each); behind it a buffer per multiplying wavefront for the
 // way out: 32 rows x 64 floats for the weight gradients, 8 KB for the bf16 tensors of the forward
@@ -132,6 +132,12 @@ struct Mm5Args {
   // EPI_DW
   int64_t offW;
   int lhs_slot0;
+  // EPI_LOSS (last layer's forward product with the loss in its epilogue; outputs o_h/o_l/o_d/o_r, bias at offb) and the
+  // last layer's EPI_DW, which finishes that layer's bias gradient from the row blocks' sums
+  const int64_t *grow;                  // global row of every padded minibatch row (its label)
+  float *lastb;                         // [workers][nrb][32][2]: per block of 32 rows, sums over the rows of G and of dG
+  int nrb;                              // blocks of 32 rows per worker
+  int lhs_slot_b;                       // slot of the bias innovation's part of the left-hand side
 };
 
 __device__ __forceinline__ float delta_theta(const DevState &s, const RefPtr &ref, int64_t i) {
@@ -612,6 +618,12 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // the movers' last barrier
 }
 
+__device__ __forceinline__ float group16_sum(float x) {
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
 // The same products for an output of at most 32 columns (the last layer: C <= 32 classes).  A
 // 128 x 128 tile would leave nine tenths of its MFMAs and of its workgroups idle and the launch
 // would run on a few CUs (32 tiles for the logits of 16 workers).  Here a workgroup computes
@@ -620,7 +632,9 @@ __global__ __launch_bounds__(2 * kBlock, 1) void k_mm5(const Mm5Args g) {
 // global memory (a fragment is 16 consecutive bytes of a chunk row) and add their partial accumulators up
 // through LDS in a fixed order.  grid (ceil(M / 32), workers), 64 nw threads, 8 KB of dynamic LDS per
 // wavefront (EPI_DW: 14 KB).
-// EPI_STORE2: logits; EPI_DW: weight gradient, innovation, its squared norm (slot lhs_slot0 + row band).
+// EPI_STORE2: logits (evaluation); EPI_LOSS: the logits stay in the workgroup, whose epilogue is the loss (the signals
+// the backward contractions read, and per-block sums for the bias gradient); EPI_DW: weight gradient, innovation, its
+// squared norm (slot lhs_slot0 + row band), and (one more workgroup) the last layer's bias gradient from those sums.
 // The weight gradient sums over the worker's rows: its operands are (row, unit) tensors, a step's part of
 // one is a [32 rows][32 units] block (2 KB of consecutive memory), which the wavefront copies into an
 // LDS area of its own and reads back transposed (tr_fragment).
@@ -636,10 +650,49 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
   // this lane's fragment in a chunk: row lane % 32 of the band (A) or of the first 32 rows (B), piece lane / 32 (+ 2)
   const int64_t offa = (((int64_t)(m0 >> 7) * g.A.kt[0]) << 12) + (((m0 & 127) + (lane & 31)) << 5) + ((lane >> 5) << 3);
   const int64_t offb = ((lane & 31) << 5) + ((lane >> 5) << 3);
+  if constexpr (EPI == EPI_DW) {
+    // The last layer's launch has one workgroup more than tiles: it forms that layer's bias gradient, its innovation
+    // and the innovation's part of the left-hand side from the sums that the forward launch left per block of 32 rows
+    // (added up in the order of the rows).
+    if (g.lastb != nullptr && (int)blockIdx.x == (g.M + 31) / 32) {
+      if (w != 0) return;
+      const bool cada1 = s.rule == CADA_RULE_CADA1;
+      float sqb = 0.f;
+      if (lane < g.N) {
+        float gsum = 0.f, iv = 0.f;
+        for (int rb = 0; rb < g.nrb; ++rb) {
+          const float *q = g.lastb + ((((int64_t)wk * g.nrb + rb) * 32 + lane) << 1);
+          gsum += q[0]; iv += q[1];
+        }
+        put_fresh_grad(s, wk, g.offb + lane, gsum);
+        if (cada1) {
+          fresh_innov(s, wk)[g.offb + lane] = f2bf(iv);
+          iv -= bf2f(stored_innov(s, wk)[g.offb + lane]);
+        }
+        sqb = iv * iv;
+      }
+      const float totb = wave_sum(sqb);
+      if (lane == 0) s.lhs_part[(int64_t)wk * s.n_lhs_part + g.lhs_slot_b] = totb;
+      return;
+    }
+  }
   const bf16_t *pa[NA], *pb[NB];
   f32x16 acc1, acc2;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { acc1[r] = 0.f; acc2[r] = 0.f; }
+  // EPI_LOSS: sixteen lanes share a row of the 32 x 32 result, each with two of the (at most 32) classes.  The
+  // biases, their differences to the reference point and the row's label are asked for here, so that their
+  // latency passes under the products.
+  float bz[2] = {0.f, 0.f}, dbz[2] = {0.f, 0.f};
+  int label = 0;
+  if constexpr (EPI == EPI_LOSS) {
+    const RefPtr ref = theta_ref(s, wk, s.k);
+    const int c0 = 2 * (t & 15);
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+      if (c0 + e < g.N) { bz[e] = s.theta[g.offb + c0 + e]; dbz[e] = delta_theta(s, ref, g.offb + c0 + e); }
+    label = static_cast<const int32_t *>(s.y)[g.grow[(int64_t)wk * g.Bp + min(m0 + (t >> 4), g.M - 1)]];
+  }
   if constexpr (EPI == EPI_DW) {
     // units m0 .. m0 + 31 of the A tensors are chunk m0 / 32 of every row tile, the (at most 32) output
     // columns chunk 0 of the B tensors; step kc covers the worker's rows 32 kc .. 32 kc + 31
@@ -719,6 +772,95 @@ __global__ __launch_bounds__(2 * kBlock) void k_skinny(const Mm5Args g) {
     red[((w * 2 + 1) * 16 + r) * 64 + lane] = acc2[r];
   }
   __syncthreads();
+  if constexpr (EPI == EPI_LOSS) {
+    // softmax cross-entropy on the tile's rows: G = (P - onehot)/B, dG = (P - Pref)/B.  With e_i = exp(-dz_i) and
+    // T = sum_j P_j e_j the reference probabilities are Pref_i = P_i e_i / T, so
+    //     P_i - Pref_i = P_i (S - expm1(-dz_i)) / (1 + S),  S = sum_j P_j expm1(-dz_j) = T - 1,
+    // which keeps the digits of a small difference (no subtraction of nearly equal probabilities) and
+    // is used while every |dz_j| of the row is below 1/2.  For larger differences (a reference point
+    // many iterations old) 1 + S cancels instead (T can be far below float32's resolution of 1), so
+    // there P_i - Pref_i is formed directly with Pref = softmax(z - dz), the exponents shifted by their
+    // maximum; the difference is then no longer small against its operands.
+    // Also the sums over the tile's rows of G and dG: the last layer's bias gradient and its innovation, which the
+    // weight-gradient launch of that layer adds up over the row blocks.
+    __shared__ float part[8][16][4];
+    const int rl = t >> 4, cp = t & 15, c0 = 2 * cp;
+    const bool on[2] = {c0 < g.N, c0 + 1 < g.N};
+    const int row = m0 + rl;
+    const bool live = row < g.M;                    // (rows past the minibatch are padding)
+    // accumulator element (r, lane) is (row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32) of the tile
+    const int ra = 4 * (rl >> 3) + (rl & 3), lb = 32 * ((rl >> 2) & 1);
+    const float invB = 1.0f / (float)s.B;
+    float z[2], x[2], ndz[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      float zs = 0.f, ds = 0.f;
+      for (int ww = 0; ww < nw; ++ww) {
+        zs += red[((ww * 2 + 0) * 16 + ra) * 64 + lb + c0 + e];
+        ds += red[((ww * 2 + 1) * 16 + ra) * 64 + lb + c0 + e];
+      }
+      z[e] = on[e] ? zs + bz[e] : -INFINITY;
+      ndz[e] = on[e] ? -(ds + dbz[e]) : 0.f;
+      x[e] = expm1f(ndz[e]);
+    }
+    const float zr[2] = {z[0] + ndz[0], z[1] + ndz[1]};       // logits at the reference point (-inf for an absent class)
+    float nabs = fmaxf(fabsf(ndz[0]), fabsf(ndz[1]));        // (an absent class contributes 0)
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) nabs = fmaxf(nabs, __shfl_xor(nabs, o, 64));
+    const bool far = !(nabs < 0.5f);             // (also taken by a NaN, which then shows in the result)
+    float zmax = fmaxf(z[0], z[1]);
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 64));
+#pragma unroll
+    for (int e = 0; e < 2; ++e) z[e] = on[e] ? expf(z[e] - zmax) : 0.f;
+    const float den = group16_sum(z[0] + z[1]);
+    z[0] = z[0] / den; z[1] = z[1] / den;
+    const float S = group16_sum(fmaf(z[0], x[0], z[1] * x[1]));
+    // the direct form: Pref = softmax of the reference logits z - dz, shifted by their maximum
+    float rmax = fmaxf(zr[0], zr[1]);
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) rmax = fmaxf(rmax, __shfl_xor(rmax, o, 64));
+    const float er[2] = {on[0] ? expf(zr[0] - rmax) : 0.f, on[1] ? expf(zr[1] - rmax) : 0.f};
+    const float rden = group16_sum(er[0] + er[1]);
+    // (row, class) tensors: a row's classes are consecutive, written two at a time (an absent odd
+    // class is a zero in the padding)
+    uint32_t ph = 0, pl = 0, pd = 0, pr = 0;
+    float sumG[2] = {0.f, 0.f}, sumD[2] = {0.f, 0.f};
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      if (on[e] && live) {
+        const int c = c0 + e;
+        const float gl = (z[e] - (c == label ? 1.f : 0.f)) * invB;
+        const float dg = (far ? z[e] - er[e] / rden : z[e] * (S - x[e]) / (1.0f + S)) * invB;
+        const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
+        ph |= (uint32_t)hi << (16 * e); pl |= (uint32_t)lo << (16 * e); pd |= (uint32_t)bd << (16 * e); pr |= (uint32_t)br << (16 * e);
+        sumG[e] = gl;
+        sumD[e] = dg;
+      }
+    }
+    if (on[0] && live) {
+      const int64_t o = tm((int64_t)wk * g.Bp + row, 0, g.kto) + c0;          // classes 0..31 lie in the row's first chunk
+      *reinterpret_cast<uint32_t *>(g.o_h + o) = ph; *reinterpret_cast<uint32_t *>(g.o_l + o) = pl;
+      *reinterpret_cast<uint32_t *>(g.o_d + o) = pd;
+      if (g.o_r) *reinterpret_cast<uint32_t *>(g.o_r + o) = pr;
+    }
+    // sums over the tile's rows in a fixed order: the wavefront's four rows, then the wavefronts
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      sumG[e] += __shfl_xor(sumG[e], 16, 64); sumG[e] += __shfl_xor(sumG[e], 32, 64);
+      sumD[e] += __shfl_xor(sumD[e], 16, 64); sumD[e] += __shfl_xor(sumD[e], 32, 64);
+    }
+    if (lane < 16) { part[w][cp][0] = sumG[0]; part[w][cp][1] = sumG[1]; part[w][cp][2] = sumD[0]; part[w][cp][3] = sumD[1]; }
+    __syncthreads();
+    if (w == 0 && lane < g.N) {
+      const int c = lane;
+      float gsum = 0.f, iv = 0.f;
+      for (int ww = 0; ww < nw; ++ww) { gsum += part[ww][c >> 1][c & 1]; iv += part[ww][c >> 1][2 + (c & 1)]; }
+      float *q = g.lastb + ((((int64_t)wk * g.nrb + blockIdx.x) * 32 + c) << 1);
+      q[0] = gsum; q[1] = iv;
+    }
+    return;
+  }
   // 2 x 16 x 64 values over the threads, each the sum of the wavefronts' partial results in wavefront order
   float *gf = nullptr;
   bf16_t *gf16 = nullptr;
@@ -792,6 +934,7 @@ struct MlpPlan {
   uint64_t *maskbits[CADA_MAX_LAYERS];                    // hidden l: ReLU mask bits per tile and lane
   int32_t *rep;                                           // CADA2: first worker with the same reference point [M]
   float *dbpart, *ddbpart;                                // [M][2 RT][max hidden width]
+  float *lastb;                                           // [M][Bp / 32][32][2]: last layer, sums of G and dG per block of 32 rows
 };
 
 namespace {
@@ -855,6 +998,7 @@ void layout(MlpPlan &P, const cada_config *cfg, int64_t total_rows, Carve &w) {
   P.dZL = w.take<float>(Rp * P.d[P.L]);
   P.dbpart = w.take<float>((size_t)cfg->M * 2 * P.RT * maxh);
   P.ddbpart = w.take<float>((size_t)cfg->M * 2 * P.RT * maxh);
+  P.lastb = w.take<float>((size_t)cfg->M * (P.Bp / 32) * 32 * 2);
 }
 }  // namespace
 
@@ -1071,133 +1215,6 @@ __global__ __launch_bounds__(kBlock) void k_stage(const StageArgs a) {
   stage_weights(a, p, sm, (int)(r % p.gx), (int)(r / p.gx), (int)z, l == 0 && r == 0);
 }
 
-struct LossArgs {
-  DevState s;
-  const float *Z, *dZ;            // logits without bias [Rp][C]
-  bf16_t *Gh, *Gl, *dG, *Gref;    // (padded row, class), ktg chunks per tile; Gref null for a single-layer network
-  const int64_t *grow;
-  int64_t offb;
-  int C, Bp; int64_t ktg;
-  int lhs_slot;
-};
-
-// softmax cross-entropy: G = (P - onehot)/B, dG = (P - Pref)/B.  With e_i = exp(-dz_i) and
-// T = sum_j P_j e_j the reference probabilities are Pref_i = P_i e_i / T, so
-//     P_i - Pref_i = P_i (S - expm1(-dz_i)) / (1 + S),  S = sum_j P_j expm1(-dz_j) = T - 1,
-// which keeps the digits of a small difference (no subtraction of nearly equal probabilities) and
-// is used while every |dz_j| of the row is below 1/2.  For larger differences (a reference point
-// many iterations old) 1 + S cancels instead (T can be far below float32's resolution of 1), so
-// there P_i - Pref_i is formed directly with Pref = softmax(z - dz), the exponents shifted by their
-// maximum; the difference is then no longer small against its operands.
-// One block of 1024 threads per worker; sixteen lanes share a row, each with two of the (at most
-// 32) classes, so a wavefront holds four rows and the block 64.  Also the last layer's bias
-// gradient, its innovation and the innovation's contribution to the rule's left-hand side.
-constexpr int kLossBlock = 1024;
-
-__device__ __forceinline__ float group16_sum(float x) {
-#pragma unroll
-  for (int o = 1; o < 16; o <<= 1) x += __shfl_xor(x, o, 64);
-  return x;
-}
-
-__global__ __launch_bounds__(kLossBlock) void k_loss(const LossArgs a) {
-  const DevState &s = a.s;
-  __shared__ float part[kLossBlock / 64][16][4];
-  const int m = blockIdx.x;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int cp = threadIdx.x & 15;               // class pair
-  const int c0 = 2 * cp;
-  const bool on[2] = {c0 < a.C, c0 + 1 < a.C};
-  const RefPtr ref = theta_ref(s, m, s.k);
-  const int32_t *yv = static_cast<const int32_t *>(s.y);
-  const float invB = 1.0f / (float)s.B;
-  float bz[2], dbz[2];
-#pragma unroll
-  for (int e = 0; e < 2; ++e) {
-    bz[e] = on[e] ? s.theta[a.offb + c0 + e] : 0.f;
-    dbz[e] = on[e] ? delta_theta(s, ref, a.offb + c0 + e) : 0.f;
-  }
-  float sumG[2] = {0.f, 0.f}, sumD[2] = {0.f, 0.f};
-  for (int b = threadIdx.x >> 4; b < s.B; b += kLossBlock / 16) {
-    const int64_t r = (int64_t)m * a.Bp + b;
-    float z[2], x[2], ndz[2];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      z[e] = on[e] ? a.Z[r * a.C + c0 + e] + bz[e] : -INFINITY;
-      ndz[e] = on[e] ? -(a.dZ[r * a.C + c0 + e] + dbz[e]) : 0.f;
-      x[e] = expm1f(ndz[e]);
-    }
-    const float zr[2] = {z[0] + ndz[0], z[1] + ndz[1]};       // logits at the reference point (-inf for an absent class)
-    float nabs = fmaxf(fabsf(ndz[0]), fabsf(ndz[1]));        // (an absent class contributes 0)
-#pragma unroll
-    for (int o = 1; o < 16; o <<= 1) nabs = fmaxf(nabs, __shfl_xor(nabs, o, 64));
-    const bool far = !(nabs < 0.5f);             // (also taken by a NaN, which then shows in the result)
-    const int label = yv[a.grow[r]];
-    float zmax = fmaxf(z[0], z[1]);
-#pragma unroll
-    for (int o = 1; o < 16; o <<= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 64));
-#pragma unroll
-    for (int e = 0; e < 2; ++e) z[e] = on[e] ? expf(z[e] - zmax) : 0.f;
-    const float den = group16_sum(z[0] + z[1]);
-    z[0] = z[0] / den; z[1] = z[1] / den;
-    const float S = group16_sum(fmaf(z[0], x[0], z[1] * x[1]));
-    // the direct form: Pref = softmax of the reference logits z - dz, shifted by their maximum
-    float rmax = fmaxf(zr[0], zr[1]);
-#pragma unroll
-    for (int o = 1; o < 16; o <<= 1) rmax = fmaxf(rmax, __shfl_xor(rmax, o, 64));
-    const float er[2] = {on[0] ? expf(zr[0] - rmax) : 0.f, on[1] ? expf(zr[1] - rmax) : 0.f};
-    const float rden = group16_sum(er[0] + er[1]);
-    // (row, class) tensors: a row's classes are consecutive, written two at a time (an absent odd
-    // class is a zero in the padding)
-    uint32_t ph = 0, pl = 0, pd = 0, pr = 0;
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      if (on[e]) {
-        const int c = c0 + e;
-        const float gl = (z[e] - (c == label ? 1.f : 0.f)) * invB;
-        const float dg = (far ? z[e] - er[e] / rden : z[e] * (S - x[e]) / (1.0f + S)) * invB;
-        const bf16_t hi = f2bf(gl), lo = f2bf(gl - bf2f(hi)), bd = f2bf(dg), br = f2bf(gl - dg);
-        ph |= (uint32_t)hi << (16 * e); pl |= (uint32_t)lo << (16 * e); pd |= (uint32_t)bd << (16 * e); pr |= (uint32_t)br << (16 * e);
-        sumG[e] += gl;
-        sumD[e] += dg;
-      }
-    }
-    if (on[0]) {
-      const int64_t o = tm(r, 0, a.ktg) + c0;          // classes 0..31 lie in the row's first chunk
-      *reinterpret_cast<uint32_t *>(a.Gh + o) = ph; *reinterpret_cast<uint32_t *>(a.Gl + o) = pl;
-      *reinterpret_cast<uint32_t *>(a.dG + o) = pd;
-      if (a.Gref) *reinterpret_cast<uint32_t *>(a.Gref + o) = pr;
-    }
-  }
-  // bias gradient of the last layer, its innovation and that innovation's part of the left-hand
-  // side: sums over the rows in a fixed order (a thread's rows, the wavefront's four row groups,
-  // then the wavefronts)
-#pragma unroll
-  for (int e = 0; e < 2; ++e) {
-    sumG[e] += __shfl_xor(sumG[e], 16, 64); sumG[e] += __shfl_xor(sumG[e], 32, 64);
-    sumD[e] += __shfl_xor(sumD[e], 16, 64); sumD[e] += __shfl_xor(sumD[e], 32, 64);
-  }
-  if (lane < 16) { part[w][cp][0] = sumG[0]; part[w][cp][1] = sumG[1]; part[w][cp][2] = sumD[0]; part[w][cp][3] = sumD[1]; }
-  __syncthreads();
-  if (w == 0) {
-    float sq = 0.f;
-    if (lane < a.C) {
-      const int c = lane;
-      float gsum = 0.f, iv = 0.f;
-#pragma unroll
-      for (int ww = 0; ww < kLossBlock / 64; ++ww) { gsum += part[ww][c >> 1][c & 1]; iv += part[ww][c >> 1][2 + (c & 1)]; }
-      put_fresh_grad(s, m, a.offb + c, gsum);
-      if (s.rule == CADA_RULE_CADA1) {
-        fresh_innov(s, m)[a.offb + c] = f2bf(iv);
-        iv -= bf2f(stored_innov(s, m)[a.offb + c]);
-      }
-      sq = iv * iv;
-    }
-    const float tot = wave_sum(sq);
-    if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + a.lhs_slot] = tot;
-  }
-}
-
 // Hidden-layer bias gradient and its innovation from the per-tile partial sums of k_mm5<EPI_DA>.
 // grid (ceil(d/256), M)
 __global__ __launch_bounds__(kBlock) void k_bias_finish(const DevState s, const float *dbpart, const float *ddbpart, int RT, int d,
@@ -1260,7 +1277,8 @@ template <int EPI, int NA, int NB, bool HAS_D> hipError_t skinny_allow_lds() {
 }
 template <int EPI, int NA, int NB, bool HAS_D> int launch_skinny_as(Ctx *c, const Mm5Args &g) {
   const int nw = skinny_waves(EPI, g.K);
-  hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((g.M + 31) / 32, g.workers), dim3(64 * nw), skinny_lds_bytes(EPI, nw), c->stream, g);
+  const unsigned extra = (EPI == EPI_DW && g.lastb != nullptr) ? 1u : 0u;      // (the workgroup that finishes the last layer's bias gradient)
+  hipLaunchKernelGGL((k_skinny<EPI, NA, NB, HAS_D>), dim3((unsigned)((g.M + 31) / 32) + extra, g.workers), dim3(64 * nw), skinny_lds_bytes(EPI, nw), c->stream, g);
   return CADA_OK;
 }
 // Returns CADA_OK after enqueueing the launch, CADA_EUNSUPPORTED (and launches nothing) when the
@@ -1268,7 +1286,7 @@ template <int EPI, int NA, int NB, bool HAS_D> int launch_skinny_as(Ctx *c, cons
 template <int EPI> int launch_mm5(Ctx *c, Mm5Args &g, int workers) {
   g.workers = workers;
   const bool has_d = g.a_d >= 0;
-  if constexpr (EPI == EPI_STORE2 || EPI == EPI_DW) {
+  if constexpr (EPI == EPI_STORE2 || EPI == EPI_DW || EPI == EPI_LOSS) {
     if (g.N <= 32) {            // at most 32 output columns (the last layer)
       for (int i = 1; i < g.A.n; ++i)
         if (g.A.kt[i] != g.A.kt[0]) { set_error("internal: A tensors with different chunk counts"); return CADA_EUNSUPPORTED; }
@@ -1286,6 +1304,10 @@ template <int EPI> int launch_mm5(Ctx *c, Mm5Args &g, int workers) {
       }
     }
   }
+  if constexpr (EPI == EPI_LOSS) {
+    set_error("internal: the loss epilogue serves at most 32 classes");
+    return CADA_EUNSUPPORTED;
+  } else {
   // every tensor must hold the chunks the tile steps walk through: the contraction indices along a row
   // tile, or (weight gradient: units are output rows, the steps walk down the worker's rows) whole
   // 128-unit tiles and the worker's padded rows
@@ -1307,6 +1329,7 @@ template <int EPI> int launch_mm5(Ctx *c, Mm5Args &g, int workers) {
   }
   set_error("internal: no MFMA kernel variant for %d + %d tensors", g.A.n, g.B.n);
   return CADA_EUNSUPPORTED;
+  }
 }
 
 Mm5Args blank(const DevState &s, const MlpPlan &P) {
@@ -1332,6 +1355,8 @@ int mlp_init_state(Ctx *c, const float *) {
   if (e == hipSuccess) e = mm5_allow_lds<EPI_DA, 4, 3, true>();
   if (e == hipSuccess) e = skinny_allow_lds<EPI_STORE2, 2, 3, false>();
   if (e == hipSuccess) e = skinny_allow_lds<EPI_STORE2, 4, 3, true>();
+  if (e == hipSuccess) e = skinny_allow_lds<EPI_LOSS, 2, 3, false>();
+  if (e == hipSuccess) e = skinny_allow_lds<EPI_LOSS, 4, 3, true>();
   if (e == hipSuccess) e = skinny_allow_lds<EPI_DW, 2, 3, false>();
   if (e == hipSuccess) e = skinny_allow_lds<EPI_DW, 3, 4, true>();
   if (e != hipSuccess) { set_error("hipFuncSetAttribute(LDS size) failed: %s", hipGetErrorString(e)); return CADA_EHIP; }
@@ -1344,7 +1369,8 @@ int mlp_init_state(Ctx *c, const float *) {
 
 // Gathers the minibatch rows, prepares the bf16 weights and runs the forward contractions:
 // leaves the activations of every layer and the logits (without bias) of the last one.
-static int mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx) {
+// with_loss: the last layer's launch also evaluates the loss (training step); else it leaves the logits (evaluation).
+static int mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx, bool with_loss) {
   hipStream_t st = c->stream;
   const int L = P.L, M = P.M, B = P.B, Bp = P.Bp;
   const bool per_worker = (P.rule == CADA_RULE_CADA2);
@@ -1400,6 +1426,11 @@ static int mlp_forward(Ctx *c, MlpPlan &P, const DevState &s, const int32_t *idx
       g.o_h = P.Ah[l]; g.o_l = P.Al[l]; g.o_d = P.dA[l]; g.o_r = P.Aref[l];
       g.maskbits = P.maskbits[l];
       if (const int rc = launch_mm5<EPI_FWD_HIDDEN>(c, g, M)) return rc;
+    } else if (with_loss) {
+      g.offb = P.offb[L - 1]; g.kto = P.kta[L];
+      g.o_h = P.Gh[L]; g.o_l = P.Gl[L]; g.o_d = P.dG[L]; g.o_r = P.Gref[L];     // (Gref: null for a single-layer network)
+      g.grow = P.grow; g.lastb = P.lastb; g.nrb = Bp / 32;
+      if (const int rc = launch_mm5<EPI_LOSS>(c, g, M)) return rc;
     } else {
       g.c1 = P.ZL; g.c2 = P.dZL;
       if (const int rc = launch_mm5<EPI_STORE2>(c, g, M)) return rc;
@@ -1418,15 +1449,7 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
   const int64_t dwn_stride = per_worker ? P.wn_total : 0;
 
   prof_mark(c);
-  if (const int rc = mlp_forward(c, P, s, idx)) return rc;
-  {
-    LossArgs la;
-    la.s = s; la.Z = P.ZL; la.dZ = P.dZL;
-    la.Gh = P.Gh[L]; la.Gl = P.Gl[L]; la.dG = P.dG[L]; la.Gref = P.Gref[L];
-    la.grow = P.grow; la.offb = P.offb[L - 1]; la.C = P.d[L]; la.Bp = Bp; la.ktg = P.kta[L];
-    la.lhs_slot = P.lhs_b_slot[L - 1];
-    hipLaunchKernelGGL(k_loss, dim3(M), dim3(kLossBlock), 0, st, la);
-  }
+  if (const int rc = mlp_forward(c, P, s, idx, true)) return rc;
 
   // ---- backward
   for (int l = L; l >= 1; --l) {
@@ -1451,6 +1474,9 @@ int mlp_gradients(Ctx *c, const int32_t *idx) {
         g.b_h = 0; g.b_l = 1; g.b_x = 2; g.b_d = 3;
       }
       g.offW = P.offW[l - 1]; g.lhs_slot0 = P.lhs_w_slot[l - 1];
+      if (l == L) {     // the last layer's launch also finishes its bias gradient from the forward launch's row-block sums
+        g.lastb = P.lastb; g.nrb = Bp / 32; g.offb = P.offb[L - 1]; g.lhs_slot_b = P.lhs_b_slot[L - 1];
+      }
       if (const int rc = launch_mm5<EPI_DW>(c, g, M)) return rc;
     }
     if (l >= 2) {   // gradient w.r.t. the activations of layer l-1, masks, bias partials
@@ -1559,7 +1585,7 @@ int mlp_eval(Ctx *c, double *out) {
   const unsigned nb = (unsigned)(((int64_t)P.M * P.B + 255) / 256);
   for (int ch = 0; ch < chunks; ++ch) {
     hipLaunchKernelGGL(k_eval_idx, dim3(nb), dim3(256), 0, st, s, c->eval_idx, ch);
-    if (const int rc = mlp_forward(c, P, s, c->eval_idx)) return rc;
+    if (const int rc = mlp_forward(c, P, s, c->eval_idx, false)) return rc;
     hipLaunchKernelGGL(k_eval_chunk, dim3((unsigned)P.M), dim3(kBlock), 0, st, s, P.ZL, P.grow, P.offb[P.L - 1], P.d[P.L], P.Bp, ch, c->eval_acc);
   }
   hipLaunchKernelGGL(k_eval_means, dim3((unsigned)((P.M + 63) / 64)), dim3(64), 0, st, s, c->eval_acc);
