@@ -27,6 +27,12 @@ def _case(cfg):
     # more tiles than CUs in every contraction shape: workgroups work through several tiles, the
     # last of them overhanging (1100 = 8 x 128 + 76 columns, 200 = 6 x 32 + 8 contraction indices)
     configs.CFG5.scaled(name="mlp3_many_tiles", layer_dims=(200, 1100, 136, 10), M=40, N_m=200, B=128, K=4, D=8),
+    # the loss in the last layer's epilogue at the ends of its class range (32 is the most the path serves, an odd
+    # count leaves half a class pair empty) and with a last block of rows that is nearly empty (B = 33)
+    configs.CFG4.scaled(name="mlp2_32_classes", layer_dims=(64, 48, 32), M=3, N_m=200, B=33, K=4, D=8),
+    configs.CFG4.scaled(name="mlp2_2_classes", layer_dims=(64, 48, 2), M=3, N_m=200, B=40, K=4, D=8),
+    configs.CFG4.scaled(name="softmax_3_classes", layer_dims=(50, 3), M=3, N_m=200, B=96, K=4, D=8),
+    configs.CFG5.scaled(name="softmax_31_classes_cada1", layer_dims=(50, 31), M=3, N_m=200, B=65, K=4, D=8),
 ], ids=lambda c: c.name)
 def test_first_step_gradients_match_oracle(cfg):
     """Step 0: every worker uploads, so the stored gradients are the fresh gradients at
@@ -65,6 +71,7 @@ def test_first_step_gradients_match_oracle(cfg):
     configs.CFG5.scaled(name="mlp3_ragged", layer_dims=(200, 136, 72, 7), M=4, N_m=300, B=130, K=30, D=8, c=2.0),
     configs.CFG4.scaled(name="mlp2_cada1", layer_dims=(150, 133, 10), M=5, N_m=300, B=70, K=50, D=8, c=20.0, rule=configs.RULE_CADA1),
     configs.CFG5.scaled(name="mlp3_cada2", layer_dims=(200, 136, 72, 7), M=4, N_m=300, B=130, K=30, D=8, c=2.0, rule=configs.RULE_CADA2),
+    configs.CFG5.scaled(name="mlp2_32_classes_cada1", layer_dims=(64, 48, 32), M=4, N_m=200, B=33, K=30, D=8, c=5.0),
 ], ids=lambda c: c.name)
 def test_reduced_protocol(cfg):
     prob, dev, sched = _case(cfg)
