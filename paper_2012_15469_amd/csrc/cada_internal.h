@@ -73,13 +73,17 @@ struct DevState {
 // second gradient: their reference point is the iterate itself, so every difference the
 // gradient kernels carry is exactly zero.
 struct RefPtr { const float *hi, *lo; };
-__device__ __forceinline__ RefPtr theta_ref(const DevState &s, int m, int64_t k) {
+// (for a caller that already holds the worker's delay tau_m^k)
+__device__ __forceinline__ RefPtr theta_ref_at(const DevState &s, int32_t tau_m, int64_t k) {
   if (s.rule == CADA_RULE_CADA1) return RefPtr{s.snap, s.snap_lo};
   if (s.rule != CADA_RULE_CADA2) return RefPtr{s.theta, s.theta_lo};
-  int64_t j = k - (int64_t)min(s.tau[m], s.D);   // tau <= D unless a replay kept m silent longer
+  int64_t j = k - (int64_t)min(tau_m, s.D);      // tau <= D unless a replay kept m silent longer
   int64_t slot = j % s.R;
   if (slot < 0) slot += s.R;
   return RefPtr{s.hist + slot * s.ps, s.hist_lo + slot * s.ps};
+}
+__device__ __forceinline__ RefPtr theta_ref(const DevState &s, int m, int64_t k) {
+  return theta_ref_at(s, s.rule == CADA_RULE_CADA2 ? s.tau[m] : 0, k);
 }
 
 // Stepsize of iteration k (constant, or the decaying 2/(mu(k+K0)) of Theorem 2).

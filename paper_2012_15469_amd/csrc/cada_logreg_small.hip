@@ -60,7 +60,8 @@ __device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target
     __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     uint32_t spins = 0;
     // (difference compared as signed so that the counter may wrap)
-    while (!dead && (int32_t)(__hip_atomic_load(a.bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+    // (relaxed polls: the fence below is the acquire, once, instead of a cache invalidation per poll)
+    while (!dead && (int32_t)(__hip_atomic_load(a.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
       if (++spins > a.spin_limit) { dead = true; atomicOr(a.s.err, 2u); break; }
       __builtin_amdgcn_s_sleep(2);
     }
@@ -93,6 +94,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   __shared__ float red[4];
   __shared__ double redd[kBlock];
   __shared__ float bcast[2];
+  __shared__ float ring_s[CADA_MAX_DMAX];      // the squared steps, kept up to date by every workgroup for itself
 
   const int m = blockIdx.x, nb = gridDim.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -100,17 +102,23 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   const float invB = 1.0f / (float)B;
   bool dead = false;
   uint32_t bar_target = a.bar_base;
+  // What only this workgroup changes during the launch -- its worker's delay and buffer selector -- and what every
+  // workgroup can keep up to date by itself -- the ring of squared steps -- is read from memory once: a step is a
+  // chain of dependent memory round trips, and each one taken off it is a microsecond.
+  int32_t tau_m = s.tau[m];
+  int cur = s.sel[m];
+  const int64_t base = s.row_off[m], n_m = s.row_off[m + 1] - base;
+  for (int j = tid; j < s.d_max; j += kBlock) ring_s[j] = s.ring[j];
 
   for (int64_t step = 0; step < a.n_steps; ++step) {
     const int64_t k = s.k + step;
     // ------------------------------------------------------------ phase A
-    const RefPtr ref = theta_ref(s, m, k);
+    const RefPtr ref = theta_ref_at(s, tau_m, k);
     for (int j = tid; j < p; j += kBlock) {
       th_s[j] = s.theta[j];
       d_s[j] = (s.theta[j] - ref.hi[j]) + (s.theta_lo[j] - ref.lo[j]);
     }
     const int32_t *idx = a.idx + (step * M + m) * (int64_t)B;
-    const int64_t base = s.row_off[m], n_m = s.row_off[m + 1] - base;
     for (int b = tid; b < B; b += kBlock) {
       int64_t r = idx[b];
       if (r < 0 || r >= n_m) { atomicOr(s.err, 1u); r = r < 0 ? 0 : n_m - 1; }
@@ -195,7 +203,6 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     }
     __syncthreads();
     // columns over the threads: fresh gradient, innovation, the rule's left-hand side
-    const int cur = s.sel[m];
     float *gf = s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p;
     const float *gs = s.gbuf + (int64_t)cur * mp + (int64_t)m * s.p;
     float sq = 0.f;
@@ -265,9 +272,10 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
       const int last = k > 0 ? (int)((k - 1) % s.d_max) : -1;
       const float newest = (float)redd[0];
       double sum = 0.0;
-      for (int j = 0; j < s.d_max; ++j) sum += (double)(j == last ? newest : s.ring[j]);
+      if (last >= 0) ring_s[last] = newest;
+      for (int j = 0; j < s.d_max; ++j) sum += (double)ring_s[j];
       const double rhs = (s.c / (double)s.d_max) * sum;
-      const int32_t tau = s.tau[m];
+      const int32_t tau = tau_m;
       const bool own = (s.rule == CADA_RULE_ALWAYS) || ((double)lhs > rhs) || (tau >= s.D);
       bool up = own;
       const uint8_t *replay = a.replay ? a.replay + step * M : nullptr;
@@ -291,8 +299,10 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
         if (s.rule == CADA_RULE_CADA2 && tau >= s.D) atomicOr(s.err, 8u);   // (a replay mask outlasting the retained iterates)
       }
       bcast[0] = newest;
+      bcast[1] = up ? 1.f : 0.f;
     }
     __syncthreads();
+    if (bcast[1] != 0.f) { tau_m = 1; cur ^= 1; } else tau_m += 1;
     bar_target += (uint32_t)nb;
     grid_barrier(a, bar_target, dead);
     // ------------------------------------------------------------ phase B
@@ -301,8 +311,13 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     const float alpha = stepsize(s, k);
     for (int64_t j = (int64_t)m * kBlock + tid; j < s.p; j += (int64_t)nb * kBlock) {
       float nab = 0.f;
+      // (both rows of every worker are asked for, beside its selector instead of behind it: one round trip, not two)
 #pragma unroll 8
-      for (int mm = 0; mm < M; ++mm) nab += s.gbuf[(int64_t)s.sel[mm] * mp + (int64_t)mm * s.p + j];
+      for (int mm = 0; mm < M; ++mm) {
+        const int sl = s.sel[mm];
+        const float g0 = s.gbuf[(int64_t)mm * s.p + j], g1 = s.gbuf[mp + (int64_t)mm * s.p + j];
+        nab += sl ? g1 : g0;
+      }
       nab = nab / (float)M;
       float hh = s.h[j], vh = s.vhat[j], vv = vh, stp;
       if (s.server_sgd) {
