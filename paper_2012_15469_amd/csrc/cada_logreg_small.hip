@@ -2,14 +2,20 @@
 // step is bound by launch and dependency latency rather than by memory (tens of workers, a few
 // hundred coordinates): four dependent launches per step cost 35-40 us, the arithmetic well
 // under one.  One workgroup per worker, launched cooperatively; n_steps iterations per launch
-// with two grid-wide barriers each:
+// with ONE grid-wide barrier each:
 //   phase A (workgroup m = worker m): both minibatch gradients in the difference form of
 //     cada_logreg.hip, the rule's left-hand side, the right-hand side from the ring, the
 //     decision, tau, the stored/fresh pointer swap, the trace           [S1-S4 of the step]
 //   -- barrier --
-//   phase B (coordinates dealt to the workgroups): aggregate of the stored gradients, the server
-//     update, the reference-point history, the squared step             [S5-S7]
-//   -- barrier --
+//   phase B (EVERY workgroup, all coordinates): aggregate of the stored gradients, the server
+//     update, the squared step                                          [S5-S7]
+// Every workgroup keeps the server's vectors (iterate, moments, snapshot) in its LDS and applies the same update
+// to them, in the same order, so all copies stay bit for bit equal and the next phase A needs neither a second
+// barrier nor the iterate from memory; workgroup (j / 256) mod M writes coordinate j's results to memory for
+// the world outside and for the reference points theta^{k - tau}, tau >= 1, which are read a barrier later at
+// the earliest.  What a fast workgroup writes in phase A of step k + 1 while a slow one is still in phase B of
+// step k never is what the slow one reads: the fresh gradient goes to the row that is not the stored one, and
+// the decisions of step k are published in slot k mod 2 of an array of their own.
 // A barrier is an agent-scope counter in the workspace; arrivals release (write back) and
 // departures acquire (invalidate) the XCD-local caches.  Every wait is bounded: a wait that
 // exceeds the bound sets bit 1 of the error flags and the workgroup stops waiting.
@@ -70,8 +76,8 @@ __device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // acquire: drop stale cached lines
 }
 
-// grid = M workgroups of kBlock threads; dynamic LDS: theta, d (2 p floats), r, dr, row offsets
-// (B each) and the worker's whole minibatch (B p floats): the rows are fetched once, with every
+// grid = M workgroups of kBlock threads; dynamic LDS: the server's vectors and theta - theta_ref (7 p floats), r, dr,
+// row offsets (B each) and the worker's whole minibatch (B p floats): the rows are fetched once, with every
 // load independent of the others, and both passes over them run from LDS
 __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   extern __shared__ __align__(16) unsigned char small_smem[];
@@ -82,11 +88,13 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   }
   DevState s = a.s;
   const int p = (int)s.p, B = s.B, M = s.M;
-  float *th_s = reinterpret_cast<float *>(small_smem);     // [p] theta (hi part + lo part rounded once)
-  float *d_s = th_s + p;                                   // [p] theta - theta_ref
+  float *th_s = reinterpret_cast<float *>(small_smem);     // [p] theta, [p] theta_lo, [p] h, [p] vhat: this workgroup's copies
+  float *tl_s = th_s + p, *h_s = tl_s + p, *vh_s = h_s + p;
+  float *sn_s = vh_s + p, *snl_s = sn_s + p;               // [p] each: CADA1's snapshot
+  float *d_s = snl_s + p;                                  // [p] theta - theta_ref
   float *r_s = d_s + p;                                    // [B]
   float *dr_s = r_s + B;                                   // [B]
-  long long *row_s = reinterpret_cast<long long *>(dr_s + B + ((2 * p + 2 * B) & 1));   // [B], 8-byte aligned
+  long long *row_s = reinterpret_cast<long long *>(dr_s + B + ((7 * p + 2 * B) & 1));   // [B], 8-byte aligned
   const size_t x_off = ((size_t)(reinterpret_cast<unsigned char *>(row_s + B) - small_smem) + 15) & ~(size_t)15;
   float *x_s = reinterpret_cast<float *>(small_smem + x_off);        // [B][p] the minibatch, 16-byte aligned
   // rows and columns are moved four floats at a time when every row starts on a 16-byte boundary
@@ -109,14 +117,36 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   int cur = s.sel[m];
   const int64_t base = s.row_off[m], n_m = s.row_off[m + 1] - base;
   for (int j = tid; j < s.d_max; j += kBlock) ring_s[j] = s.ring[j];
+  for (int j = tid; j < p; j += kBlock) {
+    th_s[j] = s.theta[j]; tl_s[j] = s.theta_lo[j]; h_s[j] = s.h[j]; vh_s[j] = s.vhat[j];
+    if (s.rule == CADA_RULE_CADA1) { sn_s[j] = s.snap[j]; snl_s[j] = s.snap_lo[j]; }
+  }
+  int32_t *dec = reinterpret_cast<int32_t *>(a.bar + 64);     // [2][M] the selectors after the decisions of step k, slot k mod 2
+  // the squared step of the iteration before this launch: partial sums that the launch before (or cada_set_state) left
+  float newest_c = 0.f;
+  {
+    double acc = 0.0;
+    if (s.k > 0)
+      for (int i = tid; i < s.n_ring_part; i += kBlock) acc += (double)s.ring_part[i];
+    redd[tid] = acc;
+    __syncthreads();
+    for (int o = kBlock / 2; o > 0; o >>= 1) {
+      if (tid < o) redd[tid] += redd[tid + o];
+      __syncthreads();
+    }
+    newest_c = (float)redd[0];
+  }
 
   for (int64_t step = 0; step < a.n_steps; ++step) {
     const int64_t k = s.k + step;
     // ------------------------------------------------------------ phase A
-    const RefPtr ref = theta_ref_at(s, tau_m, k);
-    for (int j = tid; j < p; j += kBlock) {
-      th_s[j] = s.theta[j];
-      d_s[j] = (s.theta[j] - ref.hi[j]) + (s.theta_lo[j] - ref.lo[j]);
+    if (s.rule == CADA_RULE_CADA2) {           // theta^{k - tau}: written a barrier ago at the latest (tau >= 1)
+      const RefPtr ref = theta_ref_at(s, tau_m, k);
+      for (int j = tid; j < p; j += kBlock) d_s[j] = (th_s[j] - ref.hi[j]) + (tl_s[j] - ref.lo[j]);
+    } else if (s.rule == CADA_RULE_CADA1) {
+      for (int j = tid; j < p; j += kBlock) d_s[j] = (th_s[j] - sn_s[j]) + (tl_s[j] - snl_s[j]);
+    } else {
+      for (int j = tid; j < p; j += kBlock) d_s[j] = 0.f;
     }
     const int32_t *idx = a.idx + (step * M + m) * (int64_t)B;
     for (int b = tid; b < B; b += kBlock) {
@@ -258,19 +288,10 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
       sq = fmaf(lhs_term, lhs_term, sq);
     }
     const float lhs = block_sum(sq, red);
-    // right-hand side: the squared step of iteration k-1 from the per-workgroup partial sums
-    double acc = 0.0;
-    if (k > 0)
-      for (int i = tid; i < s.n_ring_part; i += kBlock) acc += (double)s.ring_part[i];
-    redd[tid] = acc;
-    __syncthreads();
-    for (int o = kBlock / 2; o > 0; o >>= 1) {
-      if (tid < o) redd[tid] += redd[tid + o];
-      __syncthreads();
-    }
+    // right-hand side: the squared step of iteration k-1 is this workgroup's own sum of the step before
     if (tid == 0) {
       const int last = k > 0 ? (int)((k - 1) % s.d_max) : -1;
-      const float newest = (float)redd[0];
+      const float newest = newest_c;
       double sum = 0.0;
       if (last >= 0) ring_s[last] = newest;
       for (int j = 0; j < s.d_max; ++j) sum += (double)ring_s[j];
@@ -298,6 +319,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
         s.tau[m] = tau + 1;
         if (s.rule == CADA_RULE_CADA2 && tau >= s.D) atomicOr(s.err, 8u);   // (a replay mask outlasting the retained iterates)
       }
+      dec[(k & 1) * M + m] = up ? (cur ^ 1) : cur;
       bcast[0] = newest;
       bcast[1] = up ? 1.f : 0.f;
     }
@@ -306,20 +328,15 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     bar_target += (uint32_t)nb;
     grid_barrier(a, bar_target, dead);
     // ------------------------------------------------------------ phase B
-    if (m == 0 && tid == 0 && k > 0) s.ring[(k - 1) % s.d_max] = bcast[0];   // nobody reads this slot before the next barrier
+    if (m == 0 && tid == 0 && k > 0) s.ring[(k - 1) % s.d_max] = bcast[0];   // (for the world outside: every workgroup has its own copy)
     float sqs = 0.f;
     const float alpha = stepsize(s, k);
-    for (int64_t j = (int64_t)m * kBlock + tid; j < s.p; j += (int64_t)nb * kBlock) {
-      float nab = 0.f;
-      // (both rows of every worker are asked for, beside its selector instead of behind it: one round trip, not two)
-#pragma unroll 8
-      for (int mm = 0; mm < M; ++mm) {
-        const int sl = s.sel[mm];
-        const float g0 = s.gbuf[(int64_t)mm * s.p + j], g1 = s.gbuf[mp + (int64_t)mm * s.p + j];
-        nab += sl ? g1 : g0;
-      }
+    const int32_t *dk = dec + (k & 1) * M;
+    const bool snap_now = s.rule == CADA_RULE_CADA1 && (k + 1) % s.D == 0;
+    // one coordinate: this workgroup's copies of the server's vectors, and its share of the results in memory
+    auto update = [&](int j, float nab) __attribute__((always_inline)) {
       nab = nab / (float)M;
-      float hh = s.h[j], vh = s.vhat[j], vv = vh, stp;
+      float hh = h_s[j], vh = vh_s[j], vv = vh, stp;
       if (s.server_sgd) {
         stp = alpha * nab;
       } else {
@@ -329,26 +346,48 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
         stp = alpha * hh / sqrtf(s.eps + vh);
       }
       // (theta, theta_lo) - step in two-float arithmetic (TwoSum, then renormalise)
-      const float t0 = s.theta[j], ms = -stp;
+      const float t0 = th_s[j], ms = -stp;
       const float sum = t0 + ms;
       const float bb = sum - t0;
       const float er = (t0 - (sum - bb)) + (ms - bb);
-      const float lo = s.theta_lo[j] + er;
+      const float lo = tl_s[j] + er;
       const float th = sum + lo, tl = lo - (th - sum);
-      s.nabla[j] = nab; s.h[j] = hh; s.v[j] = vv; s.vhat[j] = vh; s.theta[j] = th; s.theta_lo[j] = tl;
-      if (s.rule == CADA_RULE_CADA2) {
-        s.hist[((k + 1) % s.R) * s.p + j] = th;
-        s.hist_lo[((k + 1) % s.R) * s.p + j] = tl;
-      } else if (s.rule == CADA_RULE_CADA1 && (k + 1) % s.D == 0) {
-        s.snap[j] = th;
-        s.snap_lo[j] = tl;
+      h_s[j] = hh; vh_s[j] = vh; th_s[j] = th; tl_s[j] = tl;
+      if (snap_now) { sn_s[j] = th; snl_s[j] = tl; }
+      if ((j / kBlock) % nb == m) {
+        s.nabla[j] = nab; s.h[j] = hh; s.v[j] = vv; s.vhat[j] = vh; s.theta[j] = th; s.theta_lo[j] = tl;
+        if (s.rule == CADA_RULE_CADA2) {
+          s.hist[((k + 1) % s.R) * s.p + j] = th;
+          s.hist_lo[((k + 1) % s.R) * s.p + j] = tl;
+        } else if (snap_now) {
+          s.snap[j] = th;
+          s.snap_lo[j] = tl;
+        }
       }
       sqs = fmaf(stp, stp, sqs);
+    };
+    // The aggregate: every load of a thread is independent of the others (the selectors are one cheap read for all),
+    // four coordinates per 16-byte load where the rows allow it; the sum runs over the workers in their order.
+    if (v4) {
+      for (int j = tid * 4; j < p; j += 4 * kBlock) {
+        float4 nab = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+        for (int mm = 0; mm < M; ++mm) {
+          const float4 g = *reinterpret_cast<const float4 *>(s.gbuf + (int64_t)dk[mm] * mp + (int64_t)mm * s.p + j);
+          nab.x += g.x; nab.y += g.y; nab.z += g.z; nab.w += g.w;
+        }
+        update(j, nab.x); update(j + 1, nab.y); update(j + 2, nab.z); update(j + 3, nab.w);
+      }
+    } else {
+      for (int j = tid; j < p; j += kBlock) {
+        float nab = 0.f;
+#pragma unroll 8
+        for (int mm = 0; mm < M; ++mm) nab += s.gbuf[(int64_t)dk[mm] * mp + (int64_t)mm * s.p + j];
+        update(j, nab);
+      }
     }
-    const float part = block_sum(sqs, red);
-    if (tid == 0) s.ring_part[m] = part;
-    bar_target += (uint32_t)nb;
-    grid_barrier(a, bar_target, dead);
+    newest_c = block_sum(sqs, red);              // (ends with a workgroup barrier: the next phase A sees the new copies)
+    if (tid == 0) s.ring_part[m] = m == 0 ? newest_c : 0.f;     // what a later launch, or reading the state out, adds up
   }
 }
 
@@ -367,8 +406,8 @@ bool small_plan(Ctx *c, const cada_config *cfg) {
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return false;
   if (M > cus) return false;
-  c->small_lds = (size_t)(2 * p + 2 * B + 1) * sizeof(float) + (size_t)B * sizeof(long long) + 16 + (size_t)B * p * sizeof(float);
-  if (c->small_lds > 150 * 1024) return false;      // the minibatch of a worker must fit in LDS
+  c->small_lds = (size_t)(7 * p + 2 * B + 1) * sizeof(float) + (size_t)B * sizeof(long long) + 16 + (size_t)B * p * sizeof(float);
+  if (c->small_lds > 150 * 1024) return false;      // the minibatch of a worker and the server's vectors must fit in LDS
   if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_small), hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->small_lds) != hipSuccess) {
     (void)hipGetLastError();
     return false;
@@ -437,7 +476,7 @@ int small_steps_replicas(Ctx *const *cs, int n, const int32_t *const *idx, const
     return CADA_EHIP;
   }
   // (the barrier counters advance only with a launch that was accepted)
-  for (int r = 0; r < n; ++r) cs[r]->small_seq += (uint32_t)(2 * n_steps * cs[r]->s.M);
+  for (int r = 0; r < n; ++r) cs[r]->small_seq += (uint32_t)(n_steps * cs[r]->s.M);
   return CADA_OK;
 }
 
@@ -453,7 +492,7 @@ int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_ste
     set_error("multi-step logistic launch failed: %s", hipGetErrorString(e));
     return CADA_EHIP;
   }
-  c->small_seq += (uint32_t)(2 * n_steps * c->s.M);
+  c->small_seq += (uint32_t)(n_steps * c->s.M);
   return CADA_OK;
 }
 
