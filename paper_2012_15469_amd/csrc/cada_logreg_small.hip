@@ -58,12 +58,15 @@ static_assert(sizeof(SmallLaunch) <= 4096, "kernel arguments");
 
 __device__ __forceinline__ float sigmoid_s(float a) { return 1.0f / (1.0f + expf(-a)); }
 
-// All workgroups arrive; `target` is the counter value that means everyone has.
-__device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target, bool &dead) {
+// All workgroups arrive; `target` is the counter value that means everyone has.  `while_waiting` runs between this
+// workgroup's arrival and its wait: loads issued there are under way while the others arrive.
+template <typename F>
+__device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target, bool &dead, F while_waiting) {
   __threadfence();                      // release: this workgroup's writes are visible device-wide
   __syncthreads();
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  while_waiting();
   if (threadIdx.x == 0) {
-    __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     uint32_t spins = 0;
     // (difference compared as signed so that the counter may wrap)
     // (relaxed polls: the fence below is the acquire, once, instead of a cache invalidation per poll)
@@ -95,7 +98,8 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   float *r_s = d_s + p;                                    // [B]
   float *dr_s = r_s + B;                                   // [B]
   long long *row_s = reinterpret_cast<long long *>(dr_s + B + ((7 * p + 2 * B) & 1));   // [B], 8-byte aligned
-  const size_t x_off = ((size_t)(reinterpret_cast<unsigned char *>(row_s + B) - small_smem) + 15) & ~(size_t)15;
+  long long *row_n = row_s + B;                            // [B] rows of the NEXT step's minibatch (row numbers)
+  const size_t x_off = ((size_t)(reinterpret_cast<unsigned char *>(row_n + B) - small_smem) + 15) & ~(size_t)15;
   float *x_s = reinterpret_cast<float *>(small_smem + x_off);        // [B][p] the minibatch, 16-byte aligned
   // rows and columns are moved four floats at a time when every row starts on a 16-byte boundary
   const bool v4 = (p & 3) == 0 && (reinterpret_cast<uintptr_t>(s.X) & 15) == 0;
@@ -137,8 +141,13 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     newest_c = (float)redd[0];
   }
 
+  // The next step's rows and labels are asked for while this workgroup waits at the barrier (LDS-direct loads: no
+  // registers, and the buffers they land in are free by then), so only the first step of a launch fetches its own.
+  bool have_rows = false;
+  constexpr int NW = kBlock / kWave, RB = 8;
   for (int64_t step = 0; step < a.n_steps; ++step) {
     const int64_t k = s.k + step;
+    const bool more = step + 1 < a.n_steps;
     // ------------------------------------------------------------ phase A
     if (s.rule == CADA_RULE_CADA2) {           // theta^{k - tau}: written a barrier ago at the latest (tau >= 1)
       const RefPtr ref = theta_ref_at(s, tau_m, k);
@@ -150,14 +159,21 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     }
     const int32_t *idx = a.idx + (step * M + m) * (int64_t)B;
     for (int b = tid; b < B; b += kBlock) {
-      int64_t r = idx[b];
-      if (r < 0 || r >= n_m) { atomicOr(s.err, 1u); r = r < 0 ? 0 : n_m - 1; }
-      row_s[b] = (base + r) * s.p;
+      if (!have_rows) {
+        int64_t r = idx[b];
+        if (r < 0 || r >= n_m) { atomicOr(s.err, 1u); r = r < 0 ? 0 : n_m - 1; }
+        row_s[b] = (base + r) * s.p;
+      }
+      if (more) {
+        int64_t r = idx[(int64_t)M * B + b];
+        if (r < 0 || r >= n_m) { atomicOr(s.err, 1u); r = r < 0 ? 0 : n_m - 1; }
+        row_n[b] = base + r;
+      }
     }
     __syncthreads();
     // the rows: wavefront w fetches rows w, w+4, ..., eight rows at a time so that eight loads per
     // lane are in flight (no division per element; every load independent of the others)
-    constexpr int NW = kBlock / kWave, RB = 8;
+    if (!have_rows) {
     for (int b0 = w; b0 < B; b0 += NW * RB) {
       const float *src[RB];
 #pragma unroll
@@ -186,6 +202,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     }
     if (tid < B) r_s[tid] = static_cast<const float *>(s.y)[row_s[tid] / s.p];     // the labels, for now
     for (int b = kBlock + tid; b < B; b += kBlock) r_s[b] = static_cast<const float *>(s.y)[row_s[b] / s.p];
+    }
     __syncthreads();
     // rows over the wavefronts, four at a time (their eight reductions overlap): z = x.theta,
     // dz = x.d, then the residual and its difference
@@ -326,7 +343,26 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     __syncthreads();
     if (bcast[1] != 0.f) { tau_m = 1; cur ^= 1; } else tau_m += 1;
     bar_target += (uint32_t)nb;
-    grid_barrier(a, bar_target, dead);
+    grid_barrier(a, bar_target, dead, [&]() __attribute__((always_inline)) {
+      if (!more) return;
+      // (x_s and r_s were last read by the gradient pass, several workgroup barriers ago)
+      for (int b = w; b < B; b += NW) {
+        const float *src = s.X + row_n[b] * s.p;
+        float *dst = x_s + (size_t)b * p;
+        if (v4) {
+          for (int j0 = 0; j0 < p; j0 += 4 * kWave)
+            if (j0 + lane * 4 < p) __builtin_amdgcn_global_load_lds(src + j0 + lane * 4, (__attribute__((address_space(3))) void *)(dst + j0), 16, 0, 0);
+        } else {
+          for (int j0 = 0; j0 < p; j0 += kWave)
+            if (j0 + lane < p) __builtin_amdgcn_global_load_lds(src + j0 + lane, (__attribute__((address_space(3))) void *)(dst + j0), 4, 0, 0);
+        }
+      }
+      for (int b0 = w * kWave; b0 < B; b0 += NW * kWave)
+        if (b0 + lane < B)
+          __builtin_amdgcn_global_load_lds(static_cast<const float *>(s.y) + row_n[b0 + lane],
+                                           (__attribute__((address_space(3))) void *)(r_s + b0), 4, 0, 0);
+    });
+    have_rows = more;
     // ------------------------------------------------------------ phase B
     if (m == 0 && tid == 0 && k > 0) s.ring[(k - 1) % s.d_max] = bcast[0];   // (for the world outside: every workgroup has its own copy)
     float sqs = 0.f;
@@ -406,7 +442,7 @@ bool small_plan(Ctx *c, const cada_config *cfg) {
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return false;
   if (M > cus) return false;
-  c->small_lds = (size_t)(7 * p + 2 * B + 1) * sizeof(float) + (size_t)B * sizeof(long long) + 16 + (size_t)B * p * sizeof(float);
+  c->small_lds = (size_t)(7 * p + 2 * B + 1) * sizeof(float) + (size_t)2 * B * sizeof(long long) + 16 + (size_t)B * p * sizeof(float);
   if (c->small_lds > 150 * 1024) return false;      // the minibatch of a worker and the server's vectors must fit in LDS
   if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_small), hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->small_lds) != hipSuccess) {
     (void)hipGetLastError();
