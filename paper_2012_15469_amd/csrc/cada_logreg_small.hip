@@ -58,12 +58,25 @@ static_assert(sizeof(SmallLaunch) <= 4096, "kernel arguments");
 
 __device__ __forceinline__ float sigmoid_s(float a) { return 1.0f / (1.0f + expf(-a)); }
 
+// Workgroup barrier for data that is exchanged through LDS: it waits for this wavefront's LDS operations only, not, as
+// __syncthreads() does, for the acknowledgement of every global store issued before it (a microsecond each time).
+__device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// block_sum of cada_internal.h with that barrier
+__device__ __forceinline__ float block_sum_lds(float x, float *red /* [4] LDS */) {
+  x = wave_sum(x);
+  lds_sync();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  lds_sync();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 // All workgroups arrive; `target` is the counter value that means everyone has.  `while_waiting` runs between this
 // workgroup's arrival and its wait: loads issued there are under way while the others arrive.
 template <typename F>
 __device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target, bool &dead, F while_waiting) {
-  __threadfence();                      // release: this workgroup's writes are visible device-wide
-  __syncthreads();
+  __syncthreads();                      // every thread's stores have reached the L2 (the barrier waits for them) ...
+  // ... and the arrival releases at agent scope: it writes the L2's dirty lines back before the counter moves
   if (threadIdx.x == 0) __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
   while_waiting();
   if (threadIdx.x == 0) {
@@ -236,15 +249,16 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
       for (int o = 32; o > 0; o >>= 1)
 #pragma unroll
         for (int q = 0; q < 4; ++q) { z[q] += __shfl_xor(z[q], o, 64); dz[q] += __shfl_xor(dz[q], o, 64); }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int b = b0 + q * NW;
-        if (lane == 0 && b < B) {
+      {   // lane q takes row q of the four (every lane holds all eight sums): the exponentials of four rows side by side
+        const float zq = lane == 0 ? z[0] : lane == 1 ? z[1] : lane == 2 ? z[2] : z[3];
+        const float dq = lane == 0 ? dz[0] : lane == 1 ? dz[1] : lane == 2 ? dz[2] : dz[3];
+        const int b = b0 + lane * NW;
+        if (lane < 4 && b < B) {
           const float y = r_s[b];
-          const float aa = -y * z[q], bb = aa + y * dz[q];
+          const float aa = -y * zq, bb = aa + y * dq;
           const float sa = sigmoid_s(aa);
           r_s[b] = -y * sa * invB;
-          dr_s[b] = y * sa * sigmoid_s(-bb) * expm1f(y * dz[q]) * invB;
+          dr_s[b] = y * sa * sigmoid_s(-bb) * expm1f(y * dq) * invB;
         }
       }
     }
@@ -304,7 +318,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
       gf[j] = g;
       sq = fmaf(lhs_term, lhs_term, sq);
     }
-    const float lhs = block_sum(sq, red);
+    const float lhs = block_sum_lds(sq, red);
     // right-hand side: the squared step of iteration k-1 is this workgroup's own sum of the step before
     if (tid == 0) {
       const int last = k > 0 ? (int)((k - 1) % s.d_max) : -1;
@@ -340,7 +354,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
       bcast[0] = newest;
       bcast[1] = up ? 1.f : 0.f;
     }
-    __syncthreads();
+    lds_sync();
     if (bcast[1] != 0.f) { tau_m = 1; cur ^= 1; } else tau_m += 1;
     bar_target += (uint32_t)nb;
     grid_barrier(a, bar_target, dead, [&]() __attribute__((always_inline)) {
@@ -422,7 +436,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
         update(j, nab);
       }
     }
-    newest_c = block_sum(sqs, red);              // (ends with a workgroup barrier: the next phase A sees the new copies)
+    newest_c = block_sum_lds(sqs, red);          // (ends with a workgroup barrier: the next phase A sees the new copies)
     if (tid == 0) s.ring_part[m] = m == 0 ? newest_c : 0.f;     // what a later launch, or reading the state out, adds up
   }
 }
