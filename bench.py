@@ -112,7 +112,7 @@ def kernel_bytes_per_launch(cfg) -> float:
     return cfg.M * per_worker
 
 
-def measure(cfg, K: int, W: int, plain_launch: bool = False, bf16_store: bool = False):
+def measure(cfg, K: int, W: int, plain_launch: bool = False, bf16_store: bool = False, path: str = "auto"):
     """W warm-up steps, K timed steps (no events inside the loop), then K more steps with an event
     around every kernel phase.  Returns (record for the JSON line, problem, seconds of set-up).
     bf16_store: the MLP workloads with the stored gradients kept as bf16 (CADA_STORE_BF16)."""
@@ -135,7 +135,9 @@ def measure(cfg, K: int, W: int, plain_launch: bool = False, bf16_store: bool = 
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
-    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0, plain_launch=plain_launch,
+    paths = {"auto": binding.PATH_AUTO, "two_pass": binding.PATH_TWO_PASS, "single_pass": binding.PATH_SINGLE_PASS,
+             "whole_steps": binding.PATH_WHOLE_STEPS}
+    eng = Cada.from_config(cfg, X, y, theta0, trace_steps=0, plain_launch=plain_launch, path=paths[path],
                            gradient_store=binding.STORE_BF16 if bf16_store else binding.STORE_F32)
     # small logistic workloads run whole iterations inside one kernel: the K timed steps are one
     # cada_run call (one launch); everything else is one cada_step call per step
@@ -218,6 +220,8 @@ def main() -> int:
                          "launch per call (cada_run_replicas); value counts the worker-iterations of all of them")
     ap.add_argument("--bf16-gradient-store", action="store_true",
                     help="workloads 4-5 as the headline workload with the stored gradients kept as bf16 (CADA_STORE_BF16)")
+    ap.add_argument("--path", choices=["auto", "two_pass", "single_pass", "whole_steps"], default="auto",
+                    help="logistic workloads: the kernels of the headline workload (cada_config.path); auto = the library's choice")
     ap.add_argument("--plain-launch", action="store_true",
                     help="launch the single-pass kernel without the cooperative-launch API (rocprofv3 on this "
                          "image crashes at exit after tracing a cooperative dispatch); same grid, same kernel")
@@ -239,7 +243,7 @@ def main() -> int:
     if args.replicas > 1:
         return bench_replicas(args, cfg, dev)
     K, W = args.steps, args.warmup
-    rec, prob, _ = measure(cfg, K, W, args.plain_launch, bf16_store=args.bf16_gradient_store)
+    rec, prob, _ = measure(cfg, K, W, args.plain_launch, bf16_store=args.bf16_gradient_store, path=args.path)
     out = {"metric": "worker-iterations/sec (grads+CADA rule+AMSGrad)", "value": rec["value"], "unit": rec["unit"],
            "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": rec["ms_per_step"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": rec["dtype"], "data": "synthetic",

@@ -57,8 +57,9 @@ enum {
 };
 enum { CADA_MODEL_LOGREG = 0, CADA_MODEL_MLP = 1 };
 enum {
-  CADA_PATH_AUTO = 0,        /* single pass where it applies (p >= 8192, a multiple of 4), whole steps for tiny
-                                workloads (M B p <= 32768), two passes otherwise */
+  CADA_PATH_AUTO = 0,        /* single pass where it applies (p >= 8192, a multiple of 4), whole steps for small
+                                workloads (at most 64 workers of at most 64 rows whose minibatch and the server's
+                                vectors fit one workgroup's LDS), two passes otherwise */
   CADA_PATH_TWO_PASS = 1,    /* two streaming passes over the minibatch rows (any shape) */
   CADA_PATH_SINGLE_PASS = 2, /* one pass: the rows stay in registers/LDS between the two products */
   CADA_PATH_WHOLE_STEPS = 3  /* whole iterations in one launch, one workgroup per worker, whenever the shape allows it,

@@ -421,10 +421,17 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     if (v4) {
       for (int j = tid * 4; j < p; j += 4 * kBlock) {
         float4 nab = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 8
-        for (int mm = 0; mm < M; ++mm) {
-          const float4 g = *reinterpret_cast<const float4 *>(s.gbuf + (int64_t)dk[mm] * mp + (int64_t)mm * s.p + j);
-          nab.x += g.x; nab.y += g.y; nab.z += g.z; nab.w += g.w;
+        // (sixteen workers' rows asked for before the first is added: the sum is a chain of round trips otherwise)
+        for (int m0 = 0; m0 < M; m0 += 16) {
+          float4 g[16];
+#pragma unroll
+          for (int q = 0; q < 16; ++q) {
+            const int mm = min(m0 + q, M - 1);
+            g[q] = *reinterpret_cast<const float4 *>(s.gbuf + (int64_t)dk[mm] * mp + (int64_t)mm * s.p + j);
+          }
+#pragma unroll
+          for (int q = 0; q < 16; ++q)
+            if (m0 + q < M) { nab.x += g[q].x; nab.y += g[q].y; nab.z += g[q].z; nab.w += g[q].w; }
         }
         update(j, nab.x); update(j + 1, nab.y); update(j + 2, nab.z); update(j + 3, nab.w);
       }
@@ -447,10 +454,11 @@ bool small_plan(Ctx *c, const cada_config *cfg) {
   const int64_t p = cfg->p;
   const int B = cfg->B, M = cfg->M;
   if (p >= 8192) return false;
-  // Measured: 16 us per step against 36 us for M = 10, B = 10, p = 54, but 73 us against 39 us for
-  // M = 20, B = 32, p = 784 (20 workgroups cannot hide the latency of their dependent loads, and
-  // each barrier invalidates the XCD's L2): only the tiny problems take this path unless asked to.
-  if (cfg->path != CADA_PATH_WHOLE_STEPS && (int64_t)M * B * p > 32768) return false;
+  // Measured against the two-pass kernels (four launches, about 21 us at best): 9 us against 20 us for M = 10, B = 10,
+  // p = 54; 18 against 21 us for M = 20, B = 32, p = 784; 23 against 26 us with M = 64; but 33 against 31 us with M = 128,
+  // 58 against 37 us for M = 200 tiny workers (the server phase and the barrier grow with the workers) and 29 against
+  // 28 us for B = 100 rows of p = 256: the path is taken by itself up to 64 workers of up to 64 rows.
+  if (cfg->path != CADA_PATH_WHOLE_STEPS && (M > 64 || B > 64)) return false;
   int dev = 0, coop = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;

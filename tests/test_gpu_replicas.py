@@ -72,7 +72,7 @@ def test_replica_arguments_are_checked():
     with pytest.raises(binding.CadaError, match="differs"):
         binding.cada_run_replicas([whole.ctx, other.ctx], [idx.data_ptr(), idx.data_ptr()], None, 1)
     plain = Cada.from_config(configs.CFG2.scaled(name="rep_plain", M=6, N_m=400, B=16, K=4), *upload(
-        generators.make_problem(configs.CFG2.scaled(name="rep_plain", M=6, N_m=400, B=16, K=4))))
+        generators.make_problem(configs.CFG2.scaled(name="rep_plain", M=6, N_m=400, B=16, K=4))), path=binding.PATH_TWO_PASS)
     with pytest.raises(binding.CadaError, match="WHOLE_STEPS"):
         binding.cada_run_replicas([plain.ctx], [idx.data_ptr()], None, 1)
     plain.close()

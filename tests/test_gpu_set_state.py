@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 CASES = [
     (configs.CFG1.scaled(K=90, D=12), 37, 1e-4, {}),                                     # whole iterations in one launch, CADA2
     (configs.CFG1.scaled(name="cfg1_cada1", K=90, D=12, rule=configs.RULE_CADA1), 37, 1e-4, {}),
-    (configs.CFG2.scaled(K=70, N_m=300, D=20), 33, 1e-4, {}),                            # two streaming passes, CADA1
+    (configs.CFG2.scaled(K=70, N_m=300, D=20), 33, 1e-4, {"path": PATH_TWO_PASS}),       # two streaming passes, CADA1
     (configs.CFG2.scaled(name="cfg2_cada2", K=70, N_m=300, D=20, rule=configs.RULE_CADA2, c=0.05), 45, 1e-4, {}),
     (configs.CFG3.scaled(name="fused_cada2", layer_dims=(8192,), M=5, N_m=128, B=32, K=30, D=6, alpha=0.02, c=1e-4), 13, 1e-4, {}),
     (configs.CFG4.scaled(name="mlp2_cada2", layer_dims=(150, 133, 10), M=5, N_m=300, B=70, K=40, D=8, c=20.0), 19, 2e-2, {}),
