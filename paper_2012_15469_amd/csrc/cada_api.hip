@@ -385,8 +385,8 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
     } else if (c->fused) {
       c->n_phases = 3; c->phase_names[0] = "logreg_single_pass"; c->phase_names[1] = "rule"; c->phase_names[2] = "server_update";
     } else {
-      c->n_phases = 4; c->phase_names[0] = "logreg_dots"; c->phase_names[1] = "logreg_grad";
-      c->phase_names[2] = "rule"; c->phase_names[3] = "server_update";
+      // (the two passes of a group of workers follow each other, group after group: one phase)
+      c->n_phases = 3; c->phase_names[0] = "logreg_two_pass"; c->phase_names[1] = "rule"; c->phase_names[2] = "server_update";
     }
   }
   if (cfg->model == CADA_MODEL_MLP) {

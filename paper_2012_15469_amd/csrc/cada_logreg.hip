@@ -257,7 +257,6 @@ int logreg_gradients(Ctx *c, const int32_t *idx) {
     }
   }
   prof_mark(c);
-  prof_mark(c);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     set_error("logistic gradient launch failed: %s", hipGetErrorString(e));

@@ -61,7 +61,7 @@ def test_cfg3_reduced_ragged(p, rule, fused):
         prob.X, prob.y = np.concatenate(Xs), np.concatenate(ys)
     sched = generators.make_schedule(cfg)
     stats, o, tr, rep = check_protocol(cfg, prob, upload(prob), sched, FP32_TOL, lhs_rtol=1e-4, path=path,
-                                       expect_phase={1: "logreg_single_pass", 0: "logreg_dots", -1: "logreg_whole_steps"}[fused])
+                                       expect_phase={1: "logreg_single_pass", 0: "logreg_two_pass", -1: "logreg_whole_steps"}[fused])
     print(p, rule, stats)
     free = tr["tau"] < cfg.D
     assert 0.1 < tr["mask"][free].mean() < 0.9, "the case must mix rule-driven uploads and skips"
@@ -179,7 +179,7 @@ def test_largest_minibatch_two_pass():
     cfg = configs.CFG1.scaled(name="big_batch", layer_dims=(64,), M=2, N_m=4500, B=4096, K=4, D=3, c=1e-3)
     prob, dev, sched = _case(cfg)
     o, tr = oracle_run(cfg, prob, sched)
-    out = run_library(cfg, dev, sched, replay=tr["mask"], path=PATH_TWO_PASS, expect_phase="logreg_dots")
+    out = run_library(cfg, dev, sched, replay=tr["mask"], path=PATH_TWO_PASS, expect_phase="logreg_two_pass")
     assert out["error_flags"][0] == 0
     assert np.array_equal(out["trace_own_mask"], tr["own_mask"])
     assert rel_l2(out["theta64"], o.theta) < FP32_TOL
