@@ -118,6 +118,20 @@ __device__ __forceinline__ float block_sum(float x, float *red /* [4] LDS */) {
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Workgroup barrier for data that is exchanged through LDS: it waits for this wavefront's LDS operations only, not, as
+// __syncthreads() does, for the acknowledgement of every global store issued before it (a microsecond each time).
+// Data that a thread loaded from memory and passes on through LDS is waited for where it is written to LDS.
+__device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// block_sum with that barrier
+__device__ __forceinline__ float block_sum_lds(float x, float *red /* [4] LDS */) {
+  x = wave_sum(x);
+  lds_sync();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  lds_sync();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 struct LogregLaunch;   // defined in cada_logreg.hip
 
 // Host context.

@@ -58,19 +58,6 @@ static_assert(sizeof(SmallLaunch) <= 4096, "kernel arguments");
 
 __device__ __forceinline__ float sigmoid_s(float a) { return 1.0f / (1.0f + expf(-a)); }
 
-// Workgroup barrier for data that is exchanged through LDS: it waits for this wavefront's LDS operations only, not, as
-// __syncthreads() does, for the acknowledgement of every global store issued before it (a microsecond each time).
-__device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-// block_sum of cada_internal.h with that barrier
-__device__ __forceinline__ float block_sum_lds(float x, float *red /* [4] LDS */) {
-  x = wave_sum(x);
-  lds_sync();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
-  lds_sync();
-  return (red[0] + red[1]) + (red[2] + red[3]);
-}
-
 // All workgroups arrive; `target` is the counter value that means everyone has.  `while_waiting` runs between this
 // workgroup's arrival and its wait: loads issued there are under way while the others arrive.
 template <typename F>
