@@ -101,6 +101,17 @@ def test_single_pass_kernel_wide_clusters(rule, clusters):
     assert 0.02 < tr["mask"][free].mean() < 0.98, "the case must mix rule-driven uploads and skips"
 
 
+@pytest.mark.parametrize("p,rule", [(54, 2), (64, 1)])
+def test_whole_steps_with_more_rows_than_threads(p, rule):
+    """The whole-step kernel with a minibatch of 300 rows (more than the 256 threads of a workgroup, and no multiple
+    of the rows a wavefront fetches at a time), rows of 16-byte multiples (p = 64) and not (p = 54): the fetch of the
+    first step, the prefetch of the following ones and the labels all go through their loops more than once."""
+    cfg = configs.CFG1.scaled(name="rows300", layer_dims=(p,), M=3, N_m=1000, B=300, K=40, D=6, rule=rule, c=0.05)
+    prob, dev, sched = _case(cfg)
+    stats, o, tr, rep = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_WHOLE_STEPS, expect_phase="logreg_whole_steps")
+    print(p, rule, stats, tr["mask"].mean())
+
+
 def test_special_cases_c0_and_huge_c():
     cfg = configs.CFG1.scaled(c=0.0, K=50)
     prob, dev, sched = _case(cfg)
