@@ -128,7 +128,7 @@ typedef struct cada_config {
                                 when B is even), 1 = one row per iteration */
   int32_t single_pass_clusters; /* 0 = as many workgroup clusters as the device holds; n > 0: at most n (fewer,
                                 longer-lived clusters: every cluster then changes worker in mid-stream) */
-  int32_t plain_launch;      /* 1 = launch the single-pass kernel as an ordinary grid instead of cooperatively (for
+  int32_t plain_launch;      /* 1 = launch the single-pass and the whole-step kernel as ordinary grids instead of cooperatively (for
                                 profilers that cannot trace cooperative dispatches; the device must be otherwise idle;
                                 every wait in the kernel is bounded and reports through error_flags bit 1) */
   int32_t two_pass_group;    /* CADA_PATH_TWO_PASS tuning: workers per pair of launches, 0 = all */

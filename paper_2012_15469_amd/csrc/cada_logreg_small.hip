@@ -458,6 +458,7 @@ bool small_plan(Ctx *c, const cada_config *cfg) {
     return false;
   }
   c->small = 1;
+  c->small_plain_launch = cfg->plain_launch != 0 ? 1 : 0;
   return true;
 }
 
@@ -530,8 +531,14 @@ int small_steps(Ctx *c, const int32_t *idx, const uint8_t *replay, int64_t n_ste
   l.one = small_args_of(c, idx, replay, n_steps);
   void *args[] = {&l};
   prof_mark(c);
-  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_small), dim3((unsigned)c->s.M), dim3(kBlock), args,
-                                                  (unsigned)c->small_lds, c->stream);
+  hipError_t e;
+  if (c->small_plain_launch) {      // (at most as many workgroups of 256 threads as CUs: all resident at once on an idle device)
+    hipLaunchKernelGGL(k_small, dim3((unsigned)c->s.M), dim3(kBlock), c->small_lds, c->stream, l);
+    e = hipGetLastError();
+  } else {
+    e = hipLaunchCooperativeKernel(reinterpret_cast<const void *>(k_small), dim3((unsigned)c->s.M), dim3(kBlock), args,
+                                   (unsigned)c->small_lds, c->stream);
+  }
   prof_mark(c);
   if (e != hipSuccess) {
     set_error("multi-step logistic launch failed: %s", hipGetErrorString(e));
