@@ -111,7 +111,7 @@ bool check_config(const cada_config *cfg, Geometry *g) {
   g->n_ring_part = (int)((cfg->p + 255) / 256);
   g->ring_cap = g->n_ring_part > cfg->M ? g->n_ring_part : cfg->M;
   if (cfg->model == CADA_MODEL_MLP) g->n_lhs_part = mlp_lhs_slots(cfg);
-  const int fused_slots = 4 * (int)((cfg->p + 2047) / 2048);
+  const int fused_slots = kFusedWaves * (int)((cfg->p + 2047) / 2048);
   g->lhs_cap = g->n_lhs_part > fused_slots ? g->n_lhs_part : fused_slots;
   return true;
 }
@@ -375,7 +375,7 @@ int cada_init(const cada_config *cfg, const float *theta0, cada_ctx **out) {
   if (cfg->model == CADA_MODEL_LOGREG) {
     // the requested path first; a request that the shape does not allow falls back to the others
     if (cfg->path == CADA_PATH_WHOLE_STEPS && small_plan(c, cfg)) s.n_ring_part = cfg->M;
-    else if (cfg->path != CADA_PATH_TWO_PASS && fused_plan(c, cfg)) s.n_lhs_part = 4 * c->fused_Q;
+    else if (cfg->path != CADA_PATH_TWO_PASS && fused_plan(c, cfg)) s.n_lhs_part = kFusedWaves * c->fused_Q;
     else if (cfg->path == CADA_PATH_AUTO && small_plan(c, cfg)) s.n_ring_part = cfg->M;
     if (c->small) {
       c->n_phases = 1; c->phase_names[0] = "logreg_whole_steps";

@@ -192,6 +192,7 @@ bool small_plan(Ctx *c, const cada_config *cfg);
 int small_publish_args(Ctx *c);             // after the state pointers are final, and after a checkpoint was loaded
 void small_free(Ctx *c);
 int logreg_init(Ctx *c);                    // LDS allowance of the two-pass kernels
+constexpr int kFusedWaves = 8;                      // streaming wavefronts of a single-pass workgroup: one partial sum of the left-hand side each
 constexpr size_t kFusedTailFloatsPerP = 2 * 32;     // room for the parts of 32 clusters (one per cluster, two sums)
 constexpr size_t kFusedPostWords = 1024 * 4 * 16;   // upper bound: 1024 workgroups x 4 buffers x 16 values
 // S1+S2 for the MLP.

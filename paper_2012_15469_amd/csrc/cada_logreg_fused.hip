@@ -5,7 +5,7 @@
 // rows, and a second pass over them costs as much as the first whether it is served by
 // HBM or by the memory-side cache (measured: re-reading a 64 MB window immediately runs at
 // the same 6 TB/s as HBM).  Here a cluster of Q workgroups owns one worker at a time;
-// workgroup c of the cluster owns a fixed range of columns (8 per thread) and streams the
+// workgroup c of the cluster owns a fixed range of 2048 columns (4 per streaming thread) and streams the
 // worker's rows through its registers one row (slab) at a time.  For slab t it
 //   1. forms the partial dot products z, dz of its columns (from registers) and publishes
 //      them to the cluster as 8-byte words {value, sequence tag},
@@ -21,14 +21,26 @@
 // Loads return in order within a wavefront, so waiting for a young load (a poll, an index,
 // a label) means waiting for every older one: a wavefront that keeps 16 slabs of bulk loads
 // in flight must issue no other load in its steady state.  The workgroup is therefore split
-// into roles, six wavefronts that meet at one LDS-only barrier per slab:
-//   wavefronts 0-3  stream: bulk loads (PD = 16 slabs in flight), partial dot products,
+// into roles, ten wavefronts that meet at one LDS-only barrier per iteration (one or two slabs):
+//   wavefronts 0-7  stream: bulk loads (PD = 16 slabs in flight), partial dot products,
 //                   parking, accumulation; row addresses come from LDS;
-//   wavefront 4     exchange: publishes the workgroup's partials, polls the cluster's
+//   wavefront 8     exchange: publishes the workgroup's partials, polls the cluster's
 //                   (P polls in flight, first issued LAG-2-P slabs after publication),
 //                   sums them;
-//   wavefront 5     turns (z, dz, y) into (r, dr) one slab later, and every 64 slabs fetches
-//                   the row indices and labels of 64 slabs to come into LDS.
+//   wavefront 9     turns (z, dz, y) into (r, dr) one slab later, and every 64 slabs fetches
+//                   the row indices and labels of 64 slabs to come into LDS, with the slot of
+//                   the iterate history and the half of the gradient store of their worker.
+// (Eight streaming wavefronts of four columns per thread need 150-160 registers; four of eight
+// columns needed 256 and spilled.  The time is the same.)
+// A change of worker costs a streaming wavefront no wait: theta stays in registers for the whole
+// launch, and the next worker's reference point is asked for PDI iterations ahead, together with
+// the bulk loads of that worker's first row, by loads that -- like the bulk loads -- the compiler
+// does not see; a wait for every outstanding load, which a dependent load chain at the change
+// used to need twice per worker, empties the 16-slab pipeline and costs its refill (2 % of a
+// launch at 13 workers per cluster).  Minibatches of fewer than 32 rows, which the prefetch
+// distance and the accumulation lag would overrun, compile to a variant that loads at the change
+// and waits (DRAIN): a variant of its own so that in the other no second value ever shares, or is
+// moved through, the registers with loads in flight.
 // Every global memory operation of a steady-state iteration is executed by all lanes: the
 // compiler counts outstanding operations per path, and one that a branch may skip does not
 // count, which would turn every wait into a wait for the youngest load.
@@ -53,8 +65,11 @@ namespace cada {
 constexpr int F_PD = 16;             // slabs of loads in flight per thread
 constexpr int F_NP = 32;             // publication buffers, in slabs
 constexpr int F_V = 2;               // exchanged values per slab and workgroup: z and dz
-constexpr int F_STREAM = 256;        // streaming threads (4 wavefronts)
+constexpr int F_SW = kFusedWaves;    // streaming wavefronts
+constexpr int F_STREAM = 64 * F_SW;  // streaming threads
+constexpr int F_NQ = 2048 / (4 * F_STREAM);   // 16-byte pieces of a row per streaming thread (a workgroup owns 2048 columns)
 constexpr int F_THREADS = F_STREAM + 128;   // + exchange wavefront + residual/feeder wavefront
+static_assert(F_NQ >= 1 && F_NQ * 4 * F_STREAM == 2048 && (F_SW & (F_SW - 1)) == 0, "a workgroup owns 2048 columns");
 constexpr int F_QMAX = 64;            // workgroups per cluster: 32 per poll word of an exchange lane, NJ = 1 or 2 words
 constexpr int F_NE = 256;            // slabs whose row address and label are held in LDS (4 chunks of 64)
 template <int R> struct FusedGeom {
@@ -63,7 +78,7 @@ template <int R> struct FusedGeom {
   static constexpr int PDI = F_PD / R;            // iterations of loads in flight = unroll factor of the loops
   static constexpr int P = 4 / R;                 // iterations of polls in flight in the exchange wavefront
   static constexpr int IPC = 64 / R;              // iterations per feeder chunk of 64 slabs
-  static constexpr size_t lds = (size_t)NL * 2 * F_STREAM * sizeof(float4);   // dynamic part
+  static constexpr size_t lds = (size_t)NL * F_NQ * F_STREAM * sizeof(float4);   // dynamic part
   static_assert(PDI % P == 0 && F_NP >= (LAGI + 2) * R && F_NE % 64 == 0 && NL % R == 0, "pipeline constants");
 };
 
@@ -105,9 +120,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));   // four consecutive reg
 // is invisible to the compiler's bookkeeping; wait_slab() is what orders its use.
 // The rows are read once per step and never again soon: the loads carry the non-temporal hint.
 // (Measured on a 2 GB stream over all CUs: 7.1 TB/s with it, 6.0 TB/s without.)
-__device__ __forceinline__ void issue_slab(v4f &a, v4f &b, const float *pa, const float *pb) {
-  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(a) : "v"(pa) : "memory");
-  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(b) : "v"(pb) : "memory");
+__device__ __forceinline__ void issue_slab(v4f (&x)[F_NQ], const float *row, const int64_t (&col)[F_NQ]) {
+#pragma unroll
+  for (int q = 0; q < F_NQ; ++q) asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(x[q]) : "v"(row + col[q]) : "memory");
 }
 // Workgroup barrier that orders LDS traffic only.  (__syncthreads() also fences global
 // memory, which makes every wavefront wait for all its outstanding loads and would drain the
@@ -133,14 +148,27 @@ __device__ __forceinline__ float row16_parity_sum(float v) {
 
 // Waits until at most N vector memory operations issued after the loads of x are outstanding.
 template <int N, int R>
-__device__ __forceinline__ void wait_rows(v4f (&x)[R][2]) {
-  if constexpr (R == 1) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(x[0][0]), "+v"(x[0][1]) : "n"(N));
-  else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[1][0]), "+v"(x[1][1]) : "n"(N));
+__device__ __forceinline__ void wait_rows(v4f (&x)[R][F_NQ]) {
+  static_assert(R * F_NQ == 1 || R * F_NQ == 2 || R * F_NQ == 4, "registers named below");
+  v4f *f = &x[0][0];
+  if constexpr (R * F_NQ == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(f[0]) : "n"(N));
+  else if constexpr (R * F_NQ == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(f[0]), "+v"(f[1]) : "n"(N));
+  else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(N));
+}
+
+// The same wait, naming the registers of a reference point (see issue_ref in k_fused).
+template <int N>
+__device__ __forceinline__ void wait_ref(v4f (&x)[2][F_NQ]) {
+  static_assert(F_NQ == 1 || F_NQ == 2, "registers named below");
+  v4f *f = &x[0][0];
+  if constexpr (F_NQ == 1) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(f[0]), "+v"(f[1]) : "n"(N));
+  else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(N));
 }
 
 // NJ: poll words per lane of the exchange wavefront (a lane sums the partials of workgroups j, j + 32, ...):
 // 1 for clusters of up to 32 workgroups (p <= 65536), 2 for up to 64 (p <= 131072).
-template <int R, int NJ = 1>
+// DRAIN: minibatches of fewer than 32 rows (see the worker changes of the streaming wavefronts).
+template <int R, int NJ, bool DRAIN>
 __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   using G = FusedGeom<R>;
   constexpr int NL = G::NL, LAGI = G::LAGI, PDI = G::PDI, P = G::P, IPC = G::IPC;
@@ -148,12 +176,14 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   constexpr int HEAD = (LAGI + 1 + PDI - 1) / PDI * PDI;
   const DevState &s = a.s;
   extern __shared__ __align__(16) unsigned char fused_smem[];
-  v4f *ring = reinterpret_cast<v4f *>(fused_smem);            // [NL][2][F_STREAM]
-  __shared__ __align__(16) float red[2][R][F_V][16];          // [iteration parity][row][z|dz][wavefront * 4 + row of 16 lanes]
+  v4f *ring = reinterpret_cast<v4f *>(fused_smem);            // [NL][F_NQ][F_STREAM]
+  __shared__ __align__(16) float red[2][R][F_V][4 * F_SW];    // [iteration parity][row][z|dz][wavefront * 4 + row of 16 lanes]
   __shared__ float zz_s[2][R][F_V];                           // cluster sums z, dz
   __shared__ float r_s[2][R], dr_s[2][R];
   __shared__ __align__(16) long long off_s[F_NE];             // element offset of slab t's row in X, at t % NE
   __shared__ float y_s[F_NE];                                 // label of slab t
+  __shared__ int ref_s[F_NE];                                 // slot of the iterate history that holds the reference point of slab t's worker
+  __shared__ int sel_s[F_NE];                                 // which half of the gradient store holds that worker's stored gradient
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int Q = a.Q, ncl = a.n_clusters;
@@ -182,13 +212,14 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     }
   };
 
-  if (w == 5) {
+  if (w == F_SW + 1) {
     // ================= residual / feeder wavefront =================
     const float invB = 1.0f / (float)s.B;
     // feeder registers (lane = slab 64 * chunk + lane): row index, first row and end of the
     // worker's row range, label.  Three stages several iterations apart, so that no stage
     // waits for a load it has just issued.
     int64_t f_base = 0, f_end = 0, f_r = 0;
+    int f_tau = 0, f_sel = 0;
     float f_y = 0.f;
     auto feed_issue = [&](int chunk) __attribute__((always_inline)) {                 // stage 1: index and row range
       const int t = chunk * 64 + lane;
@@ -199,6 +230,8 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       f_base = s.row_off[m];
       f_end = s.row_off[m + 1];
       f_r = a.idx[(int64_t)m * s.B + row];
+      f_tau = s.rule == CADA_RULE_CADA2 ? s.tau[m] : 0;
+      f_sel = s.sel[m];
     };
     auto feed_label = [&]() __attribute__((always_inline)) {                          // stage 2: range check, label
       const int64_t n_m = f_end - f_base;
@@ -209,6 +242,10 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       const int e = (chunk * 64 + lane) % F_NE;
       off_s[e] = (f_base + f_r) * s.p;
       y_s[e] = f_y;
+      int64_t slot = (s.k - (int64_t)min(f_tau, s.D)) % s.R;     // as theta_ref_at()
+      if (slot < 0) slot += s.R;
+      ref_s[e] = (int)slot;
+      sel_s[e] = f_sel;
     };
     feed_issue(0); feed_label(); feed_write(0);
     lds_barrier();
@@ -257,7 +294,7 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     return;
   }
 
-  if (w == 4) {
+  if (w == F_SW) {
     // ================= exchange wavefront =================
     const int j = lane & 31, half = lane >> 5, par = lane & 1, pr = (lane >> 1) & (R - 1);
     bool jok[NJ];
@@ -281,9 +318,14 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       // publish the rows of iteration it: lanes of equal (parity, row) compute and store the same word
       if (st || it < IS) {
         const float4 *rp = reinterpret_cast<const float4 *>(red[it & 1][pr][par]);
-        const float4 q0 = rp[0], q1 = rp[1], q2 = rp[2], q3 = rp[3];
-        const float tot = (((q0.x + q0.y) + (q0.z + q0.w)) + ((q1.x + q1.y) + (q1.z + q1.w))) +
-                          (((q2.x + q2.y) + (q2.z + q2.w)) + ((q3.x + q3.y) + (q3.z + q3.w)));
+        float ws[F_SW];                                     // per streaming wavefront, then a fixed tree
+#pragma unroll
+        for (int i = 0; i < F_SW; ++i) { const float4 q = rp[i]; ws[i] = (q.x + q.y) + (q.z + q.w); }
+#pragma unroll
+        for (int st2 = 1; st2 < F_SW; st2 *= 2)
+#pragma unroll
+          for (int i = 0; i < F_SW; i += 2 * st2) ws[i] += ws[i + st2];
+        const float tot = ws[0];
         const int t = it * R + pr;
         const uint32_t tag = a.seq_base + 1u + (uint32_t)t;
         const unsigned long long word = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(tot);
@@ -348,10 +390,10 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   // ================= streaming wavefronts =================
   const int64_t colbase = (int64_t)cb * a.cols_per_block;
   const int64_t colend = min(s.p, colbase + a.cols_per_block);
-  int64_t col[2];
-  bool cv[2];
+  int64_t col[F_NQ];
+  bool cv[F_NQ];
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
+  for (int q = 0; q < F_NQ; ++q) {
     col[q] = colbase + ((int64_t)q * F_STREAM + tid) * 4;
     cv[q] = col[q] < colend;
     if (!cv[q]) col[q] = 0;            // a valid address; the value is discarded
@@ -363,34 +405,61 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((unsigned long long)o >> 32));
     return s.X + (int64_t)(((unsigned long long)hi << 32) | lo);
   };
-  auto load_theta = [&](int m, float4 (&t)[2], float4 (&d)[2]) {
-    const RefPtr ref = theta_ref(s, m, s.k);
+  // th, tl: theta (two floats per value); dd: theta - reference point of the worker being produced (dd_m), ddc: of
+  // the worker before it (ddc_m), whose last rows are accumulated LAGI iterations after its last dot products
+  float4 th[F_NQ], tl[F_NQ], dd[F_NQ], ddc[F_NQ], g[F_NQ], iv[F_NQ];
+  int dd_m = -1, ddc_m = -1;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const float4 tt = *reinterpret_cast<const float4 *>(s.theta + col[q]);
-      const float4 tl = *reinterpret_cast<const float4 *>(s.theta_lo + col[q]);
-      const float4 rh = *reinterpret_cast<const float4 *>(ref.hi + col[q]);
-      const float4 rl = *reinterpret_cast<const float4 *>(ref.lo + col[q]);
-      t[q] = cv[q] ? tt : make_float4(0.f, 0.f, 0.f, 0.f);
-      d[q] = cv[q] ? make_float4((tt.x - rh.x) + (tl.x - rl.x), (tt.y - rh.y) + (tl.y - rl.y),
-                                 (tt.z - rh.z) + (tl.z - rl.z), (tt.w - rh.w) + (tl.w - rl.w))
+  for (int q = 0; q < F_NQ; ++q) {
+    th[q] = tl[q] = dd[q] = ddc[q] = g[q] = iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (cv[q]) { th[q] = *reinterpret_cast<const float4 *>(s.theta + col[q]); tl[q] = *reinterpret_cast<const float4 *>(s.theta_lo + col[q]); }
+  }
+
+  // Worker changes without draining the load pipeline.  theta is the same for every worker and stays in
+  // registers (th, tl); a worker's reference point differs.  Its columns are asked for (rq, loads the compiler does
+  // not see, like the bulk loads) in the iteration that issues the bulk loads of the worker's first row, PDI
+  // iterations before that row's dot products: they are older than that row's loads, so the wait for the row
+  // covers them.  The worker's slot of the iterate history comes from the feeder's table.
+  v4f rq[2][F_NQ];                      // reference point, high and low words
+  auto ref_of = [&](int t) __attribute__((always_inline)) -> RefPtr {     // reference point of slab t's worker
+    if (s.rule == CADA_RULE_CADA1) return RefPtr{s.snap, s.snap_lo};
+    if (s.rule != CADA_RULE_CADA2) return RefPtr{s.theta, s.theta_lo};
+    const int slot = __builtin_amdgcn_readfirstlane(ref_s[t % F_NE]);
+    return RefPtr{s.hist + (int64_t)slot * s.ps, s.hist_lo + (int64_t)slot * s.ps};
+  };
+  auto issue_ref = [&](int t) __attribute__((always_inline)) {
+    const RefPtr ref = ref_of(t);
+#pragma unroll
+    for (int q = 0; q < F_NQ; ++q) {
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(rq[0][q]) : "v"(ref.hi + col[q]) : "memory");
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(rq[1][q]) : "v"(ref.lo + col[q]) : "memory");
+    }
+  };
+  // theta - reference point of slab t's worker at this thread's columns, loaded here and now (short minibatches)
+  auto diff_now = [&](int t, float4 (&d)[F_NQ]) __attribute__((always_inline)) {
+    const RefPtr ref = ref_of(t);
+#pragma unroll
+    for (int q = 0; q < F_NQ; ++q) {
+      const float4 rh = *reinterpret_cast<const float4 *>(ref.hi + col[q]), rl = *reinterpret_cast<const float4 *>(ref.lo + col[q]);
+      d[q] = cv[q] ? make_float4((th[q].x - rh.x) + (tl[q].x - rl.x), (th[q].y - rh.y) + (tl[q].y - rl.y),
+                                 (th[q].z - rh.z) + (tl[q].z - rl.z), (th[q].w - rh.w) + (tl[q].w - rl.w))
                    : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    // a rarely taken block must leave no load the compiler still tracks in flight: a wait for
-    // it on the main path would be a wait for nearly all the bulk loads issued since
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no load that the compiler tracks stays in flight
   };
 
-  v4f xb[PDI][R][2];
-  float4 th[2], dd[2], g[2], iv[2];
-#pragma unroll
-  for (int q = 0; q < 2; ++q) th[q] = dd[q] = g[q] = iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-
+  v4f xb[PDI][R][F_NQ];
   const int m_first = rounds > 0 ? cluster : mt;
   int pm = m_first, ploc = first_of(m_first), pend = end_of(m_first);   // first slab produced (dot products, parked) this iteration
   int cm = m_first, cloc = first_of(m_first), cend = end_of(m_first);   // first slab accumulated this iteration
   int pfirst = ploc, cfirst = cloc;                                     // first slab of the worker being produced / accumulated
   lds_barrier();                        // the feeder's first chunk is in LDS
+  // Minibatches too short for that (a worker must outlast the prefetch, and the accumulation lag for ddc to hold)
+  // load the reference point where it is used and wait for the pipeline.
+  constexpr bool drain = DRAIN;
+  if constexpr (!drain) issue_ref(0);
+  int qloc = (PDI * R) % nslab;         // position within its worker of the first row whose loads an iteration issues
+  int ct = 0;                           // first slab accumulated by the next accumulate()
   // prologue: loads of the first PDI iterations
 #pragma unroll
   for (int i = 0; i < PDI; ++i)
@@ -399,13 +468,13 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       if (i * R + r < S) {
         const float *rp = to_row(off_s[(i * R + r) % F_NE]);
 #pragma unroll
-        for (int q = 0; q < 2; ++q) xb[i][r][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
+        for (int q = 0; q < F_NQ; ++q) xb[i][r][q] = *reinterpret_cast<const v4f *>(rp + col[q]);
       }
 
   // Accumulation of the consumed rows, deferred by one iteration: their residuals are read from
   // LDS right after the barrier but first used here, after the next rows' dot products, so
   // that the wavefront never waits for that read.
-  v4f xr[R][2];                         // the consumed rows' columns, from the ring
+  v4f xr[R][F_NQ];                      // the consumed rows' columns, from the ring
   float rr[R], dr[R];                   // their residuals and residual differences
 #pragma unroll
   for (int r = 0; r < R; ++r) rr[r] = dr[r] = 0.f;
@@ -414,7 +483,7 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
+      for (int q = 0; q < F_NQ; ++q) {
         const v4f x = xr[r][q];
         g[q].x = fmaf(rr[r], x.x, g[q].x); g[q].y = fmaf(rr[r], x.y, g[q].y);
         g[q].z = fmaf(rr[r], x.z, g[q].z); g[q].w = fmaf(rr[r], x.w, g[q].w);
@@ -425,7 +494,7 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       // last rows of this cluster's share of a split worker: its part of the two sums, as they are
       float *pg = a.tail_part + (((int64_t)(cluster % a.tail_f) * a.tail_rem + cluster / a.tail_f) * 2) * s.p;
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
+      for (int q = 0; q < F_NQ; ++q) {
         if (cv[q]) {
           *reinterpret_cast<float4 *>(pg + col[q]) = g[q];
           *reinterpret_cast<float4 *>(pg + s.p + col[q]) = iv[q];
@@ -433,24 +502,25 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
         g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
         iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
       }
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), see load_theta
     } else if (cloc + R == cend) {
       // last rows of worker cm: regulariser, stores, squared norm of the rule's left-hand side
       const int m = cm;
-      float4 tm[2], dm[2];
-      load_theta(m, tm, dm);
-      const int cur = s.sel[m];
+      const bool cur_worker = m == dd_m;          // (the last worker: nothing was produced after it)
+      if constexpr (drain) diff_now(ct, ddc);     // (ddc has no other use with short minibatches)
+      const int cur = __builtin_amdgcn_readfirstlane(sel_s[ct % F_NE]);
       float sq = 0.f;
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
+      for (int q = 0; q < F_NQ; ++q) {
         if (cv[q]) {
           float4 gg = g[q], ii = iv[q];
-          gg.x = fmaf(s.lam, tm[q].x, gg.x); gg.y = fmaf(s.lam, tm[q].y, gg.y);
-          gg.z = fmaf(s.lam, tm[q].z, gg.z); gg.w = fmaf(s.lam, tm[q].w, gg.w);
-          ii.x = fmaf(s.lam, dm[q].x, ii.x); ii.y = fmaf(s.lam, dm[q].y, ii.y);
-          ii.z = fmaf(s.lam, dm[q].z, ii.z); ii.w = fmaf(s.lam, dm[q].w, ii.w);
+          const float4 dm = (cur_worker && !drain) ? dd[q] : ddc[q];
+          gg.x = fmaf(s.lam, th[q].x, gg.x); gg.y = fmaf(s.lam, th[q].y, gg.y);
+          gg.z = fmaf(s.lam, th[q].z, gg.z); gg.w = fmaf(s.lam, th[q].w, gg.w);
+          ii.x = fmaf(s.lam, dm.x, ii.x); ii.y = fmaf(s.lam, dm.y, ii.y);
+          ii.z = fmaf(s.lam, dm.z, ii.z); ii.w = fmaf(s.lam, dm.w, ii.w);
           *reinterpret_cast<float4 *>(s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = gg;
           if (s.rule == CADA_RULE_CADA1) {
+            // (the one load of a worker change: CADA1 waits for the pipeline here)
             const float4 stv = *reinterpret_cast<const float4 *>(s.dtl + (int64_t)cur * mp + (int64_t)m * s.p + col[q]);
             *reinterpret_cast<float4 *>(s.dtl + (int64_t)(1 - cur) * mp + (int64_t)m * s.p + col[q]) = ii;
             ii.x -= stv.x; ii.y -= stv.y; ii.z -= stv.z; ii.w -= stv.w;
@@ -461,9 +531,12 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
         iv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
       }
       const float tot = wave_sum(sq);
-      if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + cb * 4 + w] = tot;
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), see load_theta
+      if (lane == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + cb * F_SW + w] = tot;
+      // a rarely taken block must leave no load the compiler still tracks in flight: a wait for it on the
+      // main path would be a wait for nearly all the bulk loads issued since
+      if (s.rule == CADA_RULE_CADA1) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     }
+    ct += R;
     advance(cm, cloc, cend, cfirst);
   };
 
@@ -491,28 +564,45 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
     //     thread's own columns: no synchronisation needed)
     const bool cons = st || (it >= LAGI && it - LAGI < IS);
     const int c0 = it - LAGI;
-    v4f xn[R][2];
+    v4f xn[R][F_NQ];
     if (cons) {
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        const v4f *slot = ring + (size_t)((c0 * R + r) % NL) * 2 * F_STREAM;
+        const v4f *slot = ring + (size_t)((c0 * R + r) % NL) * F_NQ * F_STREAM;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) xn[r][q] = slot[q * F_STREAM + tid];
+        for (int q = 0; q < F_NQ; ++q) xn[r][q] = slot[q * F_STREAM + tid];
       }
     }
     if (prod) {
-      if (ploc == pfirst) load_theta(pm, th, dd);
-      if constexpr (st) wait_rows<(PDI - 1) * 2 * R, R>(xb[bi]);
+      if constexpr (st) wait_rows<(PDI - 1) * F_NQ * R, R>(xb[bi]);
+      if (ploc == pfirst) {
+        // first rows of worker pm: its reference point was asked for before these rows (steady state: the wait
+        // above covers it; elsewhere the compiler's own loads are in flight too: wait for everything)
+        if constexpr (drain) {
+          diff_now(it * R, dd);
+        } else {
+          if constexpr (st) wait_ref<(PDI - 1) * F_NQ * R>(rq); else wait_ref<0>(rq);
+#pragma unroll
+          for (int q = 0; q < F_NQ; ++q) {
+            ddc[q] = dd[q];
+            const v4f rh = rq[0][q], rl = rq[1][q];
+            dd[q] = cv[q] ? make_float4((th[q].x - rh.x) + (tl[q].x - rl.x), (th[q].y - rh.y) + (tl[q].y - rl.y),
+                                        (th[q].z - rh.z) + (tl[q].z - rl.z), (th[q].w - rh.w) + (tl[q].w - rl.w))
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+          }
+          ddc_m = dd_m; dd_m = pm;
+        }
+      }
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         // 2. park the row
-        v4f *slot = ring + (size_t)((it * R + r) % NL) * 2 * F_STREAM;
+        v4f *slot = ring + (size_t)((it * R + r) % NL) * F_NQ * F_STREAM;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) slot[q * F_STREAM + tid] = xb[bi][r][q];
+        for (int q = 0; q < F_NQ; ++q) slot[q * F_STREAM + tid] = xb[bi][r][q];
         // 1. partial dot products of this thread's columns
         float z = 0.f, dz = 0.f;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < F_NQ; ++q) {
           const v4f x = xb[bi][r][q];
           z = fmaf(x.x, th[q].x, z); z = fmaf(x.y, th[q].y, z); z = fmaf(x.z, th[q].z, z); z = fmaf(x.w, th[q].w, z);
           dz = fmaf(x.x, dd[q].x, dz); dz = fmaf(x.y, dd[q].y, dz); dz = fmaf(x.z, dd[q].z, dz); dz = fmaf(x.w, dd[q].w, dz);
@@ -525,14 +615,19 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
       }
       advance(pm, ploc, pend, pfirst);
       // the registers are free for the rows PDI iterations ahead
+      if (more) {
+        if constexpr (!drain) { if (qloc == 0) issue_ref((it + PDI) * R); }
+        qloc += R;
+        if (qloc == nslab) qloc = 0;
+      }
       if constexpr (st) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) issue_slab(xb[bi][r][0], xb[bi][r][1], rp[r] + col[0], rp[r] + col[1]);
+        for (int r = 0; r < R; ++r) issue_slab(xb[bi][r], rp[r], col);
       } else if (more) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-          for (int q = 0; q < 2; ++q) xb[bi][r][q] = *reinterpret_cast<const v4f *>(rp[r] + col[q]);
+          for (int q = 0; q < F_NQ; ++q) xb[bi][r][q] = *reinterpret_cast<const v4f *>(rp[r] + col[q]);
       }
     }
     // 3b. accumulate the rows consumed in the previous iteration
@@ -543,7 +638,8 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         rr[r] = r_s[c0 & 1][r]; dr[r] = dr_s[c0 & 1][r];
-        xr[r][0] = xn[r][0]; xr[r][1] = xn[r][1];
+#pragma unroll
+        for (int q = 0; q < F_NQ; ++q) xr[r][q] = xn[r][q];
       }
     }
   };
@@ -568,10 +664,11 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
 // Adds up the parts of the workers whose rows the last round split over several clusters (in the order
 // of the row ranges), adds the regulariser's terms, stores the fresh gradient (CADA1: and the fresh
 // innovation) and the partial sums of the rule's left-hand side.  grid (4 Q, rem), 128 threads, four columns
-// each: block b owns columns [512 b, 512 b + 512) and slot b of the worker's partial sums.
+// each: block b owns columns [512 b, 512 b + 512), its two wavefronts slots 2 b and 2 b + 1 of the worker's
+// partial sums (as many slots per 2048 columns as k_fused has streaming wavefronts).
 __global__ __launch_bounds__(128) void k_fused_tail(const FusedArgs a) {
+  static_assert(F_SW == 8, "two slots per 512 columns");
   const DevState &s = a.s;
-  __shared__ float red[2];
   const int j = blockIdx.y, m = (s.M / a.n_clusters) * a.n_clusters + j;
   const int64_t c0 = ((int64_t)blockIdx.x * 128 + threadIdx.x) * 4;
   float sq = 0.f;
@@ -600,15 +697,15 @@ __global__ __launch_bounds__(128) void k_fused_tail(const FusedArgs a) {
     sq = fmaf(iv.x, iv.x, sq); sq = fmaf(iv.y, iv.y, sq); sq = fmaf(iv.z, iv.z, sq); sq = fmaf(iv.w, iv.w, sq);
   }
   const float ws = wave_sum(sq);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ws;
-  __syncthreads();
-  if (threadIdx.x == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + blockIdx.x] = red[0] + red[1];
+  if ((threadIdx.x & 63) == 0) s.lhs_part[(int64_t)m * s.n_lhs_part + blockIdx.x * 2 + (threadIdx.x >> 6)] = ws;
 }
 
-static const void *fused_kernel(int R, int NJ) {
-  if (R == 2) return NJ == 2 ? reinterpret_cast<const void *>(k_fused<2, 2>) : reinterpret_cast<const void *>(k_fused<2, 1>);
-  return NJ == 2 ? reinterpret_cast<const void *>(k_fused<1, 2>) : reinterpret_cast<const void *>(k_fused<1, 1>);
+template <bool DRAIN>
+static const void *fused_kernel_of(int R, int NJ) {
+  if (R == 2) return NJ == 2 ? reinterpret_cast<const void *>(k_fused<2, 2, DRAIN>) : reinterpret_cast<const void *>(k_fused<2, 1, DRAIN>);
+  return NJ == 2 ? reinterpret_cast<const void *>(k_fused<1, 2, DRAIN>) : reinterpret_cast<const void *>(k_fused<1, 1, DRAIN>);
 }
+static const void *fused_kernel(int R, int NJ, int B) { return B < 32 ? fused_kernel_of<true>(R, NJ) : fused_kernel_of<false>(R, NJ); }
 
 // Chooses the cluster geometry; returns false if the single-pass path does not apply.
 bool fused_plan(Ctx *c, const cada_config *cfg) {
@@ -620,13 +717,13 @@ bool fused_plan(Ctx *c, const cada_config *cfg) {
   if (hipGetDevice(&dev) != hipSuccess) return false;
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return false;
-  const int64_t per_block = (int64_t)F_STREAM * 4 * 2;           // 2048 columns per workgroup
+  const int64_t per_block = (int64_t)F_STREAM * 4 * F_NQ;        // 2048 columns per workgroup
   int Q = (int)((p + per_block - 1) / per_block);
   if (Q > F_QMAX || Q > cus) return false;
   int R = (B % 2 == 0) ? 2 : 1;                            // rows per iteration
   if (cfg->single_pass_rows == 1) R = 1;
   const int NJ = Q > 32 ? 2 : 1;
-  const void *fn = fused_kernel(R, NJ);
+  const void *fn = fused_kernel(R, NJ, B);
   const size_t lds = R == 2 ? FusedGeom<2>::lds : FusedGeom<1>::lds;
   if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
@@ -683,9 +780,9 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
     // Same grid without the cooperative-launch guarantee: one workgroup per CU is resident at once
     // on an otherwise idle device, and every wait in the kernel is bounded.  For profilers that
     // cannot trace cooperative dispatches.
-    e = hipLaunchKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1), grid, block, args, lds, c->stream);
+    e = hipLaunchKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1, a.s.B), grid, block, args, lds, c->stream);
   } else {
-    e = hipLaunchCooperativeKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1), grid, block, args, (unsigned)lds, c->stream);
+    e = hipLaunchCooperativeKernel(fused_kernel(c->fused_rs, a.Q > 32 ? 2 : 1, a.s.B), grid, block, args, (unsigned)lds, c->stream);
   }
   if (a.tail_f > 0) prof_mark(c);          // (a phase of its own)
   if (e == hipSuccess && a.tail_f > 0) {
