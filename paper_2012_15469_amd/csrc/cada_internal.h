@@ -152,7 +152,6 @@ struct Ctx {
   int ring_cap;               // entries of ring_part in the workspace
   // single-pass (register-resident) logistic path, cada_logreg_fused.hip
   int fused, fused_Q, fused_clusters, fused_rs, fused_plain_launch;
-  int64_t fused_cols;
   uint32_t fused_seq, fused_seq_per_step;
   unsigned long long *fused_post;
   int fused_tail_f, fused_tail_rows, fused_tail_rem;   // split of the last round's workers over the clusters (0: none)

@@ -5,7 +5,7 @@
 // rows, and a second pass over them costs as much as the first whether it is served by
 // HBM or by the memory-side cache (measured: re-reading a 64 MB window immediately runs at
 // the same 6 TB/s as HBM).  Here a cluster of Q workgroups owns one worker at a time;
-// workgroup c of the cluster owns a fixed range of 2048 columns (4 per streaming thread) and streams the
+// workgroup c of the cluster owns a fixed set of 2048 columns (4 per streaming thread) and streams the
 // worker's rows through its registers one row (slab) at a time.  For slab t it
 //   1. forms the partial dot products z, dz of its columns (from registers) and publishes
 //      them to the cluster as 8-byte words {value, sequence tag},
@@ -87,7 +87,6 @@ struct FusedArgs {
   const int32_t *idx;            // [M][B]
   unsigned long long *zpost;     // [n_clusters][F_NP][F_V][Q] words {hi: tag, lo: float bits}
   int Q, n_clusters;
-  int64_t cols_per_block;        // multiple of 4, <= 2048
   uint32_t seq_base;             // tag of slab t of this launch is seq_base + 1 + t
   uint32_t spin_limit;
   // Last round.  With M = full * n_clusters + rem workers, 0 < rem < n_clusters, the last round would keep only
@@ -388,14 +387,15 @@ __global__ __launch_bounds__(F_THREADS) void k_fused(const FusedArgs a) {
   }
 
   // ================= streaming wavefronts =================
-  const int64_t colbase = (int64_t)cb * a.cols_per_block;
-  const int64_t colend = min(s.p, colbase + a.cols_per_block);
+  // A row is cut into pieces of 256 columns (1 KB, one load of a wavefront); piece (q F_SW + w) Q + cb belongs to
+  // streaming wavefront w of workgroup cb: the loads a workgroup issues together are 32 KB apart rather than 8 KB
+  // in a row (measured: 1 % faster than eight consecutive pieces per workgroup).
   int64_t col[F_NQ];
   bool cv[F_NQ];
 #pragma unroll
   for (int q = 0; q < F_NQ; ++q) {
-    col[q] = colbase + ((int64_t)q * F_STREAM + tid) * 4;
-    cv[q] = col[q] < colend;
+    col[q] = (((int64_t)(q * F_SW + w) * Q + cb) * 64 + lane) * 4;
+    cv[q] = col[q] < s.p;
     if (!cv[q]) col[q] = 0;            // a valid address; the value is discarded
   }
   const int64_t mp = (int64_t)s.M * s.p;
@@ -743,7 +743,6 @@ bool fused_plan(Ctx *c, const cada_config *cfg) {
   c->fused = 1;
   c->fused_Q = Q;
   c->fused_clusters = ncl;
-  c->fused_cols = ((p + Q - 1) / Q + 3) / 4 * 4;
   c->fused_rs = R;
   c->fused_plain_launch = cfg->plain_launch != 0 ? 1 : 0;
   const int nslab = B;
@@ -766,7 +765,6 @@ int logreg_gradients_fused(Ctx *c, const int32_t *idx) {
   a.zpost = c->fused_post;
   a.Q = c->fused_Q;
   a.n_clusters = c->fused_clusters;
-  a.cols_per_block = c->fused_cols;
   a.seq_base = c->fused_seq;
   a.spin_limit = 2000000u;
   a.tail_f = c->fused_tail_f; a.tail_rows = c->fused_tail_rows; a.tail_rem = c->fused_tail_rem; a.tail_part = c->fused_tail;
