@@ -68,7 +68,9 @@ def test_cfg3_reduced_ragged(p, rule, fused):
 
 
 # even B: two rows per iteration; odd B: one row per iteration
-@pytest.mark.parametrize("rule,B,clusters", [(2, 48, 0), (1, 48, 0), (2, 100, 2), (1, 72, 2), (2, 200, 1), (2, 51, 0), (1, 75, 2)])
+# B = 32, 33: the shortest minibatches of the variant that changes worker without waiting for its loads; 30, 31: the longest of the other
+@pytest.mark.parametrize("rule,B,clusters", [(2, 48, 0), (1, 48, 0), (2, 100, 2), (1, 72, 2), (2, 200, 1), (2, 51, 0), (1, 75, 2),
+                                             (2, 32, 2), (1, 33, 2), (2, 31, 1), (1, 30, 2), (2, 34, 1)])
 def test_single_pass_kernel_steady_state(rule, B, clusters):
     """The single-pass kernel's unrolled steady-state loop only runs once a cluster of
     workgroups streams more than 40 rows: longer minibatches, and fewer clusters than workers
