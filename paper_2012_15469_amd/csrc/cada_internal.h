@@ -118,14 +118,28 @@ __device__ __forceinline__ float block_sum(float x, float *red /* [4] LDS */) {
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Sum over the 64 lanes without the LDS permute path: four data-parallel-primitive steps inside each row of 16 lanes
+// (quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_ror:4, row_ror:8), then the four rows' sums by lane reads.  Every
+// lane gets the result; a __shfl_xor butterfly is six dependent LDS-path permutes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v = dpp_add<0xB1>(v); v = dpp_add<0x4E>(v); v = dpp_add<0x124>(v); v = dpp_add<0x128>(v);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
 // Workgroup barrier for data that is exchanged through LDS: it waits for this wavefront's LDS operations only, not, as
 // __syncthreads() does, for the acknowledgement of every global store issued before it (a microsecond each time).
 // Data that a thread loaded from memory and passes on through LDS is waited for where it is written to LDS.
 __device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// block_sum with that barrier
+// block_sum with that barrier and the wavefront sums of wave_sum_dpp
 __device__ __forceinline__ float block_sum_lds(float x, float *red /* [4] LDS */) {
-  x = wave_sum(x);
+  x = wave_sum_dpp(x);
   lds_sync();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
   lds_sync();

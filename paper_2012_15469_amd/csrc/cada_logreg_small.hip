@@ -233,9 +233,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
         }
       }
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { z[q] += __shfl_xor(z[q], o, 64); dz[q] += __shfl_xor(dz[q], o, 64); }
+      for (int q = 0; q < 4; ++q) { z[q] = wave_sum_dpp(z[q]); dz[q] = wave_sum_dpp(dz[q]); }
       {   // lane q takes row q of the four (every lane holds all eight sums): the exponentials of four rows side by side
         const float zq = lane == 0 ? z[0] : lane == 1 ? z[1] : lane == 2 ? z[2] : z[3];
         const float dq = lane == 0 ? dz[0] : lane == 1 ? dz[1] : lane == 2 ? dz[2] : dz[3];
@@ -257,6 +255,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     if (v4) {
       for (int j = tid * 4; j < p; j += 4 * kBlock) {
         float g[4] = {0.f, 0.f, 0.f, 0.f}, iv[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
         for (int b = 0; b < B; ++b) {
           const float4 xv = *reinterpret_cast<const float4 *>(x_s + b * p + j);
           const float rb = r_s[b], db = dr_s[b];
