@@ -16,11 +16,12 @@
 // the earliest.  What a fast workgroup writes in phase A of step k + 1 while a slow one is still in phase B of
 // step k never is what the slow one reads: the fresh gradient goes to the row that is not the stored one, and
 // the decisions of step k are published in slot k mod 2 of an array of their own.
-// A barrier is an agent-scope counter in the workspace; arrivals release (write back) and
-// departures acquire (invalidate) the XCD-local caches.  Every wait is bounded: a wait that
-// exceeds the bound sets bit 1 of the error flags and the workgroup stops waiting.
+// The barrier is that array: a workgroup's word carries the step's tag, its publication releases (writes back) and a
+// workgroup that has seen every word of the step acquires (invalidates) the XCD-local caches.  Every wait is bounded:
+// a wait that exceeds the bound sets bit 1 of the error flags and the workgroup stops waiting.
 #include <cstring>
 #include <new>
+#include <type_traits>
 
 #include "cada_internal.h"
 
@@ -58,21 +59,35 @@ static_assert(sizeof(SmallLaunch) <= 4096, "kernel arguments");
 
 __device__ __forceinline__ float sigmoid_s(float a) { return 1.0f / (1.0f + expf(-a)); }
 
-// All workgroups arrive; `target` is the counter value that means everyone has.  `while_waiting` runs between this
-// workgroup's arrival and its wait: loads issued there are under way while the others arrive.
+// The barrier of a step is also how the decisions travel.  Workgroup m publishes the word {tag of the step, its
+// worker's buffer selector after the decision} with a release, in slot (step parity, m) of an array in the workspace; a
+// workgroup has passed the barrier when the first wavefront, one lane per worker, has seen this step's tag in every
+// word -- and then it holds every decision, which a counter plus a separate array cost a memory round trip more.
+// (Two slots per worker: a workgroup can be one step ahead of another at most, so the word that a slow workgroup
+// still waits for is not overwritten.  A tag is never 0, the value of a fresh workspace.)
+// `while_waiting` runs between this workgroup's publication and its wait: loads issued there are under way while
+// the others arrive.  dk_s[M] (LDS) receives the selectors; the function ends with a workgroup barrier.
 template <typename F>
-__device__ __forceinline__ void grid_barrier(const SmallArgs &a, uint32_t target, bool &dead, F while_waiting) {
+__device__ __forceinline__ void decision_barrier(const SmallArgs &a, uint32_t *words /* [M] of this parity */, int M, int m, uint32_t tag, int sel,
+                                                 unsigned char *dk_s, bool &dead, F while_waiting) {
   __syncthreads();                      // every thread's stores have reached the L2 (the barrier waits for them) ...
-  // ... and the arrival releases at agent scope: it writes the L2's dirty lines back before the counter moves
-  if (threadIdx.x == 0) __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  // ... and the publication releases at agent scope: it writes the L2's dirty lines back before the word changes
+  if (threadIdx.x == 0) __hip_atomic_store(words + m, (tag << 1) | (uint32_t)sel, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
   while_waiting();
-  if (threadIdx.x == 0) {
-    uint32_t spins = 0;
-    // (difference compared as signed so that the counter may wrap)
-    // (relaxed polls: the fence below is the acquire, once, instead of a cache invalidation per poll)
-    while (!dead && (int32_t)(__hip_atomic_load(a.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-      if (++spins > a.spin_limit) { dead = true; atomicOr(a.s.err, 2u); break; }
-      __builtin_amdgcn_s_sleep(2);
+  if (threadIdx.x < kWave) {
+    const int lane = threadIdx.x;
+    for (int m0 = 0; m0 < M; m0 += kWave) {
+      const int mm = m0 + lane;
+      uint32_t v = 0, spins = 0;
+      // (relaxed polls: the fence below is the acquire, once, instead of a cache invalidation per poll)
+      for (;;) {
+        if (mm < M) v = __hip_atomic_load(words + mm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool ok = mm >= M || (v >> 1) == tag;
+        if (dead || __all(ok)) break;
+        if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicOr(a.s.err, 2u); break; }    // (the whole wavefront: spins is uniform)
+        __builtin_amdgcn_s_sleep(2);
+      }
+      if (mm < M) dk_s[mm] = (unsigned char)(v & 1u);
     }
   }
   __syncthreads();
@@ -107,13 +122,13 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
   __shared__ double redd[kBlock];
   __shared__ float bcast[2];
   __shared__ float ring_s[CADA_MAX_DMAX];      // the squared steps, kept up to date by every workgroup for itself
+  __shared__ unsigned char dk_s[256];          // the workers' buffer selectors after this step's decisions (M <= CUs <= 256)
 
   const int m = blockIdx.x, nb = gridDim.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t mp = (int64_t)M * s.p;
   const float invB = 1.0f / (float)B;
   bool dead = false;
-  uint32_t bar_target = a.bar_base;
   // What only this workgroup changes during the launch -- its worker's delay and buffer selector -- and what every
   // workgroup can keep up to date by itself -- the ring of squared steps -- is read from memory once: a step is a
   // chain of dependent memory round trips, and each one taken off it is a microsecond.
@@ -125,7 +140,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     th_s[j] = s.theta[j]; tl_s[j] = s.theta_lo[j]; h_s[j] = s.h[j]; vh_s[j] = s.vhat[j];
     if (s.rule == CADA_RULE_CADA1) { sn_s[j] = s.snap[j]; snl_s[j] = s.snap_lo[j]; }
   }
-  int32_t *dec = reinterpret_cast<int32_t *>(a.bar + 64);     // [2][M] the selectors after the decisions of step k, slot k mod 2
+  uint32_t *dec = a.bar + 64;                  // [2][M] {tag, selector after the decision} of step k in slot k mod 2
   // the squared step of the iteration before this launch: partial sums that the launch before (or cada_set_state) left
   float newest_c = 0.f;
   {
@@ -336,14 +351,13 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
         s.tau[m] = tau + 1;
         if (s.rule == CADA_RULE_CADA2 && tau >= s.D) atomicOr(s.err, 8u);   // (a replay mask outlasting the retained iterates)
       }
-      dec[(k & 1) * M + m] = up ? (cur ^ 1) : cur;
       bcast[0] = newest;
       bcast[1] = up ? 1.f : 0.f;
     }
     lds_sync();
     if (bcast[1] != 0.f) { tau_m = 1; cur ^= 1; } else tau_m += 1;
-    bar_target += (uint32_t)nb;
-    grid_barrier(a, bar_target, dead, [&]() __attribute__((always_inline)) {
+    const uint32_t tag = ((a.bar_base + (uint32_t)step) & 0x3fffffffu) + 1u;      // (bar_base advances by n_steps M >= n_steps per launch)
+    decision_barrier(a, dec + (k & 1) * M, M, m, tag, cur, dk_s, dead, [&]() __attribute__((always_inline)) {
       if (!more) return;
       // (x_s and r_s were last read by the gradient pass, several workgroup barriers ago)
       for (int b = w; b < B; b += NW) {
@@ -367,7 +381,7 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     if (m == 0 && tid == 0 && k > 0) s.ring[(k - 1) % s.d_max] = bcast[0];   // (for the world outside: every workgroup has its own copy)
     float sqs = 0.f;
     const float alpha = stepsize(s, k);
-    const int32_t *dk = dec + (k & 1) * M;
+    const unsigned char *dk = dk_s;
     const bool snap_now = s.rule == CADA_RULE_CADA1 && (k + 1) % s.D == 0;
     // one coordinate: this workgroup's copies of the server's vectors, and its share of the results in memory
     auto update = [&](int j, float nab) __attribute__((always_inline)) {
@@ -405,29 +419,47 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     // The aggregate: every load of a thread is independent of the others (the selectors are one cheap read for all),
     // four coordinates per 16-byte load where the rows allow it; the sum runs over the workers in their order.
     if (v4) {
-      for (int j = tid * 4; j < p; j += 4 * kBlock) {
-        float4 nab = make_float4(0.f, 0.f, 0.f, 0.f);
-        // (sixteen workers' rows asked for before the first is added: the sum is a chain of round trips otherwise)
-        for (int m0 = 0; m0 < M; m0 += 16) {
-          float4 g[16];
+      // (NG workers' rows asked for before the first is added: the sum is a chain of memory round trips otherwise;
+      // 16 at a time, 32 when there are more workers than 16)
+      auto aggregate = [&](auto NGc) __attribute__((always_inline)) {
+        constexpr int NG = decltype(NGc)::value;
+        for (int j = tid * 4; j < p; j += 4 * kBlock) {
+          float4 nab = make_float4(0.f, 0.f, 0.f, 0.f);
+          for (int m0 = 0; m0 < M; m0 += NG) {
+            float4 g[NG];
 #pragma unroll
-          for (int q = 0; q < 16; ++q) {
-            const int mm = min(m0 + q, M - 1);
-            g[q] = *reinterpret_cast<const float4 *>(s.gbuf + (int64_t)dk[mm] * mp + (int64_t)mm * s.p + j);
+            for (int q = 0; q < NG; ++q) {
+              const int mm = min(m0 + q, M - 1);
+              g[q] = *reinterpret_cast<const float4 *>(s.gbuf + (int64_t)dk[mm] * mp + (int64_t)mm * s.p + j);
+            }
+#pragma unroll
+            for (int q = 0; q < NG; ++q)
+              if (m0 + q < M) { nab.x += g[q].x; nab.y += g[q].y; nab.z += g[q].z; nab.w += g[q].w; }
           }
-#pragma unroll
-          for (int q = 0; q < 16; ++q)
-            if (m0 + q < M) { nab.x += g[q].x; nab.y += g[q].y; nab.z += g[q].z; nab.w += g[q].w; }
+          update(j, nab.x); update(j + 1, nab.y); update(j + 2, nab.z); update(j + 3, nab.w);
         }
-        update(j, nab.x); update(j + 1, nab.y); update(j + 2, nab.z); update(j + 3, nab.w);
-      }
+      };
+      if (M > 16) aggregate(std::integral_constant<int, 32>{}); else aggregate(std::integral_constant<int, 16>{});
     } else {
-      for (int j = tid; j < p; j += kBlock) {
-        float nab = 0.f;
-#pragma unroll 8
-        for (int mm = 0; mm < M; ++mm) nab += s.gbuf[(int64_t)dk[mm] * mp + (int64_t)mm * s.p + j];
-        update(j, nab);
-      }
+      auto aggregate = [&](auto NGc) __attribute__((always_inline)) {
+        constexpr int NG = decltype(NGc)::value;
+        for (int j = tid; j < p; j += kBlock) {
+          float nab = 0.f;
+          for (int m0 = 0; m0 < M; m0 += NG) {
+            float g[NG];
+#pragma unroll
+            for (int q = 0; q < NG; ++q) {
+              const int mm = min(m0 + q, M - 1);
+              g[q] = s.gbuf[(int64_t)dk[mm] * mp + (int64_t)mm * s.p + j];
+            }
+#pragma unroll
+            for (int q = 0; q < NG; ++q)
+              if (m0 + q < M) nab += g[q];
+          }
+          update(j, nab);
+        }
+      };
+      if (M > 16) aggregate(std::integral_constant<int, 32>{}); else aggregate(std::integral_constant<int, 16>{});
     }
     newest_c = block_sum_lds(sqs, red);          // (ends with a workgroup barrier: the next phase A sees the new copies)
     if (tid == 0) s.ring_part[m] = m == 0 ? newest_c : 0.f;     // what a later launch, or reading the state out, adds up
