@@ -164,7 +164,7 @@ void carve_common(Carver &w, const cada_config *cfg, const Geometry &g, DevState
     zpart = w.take<float>(M * (size_t)cfg->B * (size_t)g.n_col_chunks * 2);
     post = w.take<unsigned long long>(kFusedPostWords);
     if (cfg->p >= 8192 && cfg->p % 4 == 0) tail = w.take<float>(kFusedTailFloatsPerP * (size_t)cfg->p);   // (shapes the single-pass kernel serves)
-    small_bar = w.take<uint32_t>(64 + 2 * M);      // the barrier counter, and behind it the decisions of the last two steps [2][M]
+    small_bar = w.take<uint32_t>(64 + 2 * M);      // (a cache line kept free,) then the tagged decision words of the last two steps [2][M]
     small_args = w.take<unsigned char>(kSmallArgsBytes);
   }
   if (!s) return;

@@ -174,7 +174,7 @@ struct Ctx {
   int small;
   size_t small_lds;
   int small_plain_launch;    // launch it as an ordinary grid (profilers that cannot trace cooperative dispatches)
-  uint32_t *small_bar;       // grid barrier counter in the workspace
+  uint32_t *small_bar;       // the whole-step kernel's barrier words in the workspace
   uint32_t small_seq;        // its value after everything enqueued so far
   void *small_args;          // room in the workspace for this context's launch-invariant arguments (replica launches)
   void *small_args_host;     // their host copy (owned by the context)

@@ -32,8 +32,8 @@ struct SmallArgs {
   const int32_t *idx;        // [n_steps][M][B]
   const uint8_t *replay;     // [n_steps][M] or nullptr
   int64_t n_steps;
-  uint32_t *bar;             // barrier counter (monotone over the life of the context)
-  uint32_t bar_base;         // its value when this launch starts
+  uint32_t *bar;             // barrier words: [64 unused][2][M] {tag, selector} of the last two steps
+  uint32_t bar_base;         // sequence number of this launch's first step (monotone over the life of the context)
   uint32_t spin_limit;
 };
 static_assert(sizeof(SmallArgs) <= kSmallArgsBytes, "room kept in the workspace for a replica launch");
