@@ -219,49 +219,54 @@ __global__ __launch_bounds__(kBlock) void k_small(const SmallLaunch launch) {
     for (int b = kBlock + tid; b < B; b += kBlock) r_s[b] = static_cast<const float *>(s.y)[row_s[b] / s.p];
     }
     __syncthreads();
-    // rows over the wavefronts, four at a time (their eight reductions overlap): z = x.theta,
-    // dz = x.d, then the residual and its difference
-    for (int b0 = w; b0 < B; b0 += 4 * NW) {
-      const float *x[4];
-      float z[4] = {0.f, 0.f, 0.f, 0.f}, dz[4] = {0.f, 0.f, 0.f, 0.f};
+    // rows over the wavefronts, RP at a time per wavefront (their 2 RP reductions overlap; RP = 8 for more than 16
+    // rows, so that 32 rows are one pass): z = x.theta, dz = x.d, then the residual and its difference
+    auto products = [&](auto RPc) __attribute__((always_inline)) {
+      constexpr int RP = decltype(RPc)::value;
+      for (int b0 = w; b0 < B; b0 += RP * NW) {
+        const float *x[RP];
+        float z[RP], dz[RP];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) x[q] = x_s + min(b0 + q * NW, B - 1) * p;      // (a row past the end repeats the last one and is dropped)
-      if (v4) {
-        for (int j = lane * 4; j < p; j += 4 * kWave) {
-          const float4 th = *reinterpret_cast<const float4 *>(th_s + j), dd = *reinterpret_cast<const float4 *>(d_s + j);
+        for (int q = 0; q < RP; ++q) { z[q] = 0.f; dz[q] = 0.f; x[q] = x_s + min(b0 + q * NW, B - 1) * p; }   // (a row past the end repeats the last one and is dropped)
+        if (v4) {
+          for (int j = lane * 4; j < p; j += 4 * kWave) {
+            const float4 th = *reinterpret_cast<const float4 *>(th_s + j), dd = *reinterpret_cast<const float4 *>(d_s + j);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float4 xv = *reinterpret_cast<const float4 *>(x[q] + j);
-            z[q] = fmaf(xv.x, th.x, z[q]); z[q] = fmaf(xv.y, th.y, z[q]); z[q] = fmaf(xv.z, th.z, z[q]); z[q] = fmaf(xv.w, th.w, z[q]);
-            dz[q] = fmaf(xv.x, dd.x, dz[q]); dz[q] = fmaf(xv.y, dd.y, dz[q]); dz[q] = fmaf(xv.z, dd.z, dz[q]); dz[q] = fmaf(xv.w, dd.w, dz[q]);
+            for (int q = 0; q < RP; ++q) {
+              const float4 xv = *reinterpret_cast<const float4 *>(x[q] + j);
+              z[q] = fmaf(xv.x, th.x, z[q]); z[q] = fmaf(xv.y, th.y, z[q]); z[q] = fmaf(xv.z, th.z, z[q]); z[q] = fmaf(xv.w, th.w, z[q]);
+              dz[q] = fmaf(xv.x, dd.x, dz[q]); dz[q] = fmaf(xv.y, dd.y, dz[q]); dz[q] = fmaf(xv.z, dd.z, dz[q]); dz[q] = fmaf(xv.w, dd.w, dz[q]);
+            }
+          }
+        } else {
+          for (int j = lane; j < p; j += kWave) {
+            const float th = th_s[j], dd = d_s[j];
+#pragma unroll
+            for (int q = 0; q < RP; ++q) {
+              const float xv = x[q][j];
+              z[q] = fmaf(xv, th, z[q]);
+              dz[q] = fmaf(xv, dd, dz[q]);
+            }
           }
         }
-      } else {
-        for (int j = lane; j < p; j += kWave) {
-          const float th = th_s[j], dd = d_s[j];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float xv = x[q][j];
-            z[q] = fmaf(xv, th, z[q]);
-            dz[q] = fmaf(xv, dd, dz[q]);
+        for (int q = 0; q < RP; ++q) { z[q] = wave_sum_dpp(z[q]); dz[q] = wave_sum_dpp(dz[q]); }
+        {   // lane q takes row q of the RP (every lane holds all the sums): the exponentials of RP rows side by side
+          float zq = z[0], dq = dz[0];
+#pragma unroll
+          for (int q = 1; q < RP; ++q) { zq = lane == q ? z[q] : zq; dq = lane == q ? dz[q] : dq; }
+          const int b = b0 + lane * NW;
+          if (lane < RP && b < B) {
+            const float y = r_s[b];
+            const float aa = -y * zq, bb = aa + y * dq;
+            const float sa = sigmoid_s(aa);
+            r_s[b] = -y * sa * invB;
+            dr_s[b] = y * sa * sigmoid_s(-bb) * expm1f(y * dq) * invB;
           }
         }
       }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) { z[q] = wave_sum_dpp(z[q]); dz[q] = wave_sum_dpp(dz[q]); }
-      {   // lane q takes row q of the four (every lane holds all eight sums): the exponentials of four rows side by side
-        const float zq = lane == 0 ? z[0] : lane == 1 ? z[1] : lane == 2 ? z[2] : z[3];
-        const float dq = lane == 0 ? dz[0] : lane == 1 ? dz[1] : lane == 2 ? dz[2] : dz[3];
-        const int b = b0 + lane * NW;
-        if (lane < 4 && b < B) {
-          const float y = r_s[b];
-          const float aa = -y * zq, bb = aa + y * dq;
-          const float sa = sigmoid_s(aa);
-          r_s[b] = -y * sa * invB;
-          dr_s[b] = y * sa * sigmoid_s(-bb) * expm1f(y * dq) * invB;
-        }
-      }
-    }
+    };
+    if (B > 16) products(std::integral_constant<int, 8>{}); else products(std::integral_constant<int, 4>{});
     __syncthreads();
     // columns over the threads: fresh gradient, innovation, the rule's left-hand side
     float *gf = s.gbuf + (int64_t)(1 - cur) * mp + (int64_t)m * s.p;
