@@ -114,6 +114,18 @@ def test_whole_steps_with_more_rows_than_threads(p, rule):
     print(p, rule, stats, tr["mask"].mean())
 
 
+@pytest.mark.parametrize("M,p,rule", [(70, 54, 2), (33, 64, 1), (17, 54, 1)])
+def test_whole_steps_with_many_workers(M, p, rule):
+    """The whole-step kernel with more workers than a wavefront has lanes (the barrier's words are polled in two
+    rounds) and more than the 16 or 32 whose rows the aggregate asks for at a time, on the 16-byte and the scalar path."""
+    cfg = configs.CFG1.scaled(name="many%d" % M, layer_dims=(p,), M=M, N_m=80, B=8, K=40, D=6, rule=rule, c=0.05)
+    prob, dev, sched = _case(cfg)
+    stats, o, tr, rep = check_protocol(cfg, prob, dev, sched, FP32_TOL, lhs_rtol=1e-4, path=PATH_WHOLE_STEPS, expect_phase="logreg_whole_steps")
+    print(M, p, rule, stats, tr["mask"].mean())
+    free = tr["tau"] < cfg.D
+    assert 0.02 < tr["mask"][free].mean() < 0.98, "the case must mix rule-driven uploads and skips"
+
+
 def test_special_cases_c0_and_huge_c():
     cfg = configs.CFG1.scaled(c=0.0, K=50)
     prob, dev, sched = _case(cfg)
